@@ -1,0 +1,180 @@
+"""Pins for the oracle's samplers: the special cases and invariants the paper states."""
+import math
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import rdlm_oracle as O
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    shape = S.TINY
+    return shape, O.RecurrentDepthLM(shape, S.make_weights(shape, 1)), S.make_prompt(shape.vocab, 16, 1)
+
+
+@pytest.fixture(scope="module")
+def tiny_conditioned():
+    """Same shape with a 6x larger embedding: the conditioning e then outweighs the state in the
+    adapter input and the recurrence settles, so that a threshold on delta_i can fire."""
+    shape = S.TINY
+    w = S.make_weights(shape, 1)
+    w["emb"] = w["emb"] * 6.0
+    return shape, O.RecurrentDepthLM(shape, w), S.make_prompt(shape.vocab, 16, 1)
+
+
+def _same_run(a: O.Trace, b: O.Trace):
+    assert np.array_equal(a.tokens, b.tokens)
+    assert a.final_states.keys() == b.final_states.keys()
+    for p in a.final_states:
+        assert np.array_equal(a.final_states[p], b.final_states[p])
+        assert a.recurrences[p] == b.recurrences[p]
+
+
+@pytest.mark.parametrize("temperature", [0.0, 1.0])
+def test_inner_recurrence_equal_to_r_recovers_autoregressive(tiny, temperature):
+    """End of Sec. 3.3: with the fixed exit rule, r' = r is exactly the autoregressive sampler."""
+    _, m, prompt = tiny
+    ar = O.generate_autoregressive(m, prompt, 12, 4, temperature=temperature, seed=3)
+    df = O.generate_diffusion_forcing(m, prompt, 12, 4, 4, temperature=temperature, seed=3)
+    _same_run(ar, df)
+    assert df.steps == 12 and max(df.window_sizes) == 1
+
+
+@pytest.mark.parametrize("r_inner", [1, 2])
+def test_wavefront_of_one_recovers_adaptive_compute(tiny_conditioned, r_inner):
+    """Sec. 3.5: a wavefront of one token is the token-per-token adaptive-compute sampler."""
+    _, m, prompt = tiny_conditioned
+    kw = dict(r_inner=r_inner, r_cap=24, eps=0.05, temperature=1.0, seed=4)
+    a = O.generate_adaptive_autoregressive(m, prompt, 10, **kw)
+    d = O.generate_diffusion_forcing_adaptive(m, prompt, 10, w_max=1, **kw)
+    _same_run(a, d)
+    assert a.steps == d.steps
+    recs = list(a.recurrences.values())
+    assert min(recs) < 24, "the threshold never fired: the test would not exercise early exit"
+    assert all(r % r_inner == 0 for r in recs)
+
+
+@pytest.mark.parametrize("r,r_inner,headway", [(4, 1, 1), (6, 2, 1), (5, 2, 1), (4, 1, 3)])
+def test_adaptive_with_zero_threshold_is_the_fixed_exit_sampler(tiny, r, r_inner, headway):
+    """eps = 0 never converges, so only the recurrence cap freezes: Alg. 2 must then walk exactly
+    like Alg. 1 (whose rule is that cap)."""
+    _, m, prompt = tiny
+    w = -(-r // r_inner) * headway
+    a = O.generate_diffusion_forcing(m, prompt, 12, r_inner, r, headway=headway, seed=2)
+    b = O.generate_diffusion_forcing_adaptive(m, prompt, 12, r_inner, r, 0.0, w, headway=headway, seed=2)
+    _same_run(a, b)
+    assert a.steps == b.steps and a.window_sizes == b.window_sizes
+
+
+@pytest.mark.parametrize("r,r_inner", [(4, 1), (8, 2), (7, 3)])
+def test_fixed_exit_wave_shape(tiny, r, r_inner):
+    """Sec. 3.3: the wave holds ceil(r/r') states, advances one token per step once full, and a
+    token is frozen exactly when its position has had ceil(r/r') sampler steps."""
+    _, m, prompt = tiny
+    n_new = 10
+    w = -(-r // r_inner)
+    tr = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r)
+    assert tr.steps == n_new + w - 1
+    assert max(tr.window_sizes) == w
+    assert tr.window_sizes[:w] == list(range(1, w + 1))
+    assert tr.frozen_per_step == [0] * (w - 1) + [1] * n_new
+    assert all(v == w * r_inner for v in tr.recurrences.values())
+    assert sorted(tr.final_states) == list(range(15, 15 + n_new))
+
+
+def test_headway_wave_shape(tiny):
+    """Sec. 4.2 (moving forward multiple steps): headway g appends g states per step, so the wave
+    holds g*r states and g tokens are frozen per step."""
+    _, m, prompt = tiny
+    tr = O.generate_diffusion_forcing(m, prompt, 12, 1, 4, headway=3, pad_token=7)
+    assert max(tr.window_sizes) == 3 * 4 and tr.window_sizes[:6] == [1, 4, 7, 10, 12, 12]
+    assert tr.frozen_per_step[:4] == [0, 0, 0, 1]
+    assert set(tr.frozen_per_step[4:]) == {3}
+    # the first generated token never sees a pad input: it cannot depend on the pad token
+    tr2 = O.generate_diffusion_forcing(m, prompt, 12, 1, 4, headway=3, pad_token=9)
+    assert tr.tokens[16] == tr2.tokens[16]
+    assert np.array_equal(tr.final_states[15], tr2.final_states[15])
+
+
+def test_wavefront_limit_stalls_and_bounds_memory(tiny):
+    """Sec. 3.5: the limiter bounds the number of states in flight; when nothing converges the
+    wave stalls at that size until the cap frees its head."""
+    _, m, prompt = tiny
+    tr = O.generate_diffusion_forcing_adaptive(m, prompt, 8, 1, 6, 0.0, 3)
+    assert max(tr.window_sizes) == 3
+    assert 3 in tr.window_sizes and tr.frozen_per_step.count(0) > 3
+    assert all(v == 6 for v in tr.recurrences.values())
+    assert len(tr.tokens) == 16 + 8
+
+
+def test_adaptive_freezes_only_converged_prefixes(tiny_conditioned):
+    _, m, prompt = tiny_conditioned
+    eps, cap = 0.05, 400
+    tr = O.generate_diffusion_forcing_adaptive(m, prompt, 10, 1, cap, eps, 8)
+    assert any(k > 0 for k in tr.frozen_per_step)
+    assert max(tr.recurrences.values()) < cap, "the cap fired: the prefix rule below would not hold"
+    for d, k in zip(tr.deltas, tr.frozen_per_step):
+        assert all(x < eps for x in d[:k])          # every frozen state was below the threshold
+        if k < len(d):
+            assert not d[k] < eps                   # and the first one kept was not
+    assert min(tr.recurrences.values()) < cap, "threshold never fired"
+    assert max(tr.window_sizes) <= 8
+    # a brand-new state is compared with its random initialisation: it cannot look converged
+    assert all(d[-1] > 0.5 for d in tr.deltas[1:] if len(d) > 1)
+
+
+def test_contraction_gives_the_autoregressive_solution():
+    """Remark of Sec. 3.5: if R is a contraction, the adaptive sampler converges to what
+    autoregressive sampling (run to its fixed point) produces."""
+    shape = S.TINY
+    w = S.make_weights(shape, 6)
+    w["wa"] = w["wa"].copy()
+    w["wa"][:, shape.hidden:] *= 0.02          # the state half of the adapter barely feeds back
+    w["emb"] = w["emb"] * 8.0                   # conditioning dominates
+    m = O.RecurrentDepthLM(shape, w)
+    prompt = S.make_prompt(shape.vocab, 12, 5)
+    ar = O.generate_autoregressive(m, prompt, 10, 48)
+    df = O.generate_diffusion_forcing_adaptive(m, prompt, 10, 1, 200, 1e-9, 6, r_prefill=48)
+    assert np.array_equal(ar.tokens, df.tokens)
+    for p in ar.final_states:
+        assert np.allclose(ar.final_states[p], df.final_states[p], rtol=0, atol=1e-6)
+    assert max(df.recurrences.values()) < 200, "only the cap fired: not a convergence test"
+
+
+def test_cost_remark(tiny):
+    """Remark of Sec. 3.5: one sampler iteration costs (cost of P and C) + r' * f per in-flight
+    token; over w tokens the fixed-exit sampler spends (r + r/r') f w against (r + 1) f w when
+    P and C together cost f."""
+    shape, m, prompt = tiny
+    h, Fm, V = shape.hidden, shape.mlp, shape.vocab
+    layer = 2 * (4 * h * h + 3 * h * Fm)
+    f_R = shape.n_core * layer + 2 * (2 * h * h)
+    f_PC = (shape.n_prelude + shape.n_coda) * layer + 2 * V * h
+    r, r_inner, n_new = 4, 2, 9
+    m.counter.flops = 0
+    O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, r_prefill=0)
+    got_df = m.counter.flops
+    m.counter.flops = 0
+    tr = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, r_prefill=0)
+    prefill_part = (len(prompt) - 1) * (f_PC - 2 * V * h)
+    assert got_df == sum(tr.window_sizes) * (f_PC + r_inner * f_R) + prefill_part
+    m.counter.flops = 0
+    O.generate_autoregressive(m, prompt, n_new, r, r_prefill=0)
+    assert m.counter.flops == n_new * (f_PC + r * f_R) + prefill_part
+    # steady state: each token spends r/r' iterations in flight
+    per_token = (r // r_inner) * (f_PC + r_inner * f_R)
+    assert per_token == (r // r_inner) * f_PC + r * f_R
+
+
+def test_streams_are_not_degenerate(tiny):
+    """Parity on token ids means little if every run emits the same few tokens, or if the prompt
+    does not matter."""
+    _, m, prompt = tiny
+    tr = O.generate_diffusion_forcing(m, prompt, 32, 1, 4)
+    assert len(set(tr.tokens[16:].tolist())) >= 16
+    p2 = prompt.copy()
+    p2[3] = (p2[3] + 1) % 256
+    tr2 = O.generate_diffusion_forcing(m, p2, 32, 1, 4)
+    assert (tr.tokens[16:] != tr2.tokens[16:]).sum() >= 2
