@@ -1,0 +1,189 @@
+/*
+ * rdlm.h -- C ABI of the diffusion-forcing sampler hot path for recurrent-depth language models
+ * on AMD MI355X (gfx950).
+ *
+ * Model (Sec. 3.1 of the paper):  e = P(x),  s_0 ~ N(0, sigma^2 I),  s_i = R(e, s_{i-1}),
+ * p = C(s_r), with prelude P, recurrent block R and coda C made of transformer layers, input
+ * injection through an adapter Linear(2h -> h) on concat(e, s), and a KV cache shared across
+ * recurrence depth (Sec. 3.2: one K/V entry per layer and position, overwritten in place).
+ * Samplers: Alg. 1 (fixed exit) and Alg. 2 (exit on the latent's relative change, Eq. 3, with a
+ * wavefront limit).
+ *
+ * Conventions
+ *   - Every function returns RDLM_OK (0) or a negative rdlm_status.  Arguments are validated on
+ *     the host before anything is enqueued; a failed call enqueues nothing.
+ *   - "device" pointers are HIP device memory owned by the caller unless stated otherwise;
+ *     "host" pointers are ordinary host memory.  No torch types cross this boundary.
+ *   - All work is enqueued on the stream given to rdlm_create and is asynchronous, except the
+ *     rdlm_read_* functions and rdlm_generate, which synchronise that stream.
+ *   - After rdlm_create the library allocates no further memory.
+ *   - Rows of a step are given per sequence as (seq id, first position, row count): row j of
+ *     sequence entry i sits at absolute position pos0[i] + j; rows of all entries are
+ *     concatenated in the order given ("M rows").  Row-major float32 [M, hidden] everywhere.
+ *   - Calls on one context must not overlap in time (one stream, one workspace).
+ */
+#ifndef RDLM_H
+#define RDLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rdlm_ctx rdlm_ctx;
+
+typedef enum {
+    RDLM_OK = 0,
+    RDLM_EINVAL = -1,     /* null pointer, non-positive size, shape the kernels do not support   */
+    RDLM_ECAPACITY = -2,  /* more sequences, rows or positions than the context was created for   */
+    RDLM_ENOMEM = -3,     /* device allocation failed in rdlm_create                              */
+    RDLM_EHIP = -4,       /* a HIP call failed; see rdlm_last_hip_error                           */
+    RDLM_ESTATE = -5      /* call out of order (e.g. sample_step before sampler_begin)            */
+} rdlm_status;
+
+enum { RDLM_F32 = 0, RDLM_BF16 = 1 };
+
+/* Shape of the model.  dtype is the storage type of the matrices (and of the KV cache and GEMM
+ * operands); accumulation, norms, softmax and the latent state are always float32.
+ * RDLM_BF16 needs hidden % 32 == 0, mlp % 32 == 0, vocab % 32 == 0, head_dim % 32 == 0. */
+typedef struct {
+    int32_t vocab, hidden, n_heads, head_dim, mlp;
+    int32_t n_prelude, n_core, n_coda;
+    float rope_base;      /* RoPE base, rotate-half pairing (i, i + head_dim/2), absolute positions */
+    float rms_eps;        /* x * g / sqrt(mean(x^2) + rms_eps)                                     */
+    float emb_scale;      /* factor applied to gathered embedding rows                             */
+    int32_t dtype;        /* RDLM_F32 or RDLM_BF16                                                 */
+} rdlm_model;
+
+/* Hyper-parameters of Alg. 1 / Alg. 2.  adaptive = 0: a state is frozen after r_total
+ * recurrences (Alg. 1).  adaptive = 1: the longest prefix of states with delta_i < eps, or with
+ * r_total recurrences, is frozen, and states are appended only while fewer than w_max are in
+ * flight (Alg. 2, Eq. 3).  headway states are appended per step (Sec. 4.2); those beyond the
+ * first read pad_token until a draft exists.  temperature 0 = greedy (lowest id wins ties),
+ * otherwise Gumbel-max sampling from softmax(logits / temperature). */
+typedef struct {
+    int32_t n_new;        /* N: tokens to generate per sequence                                   */
+    int32_t r_inner;      /* r'                                                                   */
+    int32_t r_total;      /* r (fixed exit) or the recurrence cap (adaptive)                      */
+    int32_t w_max;        /* wavefront limit; <= 0 means ceil(r_total / r_inner) * headway        */
+    int32_t headway;
+    int32_t adaptive;
+    float eps;
+    float alpha;          /* init scale of InitState                                              */
+    float temperature;
+    int32_t pad_token;
+    uint64_t seed;        /* key of the counter-based generator (state init, Gumbel noise)        */
+} rdlm_sampler;
+
+/* Number of weight tensors rdlm_create expects, and their order:
+ *   emb [V,h];  then for each layer of P, then R, then C:
+ *   g1 [h] (f32), wqkv [3h,h] (rows: all q heads, all k heads, all v heads), wo [h,h], g2 [h] (f32),
+ *   wg [F,h], wu [F,h], wd [h,F];  then wa [h,2h] (columns: e first, then s), gf [h] (f32),
+ *   gout [h] (f32).   Matrices are row-major [out_features, in_features] in the model dtype
+ *   (bf16 = upper 16 bits of the float32 pattern); gains are float32.  The LM head is emb (tied). */
+int32_t rdlm_num_weights(const rdlm_model* m);
+
+/* Create a context for up to max_seqs sequences of up to max_positions positions each and up to
+ * max_rows rows per step (window rows of all sequences, or prefill rows).  weight_ptrs: host
+ * array of rdlm_num_weights() device pointers; the library copies (and re-tiles) what it needs,
+ * so the caller may free them afterwards.  hip_stream: a hipStream_t (NULL = default stream). */
+int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out);
+int rdlm_destroy(rdlm_ctx* ctx);
+
+const char* rdlm_strerror(int status);
+int rdlm_last_hip_error(const rdlm_ctx* ctx);   /* hipError_t of the last failed HIP call, or 0 */
+
+/* Bytes of device memory the context holds (weights re-tiled, KV cache, workspace, sampler state). */
+size_t rdlm_device_bytes(const rdlm_ctx* ctx);
+
+/* ---- sequence text ------------------------------------------------------------------------ */
+/* Set the known tokens of a sequence (y_frozen = y_current = x, Alg. 1 lines 1-2); tokens_host
+ * [n] int32 in [0, vocab).  Clears the sequence's sampler state. */
+int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens_host, int32_t n);
+
+/* Parallel prefill (Sec. 3.3): positions 0..n-1 of the sequence at once: e = P(x), fresh states
+ * InitState(n, alpha), r recurrences of R, then the coda layers, so that every layer's cache holds
+ * these positions.  n may be 0 (no-op).  Needs n <= max_rows. */
+int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, float alpha, uint64_t seed);
+
+/* ---- the four calls of the sampler (Alg. 1: InitState, R, C + Sample, one whole iteration) --- */
+
+/* InitState(n, alpha): z_out[j, :] ~ alpha * N(0, I) for positions pos0..pos0+n-1 of sequence
+ * seq (device float32 [n, hidden]).  Counter-based: Philox4x32-10 keyed by seed, counter
+ * (element/4, position, seq, tag), Box-Muller on uniforms u = (x>>9 + 1/2) * 2^-23. */
+int rdlm_init_state(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float alpha,
+                    uint64_t seed, float* z_out);
+
+/* e = P(tokens) for the given rows (prelude caches at those positions are overwritten).
+ * tokens_dev: device int32 [M]; e_out: device float32 [M, hidden]. */
+int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                 const int32_t* n_rows, const int32_t* tokens_dev, float* e_out);
+
+/* r_inner recurrences z <- R(z, e) over all given rows at once (Alg. 1 lines 8-10), each row
+ * attending to the cache prefix plus the rows before it in this step; core caches at those
+ * positions are overwritten.  delta_out (device float32 [M], may be NULL) receives
+ * ||z_new - z_in|| / ||z_new|| per row (Eq. 3 with z_prev = the z passed in).
+ * seq_ids / pos0 / n_rows: host int32 [n_seqs].  e, z_inout: device float32 [M, hidden]. */
+int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                   const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
+                   float* delta_out);
+
+/* C + Sample on every given row (Alg. 1 lines 11-12): coda layers (caches overwritten), final
+ * norm, tied LM head, then greedy or Gumbel-max at (seed, step).  tokens_out: device int32 [M];
+ * logits_out: device float32 [M, vocab] or NULL. */
+int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                     const int32_t* n_rows, const float* z, float temperature, uint64_t seed,
+                     int32_t step, int32_t* tokens_out, float* logits_out);
+
+/* Start the sampler on sequences 0..n_seqs-1: each needs rdlm_set_tokens (L >= 1 tokens) and
+ * rdlm_prefill of its first L-1 positions before.  Creates one fresh state at position L-1
+ * (Alg. 1 line 3).  Needs L + n_new + w_max + headway <= max_positions and
+ * n_seqs * roundup32(w_max) <= max_rows. */
+int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t n_seqs);
+
+/* One iteration of Alg. 1 / Alg. 2 for all sequences that are not finished, entirely on the
+ * device (no host synchronisation): P on the in-flight tokens, r' x R, C, Sample, drafts written
+ * back, delta_i and k*, freeze, append. */
+int rdlm_sample_step(rdlm_ctx* ctx);
+
+/* Iterate rdlm_sample_step until every sequence has n_new frozen tokens or max_steps steps were
+ * taken; synchronises.  steps_out (host, may be NULL) receives the number of iterations run. */
+int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_out);
+
+/* ---- read-back (synchronise the stream) ------------------------------------------------- */
+/* Tokens of a sequence: frozen ones first (prompt + generated); n_frozen_out = |y_frozen|.
+ * Copies min(cap, max_positions) entries of y_current (frozen, then current drafts, then pad). */
+int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap,
+                     int32_t* n_frozen_out);
+/* Latent states kept per position by the sampler (the state a position had when last updated). */
+int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host);
+/* Sampler steps each position spent in flight (its recurrence count is this times r_inner). */
+int rdlm_read_counts(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t* counts_host);
+/* delta_i of the rows of the last sample_step, in row order of sequence seq's window at that
+ * step; n_out = number of rows it had. */
+int rdlm_read_deltas(rdlm_ctx* ctx, int32_t seq, float* delta_host, int32_t cap, int32_t* n_out);
+/* K and V rows of one layer (0-based over P, R, C layers in order) in natural order:
+ * float32 [n, n_heads, head_dim] each (host). */
+int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_t n,
+                 float* k_host, float* v_host);
+
+/* ---- kernel-level entry points (measurement and unit tests) ------------------------------- */
+/* y[M,N] = x[M,K] . W^T for weight tensor index w_index (as in the rdlm_create order; wg and wu
+ * are one fused [2F,h] matrix reachable through wg's index).  x, y: device float32 row-major.
+ * Runs the same tiled kernel the model path uses (including its split-K reduction). */
+int rdlm_linear(rdlm_ctx* ctx, int32_t w_index, const float* x, int32_t m, float* y);
+/* Time `iters` launches of that GEMM alone with HIP events on the context's stream, inputs
+ * resident; returns the average milliseconds per launch in ms_out (host). Synchronises. */
+int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m, int32_t iters, float* ms_out);
+/* Time `iters` core steps (r_inner = 1) over one sequence window [pos0, pos0+n) with HIP events;
+ * the cache content at those positions is overwritten.  Synchronises. */
+int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t iters,
+                        float* ms_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RDLM_H */

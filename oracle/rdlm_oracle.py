@@ -69,8 +69,9 @@ def philox4x32_10(c0, c1, c2, c3, k0: int, k1: int):
 
 
 def _uniform_open(x: np.ndarray) -> np.ndarray:
-    """24 high bits -> u in (0,1): u = (x>>8 + 1/2) * 2^-24 (never 0, never 1)."""
-    return ((x >> np.uint32(8)).astype(F64) + 0.5) * (2.0 ** -24)
+    """23 high bits -> u in (0,1): u = (x>>9 + 1/2) * 2^-23 (never 0, never 1; 24 significant bits,
+    so the value is exact in float32 as well)."""
+    return ((x >> np.uint32(9)).astype(F64) + 0.5) * (2.0 ** -23)
 
 
 def _draw_block(n_blocks: int, position: int, seq: int, step: int, tag: int, seed: int):

@@ -1,0 +1,576 @@
+// Row-wise kernels of the recurrent-depth LM step: tile descriptors, embedding gather, adapter
+// concat, residual-add + RMSNorm (which also folds the split-K partial sums of the preceding
+// GEMM), end-of-recurrence norm + convergence reduction (Eq. 3), RoPE + KV-cache write
+// (Sec. 3.2: in-place overwrite), SwiGLU, Gaussian state init, sampling, and the sampler's
+// device-side bookkeeping (Alg. 1 lines 13-16, Alg. 2 freeze / append).
+#include "rdlm_internal.h"
+
+namespace rdlm {
+
+// ---------------------------------------------------------------------------------------------
+__device__ inline float block_sum(float v, float* sh) {          // 256 threads
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t += sh[i];
+    return t;
+}
+
+template <int FMT>
+__device__ inline void act_store4(void* base, int K, int row, int k, float a, float b, float c, float d) {
+    if (FMT == ACT_F32) {
+        float4 v = make_float4(a, b, c, d);
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(base) + (size_t)row * K + k) = v;
+    } else {
+        ushort4 v;
+        v.x = f32_to_bf16(a); v.y = f32_to_bf16(b); v.z = f32_to_bf16(c); v.w = f32_to_bf16(d);
+        *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(base) + packed_off(row, k, K)) = v;
+    }
+}
+
+__device__ inline float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+
+// ---------------------------------------------------------------------------------------------
+// tile descriptors
+__global__ void build_tiles_api_k(SeqWindows w, int mode, int max_positions, TileDesc* tiles, int32_t* n_tiles) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int t = 0, c = 0;
+    for (int i = 0; i < w.n; ++i) {
+        for (int off = 0; off < w.rows[i]; off += TILE_ROWS) {
+            TileDesc d;
+            d.seq = w.seq[i];
+            d.pos0 = w.pos0[i] + off;
+            d.n_valid = min(TILE_ROWS, w.rows[i] - off);
+            if (mode == 0) {            // caller-owned compact arrays
+                d.zrow0 = d.erow0 = d.yrow0 = c + off;
+            } else {                    // library stores indexed by (seq, position)
+                d.zrow0 = d.yrow0 = w.seq[i] * max_positions + d.pos0;
+                d.erow0 = t * TILE_ROWS;
+            }
+            d.crow0 = c + off;
+            d.pad_ = 0;
+            tiles[t++] = d;
+        }
+        c += w.rows[i];
+    }
+    *n_tiles = t;
+}
+
+__global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positions, TileDesc* tiles,
+                                      int32_t* n_tiles) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int t = 0, c = 0;
+    for (int s = 0; s < n_seqs; ++s) {
+        SeqState& q = seqs[s];
+        q.pad_[0] = t;                                  // first tile of this sequence
+        int rows = q.done ? 0 : q.win_n;
+        q.last_rows = rows;
+        q.last_pos0 = q.win_pos0;
+        for (int off = 0; off < rows; off += TILE_ROWS) {
+            TileDesc d;
+            d.seq = s;
+            d.pos0 = q.win_pos0 + off;
+            d.n_valid = min(TILE_ROWS, rows - off);
+            d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
+            d.erow0 = t * TILE_ROWS;
+            d.crow0 = c + off;
+            d.pad_ = 0;
+            tiles[t++] = d;
+        }
+        c += rows;
+    }
+    *n_tiles = t;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float* x, int h, int V,
+                        const TileDesc* tiles, const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    bool valid = j < d.n_valid;
+    int tok = valid ? tokens[d.yrow0 + j] : 0;
+    tok = min(max(tok, 0), V - 1);
+    for (int k = threadIdx.x; k < h; k += blockDim.x) {
+        float v = 0.f;
+        if (valid) {
+            if (sizeof(T) == 2) v = bf16_to_f32(reinterpret_cast<const uint16_t*>(emb)[(size_t)tok * h + k]);
+            else v = reinterpret_cast<const float*>(emb)[(size_t)tok * h + k];
+        }
+        x[(size_t)r * h + k] = v * scale;
+    }
+}
+
+__global__ void copy_rows_in_k(const float* src, float* x, int h, int which, const TileDesc* tiles,
+                               const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    bool valid = j < d.n_valid;
+    size_t srow = (size_t)(which == 0 ? d.zrow0 : d.erow0) + j;
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = valid ? ld4(src + srow * h + k) : make_float4(0, 0, 0, 0);
+        *reinterpret_cast<float4*>(x + (size_t)r * h + k) = v;
+    }
+}
+
+__global__ void copy_rows_out_k(const float* x, float* dst, int width, int which, const TileDesc* tiles,
+                                const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    if (j >= d.n_valid) return;
+    size_t drow = (size_t)(which == 0 ? d.zrow0 : which == 1 ? d.erow0 : d.crow0) + j;
+    for (int k = threadIdx.x; k < width; k += blockDim.x)
+        dst[drow * width + k] = x[(size_t)r * width + k];
+}
+
+__global__ void copy_i32_out_k(const int32_t* src, int32_t* dst, const TileDesc* tiles, const int32_t* n_tiles) {
+    int r = blockIdx.x * blockDim.x + threadIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    if (j < d.n_valid) dst[d.crow0 + j] = src[r];
+}
+
+template <int FMT>
+__global__ void concat_k(const float* e, const float* z, void* cat, int h, const TileDesc* tiles,
+                         const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    bool valid = j < d.n_valid;
+    const float* er = e + ((size_t)d.erow0 + j) * h;
+    const float* zr = z + ((size_t)d.zrow0 + j) * h;
+    for (int k = threadIdx.x * 4; k < 2 * h; k += blockDim.x * 4) {
+        float4 v = make_float4(0, 0, 0, 0);
+        if (valid) v = (k < h) ? ld4(er + k) : ld4(zr + (k - h));
+        act_store4<FMT>(cat, 2 * h, r, k, v.x, v.y, v.z, v.w);
+    }
+}
+
+// x_out = x_in + sum_s part[s];  xn = x_out * gain / sqrt(mean(x_out^2) + eps)
+template <int FMT>
+__global__ void addnorm_k(const float* xin, float* xout, const float* part, int S, size_t part_stride,
+                          const float* gain, void* xn, int h, float eps, const int32_t* n_tiles) {
+    __shared__ float sh[8];
+    int r = blockIdx.x;
+    if ((r >> 5) >= *n_tiles) return;
+    float ss = 0.f;
+    auto value = [&](int k) {
+        float4 v = xin ? ld4(xin + (size_t)r * h + k) : make_float4(0, 0, 0, 0);
+        for (int s = 0; s < S; ++s) {
+            float4 p = ld4(part + s * part_stride + (size_t)r * h + k);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        return v;
+    };
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = value(k);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = block_sum(ss, sh);
+    float inv = 1.0f / sqrtf(ss / (float)h + eps);
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = value(k);
+        if (xout) *reinterpret_cast<float4*>(xout + (size_t)r * h + k) = v;
+        if (xn) {
+            float4 g = ld4(gain + k);
+            act_store4<FMT>(xn, h, r, k, v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+        }
+    }
+}
+
+// End of a recurrence: z' = RMSNorm(x + sum part) * gain, stored to the latent array; optionally
+// delta = ||z' - z_prev|| / ||z'|| (Eq. 3) and z_prev <- z'.
+__global__ void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
+                             const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
+                             float* delta, const TileDesc* tiles, const int32_t* n_tiles) {
+    __shared__ float sh[8];
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    bool valid = j < d.n_valid;
+    auto value = [&](int k) {
+        float4 v = xin ? ld4(xin + (size_t)r * h + k) : make_float4(0, 0, 0, 0);
+        for (int s = 0; s < S; ++s) {
+            float4 p = ld4(part + s * part_stride + (size_t)r * h + k);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        return v;
+    };
+    float ss = 0.f;
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = value(k);
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    ss = block_sum(ss, sh);
+    float inv = 1.0f / sqrtf(ss / (float)h + eps);
+    float num = 0.f, den = 0.f;
+    size_t zr = (size_t)d.zrow0 + j;
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = value(k);
+        float4 g = ld4(gain + k);
+        float4 o = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+        if (valid) {
+            if (z_prev) {
+                float4 p = ld4(z_prev + zr * h + k);
+                num += (o.x - p.x) * (o.x - p.x) + (o.y - p.y) * (o.y - p.y) + (o.z - p.z) * (o.z - p.z) +
+                       (o.w - p.w) * (o.w - p.w);
+                if (update_prev) *reinterpret_cast<float4*>(z_prev + zr * h + k) = o;
+            }
+            den += o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
+            *reinterpret_cast<float4*>(z + zr * h + k) = o;
+        }
+    }
+    if (delta) {
+        num = block_sum(num, sh);
+        den = block_sum(den, sh);
+        if (threadIdx.x == 0) delta[r] = valid ? sqrtf(num) / sqrtf(den) : 0.f;
+    }
+}
+
+// RoPE (rotate-half pairs (i, i+d/2), angle pos * theta_i) on q and k; q is written for the
+// attention kernel, k and v are written into the layer's cache at the row's position,
+// replacing what an earlier recurrence or sampler step left there.
+template <int DT>
+__global__ void rope_kv_k(const float* qkv, int S, size_t part_stride, void* qout, void* kc, void* vc, int H,
+                          int d, const float* theta, size_t seq_stride, const TileDesc* tiles,
+                          const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc ds = tiles[t];
+    bool valid = j < ds.n_valid;
+    int pos = ds.pos0 + j;
+    int h = H * d, half = d >> 1;
+    auto at = [&](int col) {
+        float v = 0.f;
+        for (int s = 0; s < S; ++s) v += qkv[s * part_stride + (size_t)r * 3 * h + col];
+        return v;
+    };
+    for (int idx = threadIdx.x; idx < H * half; idx += blockDim.x) {
+        int hd = idx / half, i = idx - hd * half;
+        float sn, cs;
+        sincosf((float)pos * theta[i], &sn, &cs);
+        int c0 = hd * d + i, c1 = c0 + half;
+        float q0 = at(c0), q1 = at(c1), k0 = at(h + c0), k1 = at(h + c1);
+        float v0 = at(2 * h + c0), v1 = at(2 * h + c1);
+        float qa = q0 * cs - q1 * sn, qb = q1 * cs + q0 * sn;
+        float ka = k0 * cs - k1 * sn, kb = k1 * cs + k0 * sn;
+        if (DT == 0) {
+            float* q = reinterpret_cast<float*>(qout);
+            q[(size_t)r * h + c0] = qa; q[(size_t)r * h + c1] = qb;
+            if (valid) {
+                float* K = reinterpret_cast<float*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
+                float* Vv = reinterpret_cast<float*>(vc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
+                K[c0] = ka; K[c1] = kb; Vv[c0] = v0; Vv[c1] = v1;
+            }
+        } else {
+            uint16_t* q = reinterpret_cast<uint16_t*>(qout);
+            q[(size_t)r * h + c0] = f32_to_bf16(qa); q[(size_t)r * h + c1] = f32_to_bf16(qb);
+            if (valid) {
+                uint16_t* K = reinterpret_cast<uint16_t*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
+                K[c0] = f32_to_bf16(ka); K[c1] = f32_to_bf16(kb);
+                // transposed V: [position block][head][dim][32 slots]
+                uint16_t* Vt = reinterpret_cast<uint16_t*>(vc) + (size_t)ds.seq * seq_stride +
+                               ((size_t)(pos >> 5) * H + hd) * d * 32 + vt_slot(pos & 31);
+                Vt[(size_t)i * 32] = f32_to_bf16(v0);
+                Vt[(size_t)(i + half) * 32] = f32_to_bf16(v1);
+            }
+        }
+    }
+}
+
+template <int FMT>
+__global__ void swiglu_k(const float* gu, int S, size_t part_stride, void* act, int F, const int32_t* n_tiles) {
+    int r = blockIdx.y;
+    if ((r >> 5) >= *n_tiles) return;
+    int k = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (k >= F) return;
+    float4 g = make_float4(0, 0, 0, 0), u = g;
+    for (int s = 0; s < S; ++s) {
+        float4 a = ld4(gu + s * part_stride + (size_t)r * 2 * F + k);
+        float4 b = ld4(gu + s * part_stride + (size_t)r * 2 * F + F + k);
+        g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+        u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+    }
+    auto f = [](float a, float b) { return a / (1.0f + expf(-a)) * b; };
+    act_store4<FMT>(act, F, r, k, f(g.x, u.x), f(g.y, u.y), f(g.z, u.z), f(g.w, u.w));
+}
+
+// ---------------------------------------------------------------------------------------------
+// InitState: four normals per Philox block through two Box-Muller pairs.
+__device__ inline void gauss4(uint32_t blk, uint32_t pos, uint32_t seq, uint32_t k0, uint32_t k1, float alpha,
+                              float out[4]) {
+    uint32_t x[4];
+    philox4x32_10(blk, pos, seq, TAG_INIT_STATE, k0, k1, x);
+    for (int p = 0; p < 2; ++p) {
+        float ua = u24_open(x[2 * p]), ub = u24_open(x[2 * p + 1]);
+        float rad = sqrtf(-2.0f * logf(ua));
+        float sn, cs;
+        sincospif(2.0f * ub, &sn, &cs);
+        out[2 * p] = alpha * rad * cs;
+        out[2 * p + 1] = alpha * rad * sn;
+    }
+}
+
+__global__ void init_state_rows_k(float* z, float* z_prev, int h, int seq, int pos0, int n, size_t zrow0,
+                                  float alpha, uint32_t k0, uint32_t k1) {
+    int row = blockIdx.y;
+    int blk = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= n || blk * 4 >= h) return;
+    float g[4];
+    gauss4(blk, pos0 + row, seq, k0, k1, alpha, g);
+    for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
+        size_t o = (zrow0 + row) * h + blk * 4 + i;
+        z[o] = g[i];
+        if (z_prev) z_prev[o] = g[i];
+    }
+}
+
+__global__ void init_state_new_k(float* z, float* z_prev, int h, const SeqState* seqs, int max_positions,
+                                 int headway, float alpha, uint32_t k0, uint32_t k1) {
+    int s = blockIdx.y / headway, a = blockIdx.y % headway;
+    SeqState q = seqs[s];
+    if (a >= q.new_n) return;
+    int blk = blockIdx.x * blockDim.x + threadIdx.x;
+    if (blk * 4 >= h) return;
+    int pos = q.new_pos0 + a;
+    float g[4];
+    gauss4(blk, pos, s, k0, k1, alpha, g);
+    for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
+        size_t o = ((size_t)s * max_positions + pos) * h + blk * 4 + i;
+        z[o] = g[i];
+        z_prev[o] = g[i];
+    }
+}
+
+// Sample: greedy or Gumbel-max, one workgroup per row; lowest token id wins ties.
+__global__ void sample_k(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
+                         int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles) {
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    int pos = d.pos0 + j;
+    const float* lg = logits + (size_t)r * V;
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int b = threadIdx.x; b * 4 < V; b += blockDim.x) {
+        float g[4] = {0.f, 0.f, 0.f, 0.f};
+        if (temperature > 0.f) {
+            uint32_t x[4];
+            philox4x32_10(b, pos, d.seq, ((uint32_t)step << 4) | TAG_SAMPLE, k0, k1, x);
+            for (int i = 0; i < 4; ++i) g[i] = -logf(-logf(u24_open(x[i])));
+        }
+        for (int i = 0; i < 4 && b * 4 + i < V; ++i) {
+            float sc = lg[b * 4 + i];
+            if (temperature > 0.f) sc = sc / temperature + g[i];
+            if (sc > best) { best = sc; bi = b * 4 + i; }      // ascending ids: first maximum kept
+        }
+    }
+    sv[threadIdx.x] = best; si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = blockDim.x >> 1; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            float ov = sv[threadIdx.x + o]; int oi = si[threadIdx.x + o];
+            if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) {
+                sv[threadIdx.x] = ov; si[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tok_out[r] = (si[0] == 0x7fffffff) ? 0 : si[0];
+}
+
+// Alg. 1 lines 13-16 / Alg. 2 freeze and append, one thread per sequence.
+__global__ void bookkeep_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
+                           int max_positions, const int32_t* drafts, const float* delta, int32_t* n_active) {
+    int s = threadIdx.x;
+    int active = 0;
+    if (s < n_seqs) {
+        SeqState q = seqs[s];
+        int rows = q.last_rows;                     // rows this sequence had in the step just run
+        if (!q.done && rows > 0) {
+            int row0 = q.pad_[0] * TILE_ROWS;       // its rows are contiguous in padded row space
+            size_t base = (size_t)s * max_positions;
+            for (int i = 0; i < rows; ++i) {        // y_current <- [y_frozen, y_hat]
+                int pos = q.win_pos0 + i;
+                y[base + pos + 1] = drafts[row0 + i];
+                counts[base + pos] += 1;
+            }
+            int k = 0;                              // longest freezable prefix
+            for (; k < rows; ++k) {
+                int pos = q.win_pos0 + k;
+                float dl = delta[row0 + k];
+                bool conv = p.adaptive && (dl == dl) && fabsf(dl) != INFINITY && dl < p.eps;
+                bool cap = counts[base + pos] * p.r_inner >= p.r_total;
+                if (!(conv || cap)) break;
+            }
+            q.n_frozen += k; q.win_pos0 += k; q.win_n -= k;
+            q.new_n = 0;
+            if (q.n_frozen - q.prompt_len >= p.n_new) {
+                q.done = 1; q.win_n = 0;
+            } else {
+                int n_app = min(p.headway, p.w_max - q.win_n);
+                if (n_app > 0) {
+                    int start = q.win_n > 0 ? q.win_pos0 + q.win_n : q.n_frozen - 1;
+                    if (q.win_n == 0) q.win_pos0 = start;
+                    q.new_pos0 = start; q.new_n = n_app;
+                    for (int a = 0; a < n_app; ++a) counts[base + start + a] = 0;
+                    q.win_n += n_app;
+                }
+            }
+            seqs[s] = q;
+        }
+        active = q.done ? 0 : 1;
+    }
+    __shared__ int tot;
+    if (threadIdx.x == 0) tot = 0;
+    __syncthreads();
+    if (active) atomicAdd(&tot, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) *n_active = tot;
+}
+
+__global__ void fill_i32_k(int32_t* p, int32_t v, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+template <int DT>
+__global__ void read_kv_k(const void* kc, const void* vc, int H, int d, int pos0, int n, float* k_out, float* v_out) {
+    int i = blockIdx.x, pos = pos0 + i, h = H * d;
+    for (int c = threadIdx.x; c < h; c += blockDim.x) {
+        if (DT == 0) {
+            k_out[(size_t)i * h + c] = reinterpret_cast<const float*>(kc)[(size_t)pos * h + c];
+            v_out[(size_t)i * h + c] = reinterpret_cast<const float*>(vc)[(size_t)pos * h + c];
+        } else {
+            int hd = c / d, dd = c - hd * d;
+            k_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(kc)[(size_t)pos * h + c]);
+            v_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(vc)[
+                (((size_t)(pos >> 5) * H + hd) * d + dd) * 32 + vt_slot(pos & 31)]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+
+void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, 0, 0, tiles, n_tiles);
+}
+void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* tiles, int32_t* n_tiles,
+                              hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, 1, max_positions, tiles, n_tiles);
+}
+void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions, TileDesc* tiles,
+                                int32_t* n_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_sampler_k, dim3(1), dim3(64), 0, st, const_cast<SeqState*>(seqs), n_seqs,
+                       max_positions, tiles, n_tiles);
+}
+void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
+                  const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    if (dtype == 0)
+        hipLaunchKernelGGL(embed_k<float>, dim3(max_tiles * 32), dim3(256), 0, st, (const float*)emb, tokens, scale,
+                           x, h, V, tiles, n_tiles);
+    else
+        hipLaunchKernelGGL(embed_k<uint16_t>, dim3(max_tiles * 32), dim3(256), 0, st, (const uint16_t*)emb, tokens,
+                           scale, x, h, V, tiles, n_tiles);
+}
+void launch_copy_rows_in(const float* src, float* x, int h, int which, const TileDesc* tiles,
+                         const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(copy_rows_in_k, dim3(max_tiles * 32), dim3(256), 0, st, src, x, h, which, tiles, n_tiles);
+}
+void launch_copy_rows_out(const float* x, float* dst, int width, int which, const TileDesc* tiles,
+                          const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(copy_rows_out_k, dim3(max_tiles * 32), dim3(256), 0, st, x, dst, width, which, tiles, n_tiles);
+}
+void launch_copy_i32_out(const int32_t* src, int32_t* dst, const TileDesc* tiles, const int32_t* n_tiles,
+                         int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(copy_i32_out_k, dim3((max_tiles * 32 + 255) / 256), dim3(256), 0, st, src, dst, tiles, n_tiles);
+}
+void launch_concat(const float* e, const float* z, void* cat, int fmt, int h, const TileDesc* tiles,
+                   const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    if (fmt == ACT_F32)
+        hipLaunchKernelGGL(concat_k<ACT_F32>, dim3(max_tiles * 32), dim3(256), 0, st, e, z, cat, h, tiles, n_tiles);
+    else
+        hipLaunchKernelGGL(concat_k<ACT_BF16P>, dim3(max_tiles * 32), dim3(256), 0, st, e, z, cat, h, tiles, n_tiles);
+}
+void launch_addnorm(const float* xin, float* xout, const float* part, int S, size_t part_stride,
+                    const float* gain, void* xn, int fmt, int h, float eps, const int32_t* n_tiles,
+                    int max_tiles, hipStream_t st) {
+    if (fmt == ACT_F32)
+        hipLaunchKernelGGL(addnorm_k<ACT_F32>, dim3(max_tiles * 32), dim3(256), 0, st, xin, xout, part, S,
+                           part_stride, gain, xn, h, eps, n_tiles);
+    else
+        hipLaunchKernelGGL(addnorm_k<ACT_BF16P>, dim3(max_tiles * 32), dim3(256), 0, st, xin, xout, part, S,
+                           part_stride, gain, xn, h, eps, n_tiles);
+}
+void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
+                       int h, float eps, float* z, float* z_prev, int update_prev, float* delta,
+                       const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(final_norm_k, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain, h,
+                       eps, z, z_prev, update_prev, delta, tiles, n_tiles);
+}
+void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc, int dtype,
+                    int H, int d, const float* theta, size_t seq_stride_elems, const TileDesc* tiles,
+                    const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    if (dtype == 0)
+        hipLaunchKernelGGL(rope_kv_k<0>, dim3(max_tiles * 32), dim3(256), 0, st, qkv, S, part_stride, q, kc, vc, H,
+                           d, theta, seq_stride_elems, tiles, n_tiles);
+    else
+        hipLaunchKernelGGL(rope_kv_k<1>, dim3(max_tiles * 32), dim3(256), 0, st, qkv, S, part_stride, q, kc, vc, H,
+                           d, theta, seq_stride_elems, tiles, n_tiles);
+}
+void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
+                   const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    dim3 grid((F / 4 + 255) / 256, max_tiles * 32);
+    if (fmt == ACT_F32)
+        hipLaunchKernelGGL(swiglu_k<ACT_F32>, grid, dim3(256), 0, st, gu, S, part_stride, act, F, n_tiles);
+    else
+        hipLaunchKernelGGL(swiglu_k<ACT_BF16P>, grid, dim3(256), 0, st, gu, S, part_stride, act, F, n_tiles);
+}
+void launch_init_state_rows(float* z, float* z_prev, int h, int seq, int pos0, int n, size_t zrow0,
+                            float alpha, uint32_t k0, uint32_t k1, hipStream_t st) {
+    if (n <= 0) return;
+    int nb = (h + 3) / 4;
+    hipLaunchKernelGGL(init_state_rows_k, dim3((nb + 255) / 256, n), dim3(256), 0, st, z, z_prev, h, seq, pos0, n,
+                       zrow0, alpha, k0, k1);
+}
+void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs, int n_seqs,
+                           int max_positions, int headway, float alpha, uint32_t k0, uint32_t k1,
+                           hipStream_t st) {
+    int nb = (h + 3) / 4;
+    hipLaunchKernelGGL(init_state_new_k, dim3((nb + 255) / 256, n_seqs * headway), dim3(256), 0, st, z, z_prev, h,
+                       seqs, max_positions, headway, alpha, k0, k1);
+}
+void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
+                   int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                   hipStream_t st) {
+    hipLaunchKernelGGL(sample_k, dim3(max_tiles * 32), dim3(256), 0, st, logits, V, temperature, k0, k1, step,
+                       tok_out, tiles, n_tiles);
+}
+void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
+                     int max_positions, const int32_t* drafts, const float* delta, const TileDesc* tiles,
+                     const int32_t* n_tiles, int32_t* n_active, hipStream_t st) {
+    (void)tiles; (void)n_tiles;
+    hipLaunchKernelGGL(bookkeep_k, dim3(1), dim3(64), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts,
+                       delta, n_active);
+}
+void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
+    if (!n) return;
+    hipLaunchKernelGGL(fill_i32_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+}
+void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n, float* k_out,
+                    float* v_out, hipStream_t st) {
+    if (n <= 0) return;
+    if (dtype == 0) hipLaunchKernelGGL(read_kv_k<0>, dim3(n), dim3(256), 0, st, kc, vc, H, d, pos0, n, k_out, v_out);
+    else hipLaunchKernelGGL(read_kv_k<1>, dim3(n), dim3(256), 0, st, kc, vc, H, d, pos0, n, k_out, v_out);
+}
+
+}  // namespace rdlm

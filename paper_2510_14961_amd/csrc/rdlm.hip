@@ -1,0 +1,812 @@
+// Host side of librdlm: context, weight re-tiling, the block forwards (P, R, C), the sampler
+// driver of Alg. 1 / Alg. 2 on one stream, and the C ABI declared in include/rdlm.h.
+#include "../../include/rdlm.h"
+#include "rdlm_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+using namespace rdlm;
+
+struct Layer {
+    float* g1 = nullptr;
+    float* g2 = nullptr;
+    void* wqkv = nullptr;
+    void* wo = nullptr;
+    void* wgu = nullptr;     // gate rows then up rows: [2F, h]
+    void* wd = nullptr;
+    void* kc = nullptr;      // K cache [max_seqs][ctx_pad][H][d]
+    void* vc = nullptr;      // V cache: f32 same layout; bf16 transposed per 32-position block
+};
+
+struct rdlm_ctx {
+    rdlm_model m;
+    int max_seqs = 0, max_positions = 0, ctx_pad = 0, max_rows = 0, max_tiles = 0, rows_pad = 0;
+    hipStream_t st = nullptr;
+    int fmt = ACT_F32;
+    size_t esz = 4;
+    std::vector<Layer> layers;
+    void* emb_canon = nullptr;
+    void* emb_w = nullptr;
+    void* wa = nullptr;
+    float* gf = nullptr;
+    float* gout = nullptr;
+    float* theta = nullptr;
+    // workspace
+    TileDesc* tiles = nullptr;
+    int32_t* n_tiles = nullptr;
+    float *x = nullptr, *e = nullptr, *qkv = nullptr, *gu = nullptr, *part = nullptr, *logits = nullptr;
+    float *delta = nullptr, *zp_api = nullptr, *att_ws = nullptr;
+    void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
+    int32_t* drafts = nullptr;
+    int att_max_split = 8;
+    // sampler state
+    SeqState* seqs = nullptr;
+    int32_t* y = nullptr;
+    int32_t* counts = nullptr;
+    float *z_store = nullptr, *z_prev = nullptr;
+    int32_t* n_active = nullptr;
+    int32_t* n_active_host = nullptr;    // pinned
+    SamplerParams sp;
+    rdlm_sampler sampler;
+    int samp_seqs = 0;
+    int step = 0;
+    bool sampler_on = false;
+    std::vector<int> prompt_len;
+    int last_hip = 0;
+    size_t bytes = 0;
+    std::vector<void*> allocs;
+    GemmPlan forced_plan = {0, 0, 0, 0};
+    int forced_att_split = 0;
+};
+
+#define HIPCHK(call)                                  \
+    do {                                              \
+        hipError_t e__ = (call);                      \
+        if (e__ != hipSuccess) {                      \
+            ctx->last_hip = (int)e__;                 \
+            return RDLM_EHIP;                         \
+        }                                             \
+    } while (0)
+
+static int dalloc(rdlm_ctx* ctx, void** p, size_t bytes, bool zero) {
+    if (bytes == 0) bytes = 256;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) { ctx->last_hip = (int)e; *p = nullptr; return RDLM_ENOMEM; }
+    ctx->allocs.push_back(*p);
+    ctx->bytes += bytes;
+    if (zero) {
+        e = hipMemsetAsync(*p, 0, bytes, ctx->st);
+        if (e != hipSuccess) { ctx->last_hip = (int)e; return RDLM_EHIP; }
+    }
+    return RDLM_OK;
+}
+#define DALLOC(ptr, bytes, zero)                                              \
+    do {                                                                      \
+        int rc__ = dalloc(ctx, reinterpret_cast<void**>(&(ptr)), (bytes), (zero)); \
+        if (rc__ != RDLM_OK) return rc__;                                     \
+    } while (0)
+
+static int check_launch(rdlm_ctx* ctx) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { ctx->last_hip = (int)e; return RDLM_EHIP; }
+    return RDLM_OK;
+}
+
+extern "C" const char* rdlm_strerror(int s) {
+    switch (s) {
+        case RDLM_OK: return "ok";
+        case RDLM_EINVAL: return "invalid argument";
+        case RDLM_ECAPACITY: return "exceeds the capacity the context was created with";
+        case RDLM_ENOMEM: return "device allocation failed";
+        case RDLM_EHIP: return "HIP call failed";
+        case RDLM_ESTATE: return "call out of order";
+        default: return "unknown status";
+    }
+}
+extern "C" int rdlm_last_hip_error(const rdlm_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+extern "C" size_t rdlm_device_bytes(const rdlm_ctx* ctx) { return ctx ? ctx->bytes : 0; }
+
+static bool model_ok(const rdlm_model* m) {
+    if (!m) return false;
+    if (m->vocab <= 0 || m->hidden <= 0 || m->n_heads <= 0 || m->head_dim <= 0 || m->mlp <= 0) return false;
+    if (m->n_prelude < 0 || m->n_core < 1 || m->n_coda < 0) return false;
+    if ((long long)m->n_heads * m->head_dim != m->hidden) return false;
+    if (m->head_dim % 2) return false;
+    if (!(m->rope_base > 0.f) || !(m->rms_eps >= 0.f)) return false;
+    if (m->dtype == RDLM_F32) {
+        if (m->hidden % 4 || m->mlp % 4) return false;
+    } else if (m->dtype == RDLM_BF16) {
+        if (m->hidden % 32 || m->mlp % 32 || m->vocab % 32) return false;
+        if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 96) return false;
+    } else {
+        return false;
+    }
+    if (m->mlp < m->hidden) return false;               // staging buffers assume h <= F
+    return true;
+}
+
+extern "C" int32_t rdlm_num_weights(const rdlm_model* m) {
+    if (!m) return 0;
+    return 1 + 7 * (m->n_prelude + m->n_core + m->n_coda) + 3;
+}
+
+extern "C" int rdlm_destroy(rdlm_ctx* ctx) {
+    if (!ctx) return RDLM_EINVAL;
+    (void)hipStreamSynchronize(ctx->st);
+    for (void* p : ctx->allocs) (void)hipFree(p);
+    if (ctx->n_active_host) (void)hipHostFree(ctx->n_active_host);
+    delete ctx;
+    return RDLM_OK;
+}
+
+// copy (f32) or re-tile (bf16) a matrix [N,K] into library memory
+static int take_matrix(rdlm_ctx* ctx, const void* src, int N, int K, void** dst) {
+    size_t bytes = (size_t)N * K * ctx->esz;
+    DALLOC(*dst, bytes, false);
+    if (ctx->m.dtype == RDLM_F32) HIPCHK(hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, ctx->st));
+    else launch_pack_weight(src, *dst, N, K, ctx->st);
+    return check_launch(ctx);
+}
+static int take_gain(rdlm_ctx* ctx, const void* src, int h, float** dst) {
+    DALLOC(*dst, (size_t)h * 4, false);
+    HIPCHK(hipMemcpyAsync(*dst, src, (size_t)h * 4, hipMemcpyDeviceToDevice, ctx->st));
+    return RDLM_OK;
+}
+
+static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden, F = m.mlp, V = m.vocab;
+    const size_t esz = ctx->esz;
+    int wi = 0, rc;
+    // embedding: canonical copy for the gather, tiled copy as the tied LM head
+    DALLOC(ctx->emb_canon, (size_t)V * h * esz, false);
+    HIPCHK(hipMemcpyAsync(ctx->emb_canon, wp[wi], (size_t)V * h * esz, hipMemcpyDeviceToDevice, ctx->st));
+    if (m.dtype == RDLM_F32) ctx->emb_w = ctx->emb_canon;
+    else if ((rc = take_matrix(ctx, wp[wi], V, h, &ctx->emb_w))) return rc;
+    ++wi;
+    const int nl = m.n_prelude + m.n_core + m.n_coda;
+    ctx->layers.resize(nl);
+    const size_t cache_elems = (size_t)ctx->max_seqs * ctx->ctx_pad * h;
+    for (int l = 0; l < nl; ++l) {
+        Layer& L = ctx->layers[l];
+        if ((rc = take_gain(ctx, wp[wi++], h, &L.g1))) return rc;
+        if ((rc = take_matrix(ctx, wp[wi++], 3 * h, h, &L.wqkv))) return rc;
+        if ((rc = take_matrix(ctx, wp[wi++], h, h, &L.wo))) return rc;
+        if ((rc = take_gain(ctx, wp[wi++], h, &L.g2))) return rc;
+        // gate and up as one [2F, h] matrix
+        DALLOC(L.wgu, (size_t)2 * F * h * esz, false);
+        for (int part = 0; part < 2; ++part) {
+            char* dst = reinterpret_cast<char*>(L.wgu) + (size_t)part * F * h * esz;
+            if (m.dtype == RDLM_F32)
+                HIPCHK(hipMemcpyAsync(dst, wp[wi], (size_t)F * h * esz, hipMemcpyDeviceToDevice, ctx->st));
+            else
+                launch_pack_weight(wp[wi], dst, F, h, ctx->st);     // blocks of gate, then blocks of up
+            ++wi;
+        }
+        if ((rc = take_matrix(ctx, wp[wi++], h, F, &L.wd))) return rc;
+        DALLOC(L.kc, cache_elems * esz, true);
+        DALLOC(L.vc, cache_elems * esz, true);
+    }
+    if ((rc = take_matrix(ctx, wp[wi++], h, 2 * h, &ctx->wa))) return rc;
+    if ((rc = take_gain(ctx, wp[wi++], h, &ctx->gf))) return rc;
+    if ((rc = take_gain(ctx, wp[wi++], h, &ctx->gout))) return rc;
+    if ((rc = check_launch(ctx))) return rc;
+
+    // RoPE angles theta_i = base^(-2i/d), rounded once from double
+    {
+        std::vector<float> th(m.head_dim / 2);
+        for (int i = 0; i < m.head_dim / 2; ++i)
+            th[i] = (float)std::pow((double)m.rope_base, -2.0 * i / (double)m.head_dim);
+        DALLOC(ctx->theta, th.size() * 4, false);
+        HIPCHK(hipMemcpy(ctx->theta, th.data(), th.size() * 4, hipMemcpyHostToDevice));
+    }
+    const size_t R = ctx->rows_pad;
+    const size_t wide = (size_t)std::max(2 * h, F);
+    DALLOC(ctx->tiles, sizeof(TileDesc) * ctx->max_tiles, true);
+    DALLOC(ctx->n_tiles, 64, true);
+    DALLOC(ctx->x, R * h * 4, true);
+    DALLOC(ctx->e, R * h * 4, true);
+    DALLOC(ctx->qkv, R * 3 * h * 4, true);
+    DALLOC(ctx->gu, R * 2 * F * 4, true);
+    DALLOC(ctx->part, 8 * R * h * 4, true);
+    DALLOC(ctx->logits, R * V * 4, true);
+    DALLOC(ctx->delta, R * 4, true);
+    DALLOC(ctx->zp_api, R * h * 4, true);
+    DALLOC(ctx->xn, R * h * esz, true);
+    DALLOC(ctx->abuf, R * wide * esz, true);
+    DALLOC(ctx->q, R * h * esz, true);
+    DALLOC(ctx->att, R * h * esz, true);
+    DALLOC(ctx->drafts, R * 4, true);
+    if (m.dtype == RDLM_BF16)
+        DALLOC(ctx->att_ws, attention_ws_floats(ctx->max_tiles, m.n_heads, m.head_dim, ctx->att_max_split) * 4, false);
+    // sampler state
+    const size_t SP = (size_t)ctx->max_seqs * ctx->max_positions;
+    DALLOC(ctx->seqs, sizeof(SeqState) * ctx->max_seqs, true);
+    DALLOC(ctx->y, (SP + 64) * 4, true);
+    DALLOC(ctx->counts, (SP + 64) * 4, true);
+    DALLOC(ctx->z_store, SP * h * 4, true);
+    DALLOC(ctx->z_prev, SP * h * 4, true);
+    DALLOC(ctx->n_active, 64, true);
+    HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&ctx->n_active_host), 64, hipHostMallocDefault));
+    ctx->prompt_len.assign(ctx->max_seqs, 0);
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                           int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out) {
+    if (!out) return RDLM_EINVAL;
+    *out = nullptr;
+    if (!model_ok(m) || !weight_ptrs) return RDLM_EINVAL;
+    if (max_seqs < 1 || max_seqs > MAX_API_SEQS || max_positions < 2 || max_rows < 1) return RDLM_EINVAL;
+    if (m->dtype == RDLM_F32 && max_positions > 8192) return RDLM_EINVAL;   // f32 attention keeps scores in LDS
+    for (int i = 0; i < rdlm_num_weights(m); ++i)
+        if (!weight_ptrs[i]) return RDLM_EINVAL;
+    rdlm_ctx* ctx = new rdlm_ctx();
+    ctx->m = *m;
+    ctx->max_seqs = max_seqs;
+    ctx->max_positions = max_positions;
+    ctx->ctx_pad = (max_positions + 31) / 32 * 32;
+    ctx->max_rows = max_rows;
+    ctx->max_tiles = (max_rows + 31) / 32 + max_seqs;
+    ctx->rows_pad = ctx->max_tiles * 32;
+    ctx->st = reinterpret_cast<hipStream_t>(hip_stream);
+    ctx->fmt = m->dtype == RDLM_F32 ? ACT_F32 : ACT_BF16P;
+    ctx->esz = m->dtype == RDLM_F32 ? 4 : 2;
+    if (const char* p = getenv("RDLM_GEMM_PLAN")) {       // tuning aid: "mt,nb,waves,ksplit"
+        GemmPlan g = {0, 0, 0, 0};
+        if (sscanf(p, "%d,%d,%d,%d", &g.mt, &g.nb, &g.waves, &g.ksplit) == 4) ctx->forced_plan = g;
+    }
+    if (const char* p = getenv("RDLM_ATT_SPLIT")) ctx->forced_att_split = atoi(p);
+    int rc = create_impl(ctx, weight_ptrs);
+    if (rc != RDLM_OK) {
+        // keep the HIP error readable through a static slot: the context is gone
+        for (void* p : ctx->allocs) (void)hipFree(p);
+        if (ctx->n_active_host) (void)hipHostFree(ctx->n_active_host);
+        delete ctx;
+        return rc;
+    }
+    *out = ctx;
+    return RDLM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM dispatch
+
+static GemmPlan plan_for(const rdlm_ctx* ctx, int N, int K, int T, bool allow_split) {
+    if (ctx->forced_plan.mt) {
+        GemmPlan g = ctx->forced_plan;
+        if (!allow_split) g.ksplit = 1;
+        return g;
+    }
+    GemmPlan g;
+    g.waves = 4;
+    g.mt = T >= 4 ? 4 : (T >= 2 ? 2 : 1);
+    const int nblk = N / 32, mch = (T + g.mt - 1) / g.mt;
+    const int target = 512;
+    g.nb = 1;
+    if (g.mt <= 2) {
+        for (int nb : {4, 2}) {
+            if (g.mt * nb > 4) continue;
+            if (((nblk + nb - 1) / nb) * mch >= target) { g.nb = nb; break; }
+        }
+    }
+    g.ksplit = 1;
+    if (allow_split) {
+        int wgs = ((nblk + g.nb - 1) / g.nb) * mch;
+        int ks = (target + wgs - 1) / wgs;
+        int kmax = std::max(1, (K / 16) / (g.waves * 8));      // at least 8 k tiles per wave
+        g.ksplit = std::max(1, std::min(std::min(ks, 8), kmax));
+    }
+    return g;
+}
+
+// out: f32 [S][rows_pad][N]; returns S through *S_out
+static void gemm(rdlm_ctx* ctx, const void* xin, const void* W, float* out, int N, int K, int T, bool allow_split,
+                 int* S_out) {
+    if (ctx->m.dtype == RDLM_F32) {
+        launch_gemm_f32(reinterpret_cast<const float*>(xin), reinterpret_cast<const float*>(W), out, N, K,
+                        ctx->n_tiles, T, ctx->st);
+        if (S_out) *S_out = 1;
+        return;
+    }
+    GemmPlan g = plan_for(ctx, N, K, T, allow_split);
+    launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, ctx->n_tiles, T, ctx->st);
+    if (S_out) *S_out = g.ksplit;
+}
+
+static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
+    if (ctx->m.dtype == RDLM_F32) return 1;
+    if (ctx->forced_att_split > 0) return std::min(ctx->forced_att_split, ctx->att_max_split);
+    int wgs = ctx->m.n_heads * T;
+    int kb = (max_keys + 31) / 32;
+    int s = 1;
+    while (s < ctx->att_max_split && wgs * s < 512 && kb / (s * 2) >= 8) s *= 2;
+    return s;
+}
+
+// One transformer layer over the current tiles.  On entry the residual stream is
+// x (+ the S_in partial sums in part, if any); on exit it is x + the *S_out partials in part.
+static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden, F = m.mlp;
+    const size_t pst = (size_t)ctx->rows_pad * h;
+    hipStream_t st = ctx->st;
+    int S;
+    launch_addnorm(x_valid ? ctx->x : nullptr, ctx->x, ctx->part, S_in, pst, L.g1, ctx->xn, ctx->fmt, h, m.rms_eps,
+                   ctx->n_tiles, T, st);
+    gemm(ctx, ctx->xn, L.wqkv, ctx->qkv, 3 * h, h, T, false, &S);
+    launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->theta,
+                   (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
+    launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
+                     att_split_for(ctx, T, max_keys), ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
+    gemm(ctx, ctx->att, L.wo, ctx->part, h, h, T, true, &S);
+    launch_addnorm(ctx->x, ctx->x, ctx->part, S, pst, L.g2, ctx->xn, ctx->fmt, h, m.rms_eps, ctx->n_tiles, T, st);
+    gemm(ctx, ctx->xn, L.wgu, ctx->gu, 2 * F, h, T, false, &S);
+    launch_swiglu(ctx->gu, 1, 0, ctx->abuf, ctx->fmt, F, ctx->n_tiles, T, st);
+    gemm(ctx, ctx->abuf, L.wd, ctx->part, h, F, T, true, S_out);
+}
+
+// e = P(tokens): embedding gather (scaled) and the prelude layers; result in e_out rows (erow0).
+static void prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys) {
+    const rdlm_model& m = ctx->m;
+    launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->tiles, ctx->n_tiles,
+                 T, ctx->st);
+    int S = 0;
+    for (int l = 0; l < m.n_prelude; ++l) layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S);
+    // fold the pending partial sums: x <- x + sum part (no norm output needed)
+    launch_addnorm(ctx->x, ctx->x, ctx->part, S, (size_t)ctx->rows_pad * m.hidden, ctx->gf, nullptr, ctx->fmt,
+                   m.hidden, m.rms_eps, ctx->n_tiles, T, ctx->st);
+    if (e_out != ctx->x) {
+        if (e_which < 0)   // internal e buffer is indexed by padded row: plain copy
+            (void)hipMemcpyAsync(e_out, ctx->x, (size_t)T * 32 * m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st);
+        else
+            launch_copy_rows_out(ctx->x, e_out, m.hidden, e_which, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    }
+}
+
+// z <- R(z, e): adapter on concat(e, z), the core layers, closing norm; optional delta vs z_prev.
+static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev, int update_prev, float* delta,
+                         int T, int max_keys) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden;
+    launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    int S;
+    gemm(ctx, ctx->abuf, ctx->wa, ctx->part, h, 2 * h, T, true, &S);
+    bool x_valid = false;
+    for (int l = 0; l < m.n_core; ++l) {
+        layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S);
+        x_valid = true;
+    }
+    launch_final_norm(ctx->x, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gf, h, m.rms_eps, z, z_prev, update_prev,
+                      delta, ctx->tiles, ctx->n_tiles, T, ctx->st);
+}
+
+// C: coda layers on z; with_head: final norm, tied LM head -> logits.
+static void coda_forward(rdlm_ctx* ctx, const float* z, bool with_head, int T, int max_keys) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden;
+    launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    int S = 0;
+    for (int l = 0; l < m.n_coda; ++l)
+        layer_forward(ctx, ctx->layers[m.n_prelude + m.n_core + l], T, max_keys, true, S, &S);
+    if (!with_head) return;
+    launch_addnorm(ctx->x, nullptr, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gout, ctx->xn, ctx->fmt, h,
+                   m.rms_eps, ctx->n_tiles, T, ctx->st);
+    gemm(ctx, ctx->xn, ctx->emb_w, ctx->logits, m.vocab, h, T, false, nullptr);
+}
+
+// ---------------------------------------------------------------------------------------------
+// argument checking shared by the row-based calls
+
+static int check_rows(const rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                      const int32_t* n_rows, SeqWindows* w, int* T, int* M, int* max_keys) {
+    if (!ctx || !seq_ids || !pos0 || !n_rows || n_seqs < 1) return RDLM_EINVAL;
+    if (n_seqs > MAX_API_SEQS) return RDLM_ECAPACITY;
+    int tiles = 0, rows = 0, mk = 0;
+    w->n = n_seqs;
+    for (int i = 0; i < n_seqs; ++i) {
+        if (seq_ids[i] < 0 || pos0[i] < 0 || n_rows[i] < 1) return RDLM_EINVAL;
+        if (seq_ids[i] >= ctx->max_seqs) return RDLM_ECAPACITY;
+        if ((long long)pos0[i] + n_rows[i] > ctx->max_positions) return RDLM_ECAPACITY;
+        for (int j = 0; j < i; ++j)
+            if (seq_ids[j] == seq_ids[i]) return RDLM_EINVAL;      // one window per sequence per step
+        w->seq[i] = seq_ids[i]; w->pos0[i] = pos0[i]; w->rows[i] = n_rows[i];
+        tiles += (n_rows[i] + 31) / 32;
+        rows += n_rows[i];
+        mk = std::max(mk, pos0[i] + n_rows[i]);
+    }
+    if (rows > ctx->max_rows || tiles > ctx->max_tiles) return RDLM_ECAPACITY;
+    *T = tiles; *M = rows; *max_keys = mk;
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens_host, int32_t n) {
+    if (!ctx || !tokens_host || n < 1 || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || n >= ctx->max_positions) return RDLM_ECAPACITY;
+    for (int i = 0; i < n; ++i)
+        if (tokens_host[i] < 0 || tokens_host[i] >= ctx->m.vocab) return RDLM_EINVAL;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    size_t base = (size_t)seq * ctx->max_positions;
+    launch_fill_i32(ctx->y + base, 0, ctx->max_positions, ctx->st);
+    launch_fill_i32(ctx->counts + base, 0, ctx->max_positions, ctx->st);
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    HIPCHK(hipMemcpy(ctx->y + base, tokens_host, (size_t)n * 4, hipMemcpyHostToDevice));
+    ctx->prompt_len[seq] = n;
+    ctx->sampler_on = false;
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, float alpha, uint64_t seed) {
+    if (!ctx || seq < 0 || n < 0 || r < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || n > ctx->max_rows || n > ctx->max_positions) return RDLM_ECAPACITY;
+    if (n == 0) return RDLM_OK;
+    SeqWindows w;
+    w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
+    const int T = (n + 31) / 32;
+    launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
+                           (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
+    prelude_forward(ctx, ctx->y, ctx->e, -1, T, n);
+    for (int i = 0; i < r; ++i) core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n);
+    coda_forward(ctx, ctx->z_store, false, T, n);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_init_state(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float alpha, uint64_t seed,
+                               float* z_out) {
+    if (!ctx || !z_out || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
+    launch_init_state_rows(z_out, nullptr, ctx->m.hidden, seq, pos0, n, 0, alpha, (uint32_t)seed,
+                           (uint32_t)(seed >> 32), ctx->st);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                            const int32_t* n_rows, const int32_t* tokens_dev, float* e_out) {
+    SeqWindows w;
+    int T, M, mk;
+    if (!tokens_dev || !e_out) return RDLM_EINVAL;
+    int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
+    if (rc) return rc;
+    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    prelude_forward(ctx, tokens_dev, e_out, 1, T, mk);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                              const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
+                              float* delta_out) {
+    SeqWindows w;
+    int T, M, mk;
+    if (!e || !z_inout || r_inner < 1) return RDLM_EINVAL;
+    int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
+    if (rc) return rc;
+    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    if (delta_out)
+        HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
+    for (int i = 0; i < r_inner; ++i) {
+        bool last = i == r_inner - 1;
+        core_forward(ctx, e, z_inout, (last && delta_out) ? ctx->zp_api : nullptr, 0,
+                     (last && delta_out) ? ctx->delta : nullptr, T, mk);
+    }
+    if (delta_out) launch_copy_rows_out(ctx->delta, delta_out, 1, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                                const int32_t* n_rows, const float* z, float temperature, uint64_t seed,
+                                int32_t step, int32_t* tokens_out, float* logits_out) {
+    SeqWindows w;
+    int T, M, mk;
+    if (!z || !tokens_out || !(temperature >= 0.f) || step < 0) return RDLM_EINVAL;
+    int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
+    if (rc) return rc;
+    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    coda_forward(ctx, z, true, T, mk);
+    launch_sample(ctx->logits, ctx->m.vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, ctx->drafts,
+                  ctx->tiles, ctx->n_tiles, T, ctx->st);
+    launch_copy_i32_out(ctx->drafts, tokens_out, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    if (logits_out) launch_copy_rows_out(ctx->logits, logits_out, ctx->m.vocab, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    return check_launch(ctx);
+}
+
+// ---------------------------------------------------------------------------------------------
+// sampler driver
+
+extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t n_seqs) {
+    if (!ctx || !s || n_seqs < 1) return RDLM_EINVAL;
+    if (n_seqs > ctx->max_seqs) return RDLM_ECAPACITY;
+    if (s->n_new < 1 || s->r_inner < 1 || s->r_total < 1 || s->headway < 1 || !(s->temperature >= 0.f) ||
+        !(s->eps >= 0.f) || s->pad_token < 0 || s->pad_token >= ctx->m.vocab)
+        return RDLM_EINVAL;
+    rdlm_sampler sp = *s;
+    const int wave = (sp.r_total + sp.r_inner - 1) / sp.r_inner;
+    if (sp.w_max <= 0 || !sp.adaptive) sp.w_max = wave * sp.headway;
+    int tiles = n_seqs * ((sp.w_max + 31) / 32);
+    if (tiles > ctx->max_tiles || n_seqs * sp.w_max > ctx->max_rows) return RDLM_ECAPACITY;
+    for (int q = 0; q < n_seqs; ++q) {
+        if (ctx->prompt_len[q] < 1) return RDLM_ESTATE;
+        if ((long long)ctx->prompt_len[q] + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
+    }
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    std::vector<SeqState> hs(n_seqs);
+    memset(hs.data(), 0, sizeof(SeqState) * n_seqs);
+    for (int q = 0; q < n_seqs; ++q) {
+        const int L = ctx->prompt_len[q];
+        hs[q].prompt_len = L; hs[q].n_frozen = L; hs[q].win_pos0 = L - 1; hs[q].win_n = 1;
+        size_t base = (size_t)q * ctx->max_positions;
+        launch_fill_i32(ctx->y + base + L, sp.pad_token, ctx->max_positions - L, ctx->st);
+        launch_fill_i32(ctx->counts + base, 0, ctx->max_positions, ctx->st);
+        launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, q, L - 1, 1, base + L - 1, sp.alpha,
+                               (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
+    }
+    HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * n_seqs, hipMemcpyHostToDevice));
+    ctx->sampler = sp;
+    ctx->sp.n_new = sp.n_new; ctx->sp.r_inner = sp.r_inner; ctx->sp.r_total = sp.r_total; ctx->sp.w_max = sp.w_max;
+    ctx->sp.headway = sp.headway; ctx->sp.adaptive = sp.adaptive; ctx->sp.eps = sp.eps; ctx->sp.alpha = sp.alpha;
+    ctx->sp.temperature = sp.temperature; ctx->sp.pad_token = sp.pad_token;
+    ctx->sp.seed_lo = (uint32_t)sp.seed; ctx->sp.seed_hi = (uint32_t)(sp.seed >> 32);
+    ctx->samp_seqs = n_seqs;
+    ctx->step = 0;
+    ctx->sampler_on = true;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
+    if (!ctx) return RDLM_EINVAL;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    const rdlm_sampler& s = ctx->sampler;
+    const rdlm_model& m = ctx->m;
+    const int t = ++ctx->step;
+    const int n = ctx->samp_seqs;
+    // upper bound of the wave size at this step (it grows by at most `headway` per step)
+    long long grow = 1 + (long long)(t - 1) * s.headway;
+    int wmax_now = (int)std::min<long long>(s.w_max, grow);
+    const int T = n * ((wmax_now + 31) / 32);
+    int max_keys = 0;
+    for (int q = 0; q < n; ++q)
+        max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
+    launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys);                       // e <- P(y_current)
+    for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
+        bool last = i == s.r_inner - 1;
+        core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
+                     last ? ctx->delta : nullptr, T, max_keys);
+    }
+    coda_forward(ctx, ctx->z_store, true, T, max_keys);                          // p <- C(z)
+    launch_sample(ctx->logits, m.vocab, s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, ctx->drafts, ctx->tiles,
+                  ctx->n_tiles, T, ctx->st);                                     // y_hat <- Sample(p)
+    launch_bookkeep(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
+                    ctx->tiles, ctx->n_tiles, ctx->n_active, ctx->st);           // freeze, append
+    launch_init_state_new(ctx->z_store, ctx->z_prev, m.hidden, ctx->seqs, n, ctx->max_positions, s.headway, s.alpha,
+                          ctx->sp.seed_lo, ctx->sp.seed_hi, ctx->st);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_out) {
+    if (!ctx || max_steps < 1) return RDLM_EINVAL;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    const rdlm_sampler& s = ctx->sampler;
+    const int wave = (s.r_total + s.r_inner - 1) / s.r_inner;
+    // fixed exit: the step count is known; adaptive: look at the device every few steps
+    int next_poll = s.adaptive ? 8 : wave + (s.n_new - 1 + s.headway - 1) / s.headway;
+    int done_steps = 0;
+    for (int i = 1; i <= max_steps; ++i) {
+        int rc = rdlm_sample_step(ctx);
+        if (rc) return rc;
+        done_steps = i;
+        if (i >= next_poll || i == max_steps) {
+            HIPCHK(hipMemcpyAsync(ctx->n_active_host, ctx->n_active, 4, hipMemcpyDeviceToHost, ctx->st));
+            HIPCHK(hipStreamSynchronize(ctx->st));
+            if (*ctx->n_active_host == 0) break;
+            next_poll = i + (s.adaptive ? 8 : 1);
+        }
+    }
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    if (steps_out) *steps_out = done_steps;
+    return RDLM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// read-back
+
+extern "C" int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap,
+                                int32_t* n_frozen_out) {
+    if (!ctx || !tokens_host || cap < 0 || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    int n = std::min(cap, ctx->max_positions);
+    HIPCHK(hipMemcpy(tokens_host, ctx->y + (size_t)seq * ctx->max_positions, (size_t)n * 4, hipMemcpyDeviceToHost));
+    if (n_frozen_out) {
+        SeqState q;
+        HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
+        *n_frozen_out = ctx->sampler_on ? q.n_frozen : ctx->prompt_len[seq];
+    }
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host) {
+    if (!ctx || !z_host || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    HIPCHK(hipMemcpy(z_host, ctx->z_store + ((size_t)seq * ctx->max_positions + pos0) * ctx->m.hidden,
+                     (size_t)n * ctx->m.hidden * 4, hipMemcpyDeviceToHost));
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_read_counts(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t* counts_host) {
+    if (!ctx || !counts_host || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    HIPCHK(hipMemcpy(counts_host, ctx->counts + (size_t)seq * ctx->max_positions + pos0, (size_t)n * 4,
+                     hipMemcpyDeviceToHost));
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_read_deltas(rdlm_ctx* ctx, int32_t seq, float* delta_host, int32_t cap, int32_t* n_out) {
+    if (!ctx || !delta_host || !n_out || seq < 0 || cap < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    SeqState q;
+    HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
+    int n = std::min(cap, q.last_rows);
+    if (n > 0)
+        HIPCHK(hipMemcpy(delta_host, ctx->delta + (size_t)q.pad_[0] * 32, (size_t)n * 4, hipMemcpyDeviceToHost));
+    *n_out = q.last_rows;
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_t n, float* k_host,
+                            float* v_host) {
+    if (!ctx || !k_host || !v_host || layer < 0 || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
+    if (layer >= (int)ctx->layers.size()) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    if (n == 0) return RDLM_OK;
+    const int h = ctx->m.hidden;
+    if ((size_t)n * h * 2 > (size_t)ctx->rows_pad * 2 * ctx->m.mlp) return RDLM_ECAPACITY;   // staged in gu
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    const Layer& L = ctx->layers[layer];
+    size_t off = (size_t)seq * ctx->ctx_pad * h * ctx->esz;
+    float* kd = ctx->gu;
+    float* vd = ctx->gu + (size_t)n * h;
+    launch_read_kv(reinterpret_cast<const char*>(L.kc) + off, reinterpret_cast<const char*>(L.vc) + off, ctx->m.dtype,
+                   ctx->m.n_heads, ctx->m.head_dim, pos0, n, kd, vd, ctx->st);
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    HIPCHK(hipMemcpy(k_host, kd, (size_t)n * h * 4, hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(v_host, vd, (size_t)n * h * 4, hipMemcpyDeviceToHost));
+    return RDLM_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernel-level entry points
+
+static int weight_by_index(const rdlm_ctx* ctx, int idx, const void** W, int* N, int* K, bool* split) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden, F = m.mlp;
+    const int nl = m.n_prelude + m.n_core + m.n_coda;
+    if (idx == 0) { *W = ctx->emb_w; *N = m.vocab; *K = h; *split = false; return RDLM_OK; }
+    if (idx >= 1 && idx < 1 + 7 * nl) {
+        const Layer& L = ctx->layers[(idx - 1) / 7];
+        switch ((idx - 1) % 7) {
+            case 1: *W = L.wqkv; *N = 3 * h; *K = h; *split = false; return RDLM_OK;
+            case 2: *W = L.wo; *N = h; *K = h; *split = true; return RDLM_OK;
+            case 4: *W = L.wgu; *N = 2 * F; *K = h; *split = false; return RDLM_OK;
+            case 6: *W = L.wd; *N = h; *K = F; *split = true; return RDLM_OK;
+            default: return RDLM_EINVAL;
+        }
+    }
+    if (idx == 1 + 7 * nl) { *W = ctx->wa; *N = h; *K = 2 * h; *split = true; return RDLM_OK; }
+    return RDLM_EINVAL;
+}
+
+static float* out_buffer_for(rdlm_ctx* ctx, int N) {
+    const rdlm_model& m = ctx->m;
+    if (N == m.vocab && N != m.hidden) return ctx->logits;
+    if (N == 2 * m.mlp) return ctx->gu;
+    if (N == 3 * m.hidden) return ctx->qkv;
+    return ctx->part;
+}
+
+static int linear_setup(rdlm_ctx* ctx, int m_rows, int* T) {
+    if (m_rows < 1) return RDLM_EINVAL;
+    if (m_rows > ctx->max_rows) return RDLM_ECAPACITY;
+    SeqWindows w;
+    w.n = 1; w.seq[0] = 0; w.pos0[0] = 0; w.rows[0] = m_rows;
+    *T = (m_rows + 31) / 32;
+    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_linear(rdlm_ctx* ctx, int32_t w_index, const float* x, int32_t m_rows, float* y) {
+    if (!ctx || !x || !y) return RDLM_EINVAL;
+    const void* W; int N, K, T; bool split;
+    int rc = weight_by_index(ctx, w_index, &W, &N, &K, &split);
+    if (rc) return rc;
+    if ((rc = linear_setup(ctx, m_rows, &T))) return rc;
+    const void* xin;
+    if (ctx->m.dtype == RDLM_F32) {
+        // stage x with zero padding rows in the (idle) latent scratch, output never aliases it
+        float* stage = ctx->zp_api;
+        if (K > ctx->m.hidden) stage = ctx->gu == out_buffer_for(ctx, N) ? ctx->qkv : ctx->gu;
+        HIPCHK(hipMemsetAsync(stage, 0, (size_t)T * 32 * K * 4, ctx->st));
+        HIPCHK(hipMemcpyAsync(stage, x, (size_t)m_rows * K * 4, hipMemcpyDeviceToDevice, ctx->st));
+        xin = stage;
+    } else {
+        launch_pack_rows(x, ctx->abuf, m_rows, K, ctx->st);
+        xin = ctx->abuf;
+    }
+    float* out = out_buffer_for(ctx, N);
+    int S;
+    gemm(ctx, xin, W, out, N, K, T, split, &S);
+    const float* res = out;
+    if (out == ctx->part) {     // fold split-K partials exactly as the model path's consumer does
+        launch_addnorm(nullptr, ctx->x, ctx->part, S, (size_t)ctx->rows_pad * N, ctx->gf, nullptr, ctx->fmt, N,
+                       ctx->m.rms_eps, ctx->n_tiles, T, ctx->st);
+        res = ctx->x;
+    }
+    launch_copy_rows_out(res, y, N, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, int32_t iters, float* ms_out) {
+    if (!ctx || !ms_out || iters < 1) return RDLM_EINVAL;
+    const void* W; int N, K, T; bool split;
+    int rc = weight_by_index(ctx, w_index, &W, &N, &K, &split);
+    if (rc) return rc;
+    if ((rc = linear_setup(ctx, m_rows, &T))) return rc;
+    // Gaussian rows as input (values do not affect timing; keeps everything finite)
+    float* stage = ctx->gu == out_buffer_for(ctx, N) ? ctx->qkv : ctx->gu;
+    if ((size_t)K > (size_t)3 * ctx->m.hidden && stage == ctx->qkv) return RDLM_EINVAL;
+    launch_init_state_rows(stage, nullptr, K, 0, 0, T * 32, 0, 1.0f, 1u, 0u, ctx->st);
+    const void* xin = stage;
+    if (ctx->m.dtype == RDLM_BF16) { launch_pack_rows(stage, ctx->abuf, T * 32, K, ctx->st); xin = ctx->abuf; }
+    float* out = out_buffer_for(ctx, N);
+    hipEvent_t a, b;
+    HIPCHK(hipEventCreate(&a));
+    HIPCHK(hipEventCreate(&b));
+    int S;
+    for (int i = 0; i < 3; ++i) gemm(ctx, xin, W, out, N, K, T, split, &S);
+    HIPCHK(hipEventRecord(a, ctx->st));
+    for (int i = 0; i < iters; ++i) gemm(ctx, xin, W, out, N, K, T, split, &S);
+    HIPCHK(hipEventRecord(b, ctx->st));
+    HIPCHK(hipEventSynchronize(b));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, a, b));
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    *ms_out = ms / iters;
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t iters,
+                                   float* ms_out) {
+    if (!ctx || !ms_out || iters < 1 || seq < 0 || pos0 < 0 || n < 1) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || n > ctx->max_rows || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    SeqWindows w;
+    w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
+    const int T = (n + 31) / 32;
+    launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;
+    launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, pos0, n, zrow0, 1.0f, 7u, 0u, ctx->st);
+    launch_init_state_rows(ctx->e, nullptr, ctx->m.hidden, seq, pos0, T * 32, 0, 1.0f, 9u, 0u, ctx->st);
+    hipEvent_t a, b;
+    HIPCHK(hipEventCreate(&a));
+    HIPCHK(hipEventCreate(&b));
+    for (int i = 0; i < 2; ++i) core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, pos0 + n);
+    HIPCHK(hipEventRecord(a, ctx->st));
+    for (int i = 0; i < iters; ++i) core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, pos0 + n);
+    HIPCHK(hipEventRecord(b, ctx->st));
+    HIPCHK(hipEventSynchronize(b));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, a, b));
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    *ms_out = ms / iters;
+    return check_launch(ctx);
+}

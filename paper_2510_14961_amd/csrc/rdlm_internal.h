@@ -1,0 +1,174 @@
+// Internal declarations shared by the HIP sources of librdlm (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace rdlm {
+
+// A step works on "tiles" of up to 32 rows.  Every tile belongs to one sequence and covers
+// contiguous positions; rows of a tile beyond n_valid are padding (computed, never stored into
+// caches or states).  Internal activations use the padded row index tile*32 + j.
+struct TileDesc {
+    int32_t seq;      // sequence (selects the KV-cache slab)
+    int32_t pos0;     // absolute position of row 0 of the tile
+    int32_t n_valid;  // 1..32
+    int32_t zrow0;    // row of the tile's first state in the latent array it is read from / written to
+    int32_t erow0;    // row of the tile's first conditioning vector e
+    int32_t yrow0;    // index of the tile's first input token in the token array it reads
+    int32_t crow0;    // compact row index (rows of all tiles concatenated without padding)
+    int32_t pad_;
+};
+
+constexpr int TILE_ROWS = 32;
+constexpr int MAX_API_SEQS = 64;      // sequences per API call (descriptor passed as a kernel argument)
+
+struct SeqWindows {                   // by-value kernel argument of build_tiles
+    int32_t n;
+    int32_t seq[MAX_API_SEQS];
+    int32_t pos0[MAX_API_SEQS];
+    int32_t rows[MAX_API_SEQS];
+};
+
+// Per-sequence sampler state kept on the device (Alg. 1 / Alg. 2 bookkeeping).
+struct SeqState {
+    int32_t prompt_len;   // |x|
+    int32_t n_frozen;     // |y_frozen|
+    int32_t win_pos0;     // position of the oldest in-flight state
+    int32_t win_n;        // number of in-flight states
+    int32_t done;         // n_frozen - prompt_len >= n_new
+    int32_t last_rows;    // rows the sequence had in the last step (for read_deltas)
+    int32_t last_pos0;
+    int32_t new_pos0;     // states appended by the last bookkeeping pass: [new_pos0, new_pos0+new_n)
+    int32_t new_n;
+    int32_t pad_[3];
+};
+
+struct SamplerParams {
+    int32_t n_new, r_inner, r_total, w_max, headway, adaptive;
+    float eps, alpha, temperature;
+    int32_t pad_token;
+    uint32_t seed_lo, seed_hi;
+};
+
+enum ActFmt { ACT_F32 = 0, ACT_BF16P = 1 };
+
+// ---------------------------------------------------------------------------------------------
+// bf16 <-> f32 (bit patterns; round to nearest even)
+__host__ __device__ inline uint16_t f32_to_bf16(float f) {
+    union { float f; uint32_t u; } v; v.f = f;
+    uint32_t lsb = (v.u >> 16) & 1u;
+    return (uint16_t)((v.u + 0x7FFFu + lsb) >> 16);
+}
+__host__ __device__ inline float bf16_to_f32(uint16_t b) {
+    union { float f; uint32_t u; } v; v.u = ((uint32_t)b) << 16; return v.f;
+}
+
+// Offset (in bf16 elements) of element (row, k) of a packed activation with K columns:
+// tiles of 32 rows x 16 columns, 1 KiB each, stored in MFMA operand order: lane = (row%32) +
+// 32*((k%16)/8) holds 8 consecutive k.  Tiles are ordered [row tile][k tile].
+__host__ __device__ inline size_t packed_off(int row, int k, int K) {
+    int t = row >> 5, m = row & 31, kt = k >> 4, kk = k & 15;
+    return (((size_t)t * (K >> 4) + kt) * 64 + m + 32 * (kk >> 3)) * 8 + (kk & 7);
+}
+
+// Position of key `kappa` (0..31) inside a 32-position block of the transposed V cache.  The
+// order is the one in which the 32x32 score accumulator of the attention kernel hands its keys to
+// the P.V contraction, so that both operands of that contraction are plain 16-byte loads.
+__host__ __device__ inline int vt_slot(int kappa) {
+    int m = kappa >> 4, w = kappa & 15;
+    return m * 16 + ((w & 7) >> 2) * 8 + (w >> 3) * 4 + (w & 3);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  counter = (block, position, seq, step*16 + tag).
+constexpr uint32_t TAG_INIT_STATE = 1, TAG_SAMPLE = 2, TAG_NOISE = 3;
+
+__host__ __device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t out[4]) {
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+// 23 random bits plus one half: u in (0,1), never 0 or 1, exactly representable in float32
+__host__ __device__ inline float u24_open(uint32_t x) {
+    return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Launchers (defined in the kernel sources).  All enqueue on `st`; none synchronises.
+
+struct GemmPlan { int mt, nb, waves, ksplit; };
+
+// elementwise / row kernels ------------------------------------------------------------------
+void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+// same, but rows map to the library's per-(sequence, position) stores instead of compact arrays
+void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* tiles, int32_t* n_tiles,
+                              hipStream_t st);
+void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions,
+                                TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
+                  const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_copy_rows_in(const float* src, float* x, int h, int which /*0=z,1=e*/,
+                         const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_copy_rows_out(const float* x, float* dst, int width, int which /*0=z,1=e,2=compact*/,
+                          const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_copy_i32_out(const int32_t* src, int32_t* dst, const TileDesc* tiles,
+                         const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_concat(const float* e, const float* z, void* cat, int fmt, int h, const TileDesc* tiles,
+                   const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_addnorm(const float* xin, float* xout, const float* part, int S, size_t part_stride,
+                    const float* gain, void* xn, int fmt, int h, float eps, const int32_t* n_tiles,
+                    int max_tiles, hipStream_t st);
+void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride,
+                       const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
+                       float* delta, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                       hipStream_t st);
+void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc,
+                    int dtype, int H, int d, const float* theta, size_t seq_stride_elems,
+                    const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
+                   const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_init_state_rows(float* z, float* z_prev, int h, int seq, int pos0, int n, size_t zrow0,
+                            float alpha, uint32_t k0, uint32_t k1, hipStream_t st);
+void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs, int n_seqs,
+                           int max_positions, int headway, float alpha, uint32_t k0, uint32_t k1,
+                           hipStream_t st);
+void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
+                   int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                   hipStream_t st);
+void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
+                     int max_positions, const int32_t* drafts, const float* delta,
+                     const TileDesc* tiles, const int32_t* n_tiles, int32_t* n_active,
+                     hipStream_t st);
+void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
+void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n,
+                    float* k_out, float* v_out, hipStream_t st);
+
+// GEMMs ---------------------------------------------------------------------------------------
+// bf16: x packed [tiles][K/16][512], w packed [N/32][K/16][512], out f32 [ksplit][rows_total][N]
+void launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
+                      GemmPlan plan, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+// f32: x [rows][K], w [N][K], out [rows][N]
+void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
+                     const int32_t* n_tiles, int max_tiles, hipStream_t st);
+void launch_pack_weight(const void* w_canon /*bf16 [N][K]*/, void* w_packed, int N, int K, hipStream_t st);
+void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st);   // f32 rows -> packed bf16
+
+// attention -----------------------------------------------------------------------------------
+// q: f32 [rows][H*d] (RDLM_F32) or bf16 [rows][H*d]; caches per the model dtype; out: activation
+// format of the model dtype, width H*d.  ws: split-KV partials.
+void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
+                      size_t seq_stride_elems, int nsplit, float* ws, const TileDesc* tiles,
+                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
+size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);
+
+}  // namespace rdlm

@@ -1,0 +1,58 @@
+"""Shared helpers of the GPU parity tests: build both sides from the same seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+
+import synth_inputs as S
+from oracle import rdlm_oracle as O
+
+# small shapes that still span several MFMA tiles and ragged tails
+SMALL_BF16_D64 = S.ModelShape(vocab=512, hidden=256, n_heads=4, head_dim=64, mlp=512,
+                              n_prelude=1, n_core=2, n_coda=1, dtype="bf16")
+SMALL_BF16_D96 = S.ModelShape(vocab=384, hidden=288, n_heads=3, head_dim=96, mlp=608,
+                              n_prelude=1, n_core=2, n_coda=1, dtype="bf16")
+SMALL_BF16_D32 = S.ModelShape(vocab=256, hidden=160, n_heads=5, head_dim=32, mlp=224,
+                              n_prelude=1, n_core=1, n_coda=1, dtype="bf16")
+
+
+def rel_l2(a, b) -> float:
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def tol_latent(shape) -> float:
+    """Bound of the benchmark spec: rel-L2 1e-4 in fp32, 2e-2 in bf16."""
+    return 1e-4 if shape.dtype == "f32" else 2e-2
+
+
+def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_jitter=0.1, emb_mul=1.0):
+    """(Context on the GPU, oracle model, numpy weights) from one weight draw."""
+    import torch
+    import paper_2510_14961_amd as R
+    w = S.make_weights(shape, seed, gain_jitter=gain_jitter)
+    if emb_mul != 1.0:
+        w["emb"] = w["emb"] * np.float32(emb_mul)
+        if shape.dtype == "bf16":
+            w["emb"] = S.bf16_bits_to_f32(S.f32_to_bf16_bits(w["emb"]))
+    dev = R.upload_weights(shape, w)
+    ctx = R.Context(shape, dev, max_seqs, max_positions, max_rows)
+    del dev
+    torch.cuda.synchronize()
+    return ctx, O.RecurrentDepthLM(shape, w), w
+
+
+def tie_aware_token_check(gpu_tokens, oracle_scores, tau):
+    """A GPU token is accepted iff the oracle's score of it is within tau of the oracle's best.
+    Returns (number of exact matches, number accepted as near-ties); raises on a real mismatch."""
+    exact = ties = 0
+    for i, t in enumerate(gpu_tokens):
+        sc = oracle_scores[i]
+        best = int(np.argmax(sc))
+        if int(t) == best:
+            exact += 1
+        else:
+            gap = float(sc[best] - sc[int(t)])
+            assert gap <= tau, f"row {i}: GPU token {int(t)} scores {gap:.4g} below the oracle's best {best} (tau {tau:.3g})"
+            ties += 1
+    return exact, ties

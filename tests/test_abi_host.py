@@ -1,0 +1,81 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared symbol, and
+rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2510_14961_amd as R
+from paper_2510_14961_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(R.library_path()):
+        import paper_2510_14961_amd.build as bld
+        bld.build(verbose=False)
+    return R.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "rdlm.h")).read()
+    declared = set(re.findall(r"\b(rdlm_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(R.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(B._Model) == 12 * 4
+    assert C.sizeof(B._Sampler) == 10 * 4 + 8
+    assert B._Sampler.seed.offset == 40
+
+
+def _model(**kw):
+    base = dict(vocab=256, hidden=128, n_heads=2, head_dim=64, mlp=512, n_prelude=1, n_core=2, n_coda=1,
+                rope_base=10000.0, rms_eps=1e-6, emb_scale=1.0, dtype=0)
+    base.update(kw)
+    return B._Model(*[base[f[0]] for f in B._Model._fields_])
+
+
+def test_num_weights(lib):
+    assert lib.rdlm_num_weights(C.byref(_model())) == 1 + 7 * 4 + 3
+
+
+@pytest.mark.parametrize("bad", [
+    dict(hidden=130), dict(n_heads=3), dict(head_dim=63, n_heads=2, hidden=126), dict(n_core=0), dict(dtype=7),
+    dict(dtype=1, hidden=144, n_heads=3, head_dim=48), dict(dtype=1, vocab=250), dict(mlp=64), dict(rope_base=0.0),
+])
+def test_create_rejects_bad_shapes_on_the_host(lib, bad):
+    m = _model(**bad)
+    n = 64
+    ptrs = (C.c_void_p * n)(*([1] * n))          # never dereferenced: validation comes first
+    out = C.c_void_p()
+    assert lib.rdlm_create(C.byref(m), ptrs, 1, 64, 32, None, C.byref(out)) == -1
+    assert not out.value
+
+
+def test_create_rejects_bad_capacities_and_null_pointers(lib):
+    m = _model()
+    n = lib.rdlm_num_weights(C.byref(m))
+    ptrs = (C.c_void_p * n)(*([1] * n))
+    out = C.c_void_p()
+    for args in ((0, 64, 32), (1, 1, 32), (1, 64, 0), (65, 64, 32)):
+        assert lib.rdlm_create(C.byref(m), ptrs, *args, None, C.byref(out)) == -1
+    ptrs[3] = None
+    assert lib.rdlm_create(C.byref(m), ptrs, 1, 64, 32, None, C.byref(out)) == -1
+    assert lib.rdlm_create(None, ptrs, 1, 64, 32, None, C.byref(out)) == -1
+    assert lib.rdlm_create(C.byref(m), None, 1, 64, 32, None, C.byref(out)) == -1
+
+
+def test_null_context_is_an_error_not_a_crash(lib):
+    assert lib.rdlm_sample_step(None) == -1
+    assert lib.rdlm_generate(None, 1, None) == -1
+    assert lib.rdlm_prefill(None, 0, 1, 1, 1.0, 1) == -1
+    assert lib.rdlm_destroy(None) == -1
+    assert lib.rdlm_strerror(-2).decode().startswith("exceeds")
+    assert lib.rdlm_strerror(0).decode() == "ok"
