@@ -150,7 +150,9 @@ int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t n_seqs);
 int rdlm_sample_step(rdlm_ctx* ctx);
 
 /* Iterate rdlm_sample_step until every sequence has n_new frozen tokens or max_steps steps were
- * taken; synchronises.  steps_out (host, may be NULL) receives the number of iterations run. */
+ * taken; synchronises.  The device is looked at only every few iterations (at the predicted last
+ * one for the fixed exit rule); iterations enqueued after the finishing one do nothing.
+ * steps_out (host, may be NULL) receives the number of iterations up to the finishing one. */
 int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_out);
 
 /* ---- read-back (synchronise the stream) ------------------------------------------------- */

@@ -48,6 +48,9 @@ def load_library():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime; it has to be in the process before librdlm.so is loaded so
+    # that both resolve to one runtime (two runtimes in one process do not share the device).
+    import torch  # noqa: F401
     path = library_path()
     if not os.path.exists(path):
         raise RdlmError(f"{path} is missing: build it first (python -m paper_2510_14961_amd.build)")

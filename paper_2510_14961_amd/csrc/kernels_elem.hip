@@ -389,7 +389,8 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
 
 // Alg. 1 lines 13-16 / Alg. 2 freeze and append, one thread per sequence.
 __global__ void bookkeep_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
-                           int max_positions, const int32_t* drafts, const float* delta, int32_t* n_active) {
+                           int max_positions, const int32_t* drafts, const float* delta, int32_t* n_active,
+                           int step) {
     int s = threadIdx.x;
     int active = 0;
     if (s < n_seqs) {
@@ -434,7 +435,11 @@ __global__ void bookkeep_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t*
     __syncthreads();
     if (active) atomicAdd(&tot, 1);
     __syncthreads();
-    if (threadIdx.x == 0) *n_active = tot;
+    if (threadIdx.x == 0) {
+        // n_active[1] remembers the step at which the last sequence finished (0 = still running)
+        if (tot == 0 && n_active[0] != 0) n_active[1] = step;
+        n_active[0] = tot;
+    }
 }
 
 __global__ void fill_i32_k(int32_t* p, int32_t v, size_t n) {
@@ -557,10 +562,10 @@ void launch_sample(const float* logits, int V, float temperature, uint32_t k0, u
 }
 void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
                      int max_positions, const int32_t* drafts, const float* delta, const TileDesc* tiles,
-                     const int32_t* n_tiles, int32_t* n_active, hipStream_t st) {
+                     const int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st) {
     (void)tiles; (void)n_tiles;
     hipLaunchKernelGGL(bookkeep_k, dim3(1), dim3(64), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts,
-                       delta, n_active);
+                       delta, n_active, step);
 }
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
     if (!n) return;

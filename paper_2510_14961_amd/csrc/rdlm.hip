@@ -63,19 +63,25 @@ struct rdlm_ctx {
     int forced_att_split = 0;
 };
 
-#define HIPCHK(call)                                  \
-    do {                                              \
-        hipError_t e__ = (call);                      \
-        if (e__ != hipSuccess) {                      \
-            ctx->last_hip = (int)e__;                 \
-            return RDLM_EHIP;                         \
-        }                                             \
+#define HIPCHK(call)                                                                          \
+    do {                                                                                      \
+        hipError_t e__ = (call);                                                              \
+        if (e__ != hipSuccess) {                                                              \
+            fprintf(stderr, "rdlm: %s failed: %s (%s:%d)\n", #call, hipGetErrorString(e__),   \
+                    __FILE__, __LINE__);                                                      \
+            ctx->last_hip = (int)e__;                                                         \
+            return RDLM_EHIP;                                                                 \
+        }                                                                                     \
     } while (0)
 
 static int dalloc(rdlm_ctx* ctx, void** p, size_t bytes, bool zero) {
     if (bytes == 0) bytes = 256;
     hipError_t e = hipMalloc(p, bytes);
-    if (e != hipSuccess) { ctx->last_hip = (int)e; *p = nullptr; return RDLM_ENOMEM; }
+    if (e != hipSuccess) {
+        fprintf(stderr, "rdlm: hipMalloc(%zu bytes) failed: %s (total so far %zu)\n", bytes, hipGetErrorString(e),
+                ctx->bytes);
+        ctx->last_hip = (int)e; *p = nullptr; return RDLM_ENOMEM;
+    }
     ctx->allocs.push_back(*p);
     ctx->bytes += bytes;
     if (zero) {
@@ -92,7 +98,11 @@ static int dalloc(rdlm_ctx* ctx, void** p, size_t bytes, bool zero) {
 
 static int check_launch(rdlm_ctx* ctx) {
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) { ctx->last_hip = (int)e; return RDLM_EHIP; }
+    if (e != hipSuccess) {
+        fprintf(stderr, "rdlm: kernel launch failed: %s\n", hipGetErrorString(e));
+        ctx->last_hip = (int)e;
+        return RDLM_EHIP;
+    }
     return RDLM_OK;
 }
 
@@ -545,6 +555,8 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
                                (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
     }
     HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * n_seqs, hipMemcpyHostToDevice));
+    int32_t act[2] = {n_seqs, 0};
+    HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
     ctx->sampler = sp;
     ctx->sp.n_new = sp.n_new; ctx->sp.r_inner = sp.r_inner; ctx->sp.r_total = sp.r_total; ctx->sp.w_max = sp.w_max;
     ctx->sp.headway = sp.headway; ctx->sp.adaptive = sp.adaptive; ctx->sp.eps = sp.eps; ctx->sp.alpha = sp.alpha;
@@ -582,7 +594,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     launch_sample(ctx->logits, m.vocab, s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, ctx->drafts, ctx->tiles,
                   ctx->n_tiles, T, ctx->st);                                     // y_hat <- Sample(p)
     launch_bookkeep(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
-                    ctx->tiles, ctx->n_tiles, ctx->n_active, ctx->st);           // freeze, append
+                    ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);        // freeze, append
     launch_init_state_new(ctx->z_store, ctx->z_prev, m.hidden, ctx->seqs, n, ctx->max_positions, s.headway, s.alpha,
                           ctx->sp.seed_lo, ctx->sp.seed_hi, ctx->st);
     return check_launch(ctx);
@@ -601,9 +613,12 @@ extern "C" int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_ou
         if (rc) return rc;
         done_steps = i;
         if (i >= next_poll || i == max_steps) {
-            HIPCHK(hipMemcpyAsync(ctx->n_active_host, ctx->n_active, 4, hipMemcpyDeviceToHost, ctx->st));
+            HIPCHK(hipMemcpyAsync(ctx->n_active_host, ctx->n_active, 8, hipMemcpyDeviceToHost, ctx->st));
             HIPCHK(hipStreamSynchronize(ctx->st));
-            if (*ctx->n_active_host == 0) break;
+            if (ctx->n_active_host[0] == 0) {            // steps after the finishing one were no-ops
+                done_steps = ctx->n_active_host[1];
+                break;
+            }
             next_poll = i + (s.adaptive ? 8 : 1);
         }
     }

@@ -147,7 +147,7 @@ void launch_sample(const float* logits, int V, float temperature, uint32_t k0, u
                    hipStream_t st);
 void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
                      int max_positions, const int32_t* drafts, const float* delta,
-                     const TileDesc* tiles, const int32_t* n_tiles, int32_t* n_active,
+                     const TileDesc* tiles, const int32_t* n_tiles, int32_t* n_active, int step,
                      hipStream_t st);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n,
