@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the diffusion-forcing sampler hot path on one MI355X.
+
+A "step" is one sampler iteration (Alg. 1): prelude on the in-flight tokens, r' recurrences of
+the core block over the window, coda + LM head + Sample on every window row, freeze / append
+bookkeeping -- all inside librdlm.so.  Default workload: the 3.5B-shaped model, 512-token prompt,
+32 recurrences, window 32, batch 1, greedy (steady state freezes one token per step).
+
+Prints ONE JSON line: tokens/s (inputs resident in HBM, prefill not timed), the roofline of the
+dominant kernel (the weight-streaming GEMM of the gate/up projection, timed per launch with HIP
+events inside the timed region) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as S  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_weights(shape, seed, keep_f64: bool, threads: int):
+    """Upload the seeded weights tensor by tensor; optionally keep float64 host copies (oracle)."""
+    import torch
+    import paper_2510_14961_amd as R
+    dev, host = {}, {}
+    pool = ThreadPoolExecutor(max_workers=4)
+    futs = []
+    t0 = time.time()
+    for name, arr in S.iter_weights(shape, seed, threads=threads):
+        dev.update(R.upload_weights(shape, [(name, arr)]))
+        if keep_f64:
+            futs.append((name, pool.submit(lambda a: a.astype(np.float64), arr)))
+        del arr
+    for name, f in futs:
+        host[name] = f.result()
+    pool.shutdown()
+    torch.cuda.synchronize()
+    log(f"[bench] weights generated and uploaded in {time.time() - t0:.1f}s")
+    return dev, host
+
+
+def cpu_baseline(shape, w64, prompt_len, window, budget_s=20.0):
+    """Time the oracle (as it is) on steady-state sampler steps of the same shape: window rows
+    behind a context of prompt_len positions.  Cache content is random (only timing is read)."""
+    from oracle import rdlm_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    m = O.RecurrentDepthLM(shape, w64)
+    max_steps = 8
+    cache = m.new_cache(prompt_len + window + max_steps + 2)
+    rng = np.random.default_rng(0)
+    for d in (cache.k, cache.v):
+        for name in d:
+            d[name][: prompt_len] = rng.standard_normal((prompt_len, shape.n_heads, shape.head_dim))
+    y = np.concatenate([S.make_prompt(shape.vocab, prompt_len, 1), np.zeros(window + max_steps + 2, dtype=np.int32)])
+    p0 = prompt_len - 1
+    z = np.stack([O.init_state(shape.hidden, p0 + j, 0, 1.0, 1) for j in range(window)])
+    times = []
+    for t in range(1, max_steps + 1):
+        t0 = time.time()
+        pos = np.arange(p0, p0 + window)
+        e = m.prelude(y[pos], pos, cache)
+        z = m.core(e, z, pos, cache)
+        logits = m.coda(z, pos, cache)
+        for i, p in enumerate(pos):
+            y[p + 1] = O.sample(logits[i], 0.0, int(p), 0, t, 1)
+        # steady state: the oldest state leaves, a fresh one enters
+        z = np.concatenate([z[1:], O.init_state(shape.hidden, p0 + window, 0, 1.0, 1)[None]])
+        p0 += 1
+        times.append(time.time() - t0)
+        if sum(times) > budget_s:
+            break
+    per_step = float(np.mean(times))
+    return {"value": 1.0 / per_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{len(times)} steady-state sampler steps (window {window}, context {prompt_len}+, float64 numpy; "
+                      f"cache prefix filled with random values, prefill not run), {per_step:.2f} s/step, 1 token/step"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=511)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--threads", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2510_14961_amd as R
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = S.WORKLOADS[args.workload]
+    shape, sp = wl.shape, wl.sampler
+    K, W = args.steps, args.warmup
+    window = -(-sp.r // sp.r_inner) * sp.headway
+    n_new = max(sp.n_new, K + W + 1)                 # never finish inside the timed steps
+    max_positions = wl.prompt_len + n_new + window + sp.headway + 8
+    want_cpu = not args.no_cpu_baseline
+
+    dev, w64 = build_weights(shape, wl.weight_seed, want_cpu, args.threads)
+    t0 = time.time()
+    ctx = R.Context(shape, dev, 1, max_positions, max(wl.prompt_len, window))
+    del dev
+    torch.cuda.empty_cache()
+    log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 2**30:.1f} GiB on device")
+
+    prompt = S.make_prompt(shape.vocab, wl.prompt_len, wl.prompt_seed)
+    ctx.set_tokens(0, prompt)
+    t0 = time.time()
+    ctx.prefill(0, wl.prompt_len - 1, sp.r, sp.alpha, sp.seed)
+    torch.cuda.synchronize()
+    log(f"[bench] prefill of {wl.prompt_len - 1} positions x {sp.r} recurrences: {time.time() - t0:.2f}s")
+    ctx.sampler_begin(1, n_new=n_new, r_inner=sp.r_inner, r_total=sp.r, headway=sp.headway, alpha=sp.alpha,
+                      temperature=sp.temperature, seed=sp.seed)
+    for _ in range(W):
+        ctx.sample_step()
+    torch.cuda.synchronize()
+    _, nf0 = ctx.read_tokens(0, 1)
+    n_gu, k_gu = 2 * shape.mlp, shape.hidden
+    per_step_launches = shape.n_prelude + sp.r_inner * shape.n_core + shape.n_coda     # one per layer pass
+    ctx.profile_gemm_begin(n_gu, k_gu, K * per_step_launches)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        ctx.sample_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gemm_ms, gemm_launches = ctx.profile_gemm_read()
+    _, nf1 = ctx.read_tokens(0, 1)
+    tokens = nf1 - nf0
+    ms_per_step = dt / K * 1e3
+
+    # dominant kernel: gate/up projection, rows = window padded to 32
+    rows = -(-window // 32) * 32
+    algo_bytes = n_gu * k_gu * 2 + rows * k_gu * 2 + rows * n_gu * 4
+    achieved = algo_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"gemm_gu_{args.workload}")
+        except Exception:
+            traffic = None
+    core_ms = ctx.time_core_step(0, wl.prompt_len, window, 20)
+    h, F, V = shape.hidden, shape.mlp, shape.vocab
+    layer_b = (4 * h * h + 3 * h * F) * 2
+    core_bytes = shape.n_core * layer_b + 2 * h * h * 2
+    step_bytes = shape.n_layers * layer_b + 2 * h * h * 2 + V * h * 2
+
+    out = {
+        "metric": "generated tokens/sec @batch1 (3.5B-shaped)" if args.workload == "cfg3" else "generated tokens/sec @batch1",
+        "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {h}x{shape.n_heads}x{shape.head_dim}, mlp {F}, vocab {V}, "
+                               f"P{shape.n_prelude}/R{shape.n_core}/C{shape.n_coda}, prompt {wl.prompt_len}, "
+                               f"r={sp.r}, r'={sp.r_inner}, window {window}, batch 1, greedy",
+                   "tokens_in_timed_region": int(tokens), "context_at_end": int(nf1)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "gemm_bf16_k (gate/up projection, [2F x h] weights, 32 rows)",
+                     "bytes_per_launch": algo_bytes, "avg_ms_per_launch": gemm_ms, "launches_timed": gemm_launches},
+        "whole_step": {"weight_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "core_step": {"ms": core_ms, "weight_bytes": core_bytes, "GBps": core_bytes / (core_ms * 1e-3) / 1e9},
+    }
+    ctx.close()
+    torch.cuda.empty_cache()
+    if want_cpu:
+        t0 = time.time()
+        out["cpu_baseline"] = cpu_baseline(shape, w64, wl.prompt_len, window)
+        log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

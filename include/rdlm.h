@@ -185,6 +185,14 @@ int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m, int32_t iters, f
 int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t iters,
                         float* ms_out);
 
+/* Per-launch timing of one GEMM shape inside the model path: while enabled, every launch of the
+ * projection with n_out output and k_in input features (e.g. 2*mlp x hidden = gate/up) is
+ * bracketed by HIP events on the context's stream, up to max_launches launches.
+ * rdlm_profile_gemm_read synchronises, returns the average milliseconds per launch and the
+ * number of launches recorded, and disables the recording. */
+int rdlm_profile_gemm_begin(rdlm_ctx* ctx, int32_t n_out, int32_t k_in, int32_t max_launches);
+int rdlm_profile_gemm_read(rdlm_ctx* ctx, float* avg_ms_out, int32_t* launches_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,8 @@ EXPORTED_SYMBOLS = [
     "rdlm_device_bytes", "rdlm_set_tokens", "rdlm_prefill", "rdlm_init_state", "rdlm_prelude",
     "rdlm_core_step", "rdlm_coda_decode", "rdlm_sampler_begin", "rdlm_sample_step", "rdlm_generate",
     "rdlm_read_tokens", "rdlm_read_states", "rdlm_read_counts", "rdlm_read_deltas", "rdlm_read_kv",
-    "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step",
+    "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
+    "rdlm_profile_gemm_read",
 ]
 
 
@@ -81,6 +82,8 @@ def load_library():
         "rdlm_linear": (C.c_int, [vp, i32, vp, i32, vp]),
         "rdlm_time_linear": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float)]),
         "rdlm_time_core_step": (C.c_int, [vp, i32, i32, i32, i32, C.POINTER(C.c_float)]),
+        "rdlm_profile_gemm_begin": (C.c_int, [vp, i32, i32, i32]),
+        "rdlm_profile_gemm_read": (C.c_int, [vp, C.POINTER(C.c_float), pi32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -266,3 +269,11 @@ class Context:
         ms = C.c_float(0)
         self._chk(self.lib.rdlm_time_core_step(self.ctx, seq, pos0, n, iters, C.byref(ms)), "rdlm_time_core_step")
         return ms.value
+
+    def profile_gemm_begin(self, n_out: int, k_in: int, max_launches: int):
+        self._chk(self.lib.rdlm_profile_gemm_begin(self.ctx, n_out, k_in, max_launches), "rdlm_profile_gemm_begin")
+
+    def profile_gemm_read(self):
+        ms, n = C.c_float(0), C.c_int32(0)
+        self._chk(self.lib.rdlm_profile_gemm_read(self.ctx, C.byref(ms), C.byref(n)), "rdlm_profile_gemm_read")
+        return ms.value, n.value

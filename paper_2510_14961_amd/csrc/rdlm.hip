@@ -61,6 +61,9 @@ struct rdlm_ctx {
     std::vector<void*> allocs;
     GemmPlan forced_plan = {0, 0, 0, 0};
     int forced_att_split = 0;
+    // per-launch GEMM timing
+    int prof_n = 0, prof_k = 0, prof_used = 0;
+    std::vector<hipEvent_t> prof_ev;
 };
 
 #define HIPCHK(call)                                                                          \
@@ -148,6 +151,7 @@ extern "C" int rdlm_destroy(rdlm_ctx* ctx) {
     if (!ctx) return RDLM_EINVAL;
     (void)hipStreamSynchronize(ctx->st);
     for (void* p : ctx->allocs) (void)hipFree(p);
+    for (hipEvent_t ev : ctx->prof_ev) (void)hipEventDestroy(ev);
     if (ctx->n_active_host) (void)hipHostFree(ctx->n_active_host);
     delete ctx;
     return RDLM_OK;
@@ -325,7 +329,10 @@ static void gemm(rdlm_ctx* ctx, const void* xin, const void* W, float* out, int 
         return;
     }
     GemmPlan g = plan_for(ctx, N, K, T, allow_split);
+    const bool prof = ctx->prof_n == N && ctx->prof_k == K && (size_t)ctx->prof_used + 2 <= ctx->prof_ev.size();
+    if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
     launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, ctx->n_tiles, T, ctx->st);
+    if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
     if (S_out) *S_out = g.ksplit;
 }
 
@@ -797,6 +804,33 @@ extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, 
     (void)hipEventDestroy(b);
     *ms_out = ms / iters;
     return check_launch(ctx);
+}
+
+extern "C" int rdlm_profile_gemm_begin(rdlm_ctx* ctx, int32_t n_out, int32_t k_in, int32_t max_launches) {
+    if (!ctx || n_out < 1 || k_in < 1 || max_launches < 1 || max_launches > (1 << 20)) return RDLM_EINVAL;
+    while ((int)ctx->prof_ev.size() < 2 * max_launches) {
+        hipEvent_t ev;
+        HIPCHK(hipEventCreate(&ev));
+        ctx->prof_ev.push_back(ev);
+    }
+    ctx->prof_n = n_out; ctx->prof_k = k_in; ctx->prof_used = 0;
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_profile_gemm_read(rdlm_ctx* ctx, float* avg_ms_out, int32_t* launches_out) {
+    if (!ctx || !avg_ms_out || !launches_out) return RDLM_EINVAL;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    double tot = 0.0;
+    int n = ctx->prof_used / 2;
+    for (int i = 0; i < n; ++i) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+        tot += ms;
+    }
+    *avg_ms_out = n ? (float)(tot / n) : 0.f;
+    *launches_out = n;
+    ctx->prof_n = ctx->prof_k = 0; ctx->prof_used = 0;
+    return RDLM_OK;
 }
 
 extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t iters,
