@@ -152,70 +152,84 @@ __global__ void concat_k(const float* e, const float* z, void* cat, int h, const
     }
 }
 
-// x_out = x_in + sum_s part[s];  xn = x_out * gain / sqrt(mean(x_out^2) + eps)
+// x_out = x_in + sum_s part[s];  xn = x_out * gain / sqrt(mean(x_out^2) + eps).
+// One workgroup per row; the row stays in registers between the reduction and the stores
+// (up to ROW_VEC float4 per thread, i.e. h <= 256*4*ROW_VEC).
+constexpr int ROW_VEC = 8;
+
+__device__ inline float4 row_value(const float* xin, const float* part, int S, size_t part_stride, size_t off) {
+    float4 v = xin ? ld4(xin + off) : make_float4(0, 0, 0, 0);
+    for (int s = 0; s < S; ++s) {
+        float4 p = ld4(part + s * part_stride + off);
+        v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    return v;
+}
+
 template <int FMT>
-__global__ void addnorm_k(const float* xin, float* xout, const float* part, int S, size_t part_stride,
-                          const float* gain, void* xn, int h, float eps, const int32_t* n_tiles) {
+__global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, const float* part, int S,
+                                                  size_t part_stride, const float* gain, void* xn, int h, float eps,
+                                                  const int32_t* n_tiles) {
     __shared__ float sh[8];
     int r = blockIdx.x;
     if ((r >> 5) >= *n_tiles) return;
+    float4 v[ROW_VEC];
     float ss = 0.f;
-    auto value = [&](int k) {
-        float4 v = xin ? ld4(xin + (size_t)r * h + k) : make_float4(0, 0, 0, 0);
-        for (int s = 0; s < S; ++s) {
-            float4 p = ld4(part + s * part_stride + (size_t)r * h + k);
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+#pragma unroll
+    for (int i = 0; i < ROW_VEC; ++i) {
+        int k = (threadIdx.x + i * 256) * 4;
+        if (k < h) {
+            v[i] = row_value(xin, part, S, part_stride, (size_t)r * h + k);
+            ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
         }
-        return v;
-    };
-    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
-        float4 v = value(k);
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     ss = block_sum(ss, sh);
     float inv = 1.0f / sqrtf(ss / (float)h + eps);
-    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
-        float4 v = value(k);
-        if (xout) *reinterpret_cast<float4*>(xout + (size_t)r * h + k) = v;
-        if (xn) {
-            float4 g = ld4(gain + k);
-            act_store4<FMT>(xn, h, r, k, v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
+#pragma unroll
+    for (int i = 0; i < ROW_VEC; ++i) {
+        int k = (threadIdx.x + i * 256) * 4;
+        if (k < h) {
+            if (xout) *reinterpret_cast<float4*>(xout + (size_t)r * h + k) = v[i];
+            if (xn) {
+                float4 g = ld4(gain + k);
+                act_store4<FMT>(xn, h, r, k, v[i].x * inv * g.x, v[i].y * inv * g.y, v[i].z * inv * g.z,
+                                v[i].w * inv * g.w);
+            }
         }
     }
 }
 
 // End of a recurrence: z' = RMSNorm(x + sum part) * gain, stored to the latent array; optionally
 // delta = ||z' - z_prev|| / ||z'|| (Eq. 3) and z_prev <- z'.
-__global__ void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
-                             const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
-                             float* delta, const TileDesc* tiles, const int32_t* n_tiles) {
+__global__ __launch_bounds__(256) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
+                                                     const float* gain, int h, float eps, float* z, float* z_prev,
+                                                     int update_prev, float* delta, const TileDesc* tiles,
+                                                     const int32_t* n_tiles) {
     __shared__ float sh[8];
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
     bool valid = j < d.n_valid;
-    auto value = [&](int k) {
-        float4 v = xin ? ld4(xin + (size_t)r * h + k) : make_float4(0, 0, 0, 0);
-        for (int s = 0; s < S; ++s) {
-            float4 p = ld4(part + s * part_stride + (size_t)r * h + k);
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-        }
-        return v;
-    };
+    float4 v[ROW_VEC];
     float ss = 0.f;
-    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
-        float4 v = value(k);
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+    for (int i = 0; i < ROW_VEC; ++i) {
+        int k = (threadIdx.x + i * 256) * 4;
+        if (k < h) {
+            v[i] = row_value(xin, part, S, part_stride, (size_t)r * h + k);
+            ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+        }
     }
     ss = block_sum(ss, sh);
     float inv = 1.0f / sqrtf(ss / (float)h + eps);
     float num = 0.f, den = 0.f;
     size_t zr = (size_t)d.zrow0 + j;
-    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
-        float4 v = value(k);
-        float4 g = ld4(gain + k);
-        float4 o = make_float4(v.x * inv * g.x, v.y * inv * g.y, v.z * inv * g.z, v.w * inv * g.w);
-        if (valid) {
+#pragma unroll
+    for (int i = 0; i < ROW_VEC; ++i) {
+        int k = (threadIdx.x + i * 256) * 4;
+        if (k < h && valid) {
+            float4 g = ld4(gain + k);
+            float4 o = make_float4(v[i].x * inv * g.x, v[i].y * inv * g.y, v[i].z * inv * g.z, v[i].w * inv * g.w);
             if (z_prev) {
                 float4 p = ld4(z_prev + zr * h + k);
                 num += (o.x - p.x) * (o.x - p.x) + (o.y - p.y) * (o.y - p.y) + (o.z - p.z) * (o.z - p.z) +
@@ -233,40 +247,55 @@ __global__ void final_norm_k(const float* xin, const float* part, int S, size_t 
     }
 }
 
-// RoPE (rotate-half pairs (i, i+d/2), angle pos * theta_i) on q and k; q is written for the
-// attention kernel, k and v are written into the layer's cache at the row's position,
-// replacing what an earlier recurrence or sampler step left there.
-template <int DT>
-__global__ void rope_kv_k(const float* qkv, int S, size_t part_stride, void* qout, void* kc, void* vc, int H,
-                          int d, const float* theta, size_t seq_stride, const TileDesc* tiles,
-                          const int32_t* n_tiles) {
+// cos / sin of pos * theta_i for every row of the step, computed once per step.
+__global__ void rope_table_k(float2* table, const float* theta, int half, const TileDesc* tiles,
+                             const int32_t* n_tiles) {
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
-    TileDesc ds = tiles[t];
-    bool valid = j < ds.n_valid;
-    int pos = ds.pos0 + j;
-    int h = H * d, half = d >> 1;
-    auto at = [&](int col) {
-        float v = 0.f;
-        for (int s = 0; s < S; ++s) v += qkv[s * part_stride + (size_t)r * 3 * h + col];
-        return v;
-    };
-    for (int idx = threadIdx.x; idx < H * half; idx += blockDim.x) {
-        int hd = idx / half, i = idx - hd * half;
+    int pos = tiles[t].pos0 + j;
+    for (int i = threadIdx.x; i < half; i += blockDim.x) {
         float sn, cs;
         sincosf((float)pos * theta[i], &sn, &cs);
-        int c0 = hd * d + i, c1 = c0 + half;
-        float q0 = at(c0), q1 = at(c1), k0 = at(h + c0), k1 = at(h + c1);
-        float v0 = at(2 * h + c0), v1 = at(2 * h + c1);
-        float qa = q0 * cs - q1 * sn, qb = q1 * cs + q0 * sn;
-        float ka = k0 * cs - k1 * sn, kb = k1 * cs + k0 * sn;
+        table[(size_t)r * half + i] = make_float2(cs, sn);
+    }
+}
+
+// RoPE (rotate-half pairs (i, i+d/2), angle pos * theta_i) on q and k; q is written for the
+// attention kernel, k and v are written into the layer's cache at the row's position,
+// replacing what an earlier recurrence or sampler step left there.  One workgroup per
+// (head, tile); v goes through LDS so that the writes into the transposed bf16 V cache walk the
+// 32 positions of a block together.
+template <int DT>
+__global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t part_stride, void* qout, void* kc,
+                                                  void* vc, int H, int d, const float2* table, size_t seq_stride,
+                                                  const TileDesc* tiles, const int32_t* n_tiles) {
+    extern __shared__ float sv[];                       // [32][d + 1]
+    const int hd = blockIdx.x, t = blockIdx.y;
+    if (t >= *n_tiles) return;
+    const TileDesc ds = tiles[t];
+    const int h = H * d, half = d >> 1;
+    auto at = [&](int row, int colidx) {
+        float v = 0.f;
+        for (int s = 0; s < S; ++s) v += qkv[s * part_stride + (size_t)row * 3 * h + colidx];
+        return v;
+    };
+    for (int idx = threadIdx.x; idx < 32 * half; idx += blockDim.x) {
+        const int j = idx / half, i = idx - j * half;
+        const int r = t * 32 + j, pos = ds.pos0 + j;
+        const bool valid = j < ds.n_valid;
+        const float2 cssn = table[(size_t)r * half + i];
+        const int c0 = hd * d + i, c1 = c0 + half;
+        const float q0 = at(r, c0), q1 = at(r, c1), k0 = at(r, h + c0), k1 = at(r, h + c1);
+        const float qa = q0 * cssn.x - q1 * cssn.y, qb = q1 * cssn.x + q0 * cssn.y;
+        const float ka = k0 * cssn.x - k1 * cssn.y, kb = k1 * cssn.x + k0 * cssn.y;
+        sv[j * (d + 1) + i] = at(r, 2 * h + c0);
+        sv[j * (d + 1) + i + half] = at(r, 2 * h + c1);
         if (DT == 0) {
             float* q = reinterpret_cast<float*>(qout);
             q[(size_t)r * h + c0] = qa; q[(size_t)r * h + c1] = qb;
             if (valid) {
                 float* K = reinterpret_cast<float*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
-                float* Vv = reinterpret_cast<float*>(vc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
-                K[c0] = ka; K[c1] = kb; Vv[c0] = v0; Vv[c1] = v1;
+                K[c0] = ka; K[c1] = kb;
             }
         } else {
             uint16_t* q = reinterpret_cast<uint16_t*>(qout);
@@ -274,12 +303,25 @@ __global__ void rope_kv_k(const float* qkv, int S, size_t part_stride, void* qou
             if (valid) {
                 uint16_t* K = reinterpret_cast<uint16_t*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
                 K[c0] = f32_to_bf16(ka); K[c1] = f32_to_bf16(kb);
-                // transposed V: [position block][head][dim][32 slots]
-                uint16_t* Vt = reinterpret_cast<uint16_t*>(vc) + (size_t)ds.seq * seq_stride +
-                               ((size_t)(pos >> 5) * H + hd) * d * 32 + vt_slot(pos & 31);
-                Vt[(size_t)i * 32] = f32_to_bf16(v0);
-                Vt[(size_t)(i + half) * 32] = f32_to_bf16(v1);
             }
+        }
+    }
+    __syncthreads();
+    if (DT == 0) {
+        for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
+            const int j = idx / d, dd = idx - j * d;
+            if (j < ds.n_valid)
+                reinterpret_cast<float*>(vc)[(size_t)ds.seq * seq_stride + (size_t)(ds.pos0 + j) * h + hd * d + dd] =
+                    sv[j * (d + 1) + dd];
+        }
+    } else {
+        // transposed V: [position block][head][dim][32 slots]; lanes run over the rows of the tile
+        for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
+            const int dd = idx >> 5, j = idx & 31, pos = ds.pos0 + j;
+            if (j < ds.n_valid)
+                reinterpret_cast<uint16_t*>(vc)[(size_t)ds.seq * seq_stride +
+                                                (((size_t)(pos >> 5) * H + hd) * d + dd) * 32 + vt_slot(pos & 31)] =
+                    f32_to_bf16(sv[j * (d + 1) + dd]);
         }
     }
 }
@@ -522,15 +564,22 @@ void launch_final_norm(const float* xin, const float* part, int S, size_t part_s
     hipLaunchKernelGGL(final_norm_k, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain, h,
                        eps, z, z_prev, update_prev, delta, tiles, n_tiles);
 }
+void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
+                       int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(rope_table_k, dim3(max_tiles * 32), dim3(64), 0, st, reinterpret_cast<float2*>(table), theta,
+                       half, tiles, n_tiles);
+}
 void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc, int dtype,
-                    int H, int d, const float* theta, size_t seq_stride_elems, const TileDesc* tiles,
+                    int H, int d, const float* table, size_t seq_stride_elems, const TileDesc* tiles,
                     const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    const size_t lds = (size_t)32 * (d + 1) * sizeof(float);
+    const float2* tb = reinterpret_cast<const float2*>(table);
     if (dtype == 0)
-        hipLaunchKernelGGL(rope_kv_k<0>, dim3(max_tiles * 32), dim3(256), 0, st, qkv, S, part_stride, q, kc, vc, H,
-                           d, theta, seq_stride_elems, tiles, n_tiles);
+        hipLaunchKernelGGL(rope_kv_k<0>, dim3(H, max_tiles), dim3(256), lds, st, qkv, S, part_stride, q, kc, vc, H, d,
+                           tb, seq_stride_elems, tiles, n_tiles);
     else
-        hipLaunchKernelGGL(rope_kv_k<1>, dim3(max_tiles * 32), dim3(256), 0, st, qkv, S, part_stride, q, kc, vc, H,
-                           d, theta, seq_stride_elems, tiles, n_tiles);
+        hipLaunchKernelGGL(rope_kv_k<1>, dim3(H, max_tiles), dim3(256), lds, st, qkv, S, part_stride, q, kc, vc, H, d,
+                           tb, seq_stride_elems, tiles, n_tiles);
 }
 void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
                    const int32_t* n_tiles, int max_tiles, hipStream_t st) {

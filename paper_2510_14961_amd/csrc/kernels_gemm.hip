@@ -19,25 +19,35 @@ namespace rdlm {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int UNROLL = 4;   // k tiles fetched ahead per wave
+struct GemmArgs {
+    const bf16x8* xp;
+    const bf16x8* wp;
+    float* out;             // EPI_F32: [ksplit][rows][N] partial sums; EPI_ARGMAX: logits [rows][N] or null
+    int N, K16, n_groups, m_chunks, ksplit;
+    size_t part_stride;
+    const int32_t* n_tiles;
+    GemmEpilogue epi;
+};
 
-template <int MT, int NB, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(const bf16x8* __restrict__ xp,
-                                                            const bf16x8* __restrict__ wp, float* __restrict__ out,
-                                                            int N, int K16, int n_groups, int m_chunks, int ksplit,
-                                                            size_t part_stride, const int32_t* n_tiles_p) {
+// Epilogue helpers ---------------------------------------------------------------------------
+__device__ inline float silu_f(float a) { return a / (1.0f + __expf(-a)); }
+
+template <int MT, int NB, int WAVES, int U, int EPI>
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     extern __shared__ float red[];                 // [WAVES][NB*MT*16][64]
+    __shared__ float cand_v[WAVES > 1 ? WAVES : 1][MT][32];
+    __shared__ int cand_i[WAVES > 1 ? WAVES : 1][MT][32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int bid = blockIdx.x;
-    const int mc = bid % m_chunks; bid /= m_chunks;  // row chunk fastest: neighbours share weights
-    const int ks = bid % ksplit;
-    const int grp = bid / ksplit;
-    const int n_tiles = *n_tiles_p;
+    const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
+    const int ks = bid % A.ksplit;
+    const int grp = bid / A.ksplit;
+    const int n_tiles = *A.n_tiles;
     const int t0 = mc * MT;
     if (t0 >= n_tiles) return;
-    const int nblk = N >> 5;
+    const int nblk = A.N >> 5, K16 = A.K16;
     // K range of this wave: K16 tiles split evenly over ksplit * WAVES slices
-    const int slices = ksplit * WAVES, sl = ks * WAVES + wave;
+    const int slices = A.ksplit * WAVES, sl = ks * WAVES + wave;
     const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
 
     f32x16 acc[NB][MT];
@@ -48,36 +58,63 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(const bf16x8* __restri
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
+    // feature blocks of this workgroup: consecutive ones, except for the SwiGLU epilogue, which
+    // pairs gate block `grp` with up block `grp + nblk/2`
+    int blk[NB];
     const bf16x8* wbase[NB];
     const bf16x8* xbase[MT];
 #pragma unroll
     for (int a = 0; a < NB; ++a) {
-        int nb = min(grp * NB + a, nblk - 1);       // clamp: a ragged last group re-reads a valid block
-        wbase[a] = wp + ((size_t)nb * K16) * 64 + lane;
+        blk[a] = (EPI == EPI_SWIGLU) ? grp + a * (nblk >> 1) : grp * NB + a;
+        int nb = min(blk[a], nblk - 1);             // a ragged last group re-reads a valid block
+        wbase[a] = A.wp + ((size_t)nb * K16) * 64 + lane;
     }
 #pragma unroll
     for (int b = 0; b < MT; ++b) {
         int t = min(t0 + b, n_tiles - 1);
-        xbase[b] = xp + ((size_t)t * K16) * 64 + lane;
+        xbase[b] = A.xp + ((size_t)t * K16) * 64 + lane;
     }
 
-    int kt = kbeg;
-    for (; kt + UNROLL <= kend; kt += UNROLL) {
-        bf16x8 wv[UNROLL][NB], xv[UNROLL][MT];
+    bf16x8 wa[U][NB], xa[U][MT], wb[U][NB], xb[U][MT];
+    auto load = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT], int kt) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int a = 0; a < NB; ++a) wv[u][a] = __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64);
 #pragma unroll
             for (int b = 0; b < MT; ++b) xv[u][b] = xbase[b][(size_t)(kt + u) * 64];
         }
+        __builtin_amdgcn_sched_barrier(0);          // all loads of the batch are issued before any MFMA
+    };
+    auto compute = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT]) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int a = 0; a < NB; ++a)
 #pragma unroll
                 for (int b = 0; b < MT; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv[u][b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = kbeg;
+    int batches = (kend - kbeg) / U;
+    if (batches > 0) {                              // double-buffered: one batch in flight while one is consumed
+        load(wa, xa, kt); kt += U;
+        int rem = batches - 1;
+        while (rem >= 2) {
+            load(wb, xb, kt); kt += U;
+            compute(wa, xa);
+            load(wa, xa, kt); kt += U;
+            compute(wb, xb);
+            rem -= 2;
+        }
+        if (rem == 1) {
+            load(wb, xb, kt); kt += U;
+            compute(wa, xa);
+            compute(wb, xb);
+        } else {
+            compute(wa, xa);
+        }
     }
     for (; kt < kend; ++kt) {
 #pragma unroll
@@ -89,8 +126,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(const bf16x8* __restri
         }
     }
 
-    // cross-wave sum in a fixed order: every wave deposits its accumulators, then wave w adds up
-    // and stores the registers r with r % WAVES == w
+    // cross-wave sum in a fixed order: every wave deposits its accumulators, then wave w finishes
+    // the register quads (b, q) with (b*4+q) % WAVES == w, for all feature blocks a
     constexpr int REGS = NB * MT * 16;
     if (WAVES > 1) {
 #pragma unroll
@@ -101,63 +138,198 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(const bf16x8* __restri
                 for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
         __syncthreads();
     }
-    float* o = out + (size_t)ks * part_stride;
     const int col = lane & 31, g = lane >> 5;
+    float best_v[MT];
+    int best_i[MT];
 #pragma unroll
-    for (int a = 0; a < NB; ++a) {
-        int nb = grp * NB + a;
-        if (nb >= nblk) continue;
+    for (int b = 0; b < MT; ++b) { best_v[b] = -INFINITY; best_i[b] = 0x7fffffff; }
+
 #pragma unroll
-        for (int b = 0; b < MT; ++b) {
-            int t = t0 + b;
+    for (int b = 0; b < MT; ++b) {
+        const int t = t0 + b;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (WAVES > 1 && (b * 4 + q) % WAVES != wave) continue;
             if (t >= n_tiles) continue;
+            float v[NB][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (WAVES > 1 && ((a * MT + b) * 4 + q) % WAVES != wave) continue;
-                float4 v;
-                float* vv = reinterpret_cast<float*>(&v);
+            for (int a = 0; a < NB; ++a)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    int r = (a * MT + b) * 16 + q * 4 + i;
+                    const int r = (a * MT + b) * 16 + q * 4 + i;
                     if (WAVES > 1) {
                         float s = 0.f;
 #pragma unroll
                         for (int w = 0; w < WAVES; ++w) s += red[((size_t)w * REGS + r) * 64 + lane];
-                        vv[i] = s;
+                        v[a][i] = s;
                     } else {
-                        vv[i] = acc[a][b][q * 4 + i];
+                        v[a][i] = acc[a][b][q * 4 + i];
                     }
                 }
-                // accumulator register q*4+i of lane (col, g) is feature 8q + 4g + i of the block, row `col`
-                size_t row = (size_t)t * 32 + col;
-                *reinterpret_cast<float4*>(o + row * N + nb * 32 + q * 8 + g * 4) = v;
+            // accumulator register q*4+i of lane (col, g) is feature 8q + 4g + i of its block, row `col`
+            const size_t row = (size_t)t * 32 + col;
+            const int foff = q * 8 + g * 4;
+            if (EPI == EPI_F32) {
+                float* o = A.out + (size_t)ks * A.part_stride;
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    if (blk[a] < nblk)
+                        *reinterpret_cast<float4*>(o + row * A.N + blk[a] * 32 + foff) =
+                            make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
+            } else if (EPI == EPI_SWIGLU) {
+                // blocks (0,1) = (gate, up) of the same 32 features: act = silu(gate) * up, stored as a
+                // packed bf16 activation of width F = N/2
+                const int F = A.N >> 1;
+                ushort4 pk;
+                pk.x = f32_to_bf16(silu_f(v[0][0]) * v[NB - 1][0]);
+                pk.y = f32_to_bf16(silu_f(v[0][1]) * v[NB - 1][1]);
+                pk.z = f32_to_bf16(silu_f(v[0][2]) * v[NB - 1][2]);
+                pk.w = f32_to_bf16(silu_f(v[0][3]) * v[NB - 1][3]);
+                *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.act) +
+                                            packed_off((int)row, grp * 32 + foff, F)) = pk;
+            } else {   // EPI_ARGMAX
+                const TileDesc td = A.epi.tiles[t];
+#pragma unroll
+                for (int a = 0; a < NB; ++a) {
+                    if (blk[a] >= nblk) continue;
+                    const int f0 = blk[a] * 32 + foff;
+                    if (A.out)
+                        *reinterpret_cast<float4*>(A.out + row * A.N + f0) = make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
+                    float gn[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (A.epi.temperature > 0.f) {
+                        uint32_t x[4];
+                        philox4x32_10(f0 >> 2, td.pos0 + col, td.seq, ((uint32_t)A.epi.step << 4) | TAG_SAMPLE,
+                                      A.epi.k0, A.epi.k1, x);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float sc = v[a][i];
+                        if (A.epi.temperature > 0.f) sc = sc / A.epi.temperature + gn[i];
+                        if (sc > best_v[b] || (sc == best_v[b] && f0 + i < best_i[b])) { best_v[b] = sc; best_i[b] = f0 + i; }
+                    }
+                }
+            }
+        }
+    }
+    if (EPI == EPI_ARGMAX) {
+        // best over the two half-waves, then over the waves; one candidate per (group, row)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+            float ov = __shfl_xor(best_v[b], 32);
+            int oi = __shfl_xor(best_i[b], 32);
+            if (ov > best_v[b] || (ov == best_v[b] && oi < best_i[b])) { best_v[b] = ov; best_i[b] = oi; }
+            if (g == 0) { cand_v[wave][b][col] = best_v[b]; cand_i[wave][b][col] = best_i[b]; }
+        }
+        __syncthreads();
+        if (wave == 0 && g == 0) {
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+                if (t0 + b >= n_tiles) continue;
+                float bv = cand_v[0][b][col];
+                int bi = cand_i[0][b][col];
+#pragma unroll
+                for (int w = 1; w < WAVES; ++w) {
+                    float ov = cand_v[w][b][col];
+                    int oi = cand_i[w][b][col];
+                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                }
+                size_t o = (size_t)grp * A.epi.cand_stride + (size_t)(t0 + b) * 32 + col;
+                A.epi.cand_val[o] = bv;
+                A.epi.cand_idx[o] = bi;
             }
         }
     }
 }
 
-template <int MT, int NB, int WAVES>
-static void launch_cfg(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride, int ksplit,
-                       const int32_t* n_tiles, int max_tiles, hipStream_t st) {
-    int nblk = N / 32, groups = (nblk + NB - 1) / NB, m_chunks = (max_tiles + MT - 1) / MT;
-    size_t lds = WAVES > 1 ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
-    hipLaunchKernelGGL((gemm_bf16_k<MT, NB, WAVES>), dim3(groups * ksplit * m_chunks), dim3(WAVES * 64), lds, st,
-                       (const bf16x8*)xp, (const bf16x8*)wp, out, N, K / 16, groups, m_chunks, ksplit, part_stride,
-                       n_tiles);
+// one candidate (score, token) per (feature group, row) -> the row's token; lowest id wins ties
+__global__ void argmax_final_k(const float* cand_val, const int32_t* cand_idx, int n_groups, size_t cand_stride,
+                               int32_t* tok_out, const int32_t* n_tiles) {
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    const int r = blockIdx.x;
+    if ((r >> 5) >= *n_tiles) return;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int gq = threadIdx.x; gq < n_groups; gq += blockDim.x) {
+        float ov = cand_val[(size_t)gq * cand_stride + r];
+        int oi = cand_idx[(size_t)gq * cand_stride + r];
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    sv[threadIdx.x] = bv; si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = blockDim.x >> 1; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            float ov = sv[threadIdx.x + o]; int oi = si[threadIdx.x + o];
+            if (ov > sv[threadIdx.x] || (ov == sv[threadIdx.x] && oi < si[threadIdx.x])) {
+                sv[threadIdx.x] = ov; si[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) tok_out[r] = (si[0] == 0x7fffffff) ? 0 : si[0];
 }
 
-void launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
-                      GemmPlan plan, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
-#define RDLM_CASE(MT_, NB_, W_)                                                                        \
-    if (plan.mt == MT_ && plan.nb == NB_ && plan.waves == W_) {                                        \
-        launch_cfg<MT_, NB_, W_>(xp, wp, out, N, K, part_stride, plan.ksplit, n_tiles, max_tiles, st); \
-        return;                                                                                        \
+void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_groups, size_t cand_stride,
+                         int32_t* tok_out, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_final_k, dim3(max_tiles * 32), dim3(256), 0, st, cand_val, cand_idx, n_groups,
+                       cand_stride, tok_out, n_tiles);
+}
+
+template <int MT, int NB, int WAVES, int U, int EPI>
+static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride, int ksplit,
+                       const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    const int nblk = N / 32;
+    const int groups = (EPI == EPI_SWIGLU) ? nblk / 2 : (nblk + NB - 1) / NB;
+    const int m_chunks = (max_tiles + MT - 1) / MT;
+    const size_t lds = WAVES > 1 ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
+    auto kern = gemm_bf16_k<MT, NB, WAVES, U, EPI>;
+    if (lds > 64 * 1024) {
+        static bool raised = false, ok = false;
+        if (!raised) {
+            raised = true;
+            ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds) == hipSuccess;
+            if (!ok) (void)hipGetLastError();
+        }
+        if (!ok) return false;
     }
-    RDLM_CASE(1, 1, 4) RDLM_CASE(1, 2, 4) RDLM_CASE(1, 4, 4) RDLM_CASE(1, 1, 8) RDLM_CASE(1, 2, 8)
-    RDLM_CASE(2, 1, 4) RDLM_CASE(2, 2, 4) RDLM_CASE(4, 1, 4) RDLM_CASE(4, 2, 4)
-    RDLM_CASE(1, 2, 2) RDLM_CASE(1, 4, 2) RDLM_CASE(1, 2, 1) RDLM_CASE(1, 4, 1)
+    GemmArgs a;
+    a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
+    a.m_chunks = m_chunks; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
+    hipLaunchKernelGGL(kern, dim3(groups * ksplit * m_chunks), dim3(WAVES * 64), lds, st, a);
+    return true;
+}
+
+int gemm_groups(int N, const GemmPlan& plan, int epi_kind) {
+    const int nblk = N / 32;
+    return epi_kind == EPI_SWIGLU ? nblk / 2 : (nblk + plan.nb - 1) / plan.nb;
+}
+
+bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
+                      GemmPlan plan, const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+#define RDLM_CASE(MT_, NB_, W_, U_)                                                                              \
+    if (plan.mt == MT_ && plan.nb == NB_ && plan.waves == W_ && plan.unroll == U_) {                             \
+        if (epi.kind == EPI_F32)                                                                                 \
+            return launch_cfg<MT_, NB_, W_, U_, EPI_F32>(xp, wp, out, N, K, part_stride, plan.ksplit, epi,       \
+                                                         n_tiles, max_tiles, st);                                \
+        if (epi.kind == EPI_ARGMAX)                                                                              \
+            return launch_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
+                                                            max_tiles, st);                                      \
+        if (epi.kind == EPI_SWIGLU && NB_ == 2)                                                                  \
+            return launch_cfg<MT_, 2, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,       \
+                                                          max_tiles, st);                                        \
+        return false;                                                                                            \
+    }
+    RDLM_CASE(1, 1, 4, 4) RDLM_CASE(1, 1, 4, 8) RDLM_CASE(1, 1, 8, 4) RDLM_CASE(1, 1, 8, 8) RDLM_CASE(1, 1, 2, 8)
+    RDLM_CASE(1, 2, 4, 2) RDLM_CASE(1, 2, 4, 4) RDLM_CASE(1, 2, 4, 8) RDLM_CASE(1, 2, 8, 4) RDLM_CASE(1, 2, 2, 4)
+    RDLM_CASE(1, 2, 2, 8) RDLM_CASE(1, 2, 8, 2)
+    RDLM_CASE(1, 4, 4, 2) RDLM_CASE(1, 4, 4, 4) RDLM_CASE(1, 4, 2, 4) RDLM_CASE(1, 4, 2, 2) RDLM_CASE(1, 4, 8, 2)
+    RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8)
+    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2)
 #undef RDLM_CASE
-    launch_cfg<1, 1, 4>(xp, wp, out, N, K, part_stride, plan.ksplit, n_tiles, max_tiles, st);
+    return false;
 }
 
 // canonical bf16 [N][K] -> MFMA-ordered tiles [N/32][K/16][64 lanes][8]

@@ -35,6 +35,7 @@ struct rdlm_ctx {
     float* gf = nullptr;
     float* gout = nullptr;
     float* theta = nullptr;
+    float* rope_tab = nullptr;      // [rows_pad][d/2] (cos, sin) of the current step's rows
     // workspace
     TileDesc* tiles = nullptr;
     int32_t* n_tiles = nullptr;
@@ -59,7 +60,8 @@ struct rdlm_ctx {
     int last_hip = 0;
     size_t bytes = 0;
     std::vector<void*> allocs;
-    GemmPlan forced_plan = {0, 0, 0, 0};
+    float* cand_val = nullptr;
+    int32_t* cand_idx = nullptr;
     int forced_att_split = 0;
     // per-launch GEMM timing
     int prof_n = 0, prof_k = 0, prof_used = 0;
@@ -125,6 +127,7 @@ extern "C" size_t rdlm_device_bytes(const rdlm_ctx* ctx) { return ctx ? ctx->byt
 
 static bool model_ok(const rdlm_model* m) {
     if (!m) return false;
+    if (m->hidden > 8192) return false;                 // row kernels keep a row in registers
     if (m->vocab <= 0 || m->hidden <= 0 || m->n_heads <= 0 || m->head_dim <= 0 || m->mlp <= 0) return false;
     if (m->n_prelude < 0 || m->n_core < 1 || m->n_coda < 0) return false;
     if ((long long)m->n_heads * m->head_dim != m->hidden) return false;
@@ -235,6 +238,9 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->q, R * h * esz, true);
     DALLOC(ctx->att, R * h * esz, true);
     DALLOC(ctx->drafts, R * 4, true);
+    DALLOC(ctx->rope_tab, R * (m.head_dim / 2) * 8, true);
+    DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
+    DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
     if (m.dtype == RDLM_BF16)
         DALLOC(ctx->att_ws, attention_ws_floats(ctx->max_tiles, m.n_heads, m.head_dim, ctx->att_max_split) * 4, false);
     // sampler state
@@ -271,10 +277,6 @@ extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, 
     ctx->st = reinterpret_cast<hipStream_t>(hip_stream);
     ctx->fmt = m->dtype == RDLM_F32 ? ACT_F32 : ACT_BF16P;
     ctx->esz = m->dtype == RDLM_F32 ? 4 : 2;
-    if (const char* p = getenv("RDLM_GEMM_PLAN")) {       // tuning aid: "mt,nb,waves,ksplit"
-        GemmPlan g = {0, 0, 0, 0};
-        if (sscanf(p, "%d,%d,%d,%d", &g.mt, &g.nb, &g.waves, &g.ksplit) == 4) ctx->forced_plan = g;
-    }
     if (const char* p = getenv("RDLM_ATT_SPLIT")) ctx->forced_att_split = atoi(p);
     int rc = create_impl(ctx, weight_ptrs);
     if (rc != RDLM_OK) {
@@ -291,49 +293,111 @@ extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, 
 // ---------------------------------------------------------------------------------------------
 // GEMM dispatch
 
-static GemmPlan plan_for(const rdlm_ctx* ctx, int N, int K, int T, bool allow_split) {
-    if (ctx->forced_plan.mt) {
-        GemmPlan g = ctx->forced_plan;
-        if (!allow_split) g.ksplit = 1;
-        return g;
-    }
+enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT };
+static const char* kProjEnv[PROJ_COUNT] = {"RDLM_PLAN_QKV", "RDLM_PLAN_O", "RDLM_PLAN_GU",
+                                           "RDLM_PLAN_D", "RDLM_PLAN_A", "RDLM_PLAN_HEAD"};
+
+// Launch shape of a projection for T row tiles: {row tiles per workgroup, feature blocks per
+// workgroup, waves, k tiles fetched per batch, split of K across workgroups}.  The defaults come
+// from sweeps on MI355X at the 3.5B shape; RDLM_PLAN_<proj>="nb,waves,unroll,ksplit" overrides the
+// one-tile case (tuning aid).
+static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     GemmPlan g;
-    g.waves = 4;
-    g.mt = T >= 4 ? 4 : (T >= 2 ? 2 : 1);
-    const int nblk = N / 32, mch = (T + g.mt - 1) / g.mt;
-    const int target = 512;
-    g.nb = 1;
-    if (g.mt <= 2) {
-        for (int nb : {4, 2}) {
-            if (g.mt * nb > 4) continue;
-            if (((nblk + nb - 1) / nb) * mch >= target) { g.nb = nb; break; }
+    const bool split_ok = proj == PROJ_O || proj == PROJ_D || proj == PROJ_A;
+    if (T == 1) {
+        switch (proj) {
+            case PROJ_GU: g = {1, 2, 8, 2, 1}; break;
+            case PROJ_HEAD: g = {1, 4, 4, 2, 1}; break;
+            case PROJ_QKV: g = {1, 2, 2, 4, 1}; break;
+            case PROJ_D: g = {1, 4, 2, 2, 4}; break;
+            default: g = {1, 2, 2, 4, 8}; break;       // O, A
         }
+        if (const char* p = getenv(kProjEnv[proj])) {
+            GemmPlan o = {1, 0, 0, 0, 0};
+            if (sscanf(p, "%d,%d,%d,%d", &o.nb, &o.waves, &o.unroll, &o.ksplit) == 4) g = o;
+        }
+    } else if (T <= 3) {
+        g = {2, proj == PROJ_GU ? 2 : 1, 4, proj == PROJ_GU ? 2 : 4, 4};
+    } else {
+        g = {4, proj == PROJ_GU ? 2 : 1, 4, 2, 4};
     }
-    g.ksplit = 1;
-    if (allow_split) {
-        int wgs = ((nblk + g.nb - 1) / g.nb) * mch;
-        int ks = (target + wgs - 1) / wgs;
-        int kmax = std::max(1, (K / 16) / (g.waves * 8));      // at least 8 k tiles per wave
-        g.ksplit = std::max(1, std::min(std::min(ks, 8), kmax));
+    if (proj == PROJ_GU) g.nb = 2;
+    if (!split_ok) g.ksplit = 1;
+    if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
+        int kmax = std::max(1, (K / 16) / (g.waves * 4));
+        g.ksplit = std::max(1, std::min(std::min(g.ksplit, 8), kmax));
     }
     return g;
 }
 
-// out: f32 [S][rows_pad][N]; returns S through *S_out
-static void gemm(rdlm_ctx* ctx, const void* xin, const void* W, float* out, int N, int K, int T, bool allow_split,
-                 int* S_out) {
-    if (ctx->m.dtype == RDLM_F32) {
+struct SampleArgs {
+    float temperature;
+    uint32_t k0, k1;
+    int step;
+    bool want_logits;
+};
+
+// One projection of the model path.  Output by projection:
+//   QKV -> ctx->qkv (f32), O / D / A -> ctx->part ([S] partial sums, *S_out = S),
+//   GU -> ctx->abuf (SwiGLU applied; bf16 path fuses it into the GEMM), HEAD -> ctx->drafts
+//   (sampled tokens; logits in ctx->logits when asked for, always on the f32 path).
+static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int T, int* S_out,
+                    const SampleArgs* sa = nullptr, bool plain = false) {
+    const rdlm_model& m = ctx->m;
+    const int h = m.hidden, F = m.mlp;
+    int N, K;
+    float* out;
+    switch (proj) {
+        case PROJ_QKV: N = 3 * h; K = h; out = ctx->qkv; break;
+        case PROJ_O: N = h; K = h; out = ctx->part; break;
+        case PROJ_GU: N = 2 * F; K = h; out = ctx->gu; break;
+        case PROJ_D: N = h; K = F; out = ctx->part; break;
+        case PROJ_A: N = h; K = 2 * h; out = ctx->part; break;
+        default: N = m.vocab; K = h; out = ctx->logits; break;
+    }
+    if (S_out) *S_out = 1;
+    if (m.dtype == RDLM_F32) {
         launch_gemm_f32(reinterpret_cast<const float*>(xin), reinterpret_cast<const float*>(W), out, N, K,
                         ctx->n_tiles, T, ctx->st);
-        if (S_out) *S_out = 1;
-        return;
+        if (plain) return RDLM_OK;
+        if (proj == PROJ_GU) launch_swiglu(ctx->gu, 1, 0, ctx->abuf, ctx->fmt, F, ctx->n_tiles, T, ctx->st);
+        if (proj == PROJ_HEAD && sa)
+            launch_sample(ctx->logits, m.vocab, sa->temperature, sa->k0, sa->k1, sa->step, ctx->drafts, ctx->tiles,
+                          ctx->n_tiles, T, ctx->st);
+        return RDLM_OK;
     }
-    GemmPlan g = plan_for(ctx, N, K, T, allow_split);
+    GemmPlan g = plan_for(ctx, proj, N, K, T);
+    GemmEpilogue epi;
+    if (!plain && proj == PROJ_GU) {
+        epi.kind = EPI_SWIGLU;
+        epi.act = ctx->abuf;
+    } else if (!plain && proj == PROJ_HEAD && sa) {
+        epi.kind = EPI_ARGMAX;
+        epi.cand_val = ctx->cand_val; epi.cand_idx = ctx->cand_idx; epi.cand_stride = ctx->rows_pad;
+        epi.temperature = sa->temperature; epi.k0 = sa->k0; epi.k1 = sa->k1; epi.step = sa->step;
+        epi.tiles = ctx->tiles;
+        if (!sa->want_logits) out = nullptr;
+    }
     const bool prof = ctx->prof_n == N && ctx->prof_k == K && (size_t)ctx->prof_used + 2 <= ctx->prof_ev.size();
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
-    launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, ctx->n_tiles, T, ctx->st);
+    bool ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
+    if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
+        g = {g.mt, epi.kind == EPI_SWIGLU ? 2 : 1, 4, 4, g.ksplit};
+        if (g.mt == 4) g.unroll = 2;
+        if (g.mt == 2 && g.nb == 2) g.unroll = 2;
+        ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
+        if (!ok) {
+            fprintf(stderr, "rdlm: no GEMM kernel instance for plan {%d,%d,%d,%d} epilogue %d\n", g.mt, g.nb, g.waves,
+                    g.unroll, epi.kind);
+            return RDLM_EINVAL;
+        }
+    }
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
+    if (epi.kind == EPI_ARGMAX)
+        launch_argmax_final(ctx->cand_val, ctx->cand_idx, gemm_groups(N, g, EPI_ARGMAX), ctx->rows_pad, ctx->drafts,
+                            ctx->n_tiles, T, ctx->st);
     if (S_out) *S_out = g.ksplit;
+    return RDLM_OK;
 }
 
 static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
@@ -350,22 +414,21 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
 // x (+ the S_in partial sums in part, if any); on exit it is x + the *S_out partials in part.
 static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out) {
     const rdlm_model& m = ctx->m;
-    const int h = m.hidden, F = m.mlp;
+    const int h = m.hidden;
     const size_t pst = (size_t)ctx->rows_pad * h;
     hipStream_t st = ctx->st;
     int S;
     launch_addnorm(x_valid ? ctx->x : nullptr, ctx->x, ctx->part, S_in, pst, L.g1, ctx->xn, ctx->fmt, h, m.rms_eps,
                    ctx->n_tiles, T, st);
-    gemm(ctx, ctx->xn, L.wqkv, ctx->qkv, 3 * h, h, T, false, &S);
-    launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->theta,
+    run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S);
+    launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                    (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
                      att_split_for(ctx, T, max_keys), ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
-    gemm(ctx, ctx->att, L.wo, ctx->part, h, h, T, true, &S);
+    run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S);
     launch_addnorm(ctx->x, ctx->x, ctx->part, S, pst, L.g2, ctx->xn, ctx->fmt, h, m.rms_eps, ctx->n_tiles, T, st);
-    gemm(ctx, ctx->xn, L.wgu, ctx->gu, 2 * F, h, T, false, &S);
-    launch_swiglu(ctx->gu, 1, 0, ctx->abuf, ctx->fmt, F, ctx->n_tiles, T, st);
-    gemm(ctx, ctx->abuf, L.wd, ctx->part, h, F, T, true, S_out);
+    run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S);               // leaves silu(gate) * up in abuf
+    run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out);
 }
 
 // e = P(tokens): embedding gather (scaled) and the prelude layers; result in e_out rows (erow0).
@@ -393,7 +456,7 @@ static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev,
     const int h = m.hidden;
     launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S;
-    gemm(ctx, ctx->abuf, ctx->wa, ctx->part, h, 2 * h, T, true, &S);
+    run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S);
     bool x_valid = false;
     for (int l = 0; l < m.n_core; ++l) {
         layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S);
@@ -403,18 +466,18 @@ static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev,
                       delta, ctx->tiles, ctx->n_tiles, T, ctx->st);
 }
 
-// C: coda layers on z; with_head: final norm, tied LM head -> logits.
-static void coda_forward(rdlm_ctx* ctx, const float* z, bool with_head, int T, int max_keys) {
+// C: coda layers on z; with sa: final norm, tied LM head and Sample -> ctx->drafts (+ logits).
+static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int T, int max_keys) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
     launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
     for (int l = 0; l < m.n_coda; ++l)
         layer_forward(ctx, ctx->layers[m.n_prelude + m.n_core + l], T, max_keys, true, S, &S);
-    if (!with_head) return;
+    if (!sa) return;
     launch_addnorm(ctx->x, nullptr, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gout, ctx->xn, ctx->fmt, h,
                    m.rms_eps, ctx->n_tiles, T, ctx->st);
-    gemm(ctx, ctx->xn, ctx->emb_w, ctx->logits, m.vocab, h, T, false, nullptr);
+    run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -466,11 +529,12 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
                            (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
     prelude_forward(ctx, ctx->y, ctx->e, -1, T, n);
     for (int i = 0; i < r; ++i) core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n);
-    coda_forward(ctx, ctx->z_store, false, T, n);
+    coda_forward(ctx, ctx->z_store, nullptr, T, n);
     return check_launch(ctx);
 }
 
@@ -490,6 +554,7 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     prelude_forward(ctx, tokens_dev, e_out, 1, T, mk);
     return check_launch(ctx);
 }
@@ -503,6 +568,7 @@ extern "C" int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (delta_out)
         HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
     for (int i = 0; i < r_inner; ++i) {
@@ -523,9 +589,9 @@ extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* se
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
-    coda_forward(ctx, z, true, T, mk);
-    launch_sample(ctx->logits, ctx->m.vocab, temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, ctx->drafts,
-                  ctx->tiles, ctx->n_tiles, T, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr};
+    coda_forward(ctx, z, &sa, T, mk);
     launch_copy_i32_out(ctx->drafts, tokens_out, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (logits_out) launch_copy_rows_out(ctx->logits, logits_out, ctx->m.vocab, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     return check_launch(ctx);
@@ -591,15 +657,15 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     for (int q = 0; q < n; ++q)
         max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
     launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys);                       // e <- P(y_current)
     for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
         bool last = i == s.r_inner - 1;
         core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
                      last ? ctx->delta : nullptr, T, max_keys);
     }
-    coda_forward(ctx, ctx->z_store, true, T, max_keys);                          // p <- C(z)
-    launch_sample(ctx->logits, m.vocab, s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, ctx->drafts, ctx->tiles,
-                  ctx->n_tiles, T, ctx->st);                                     // y_hat <- Sample(p)
+    SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false};
+    coda_forward(ctx, ctx->z_store, &sa, T, max_keys);                           // p <- C(z); y_hat <- Sample(p)
     launch_bookkeep(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
                     ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);        // freeze, append
     launch_init_state_new(ctx->z_store, ctx->z_prev, m.hidden, ctx->seqs, n, ctx->max_positions, s.headway, s.alpha,
@@ -708,31 +774,23 @@ extern "C" int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t p
 // ---------------------------------------------------------------------------------------------
 // kernel-level entry points
 
-static int weight_by_index(const rdlm_ctx* ctx, int idx, const void** W, int* N, int* K, bool* split) {
+static int weight_by_index(const rdlm_ctx* ctx, int idx, const void** W, int* proj, int* N, int* K) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden, F = m.mlp;
     const int nl = m.n_prelude + m.n_core + m.n_coda;
-    if (idx == 0) { *W = ctx->emb_w; *N = m.vocab; *K = h; *split = false; return RDLM_OK; }
+    if (idx == 0) { *W = ctx->emb_w; *proj = PROJ_HEAD; *N = m.vocab; *K = h; return RDLM_OK; }
     if (idx >= 1 && idx < 1 + 7 * nl) {
         const Layer& L = ctx->layers[(idx - 1) / 7];
         switch ((idx - 1) % 7) {
-            case 1: *W = L.wqkv; *N = 3 * h; *K = h; *split = false; return RDLM_OK;
-            case 2: *W = L.wo; *N = h; *K = h; *split = true; return RDLM_OK;
-            case 4: *W = L.wgu; *N = 2 * F; *K = h; *split = false; return RDLM_OK;
-            case 6: *W = L.wd; *N = h; *K = F; *split = true; return RDLM_OK;
+            case 1: *W = L.wqkv; *proj = PROJ_QKV; *N = 3 * h; *K = h; return RDLM_OK;
+            case 2: *W = L.wo; *proj = PROJ_O; *N = h; *K = h; return RDLM_OK;
+            case 4: *W = L.wgu; *proj = PROJ_GU; *N = 2 * F; *K = h; return RDLM_OK;
+            case 6: *W = L.wd; *proj = PROJ_D; *N = h; *K = F; return RDLM_OK;
             default: return RDLM_EINVAL;
         }
     }
-    if (idx == 1 + 7 * nl) { *W = ctx->wa; *N = h; *K = 2 * h; *split = true; return RDLM_OK; }
+    if (idx == 1 + 7 * nl) { *W = ctx->wa; *proj = PROJ_A; *N = h; *K = 2 * h; return RDLM_OK; }
     return RDLM_EINVAL;
-}
-
-static float* out_buffer_for(rdlm_ctx* ctx, int N) {
-    const rdlm_model& m = ctx->m;
-    if (N == m.vocab && N != m.hidden) return ctx->logits;
-    if (N == 2 * m.mlp) return ctx->gu;
-    if (N == 3 * m.hidden) return ctx->qkv;
-    return ctx->part;
 }
 
 static int linear_setup(rdlm_ctx* ctx, int m_rows, int* T) {
@@ -745,29 +803,26 @@ static int linear_setup(rdlm_ctx* ctx, int m_rows, int* T) {
     return RDLM_OK;
 }
 
+// input operand buffer of a projection with K input features (the one the model path uses)
+static void* proj_input(rdlm_ctx* ctx, int K) { return K == ctx->m.hidden ? ctx->xn : ctx->abuf; }
+
 extern "C" int rdlm_linear(rdlm_ctx* ctx, int32_t w_index, const float* x, int32_t m_rows, float* y) {
     if (!ctx || !x || !y) return RDLM_EINVAL;
-    const void* W; int N, K, T; bool split;
-    int rc = weight_by_index(ctx, w_index, &W, &N, &K, &split);
+    const void* W; int proj, N, K, T;
+    int rc = weight_by_index(ctx, w_index, &W, &proj, &N, &K);
     if (rc) return rc;
     if ((rc = linear_setup(ctx, m_rows, &T))) return rc;
-    const void* xin;
-    if (ctx->m.dtype == RDLM_F32) {
-        // stage x with zero padding rows in the (idle) latent scratch, output never aliases it
-        float* stage = ctx->zp_api;
-        if (K > ctx->m.hidden) stage = ctx->gu == out_buffer_for(ctx, N) ? ctx->qkv : ctx->gu;
-        HIPCHK(hipMemsetAsync(stage, 0, (size_t)T * 32 * K * 4, ctx->st));
-        HIPCHK(hipMemcpyAsync(stage, x, (size_t)m_rows * K * 4, hipMemcpyDeviceToDevice, ctx->st));
-        xin = stage;
+    void* xin = proj_input(ctx, K);
+    if (ctx->m.dtype == RDLM_F32) {       // rows beyond m_rows of the last tile are zero
+        HIPCHK(hipMemsetAsync(xin, 0, (size_t)T * 32 * K * 4, ctx->st));
+        HIPCHK(hipMemcpyAsync(xin, x, (size_t)m_rows * K * 4, hipMemcpyDeviceToDevice, ctx->st));
     } else {
-        launch_pack_rows(x, ctx->abuf, m_rows, K, ctx->st);
-        xin = ctx->abuf;
+        launch_pack_rows(x, xin, m_rows, K, ctx->st);
     }
-    float* out = out_buffer_for(ctx, N);
     int S;
-    gemm(ctx, xin, W, out, N, K, T, split, &S);
-    const float* res = out;
-    if (out == ctx->part) {     // fold split-K partials exactly as the model path's consumer does
+    if ((rc = run_proj(ctx, proj, xin, W, T, &S, nullptr, true))) return rc;
+    const float* res = proj == PROJ_QKV ? ctx->qkv : proj == PROJ_GU ? ctx->gu : proj == PROJ_HEAD ? ctx->logits : nullptr;
+    if (!res) {     // fold split-K partials exactly as the model path's consumer does
         launch_addnorm(nullptr, ctx->x, ctx->part, S, (size_t)ctx->rows_pad * N, ctx->gf, nullptr, ctx->fmt, N,
                        ctx->m.rms_eps, ctx->n_tiles, T, ctx->st);
         res = ctx->x;
@@ -778,24 +833,26 @@ extern "C" int rdlm_linear(rdlm_ctx* ctx, int32_t w_index, const float* x, int32
 
 extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, int32_t iters, float* ms_out) {
     if (!ctx || !ms_out || iters < 1) return RDLM_EINVAL;
-    const void* W; int N, K, T; bool split;
-    int rc = weight_by_index(ctx, w_index, &W, &N, &K, &split);
+    const void* W; int proj, N, K, T;
+    int rc = weight_by_index(ctx, w_index, &W, &proj, &N, &K);
     if (rc) return rc;
     if ((rc = linear_setup(ctx, m_rows, &T))) return rc;
     // Gaussian rows as input (values do not affect timing; keeps everything finite)
-    float* stage = ctx->gu == out_buffer_for(ctx, N) ? ctx->qkv : ctx->gu;
-    if ((size_t)K > (size_t)3 * ctx->m.hidden && stage == ctx->qkv) return RDLM_EINVAL;
+    void* xin = proj_input(ctx, K);
+    float* stage = (size_t)K <= (size_t)3 * ctx->m.hidden ? ctx->qkv : ctx->gu;   // both idle here
+    if (stage == ctx->gu && (proj == PROJ_GU || K > 2 * ctx->m.mlp)) return RDLM_EINVAL;
     launch_init_state_rows(stage, nullptr, K, 0, 0, T * 32, 0, 1.0f, 1u, 0u, ctx->st);
-    const void* xin = stage;
-    if (ctx->m.dtype == RDLM_BF16) { launch_pack_rows(stage, ctx->abuf, T * 32, K, ctx->st); xin = ctx->abuf; }
-    float* out = out_buffer_for(ctx, N);
+    if (ctx->m.dtype == RDLM_BF16) launch_pack_rows(stage, xin, T * 32, K, ctx->st);
+    else HIPCHK(hipMemcpyAsync(xin, stage, (size_t)T * 32 * K * 4, hipMemcpyDeviceToDevice, ctx->st));
+    SampleArgs sa = {0.f, 1u, 0u, 1, false};
     hipEvent_t a, b;
     HIPCHK(hipEventCreate(&a));
     HIPCHK(hipEventCreate(&b));
     int S;
-    for (int i = 0; i < 3; ++i) gemm(ctx, xin, W, out, N, K, T, split, &S);
+    for (int i = 0; i < 3; ++i)
+        if ((rc = run_proj(ctx, proj, xin, W, T, &S, &sa))) return rc;
     HIPCHK(hipEventRecord(a, ctx->st));
-    for (int i = 0; i < iters; ++i) gemm(ctx, xin, W, out, N, K, T, split, &S);
+    for (int i = 0; i < iters; ++i) run_proj(ctx, proj, xin, W, T, &S, &sa);
     HIPCHK(hipEventRecord(b, ctx->st));
     HIPCHK(hipEventSynchronize(b));
     float ms = 0.f;
@@ -841,6 +898,7 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, pos0, n, zrow0, 1.0f, 7u, 0u, ctx->st);
     launch_init_state_rows(ctx->e, nullptr, ctx->m.hidden, seq, pos0, T * 32, 0, 1.0f, 9u, 0u, ctx->st);

@@ -106,7 +106,21 @@ __host__ __device__ inline float u24_open(uint32_t x) {
 // ---------------------------------------------------------------------------------------------
 // Launchers (defined in the kernel sources).  All enqueue on `st`; none synchronises.
 
-struct GemmPlan { int mt, nb, waves, ksplit; };
+struct GemmPlan { int mt, nb, waves, unroll, ksplit; };
+
+// What the GEMM does with a finished output tile.
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
+struct GemmEpilogue {
+    int kind = EPI_F32;
+    void* act = nullptr;              // EPI_SWIGLU: packed bf16 activation [rows][F]
+    float* cand_val = nullptr;        // EPI_ARGMAX: best score / token per (feature group, row)
+    int32_t* cand_idx = nullptr;
+    size_t cand_stride = 0;           // rows per group in the candidate arrays
+    float temperature = 0.f;          // > 0: Gumbel-max on logits / temperature
+    uint32_t k0 = 0, k1 = 0;
+    int step = 0;
+    const TileDesc* tiles = nullptr;
+};
 
 // elementwise / row kernels ------------------------------------------------------------------
 void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
@@ -132,8 +146,11 @@ void launch_final_norm(const float* xin, const float* part, int S, size_t part_s
                        const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
                        float* delta, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
                        hipStream_t st);
+// table: [rows][d/2] (cos, sin) pairs written by launch_rope_table for the current tiles
+void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles,
+                       const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc,
-                    int dtype, int H, int d, const float* theta, size_t seq_stride_elems,
+                    int dtype, int H, int d, const float* table, size_t seq_stride_elems,
                     const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
                    const int32_t* n_tiles, int max_tiles, hipStream_t st);
@@ -154,9 +171,14 @@ void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int
                     float* k_out, float* v_out, hipStream_t st);
 
 // GEMMs ---------------------------------------------------------------------------------------
-// bf16: x packed [tiles][K/16][512], w packed [N/32][K/16][512], out f32 [ksplit][rows_total][N]
-void launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
-                      GemmPlan plan, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+// bf16: x packed [tiles][K/16][512], w packed [N/32][K/16][512]; EPI_F32 writes f32
+// [ksplit][rows_total][N].  Returns false if no kernel instance exists for (plan, epilogue).
+bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
+                      GemmPlan plan, const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles,
+                      hipStream_t st);
+int gemm_groups(int N, const GemmPlan& plan, int epi_kind);
+void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_groups, size_t cand_stride,
+                         int32_t* tok_out, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 // f32: x [rows][K], w [N][K], out [rows][N]
 void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
