@@ -199,6 +199,31 @@ __global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, 
     }
 }
 
+// Residual add + split-K fold with the RMS factor left to the consumer: a row is cut into
+// `chunks` pieces handled by different workgroups; each writes x_out, bf16(x_out * gain) in the
+// packed operand layout and its piece of the row's sum of squares.
+__global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, const float* part, int S,
+                                               size_t part_stride, const float* gain, void* xg, float* ssq, int h,
+                                               int chunks, const int32_t* n_tiles) {
+    __shared__ float sh[8];
+    const int r = blockIdx.y, c = blockIdx.x;
+    if ((r >> 5) >= *n_tiles) return;
+    const int cw = h / chunks;
+    const int k = c * cw + threadIdx.x * 4;
+    float ss = 0.f;
+    if ((int)threadIdx.x * 4 < cw) {
+        float4 v = row_value(xin, part, S, part_stride, (size_t)r * h + k);
+        ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        if (xout) *reinterpret_cast<float4*>(xout + (size_t)r * h + k) = v;
+        if (xg) {
+            float4 g = ld4(gain + k);
+            act_store4<ACT_BF16P>(xg, h, r, k, v.x * g.x, v.y * g.y, v.z * g.z, v.w * g.w);
+        }
+    }
+    ss = block_sum(ss, sh);
+    if (threadIdx.x == 0 && ssq) ssq[(size_t)r * SSQ_MAX_CHUNKS + c] = ss;
+}
+
 // End of a recurrence: z' = RMSNorm(x + sum part) * gain, stored to the latent array; optionally
 // delta = ||z' - z_prev|| / ||z'|| (Eq. 3) and z_prev <- z'.
 __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
@@ -557,6 +582,19 @@ void launch_addnorm(const float* xin, float* xout, const float* part, int S, siz
     else
         hipLaunchKernelGGL(addnorm_k<ACT_BF16P>, dim3(max_tiles * 32), dim3(256), 0, st, xin, xout, part, S,
                            part_stride, gain, xn, h, eps, n_tiles);
+}
+int fold_chunks(int h) {
+    for (int c : {8, 4, 2})
+        if (h % (4 * c) == 0 && h / c <= 1024 * 1 && h / c >= 64) return c;
+    for (int c : {8, 4, 2})
+        if (h % (4 * c) == 0 && h / c <= 1024) return c;
+    return h <= 1024 ? 1 : 0;
+}
+void launch_fold(const float* xin, float* xout, const float* part, int S, size_t part_stride, const float* gain,
+                 void* xg, float* ssq, int h, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    const int c = fold_chunks(h);
+    hipLaunchKernelGGL(fold_k, dim3(c, max_tiles * 32), dim3(256), 0, st, xin, xout, part, S, part_stride, gain, xg,
+                       ssq, h, c, n_tiles);
 }
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
                        int h, float eps, float* z, float* z_prev, int update_prev, float* delta,

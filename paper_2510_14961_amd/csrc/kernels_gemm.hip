@@ -58,14 +58,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    // feature blocks of this workgroup: consecutive ones, except for the SwiGLU epilogue, which
-    // pairs gate block `grp` with up block `grp + nblk/2`
+    // feature blocks of this workgroup: NB consecutive ones (the gate/up matrix is stored with gate
+    // block j and up block j adjacent, so the SwiGLU epilogue finds its pair in blocks 2j, 2j+1)
     int blk[NB];
     const bf16x8* wbase[NB];
     const bf16x8* xbase[MT];
 #pragma unroll
     for (int a = 0; a < NB; ++a) {
-        blk[a] = (EPI == EPI_SWIGLU) ? grp + a * (nblk >> 1) : grp * NB + a;
+        blk[a] = grp * NB + a;
         int nb = min(blk[a], nblk - 1);             // a ragged last group re-reads a valid block
         wbase[a] = A.wp + ((size_t)nb * K16) * 64 + lane;
     }
@@ -139,6 +139,92 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
         __syncthreads();
     }
     const int col = lane & 31, g = lane >> 5;
+    if constexpr (EPI == EPI_ROPE_KV) {
+        // The workgroup holds one whole head (NB*32 = head_dim features) of q, k or v for MT row
+        // tiles.  RoPE pairs feature u with u +- d/2: that is the same lane, register quad q +- (d/2 % 32)/8
+        // of another (or the same) block, so a wave that finishes the quads of one parity has both
+        // members of every pair.  Waves 0 and 1 share the epilogue (quads of even / odd q).
+        constexpr int D = NB * 32, HALF = D / 2;
+        constexpr int OWNERS = WAVES >= 2 ? 2 : 1;
+        constexpr int NQ = 4 / OWNERS;
+        if (wave < OWNERS) {
+            const int H = A.epi.n_heads, h = H * D;
+            const int section = grp / H, head = grp - section * H;      // 0 = q, 1 = k, 2 = v
+            const float2* table = reinterpret_cast<const float2*>(A.epi.rope_table);
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+                const int t = t0 + b;
+                if (t >= n_tiles) continue;
+                const TileDesc td = A.epi.tiles[t];
+                const size_t row = (size_t)t * 32 + col;
+                const int pos = td.pos0 + col;
+                const bool valid = col < td.n_valid;
+                float sc = 1.0f;
+                if (A.epi.row_ssq) {
+                    float ssq = 0.f;
+                    for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
+                    sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+                }
+                float val[NB][NQ][4];
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+#pragma unroll
+                    for (int qq = 0; qq < NQ; ++qq)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int q = OWNERS == 2 ? wave + 2 * qq : qq;
+                            const int r = (a * MT + b) * 16 + q * 4 + i;
+                            float sum = 0.f;
+                            if (WAVES > 1) {
+#pragma unroll
+                                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
+                            } else {
+                                sum = OWNERS == 1 ? acc[a][b][qq * 4 + i] : 0.f;
+                            }
+                            val[a][qq][i] = sum * sc;
+                        }
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+#pragma unroll
+                    for (int qq = 0; qq < NQ; ++qq) {
+                        const int q = OWNERS == 2 ? wave + 2 * qq : qq;
+                        const int u0 = 32 * a + 8 * q + 4 * g;            // first of 4 consecutive head dims
+                        if (section == 2) {
+                            if (valid) {
+                                uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td.seq * A.epi.seq_stride +
+                                               (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
+#pragma unroll
+                                for (int i = 0; i < 4; ++i) Vt[(size_t)i * 32] = f32_to_bf16(val[a][qq][i]);
+                            }
+                            continue;
+                        }
+                        // partner quad: (32a + 8q + HALF) mod D, same lane
+                        const int ub = 32 * a + 8 * q;                    // without the lane's 4g: compile-time per (a, q)
+                        const int pb = (ub + HALF) % D;
+                        const int pa = pb >> 5;
+                        const int pq = (pb & 31) >> 3;
+                        const int pqq = OWNERS == 2 ? pq >> 1 : pq;
+                        const bool first_half = ub < HALF;
+                        ushort4 pk;
+                        uint16_t* pkp = reinterpret_cast<uint16_t*>(&pk);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int ii = (u0 + i) % HALF;
+                            const float2 cs = table[row * HALF + ii];
+                            const float x = val[a][qq][i], p = val[pa][pqq][i];
+                            pkp[i] = f32_to_bf16(first_half ? x * cs.x - p * cs.y : x * cs.x + p * cs.y);
+                        }
+                        if (section == 0) {
+                            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0) = pk;
+                        } else if (valid) {
+                            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td.seq * A.epi.seq_stride +
+                                                        (size_t)pos * h + head * D + u0) = pk;
+                        }
+                    }
+            }
+        }
+        return;
+    }
     float best_v[MT];
     int best_i[MT];
 #pragma unroll
@@ -169,13 +255,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
             // accumulator register q*4+i of lane (col, g) is feature 8q + 4g + i of its block, row `col`
             const size_t row = (size_t)t * 32 + col;
             const int foff = q * 8 + g * 4;
+            if (A.epi.row_ssq) {                   // deferred RMSNorm factor of this output row
+                float ssq = 0.f;
+                for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
+                const float sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[a][i] *= sc;
+            }
             if (EPI == EPI_F32) {
                 float* o = A.out + (size_t)ks * A.part_stride;
 #pragma unroll
                 for (int a = 0; a < NB; ++a)
-                    if (blk[a] < nblk)
-                        *reinterpret_cast<float4*>(o + row * A.N + blk[a] * 32 + foff) =
+                    if (blk[a] < nblk) {
+                        // pair-interleaved weights (gate/up): block 2j is column block j, 2j+1 is nblk/2 + j
+                        const int cb = A.epi.pair_interleaved ? (blk[a] & 1) * (nblk >> 1) + (blk[a] >> 1) : blk[a];
+                        *reinterpret_cast<float4*>(o + row * A.N + cb * 32 + foff) =
                             make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
+                    }
             } else if (EPI == EPI_SWIGLU) {
                 // blocks (0,1) = (gate, up) of the same 32 features: act = silu(gate) * up, stored as a
                 // packed bf16 activation of width F = N/2
@@ -317,23 +415,30 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
         if (epi.kind == EPI_ARGMAX)                                                                              \
             return launch_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
                                                             max_tiles, st);                                      \
-        if (epi.kind == EPI_SWIGLU && NB_ == 2)                                                                  \
-            return launch_cfg<MT_, 2, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,       \
-                                                          max_tiles, st);                                        \
+        if constexpr (NB_ == 2)                                                                                  \
+            if (epi.kind == EPI_SWIGLU)                                                                          \
+                return launch_cfg<MT_, NB_, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles, \
+                                                                max_tiles, st);                                  \
+        if constexpr (NB_ <= 3)                                                                                  \
+            if (epi.kind == EPI_ROPE_KV && NB_ * 32 == epi.head_dim)                                             \
+                return launch_cfg<MT_, NB_, W_, U_, EPI_ROPE_KV>(xp, wp, out, N, K, part_stride, 1, epi,         \
+                                                                 n_tiles, max_tiles, st);                        \
         return false;                                                                                            \
     }
     RDLM_CASE(1, 1, 4, 4) RDLM_CASE(1, 1, 4, 8) RDLM_CASE(1, 1, 8, 4) RDLM_CASE(1, 1, 8, 8) RDLM_CASE(1, 1, 2, 8)
     RDLM_CASE(1, 2, 4, 2) RDLM_CASE(1, 2, 4, 4) RDLM_CASE(1, 2, 4, 8) RDLM_CASE(1, 2, 8, 4) RDLM_CASE(1, 2, 2, 4)
     RDLM_CASE(1, 2, 2, 8) RDLM_CASE(1, 2, 8, 2)
+    RDLM_CASE(1, 3, 4, 2) RDLM_CASE(1, 3, 4, 4) RDLM_CASE(1, 3, 2, 4) RDLM_CASE(1, 3, 8, 2) RDLM_CASE(1, 3, 2, 8)
     RDLM_CASE(1, 4, 4, 2) RDLM_CASE(1, 4, 4, 4) RDLM_CASE(1, 4, 2, 4) RDLM_CASE(1, 4, 2, 2) RDLM_CASE(1, 4, 8, 2)
-    RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8)
-    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2)
+    RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8) RDLM_CASE(2, 3, 4, 2)
+    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2) RDLM_CASE(4, 3, 2, 2)
 #undef RDLM_CASE
     return false;
 }
 
-// canonical bf16 [N][K] -> MFMA-ordered tiles [N/32][K/16][64 lanes][8]
-__global__ void pack_weight_k(const uint16_t* w, uint16_t* wp, int N, int K) {
+// canonical bf16 [N][K] -> MFMA-ordered tiles [N/32][K/16][64 lanes][8]; source block nb lands at
+// packed block nb * blk_stride + blk_off (used to interleave the gate and up matrices)
+__global__ void pack_weight_k(const uint16_t* w, uint16_t* wp, int N, int K, int blk_stride, int blk_off) {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;       // one lane-vector (8 elements) each
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
     if (idx >= total) return;
@@ -343,12 +448,13 @@ __global__ void pack_weight_k(const uint16_t* w, uint16_t* wp, int N, int K) {
     int nb = (int)(tile / (K / 16));
     const uint16_t* src = w + ((size_t)nb * 32 + (lane & 31)) * K + kt * 16 + (lane >> 5) * 8;
     uint4 v = *reinterpret_cast<const uint4*>(src);
-    *reinterpret_cast<uint4*>(wp + idx * 8) = v;
+    size_t dst = (((size_t)nb * blk_stride + blk_off) * (K / 16) + kt) * 64 + lane;
+    *reinterpret_cast<uint4*>(wp + dst * 8) = v;
 }
-void launch_pack_weight(const void* w, void* wp, int N, int K, hipStream_t st) {
+void launch_pack_weight(const void* w, void* wp, int N, int K, int blk_stride, int blk_off, hipStream_t st) {
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
     hipLaunchKernelGGL(pack_weight_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t*)w,
-                       (uint16_t*)wp, N, K);
+                       (uint16_t*)wp, N, K, blk_stride, blk_off);
 }
 
 // f32 rows [rows][K] -> packed bf16 activation tiles (rows rounded up to 32 must be allocated)

@@ -35,6 +35,7 @@ struct rdlm_ctx {
     float* gf = nullptr;
     float* gout = nullptr;
     float* theta = nullptr;
+    float* ssq = nullptr;           // [rows_pad][8] partial sums of squares of the folded rows
     float* rope_tab = nullptr;      // [rows_pad][d/2] (cos, sin) of the current step's rows
     // workspace
     TileDesc* tiles = nullptr;
@@ -165,7 +166,7 @@ static int take_matrix(rdlm_ctx* ctx, const void* src, int N, int K, void** dst)
     size_t bytes = (size_t)N * K * ctx->esz;
     DALLOC(*dst, bytes, false);
     if (ctx->m.dtype == RDLM_F32) HIPCHK(hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, ctx->st));
-    else launch_pack_weight(src, *dst, N, K, ctx->st);
+    else launch_pack_weight(src, *dst, N, K, 1, 0, ctx->st);
     return check_launch(ctx);
 }
 static int take_gain(rdlm_ctx* ctx, const void* src, int h, float** dst) {
@@ -201,7 +202,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
             if (m.dtype == RDLM_F32)
                 HIPCHK(hipMemcpyAsync(dst, wp[wi], (size_t)F * h * esz, hipMemcpyDeviceToDevice, ctx->st));
             else
-                launch_pack_weight(wp[wi], dst, F, h, ctx->st);     // blocks of gate, then blocks of up
+                launch_pack_weight(wp[wi], L.wgu, F, h, 2, part, ctx->st);   // gate block j, up block j adjacent
             ++wi;
         }
         if ((rc = take_matrix(ctx, wp[wi++], h, F, &L.wd))) return rc;
@@ -238,6 +239,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->q, R * h * esz, true);
     DALLOC(ctx->att, R * h * esz, true);
     DALLOC(ctx->drafts, R * 4, true);
+    DALLOC(ctx->ssq, R * SSQ_MAX_CHUNKS * 4, true);
     DALLOC(ctx->rope_tab, R * (m.head_dim / 2) * 8, true);
     DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
     DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
@@ -342,7 +344,8 @@ struct SampleArgs {
 //   GU -> ctx->abuf (SwiGLU applied; bf16 path fuses it into the GEMM), HEAD -> ctx->drafts
 //   (sampled tokens; logits in ctx->logits when asked for, always on the f32 path).
 static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int T, int* S_out,
-                    const SampleArgs* sa = nullptr, bool plain = false) {
+                    const SampleArgs* sa = nullptr, bool plain = false, bool deferred_norm = false,
+                    const Layer* rope_layer = nullptr, bool* rope_fused = nullptr) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden, F = m.mlp;
     int N, K;
@@ -371,6 +374,26 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
     if (!plain && proj == PROJ_GU) {
         epi.kind = EPI_SWIGLU;
         epi.act = ctx->abuf;
+    } else if (proj == PROJ_GU) {
+        epi.pair_interleaved = 1;
+    } else if (!plain && proj == PROJ_QKV && rope_layer && !getenv("RDLM_NO_ROPE_FUSION")) {
+        // one workgroup per head: RoPE and the cache writes happen in the GEMM epilogue
+        epi.kind = EPI_ROPE_KV;
+        epi.q_out = ctx->q; epi.kc = rope_layer->kc; epi.vc = rope_layer->vc; epi.rope_table = ctx->rope_tab;
+        epi.n_heads = m.n_heads; epi.head_dim = m.head_dim; epi.seq_stride = (size_t)ctx->ctx_pad * h;
+        epi.tiles = ctx->tiles;
+        const int nb = m.head_dim / 32;
+        if (T == 1) {
+            g = {1, nb, nb == 3 ? 2 : 4, nb == 1 ? 8 : 4, 1};
+            if (const char* p = getenv("RDLM_PLAN_QKVR")) {
+                GemmPlan o = {1, nb, 0, 0, 1};
+                if (sscanf(p, "%d,%d", &o.waves, &o.unroll) == 2) g = o;
+            }
+        } else if (T <= 3) {
+            g = {2, nb, 4, nb == 1 ? 4 : 2, 1};
+        } else {
+            g = {4, nb, nb == 3 ? 2 : 4, 2, 1};
+        }
     } else if (!plain && proj == PROJ_HEAD && sa) {
         epi.kind = EPI_ARGMAX;
         epi.cand_val = ctx->cand_val; epi.cand_idx = ctx->cand_idx; epi.cand_stride = ctx->rows_pad;
@@ -378,9 +401,18 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.tiles = ctx->tiles;
         if (!sa->want_logits) out = nullptr;
     }
+    if (deferred_norm) {
+        epi.row_ssq = ctx->ssq; epi.ssq_chunks = fold_chunks(h); epi.norm_h = h; epi.norm_eps = m.rms_eps;
+    }
     const bool prof = ctx->prof_n == N && ctx->prof_k == K && (size_t)ctx->prof_used + 2 <= ctx->prof_ev.size();
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
     bool ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
+    if (rope_fused) *rope_fused = ok && epi.kind == EPI_ROPE_KV;
+    if (!ok && epi.kind == EPI_ROPE_KV) {      // no fused instance: plain projection, the caller runs the RoPE kernel
+        epi.kind = EPI_F32;
+        g = plan_for(ctx, proj, N, K, T);
+        ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
+    }
     if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
         g = {g.mt, epi.kind == EPI_SWIGLU ? 2 : 1, 4, 4, g.ksplit};
         if (g.mt == 4) g.unroll = 2;
@@ -410,24 +442,37 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
     return s;
 }
 
+// x_out = x_in + pending partial sums, and the normalised GEMM operand of it.  bf16 path: the
+// 1/rms factor is left to the consuming GEMM's epilogue (returns true); f32 path: full RMSNorm.
+static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, const float* gain, void* xn, int T) {
+    const rdlm_model& m = ctx->m;
+    const size_t pst = (size_t)ctx->rows_pad * m.hidden;
+    if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0) {
+        launch_fold(xin, xout, ctx->part, S, pst, gain, xn, ctx->ssq, m.hidden, ctx->n_tiles, T, ctx->st);
+        return true;
+    }
+    launch_addnorm(xin, xout, ctx->part, S, pst, gain, xn, ctx->fmt, m.hidden, m.rms_eps, ctx->n_tiles, T, ctx->st);
+    return false;
+}
+
 // One transformer layer over the current tiles.  On entry the residual stream is
 // x (+ the S_in partial sums in part, if any); on exit it is x + the *S_out partials in part.
 static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
-    const size_t pst = (size_t)ctx->rows_pad * h;
     hipStream_t st = ctx->st;
     int S;
-    launch_addnorm(x_valid ? ctx->x : nullptr, ctx->x, ctx->part, S_in, pst, L.g1, ctx->xn, ctx->fmt, h, m.rms_eps,
-                   ctx->n_tiles, T, st);
-    run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S);
-    launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
-                   (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
+    bool dn = norm_operand(ctx, x_valid ? ctx->x : nullptr, ctx->x, S_in, L.g1, ctx->xn, T);
+    bool rope_done = false;
+    run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S, nullptr, false, dn, &L, &rope_done);
+    if (!rope_done)
+        launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
+                       (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
                      att_split_for(ctx, T, max_keys), ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
     run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S);
-    launch_addnorm(ctx->x, ctx->x, ctx->part, S, pst, L.g2, ctx->xn, ctx->fmt, h, m.rms_eps, ctx->n_tiles, T, st);
-    run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S);               // leaves silu(gate) * up in abuf
+    dn = norm_operand(ctx, ctx->x, ctx->x, S, L.g2, ctx->xn, T);
+    run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S, nullptr, false, dn);   // leaves silu(gate) * up in abuf
     run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out);
 }
 
@@ -475,9 +520,8 @@ static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, in
     for (int l = 0; l < m.n_coda; ++l)
         layer_forward(ctx, ctx->layers[m.n_prelude + m.n_core + l], T, max_keys, true, S, &S);
     if (!sa) return;
-    launch_addnorm(ctx->x, nullptr, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gout, ctx->xn, ctx->fmt, h,
-                   m.rms_eps, ctx->n_tiles, T, ctx->st);
-    run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa);
+    bool dn = norm_operand(ctx, ctx->x, nullptr, S, ctx->gout, ctx->xn, T);
+    run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa, false, dn);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -109,7 +109,7 @@ __host__ __device__ inline float u24_open(uint32_t x) {
 struct GemmPlan { int mt, nb, waves, unroll, ksplit; };
 
 // What the GEMM does with a finished output tile.
-enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3 };
 struct GemmEpilogue {
     int kind = EPI_F32;
     void* act = nullptr;              // EPI_SWIGLU: packed bf16 activation [rows][F]
@@ -120,7 +120,23 @@ struct GemmEpilogue {
     uint32_t k0 = 0, k1 = 0;
     int step = 0;
     const TileDesc* tiles = nullptr;
+    // EPI_ROPE_KV (QKV projection, one workgroup per head): rotate q and k, store q (bf16 rows),
+    // k and v into the layer's cache at the rows' positions
+    void* q_out = nullptr;
+    void* kc = nullptr;
+    void* vc = nullptr;
+    const float* rope_table = nullptr;   // [rows][d/2] (cos, sin)
+    int n_heads = 0, head_dim = 0;
+    size_t seq_stride = 0;
+    int pair_interleaved = 0;         // EPI_F32 on the gate/up matrix: undo the block interleave in the output
+    // Deferred RMSNorm: when row_ssq is set, the input rows were stored as x * gain without the
+    // 1/rms factor; every output row is multiplied by 1/sqrt(sum_c row_ssq[row][c] / h + eps).
+    const float* row_ssq = nullptr;
+    int ssq_chunks = 0;
+    int norm_h = 0;
+    float norm_eps = 0.f;
 };
+constexpr int SSQ_MAX_CHUNKS = 8;
 
 // elementwise / row kernels ------------------------------------------------------------------
 void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
@@ -142,6 +158,13 @@ void launch_concat(const float* e, const float* z, void* cat, int fmt, int h, co
 void launch_addnorm(const float* xin, float* xout, const float* part, int S, size_t part_stride,
                     const float* gain, void* xn, int fmt, int h, float eps, const int32_t* n_tiles,
                     int max_tiles, hipStream_t st);
+// bf16 path: x_out = x_in + sum_s part[s];  xg = bf16(x_out * gain) (packed, NOT divided by the rms);
+// ssq[row][c] = sum of x_out^2 over chunk c of the row (SSQ_MAX_CHUNKS slots per row).  The
+// row is split over `chunks` workgroups, so a 32-row step still fills the chip.
+int fold_chunks(int h);
+void launch_fold(const float* xin, float* xout, const float* part, int S, size_t part_stride,
+                 const float* gain, void* xg, float* ssq, int h, const int32_t* n_tiles, int max_tiles,
+                 hipStream_t st);
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride,
                        const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
                        float* delta, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
@@ -182,7 +205,8 @@ void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_g
 // f32: x [rows][K], w [N][K], out [rows][N]
 void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
-void launch_pack_weight(const void* w_canon /*bf16 [N][K]*/, void* w_packed, int N, int K, hipStream_t st);
+void launch_pack_weight(const void* w_canon /*bf16 [N][K]*/, void* w_packed, int N, int K, int blk_stride,
+                        int blk_off, hipStream_t st);
 void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st);   // f32 rows -> packed bf16
 
 // attention -----------------------------------------------------------------------------------
