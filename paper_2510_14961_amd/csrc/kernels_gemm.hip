@@ -275,16 +275,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
                             make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
                     }
             } else if (EPI == EPI_SWIGLU) {
-                // blocks (0,1) = (gate, up) of the same 32 features: act = silu(gate) * up, stored as a
-                // packed bf16 activation of width F = N/2
+                // blocks (2p, 2p+1) = (gate, up) of the same 32 features: act = silu(gate) * up, stored
+                // as a packed bf16 activation of width F = N/2
                 const int F = A.N >> 1;
-                ushort4 pk;
-                pk.x = f32_to_bf16(silu_f(v[0][0]) * v[NB - 1][0]);
-                pk.y = f32_to_bf16(silu_f(v[0][1]) * v[NB - 1][1]);
-                pk.z = f32_to_bf16(silu_f(v[0][2]) * v[NB - 1][2]);
-                pk.w = f32_to_bf16(silu_f(v[0][3]) * v[NB - 1][3]);
-                *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.act) +
-                                            packed_off((int)row, grp * 32 + foff, F)) = pk;
+#pragma unroll
+                for (int a = 0; a + 1 < NB; a += 2) {
+                    if (blk[a] >= nblk) continue;
+                    ushort4 pk;
+                    pk.x = f32_to_bf16(silu_f(v[a][0]) * v[a + 1][0]);
+                    pk.y = f32_to_bf16(silu_f(v[a][1]) * v[a + 1][1]);
+                    pk.z = f32_to_bf16(silu_f(v[a][2]) * v[a + 1][2]);
+                    pk.w = f32_to_bf16(silu_f(v[a][3]) * v[a + 1][3]);
+                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.act) +
+                                                packed_off((int)row, (blk[a] >> 1) * 32 + foff, F)) = pk;
+                }
             } else {   // EPI_ARGMAX
                 const TileDesc td = A.epi.tiles[t];
 #pragma unroll
@@ -379,7 +383,7 @@ template <int MT, int NB, int WAVES, int U, int EPI>
 static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride, int ksplit,
                        const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     const int nblk = N / 32;
-    const int groups = (EPI == EPI_SWIGLU) ? nblk / 2 : (nblk + NB - 1) / NB;
+    const int groups = (nblk + NB - 1) / NB;
     const int m_chunks = (max_tiles + MT - 1) / MT;
     const size_t lds = WAVES > 1 ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
     auto kern = gemm_bf16_k<MT, NB, WAVES, U, EPI>;
@@ -402,7 +406,8 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
 
 int gemm_groups(int N, const GemmPlan& plan, int epi_kind) {
     const int nblk = N / 32;
-    return epi_kind == EPI_SWIGLU ? nblk / 2 : (nblk + plan.nb - 1) / plan.nb;
+    (void)epi_kind;
+    return (nblk + plan.nb - 1) / plan.nb;
 }
 
 bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
@@ -415,7 +420,7 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
         if (epi.kind == EPI_ARGMAX)                                                                              \
             return launch_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
                                                             max_tiles, st);                                      \
-        if constexpr (NB_ == 2)                                                                                  \
+        if constexpr (NB_ == 2 || NB_ == 4)                                                                      \
             if (epi.kind == EPI_SWIGLU)                                                                          \
                 return launch_cfg<MT_, NB_, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles, \
                                                                 max_tiles, st);                                  \

@@ -323,7 +323,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     } else {
         g = {4, proj == PROJ_GU ? 2 : 1, 4, 2, 4};
     }
-    if (proj == PROJ_GU) g.nb = 2;
+    if (proj == PROJ_GU && g.nb != 4) g.nb = 2;
     if (!split_ok) g.ksplit = 1;
     if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
         int kmax = std::max(1, (K / 16) / (g.waves * 4));
