@@ -447,7 +447,7 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
 static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, const float* gain, void* xn, int T) {
     const rdlm_model& m = ctx->m;
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
-    if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0) {
+    if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
         launch_fold(xin, xout, ctx->part, S, pst, gain, xn, ctx->ssq, m.hidden, ctx->n_tiles, T, ctx->st);
         return true;
     }

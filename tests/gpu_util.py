@@ -56,3 +56,44 @@ def tie_aware_token_check(gpu_tokens, oracle_scores, tau):
             assert gap <= tau, f"row {i}: GPU token {int(t)} scores {gap:.4g} below the oracle's best {best} (tau {tau:.3g})"
             ties += 1
     return exact, ties
+
+
+def teacher_forced_sampler_run(ctx, m, shape, prompt, r, n_new, seed, tol, max_positions):
+    """Drive the GPU sampler (fixed exit, r' = 1) step by step; before each step read the GPU's own
+    inputs (tokens, in-flight states), run the same step in the oracle from them, and compare the
+    new latents, the deltas' count and the drafted tokens (tie-aware).  Returns (exact, ties)."""
+    L = len(prompt)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, L - 1, r, 1.0, seed)
+    cache = m.new_cache(max_positions)
+    m.prefill(prompt[: L - 1], r, 1.0, seed, 0, cache)
+    ctx.sampler_begin(1, n_new=n_new, r_inner=1, r_total=r, seed=seed)
+    win_pos0, win_n, n_frozen = L - 1, 1, L
+    total_exact = total_ties = 0
+    for t in range(1, n_new + r):
+        y_before, _ = ctx.read_tokens(0)
+        z_before = ctx.read_states(0, win_pos0, win_n).astype(np.float64)
+        ctx.sample_step()
+        pos = np.arange(win_pos0, win_pos0 + win_n)
+        e = m.prelude(y_before[pos], pos, cache)
+        z_ref = m.core(e, z_before, pos, cache)
+        logits = m.coda(z_ref, pos, cache)
+        z_gpu = ctx.read_states(0, win_pos0, win_n)
+        err = rel_l2(z_gpu, z_ref)
+        assert err < tol, (t, err)
+        d_gpu = ctx.read_deltas(0)
+        assert len(d_gpu) == win_n
+        d_ref = O.delta(z_ref, z_before)
+        assert np.max(np.abs(d_gpu - d_ref)) < 4 * tol, t
+        y_after, nf = ctx.read_tokens(0)
+        ex, ti = tie_aware_token_check(y_after[pos + 1], logits, tau=0.05 * float(np.std(logits)) + 1e-3)
+        total_exact += ex
+        total_ties += ti
+        k = 1 if t >= r else 0                      # the oldest state has had r recurrences
+        assert nf == n_frozen + k
+        n_frozen += k
+        win_pos0 += k
+        win_n = win_n - k + (1 if n_frozen - L < n_new else 0)
+        if n_frozen - L >= n_new:
+            break
+    return total_exact, total_ties

@@ -11,8 +11,8 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import (SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, make_pair, rel_l2, tie_aware_token_check,
-                      tol_latent)
+from gpu_util import (SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, make_pair, rel_l2,
+                      teacher_forced_sampler_run, tie_aware_token_check, tol_latent)
 
 pytestmark = pytest.mark.gpu
 
@@ -244,41 +244,10 @@ def test_bf16_sampler_steps_teacher_forced(shape):
     started from the GPU's own inputs of that step (tokens and states read back), so that one
     near-tie cannot void the rest of the run."""
     ctx, m, _ = make_pair(shape, seed=4, max_positions=128, max_rows=64)
-    L, r, n_new = 24, 6, 10
-    prompt = S.make_prompt(shape.vocab, L, 6)
-    ctx.set_tokens(0, prompt)
-    ctx.prefill(0, L - 1, r, 1.0, 2)
-    cache = m.new_cache(128)
-    m.prefill(prompt[: L - 1], r, 1.0, 2, 0, cache)
-    ctx.sampler_begin(1, n_new=n_new, r_inner=1, r_total=r, seed=2)
-    tol = tol_latent(shape)
-    win_pos0, win_n, n_frozen = L - 1, 1, L
-    total_exact = total_ties = 0
-    for t in range(1, n_new + r):
-        y_before, _ = ctx.read_tokens(0)
-        z_before = ctx.read_states(0, win_pos0, win_n).astype(np.float64)
-        ctx.sample_step()
-        pos = np.arange(win_pos0, win_pos0 + win_n)
-        e = m.prelude(y_before[pos], pos, cache)
-        z_ref = m.core(e, z_before, pos, cache)
-        logits = m.coda(z_ref, pos, cache)
-        z_gpu = ctx.read_states(0, win_pos0, win_n)
-        assert rel_l2(z_gpu, z_ref) < tol, t
-        d_gpu = ctx.read_deltas(0)
-        assert len(d_gpu) == win_n
-        y_after, nf = ctx.read_tokens(0)
-        ex, ti = tie_aware_token_check(y_after[pos + 1], logits, tau=0.05 * float(np.std(logits)) + 1e-3)
-        total_exact += ex
-        total_ties += ti
-        # the oracle's caches follow the GPU's token choices from here on (teacher forcing)
-        k = 1 if t >= r else 0
-        assert nf == n_frozen + k
-        n_frozen += k
-        win_pos0 += k
-        win_n = win_n - k + (1 if n_frozen - L < n_new else 0)
-        if n_frozen - L >= n_new:
-            break
-    assert total_exact >= 0.8 * (total_exact + total_ties)
+    prompt = S.make_prompt(shape.vocab, 24, 6)
+    exact, ties = teacher_forced_sampler_run(ctx, m, shape, prompt, r=6, n_new=10, seed=2, tol=tol_latent(shape),
+                                             max_positions=128)
+    assert exact >= 0.8 * (exact + ties)
     ctx.close()
 
 
