@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--threads", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -120,6 +122,14 @@ def main():
     max_positions = wl.prompt_len + n_new + window + sp.headway + 8
     want_cpu = not args.no_cpu_baseline
 
+    if args.copy_calibration:       # 2^30 bytes read + 2^30 bytes written per copy
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     dev, w64 = build_weights(shape, wl.weight_seed, want_cpu, args.threads)
     t0 = time.time()
     ctx = R.Context(shape, dev, 1, max_positions, max(wl.prompt_len, window))
@@ -155,7 +165,8 @@ def main():
 
     # dominant kernel: gate/up projection, rows = window padded to 32
     rows = -(-window // 32) * 32
-    algo_bytes = n_gu * k_gu * 2 + rows * k_gu * 2 + rows * n_gu * 4
+    # weights once + the packed bf16 operand + the bf16 SwiGLU output (width F = n_gu / 2)
+    algo_bytes = n_gu * k_gu * 2 + rows * k_gu * 2 + rows * (n_gu // 2) * 2
     achieved = algo_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -181,7 +192,7 @@ def main():
                    "tokens_in_timed_region": int(tokens), "context_at_end": int(nf1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "gemm_bf16_k (gate/up projection, [2F x h] weights, 32 rows)",
+                     "kernel": "gemm_bf16_k (gate/up projection with fused SwiGLU, [2F x h] weights, 32 rows)",
                      "bytes_per_launch": algo_bytes, "avg_ms_per_launch": gemm_ms, "launches_timed": gemm_launches},
         "whole_step": {"weight_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
