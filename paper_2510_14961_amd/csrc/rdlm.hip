@@ -401,6 +401,9 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.tiles = ctx->tiles;
         if (!sa->want_logits) out = nullptr;
     }
+    if (const char* pv = getenv("RDLM_EPI_NONE")) {        // measurement probe (results are not produced)
+        epi.kind = atoi(pv) == 1 ? EPI_NONE_NOX : EPI_NONE;
+    }
     if (deferred_norm) {
         epi.row_ssq = ctx->ssq; epi.ssq_chunks = fold_chunks(h); epi.norm_h = h; epi.norm_eps = m.rms_eps;
     }
@@ -425,7 +428,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         }
     }
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
-    if (epi.kind == EPI_ARGMAX)
+    if (epi.kind == EPI_ARGMAX && !getenv("RDLM_EPI_NONE"))
         launch_argmax_final(ctx->cand_val, ctx->cand_idx, gemm_groups(N, g, EPI_ARGMAX), ctx->rows_pad, ctx->drafts,
                             ctx->n_tiles, T, ctx->st);
     if (S_out) *S_out = g.ksplit;

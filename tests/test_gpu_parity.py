@@ -303,3 +303,32 @@ def test_same_seed_twice_is_bitwise_identical():
     assert np.array_equal(outs[0][0], outs[1][0])
     assert np.array_equal(outs[0][1], outs[1][1])
     ctx.close()
+
+
+def test_long_context_attention_splits():
+    """A context of more than a thousand positions (many key blocks, several KV splits merged) in
+    front of a ragged window, head dim 96."""
+    torch = _torch()
+    shape = SMALL_BF16_D96
+    ctx, m, _ = make_pair(shape, max_positions=1200, max_rows=1152)
+    L, n = 1100, 45
+    tokens = S.make_prompt(shape.vocab, L + n, 12)
+    ctx.set_tokens(0, tokens[:L])
+    ctx.prefill(0, L, 1, 1.0, 5)
+    cache = m.new_cache(1200)
+    s_ref = m.prefill(tokens[:L], 1, 1.0, 5, 0, cache)
+    tol = tol_latent(shape)
+    got = ctx.read_states(0, 0, L)
+    assert rel_l2(got, s_ref) < tol
+    assert rel_l2(got[-64:], s_ref[-64:]) < tol          # the rows with the longest context
+    pos = np.arange(L, L + n)
+    e_ref = m.prelude(tokens[L:], pos, cache)
+    z0 = np.stack([O.init_state(shape.hidden, p, 0, 1.0, 5) for p in pos])
+    z1 = m.core(e_ref, z0, pos, cache)
+    z = _dev(z0.astype(np.float32))
+    e = torch.zeros(n, shape.hidden, device="cuda")
+    ctx.prelude([0], [L], [n], _dev(tokens[L:].astype(np.int32)), e)
+    assert rel_l2(e.cpu().numpy(), e_ref) < tol
+    ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z, 1, None)
+    assert max(rel_l2(a, b) for a, b in zip(z.cpu().numpy(), z1)) < tol
+    ctx.close()

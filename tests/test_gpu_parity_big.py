@@ -94,3 +94,54 @@ def test_big_shape_sampler_steps_teacher_forced(big_pair):
                                              max_positions=160)
     print(f"[big] sampler steps: drafted tokens exact {exact}, near-ties {ties}", flush=True)
     assert exact >= 0.7 * (exact + ties)
+
+
+def test_big_shape_wide_window_and_ragged_batch(big_pair):
+    """The row counts of workloads 4 and 5 at the full shape: a 128-row window (four tiles per
+    GEMM workgroup) and three sequences with ragged windows in one step (R is applied to all rows
+    at once, each sequence attending only to its own cache)."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape, _, m = big_pair
+    # a context with room for three sequences; the module fixture's context holds one
+    w = {n: a for n, a in m.w.items()}
+    dev = R.upload_weights(shape, [(n, a.astype(np.float32)) for n, a in w.items()])
+    ctx = R.Context(shape, dev, 3, 192, 192)
+    del dev
+    torch.cuda.empty_cache()
+    tol = 2e-2
+    dev_t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    # (a) one sequence, 128 rows from position 0 (no prefix: the block's own error only)
+    n = 128
+    pos = np.arange(n)
+    cache = m.new_cache(192)
+    e = S.make_rows(n, shape.hidden, 21, scale=3.0).astype(np.float64)
+    z0 = np.stack([O.init_state(shape.hidden, p, 0, 1.0, 8) for p in pos])
+    z1 = m.core(e, z0, pos, cache)
+    z = dev_t(z0.astype(np.float32))
+    d = torch.zeros(n, device="cuda")
+    ctx.core_step([0], [0], [n], dev_t(e.astype(np.float32)), z, 1, d)
+    got = z.cpu().numpy()
+    assert max(rel_l2(got[i], z1[i]) for i in range(n)) < tol
+    assert np.max(np.abs(d.cpu().numpy() - O.delta(z1, z0))) < 4 * tol
+    # (b) three sequences, windows of 40, 33 and 7 rows at different positions
+    wins = [(1, 0, 40), (2, 5, 33), (0, 128, 7)]          # (seq, pos0, rows); seq 0 continues behind (a)
+    rows = sum(wn for _, _, wn in wins)
+    e2 = S.make_rows(rows, shape.hidden, 22, scale=3.0).astype(np.float64)
+    zs, refs, off = [], [], 0
+    caches = {0: cache, 1: m.new_cache(192), 2: m.new_cache(192)}
+    for seq, p0, wn in wins:
+        pp = np.arange(p0, p0 + wn)
+        zi = np.stack([O.init_state(shape.hidden, p, seq, 1.0, 8) for p in pp])
+        zs.append(zi)
+        refs.append(m.core(e2[off:off + wn], zi, pp, caches[seq]))
+        off += wn
+    zcat = dev_t(np.concatenate(zs).astype(np.float32))
+    ctx.core_step([s for s, _, _ in wins], [p for _, p, _ in wins], [wn for _, _, wn in wins],
+                  dev_t(e2.astype(np.float32)), zcat, 1, None)
+    got = zcat.cpu().numpy()
+    ref = np.concatenate(refs)
+    errs = [rel_l2(got[i], ref[i]) for i in range(rows)]
+    print(f"[big] ragged batch: worst row rel-L2 {max(errs):.4f}", flush=True)
+    assert max(errs) < tol
+    ctx.close()
