@@ -82,10 +82,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 #pragma unroll
             for (int a = 0; a < NB; ++a) wv[u][a] = __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64);
 #pragma unroll
-            for (int b = 0; b < MT; ++b) {
-                if (EPI == EPI_NONE_NOX) xv[u][b] = wv[u][0];     // probe: no activation loads
-                else xv[u][b] = xbase[b][(size_t)(kt + u) * 64];
-            }
+            for (int b = 0; b < MT; ++b) xv[u][b] = xbase[b][(size_t)(kt + u) * 64];
         }
         __builtin_amdgcn_sched_barrier(0);          // all loads of the batch are issued before any MFMA
     };
@@ -129,17 +126,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
         }
     }
 
-    if constexpr (EPI == EPI_NONE || EPI == EPI_NONE_NOX) {      // measurement probe: the weight stream and MFMAs only
-        float s = 0.f;
-#pragma unroll
-        for (int a = 0; a < NB; ++a)
-#pragma unroll
-            for (int b = 0; b < MT; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s += acc[a][b][i];
-        if (s == 12345.678f) A.out[0] = s;
-        return;
-    }
     // cross-wave sum in a fixed order: every wave deposits its accumulators, then wave w finishes
     // the register quads (b, q) with (b*4+q) % WAVES == w, for all feature blocks a
     constexpr int REGS = NB * MT * 16;
@@ -155,86 +141,77 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     const int col = lane & 31, g = lane >> 5;
     if constexpr (EPI == EPI_ROPE_KV) {
         // The workgroup holds one whole head (NB*32 = head_dim features) of q, k or v for MT row
-        // tiles.  RoPE pairs feature u with u +- d/2: that is the same lane, register quad q +- (d/2 % 32)/8
-        // of another (or the same) block, so a wave that finishes the quads of one parity has both
-        // members of every pair.  Waves 0 and 1 share the epilogue (quads of even / odd q).
-        constexpr int D = NB * 32, HALF = D / 2;
-        constexpr int OWNERS = WAVES >= 2 ? 2 : 1;
-        constexpr int NQ = 4 / OWNERS;
-        if (wave < OWNERS) {
-            const int H = A.epi.n_heads, h = H * D;
-            const int section = grp / H, head = grp - section * H;      // 0 = q, 1 = k, 2 = v
-            const float2* table = reinterpret_cast<const float2*>(A.epi.rope_table);
+        // tiles.  RoPE pairs feature u with u +- d/2: that is the same lane, register quad
+        // q +- (d/2 % 32)/8 of another (or the same) block.  The (block, quad) units are dealt round
+        // robin to the waves; a wave sums its unit and the partner unit from the deposited partials.
+        constexpr int D = NB * 32, HALF = D / 2, UNITS = NB * 4;
+        const int H = A.epi.n_heads, h = H * D;
+        const int section = grp / H, head = grp - section * H;      // 0 = q, 1 = k, 2 = v
+        const float2* __restrict__ table = reinterpret_cast<const float2*>(A.epi.rope_table);
+        auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
 #pragma unroll
-            for (int b = 0; b < MT; ++b) {
-                const int t = t0 + b;
-                if (t >= n_tiles) continue;
-                const TileDesc td = A.epi.tiles[t];
-                const size_t row = (size_t)t * 32 + col;
-                const int pos = td.pos0 + col;
-                const bool valid = col < td.n_valid;
-                float sc = 1.0f;
-                if (A.epi.row_ssq) {
-                    float ssq = 0.f;
-                    for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
-                    sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+            for (int i = 0; i < 4; ++i) {
+                const int r = (a * MT + b) * 16 + q * 4 + i;
+                if (WAVES > 1) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
+                    o[i] = sum;
+                } else {
+                    o[i] = acc[a][b][q * 4 + i];
                 }
-                float val[NB][NQ][4];
+            }
+        };
 #pragma unroll
-                for (int a = 0; a < NB; ++a)
+        for (int b = 0; b < MT; ++b) {
+            const int t = t0 + b;
+            if (t >= n_tiles) continue;
+            const TileDesc td = A.epi.tiles[t];
+            const size_t row = (size_t)t * 32 + col;
+            const int pos = td.pos0 + col;
+            const bool valid = col < td.n_valid;
+            float sc = 1.0f;
+            if (A.epi.row_ssq) {
+                float ssq = 0.f;
+                for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
+                sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+            }
 #pragma unroll
-                    for (int qq = 0; qq < NQ; ++qq)
+            for (int unit = 0; unit < UNITS; ++unit) {
+                if (WAVES > 1 && unit % WAVES != wave) continue;
+                const int a = unit >> 2, q = unit & 3;
+                const int ub = 32 * a + 8 * q;                    // head dim of the quad without the lane's 4g
+                const int u0 = ub + 4 * g;
+                float x[4];
+                quad_sum(a, b, q, x);
+                if (section == 2) {
+                    if (valid) {
+                        uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td.seq * A.epi.seq_stride +
+                                       (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int q = OWNERS == 2 ? wave + 2 * qq : qq;
-                            const int r = (a * MT + b) * 16 + q * 4 + i;
-                            float sum = 0.f;
-                            if (WAVES > 1) {
-#pragma unroll
-                                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
-                            } else {
-                                sum = OWNERS == 1 ? acc[a][b][qq * 4 + i] : 0.f;
-                            }
-                            val[a][qq][i] = sum * sc;
-                        }
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-#pragma unroll
-                    for (int qq = 0; qq < NQ; ++qq) {
-                        const int q = OWNERS == 2 ? wave + 2 * qq : qq;
-                        const int u0 = 32 * a + 8 * q + 4 * g;            // first of 4 consecutive head dims
-                        if (section == 2) {
-                            if (valid) {
-                                uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td.seq * A.epi.seq_stride +
-                                               (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) Vt[(size_t)i * 32] = f32_to_bf16(val[a][qq][i]);
-                            }
-                            continue;
-                        }
-                        // partner quad: (32a + 8q + HALF) mod D, same lane
-                        const int ub = 32 * a + 8 * q;                    // without the lane's 4g: compile-time per (a, q)
-                        const int pb = (ub + HALF) % D;
-                        const int pa = pb >> 5;
-                        const int pq = (pb & 31) >> 3;
-                        const int pqq = OWNERS == 2 ? pq >> 1 : pq;
-                        const bool first_half = ub < HALF;
-                        ushort4 pk;
-                        uint16_t* pkp = reinterpret_cast<uint16_t*>(&pk);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int ii = (u0 + i) % HALF;
-                            const float2 cs = table[row * HALF + ii];
-                            const float x = val[a][qq][i], p = val[pa][pqq][i];
-                            pkp[i] = f32_to_bf16(first_half ? x * cs.x - p * cs.y : x * cs.x + p * cs.y);
-                        }
-                        if (section == 0) {
-                            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0) = pk;
-                        } else if (valid) {
-                            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td.seq * A.epi.seq_stride +
-                                                        (size_t)pos * h + head * D + u0) = pk;
-                        }
+                        for (int i = 0; i < 4; ++i) Vt[(size_t)i * 32] = f32_to_bf16(x[i] * sc);
                     }
+                    continue;
+                }
+                const int pb = (ub + HALF) % D;                   // partner quad: compile-time per unit
+                float p[4];
+                quad_sum(pb >> 5, b, (pb & 31) >> 3, p);
+                float2 cs[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) cs[i] = table[row * HALF + (u0 + i) % HALF];
+                ushort4 pk;
+                uint16_t* pkp = reinterpret_cast<uint16_t*>(&pk);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float xv = x[i] * sc, pv = p[i] * sc;
+                    pkp[i] = f32_to_bf16(ub < HALF ? xv * cs[i].x - pv * cs[i].y : xv * cs[i].x + pv * cs[i].y);
+                }
+                if (section == 0) {
+                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0) = pk;
+                } else if (valid) {
+                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td.seq * A.epi.seq_stride +
+                                                (size_t)pos * h + head * D + u0) = pk;
+                }
             }
         }
         return;
@@ -399,7 +376,7 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
     const int nblk = N / 32;
     const int groups = (nblk + NB - 1) / NB;
     const int m_chunks = (max_tiles + MT - 1) / MT;
-    const size_t lds = (WAVES > 1 && EPI != EPI_NONE && EPI != EPI_NONE_NOX) ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
+    const size_t lds = WAVES > 1 ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
     auto kern = gemm_bf16_k<MT, NB, WAVES, U, EPI>;
     if (lds > 64 * 1024) {
         static bool raised = false, ok = false;
@@ -431,14 +408,6 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
         if (epi.kind == EPI_F32)                                                                                 \
             return launch_cfg<MT_, NB_, W_, U_, EPI_F32>(xp, wp, out, N, K, part_stride, plan.ksplit, epi,       \
                                                          n_tiles, max_tiles, st);                                \
-        if constexpr (MT_ == 1)                                                                                  \
-            if (epi.kind == EPI_NONE)                                                                            \
-                return launch_cfg<MT_, NB_, W_, U_, EPI_NONE>(xp, wp, out, N, K, part_stride, plan.ksplit, epi,  \
-                                                              n_tiles, max_tiles, st);                           \
-        if constexpr (MT_ == 1)                                                                                  \
-            if (epi.kind == EPI_NONE_NOX)                                                                        \
-                return launch_cfg<MT_, NB_, W_, U_, EPI_NONE_NOX>(xp, wp, out, N, K, part_stride, plan.ksplit,   \
-                                                                  epi, n_tiles, max_tiles, st);                  \
         if (epi.kind == EPI_ARGMAX)                                                                              \
             return launch_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
                                                             max_tiles, st);                                      \
@@ -456,6 +425,7 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
     RDLM_CASE(1, 2, 4, 2) RDLM_CASE(1, 2, 4, 4) RDLM_CASE(1, 2, 4, 8) RDLM_CASE(1, 2, 8, 4) RDLM_CASE(1, 2, 2, 4)
     RDLM_CASE(1, 2, 2, 8) RDLM_CASE(1, 2, 8, 2)
     RDLM_CASE(1, 3, 4, 2) RDLM_CASE(1, 3, 4, 4) RDLM_CASE(1, 3, 2, 4) RDLM_CASE(1, 3, 8, 2) RDLM_CASE(1, 3, 2, 8)
+    RDLM_CASE(1, 3, 8, 1)
     RDLM_CASE(1, 4, 4, 2) RDLM_CASE(1, 4, 4, 4) RDLM_CASE(1, 4, 2, 4) RDLM_CASE(1, 4, 2, 2) RDLM_CASE(1, 4, 8, 2)
     RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8) RDLM_CASE(2, 3, 4, 2)
     RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2) RDLM_CASE(4, 3, 2, 2)

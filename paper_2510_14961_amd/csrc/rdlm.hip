@@ -384,7 +384,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.tiles = ctx->tiles;
         const int nb = m.head_dim / 32;
         if (T == 1) {
-            g = {1, nb, nb == 3 ? 2 : 4, nb == 1 ? 8 : 4, 1};
+            g = {1, nb, nb == 3 ? 8 : 4, nb == 1 ? 8 : (nb == 2 ? 4 : 1), 1};
             if (const char* p = getenv("RDLM_PLAN_QKVR")) {
                 GemmPlan o = {1, nb, 0, 0, 1};
                 if (sscanf(p, "%d,%d", &o.waves, &o.unroll) == 2) g = o;
@@ -400,9 +400,6 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.temperature = sa->temperature; epi.k0 = sa->k0; epi.k1 = sa->k1; epi.step = sa->step;
         epi.tiles = ctx->tiles;
         if (!sa->want_logits) out = nullptr;
-    }
-    if (const char* pv = getenv("RDLM_EPI_NONE")) {        // measurement probe (results are not produced)
-        epi.kind = atoi(pv) == 1 ? EPI_NONE_NOX : EPI_NONE;
     }
     if (deferred_norm) {
         epi.row_ssq = ctx->ssq; epi.ssq_chunks = fold_chunks(h); epi.norm_h = h; epi.norm_eps = m.rms_eps;
@@ -428,7 +425,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         }
     }
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
-    if (epi.kind == EPI_ARGMAX && !getenv("RDLM_EPI_NONE"))
+    if (epi.kind == EPI_ARGMAX)
         launch_argmax_final(ctx->cand_val, ctx->cand_idx, gemm_groups(N, g, EPI_ARGMAX), ctx->rows_pad, ctx->drafts,
                             ctx->n_tiles, T, ctx->st);
     if (S_out) *S_out = g.ksplit;
@@ -896,10 +893,15 @@ extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, 
     HIPCHK(hipEventCreate(&a));
     HIPCHK(hipEventCreate(&b));
     int S;
+    // the QKV projection is timed as the model runs it: RoPE and the cache writes in its epilogue
+    // (rows land at positions 0.. of sequence 0 in the first layer's cache)
+    const Layer* rl = proj == PROJ_QKV ? &ctx->layers[0] : nullptr;
+    bool fused = false;
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     for (int i = 0; i < 3; ++i)
-        if ((rc = run_proj(ctx, proj, xin, W, T, &S, &sa))) return rc;
+        if ((rc = run_proj(ctx, proj, xin, W, T, &S, &sa, false, false, rl, &fused))) return rc;
     HIPCHK(hipEventRecord(a, ctx->st));
-    for (int i = 0; i < iters; ++i) run_proj(ctx, proj, xin, W, T, &S, &sa);
+    for (int i = 0; i < iters; ++i) run_proj(ctx, proj, xin, W, T, &S, &sa, false, false, rl, &fused);
     HIPCHK(hipEventRecord(b, ctx->st));
     HIPCHK(hipEventSynchronize(b));
     float ms = 0.f;

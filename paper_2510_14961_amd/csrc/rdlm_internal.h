@@ -109,7 +109,7 @@ __host__ __device__ inline float u24_open(uint32_t x) {
 struct GemmPlan { int mt, nb, waves, unroll, ksplit; };
 
 // What the GEMM does with a finished output tile.
-enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3, EPI_NONE = 4, EPI_NONE_NOX = 5 /* timing probes: no output / also no activation loads */ };
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3 };
 struct GemmEpilogue {
     int kind = EPI_F32;
     void* act = nullptr;              // EPI_SWIGLU: packed bf16 activation [rows][F]
