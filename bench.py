@@ -99,7 +99,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=511)
     ap.add_argument("--warmup", type=int, default=32)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--ar-tokens", type=int, default=8,
+                    help="tokens of the autoregressive (r' = r) run timed for comparison; 0 = skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
@@ -117,10 +119,13 @@ def main():
     wl = S.WORKLOADS[args.workload]
     shape, sp = wl.shape, wl.sampler
     K, W = args.steps, args.warmup
-    window = -(-sp.r // sp.r_inner) * sp.headway
-    n_new = max(sp.n_new, K + W + 1)                 # never finish inside the timed steps
+    wave = -(-sp.r // sp.r_inner) * sp.headway
+    window = sp.w_max if (sp.adaptive and sp.w_max > 0) else wave
+    n_seqs = wl.n_seqs
+    n_new = max(sp.n_new, (K + W + 1) * sp.headway)          # never finish inside the timed steps
     max_positions = wl.prompt_len + n_new + window + sp.headway + 8
-    want_cpu = not args.no_cpu_baseline
+    max_rows = max(wl.prompt_len, n_seqs * (-(-window // 32) * 32))
+    want_cpu = not args.no_cpu_baseline and args.workload in ("cfg2", "cfg3")
 
     if args.copy_calibration:       # 2^30 bytes read + 2^30 bytes written per copy
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -132,23 +137,27 @@ def main():
         torch.cuda.empty_cache()
     dev, w64 = build_weights(shape, wl.weight_seed, want_cpu, args.threads)
     t0 = time.time()
-    ctx = R.Context(shape, dev, 1, max_positions, max(wl.prompt_len, window))
+    ctx = R.Context(shape, dev, n_seqs, max_positions, max_rows)
     del dev
     torch.cuda.empty_cache()
     log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 2**30:.1f} GiB on device")
 
-    prompt = S.make_prompt(shape.vocab, wl.prompt_len, wl.prompt_seed)
-    ctx.set_tokens(0, prompt)
+    prompts = [S.make_prompt(shape.vocab, wl.prompt_len, wl.prompt_seed, seq=q) for q in range(n_seqs)]
     t0 = time.time()
-    ctx.prefill(0, wl.prompt_len - 1, sp.r, sp.alpha, sp.seed)
+    for q, prompt in enumerate(prompts):
+        ctx.set_tokens(q, prompt)
+        ctx.prefill(q, wl.prompt_len - 1, sp.r, sp.alpha, sp.seed)
     torch.cuda.synchronize()
-    log(f"[bench] prefill of {wl.prompt_len - 1} positions x {sp.r} recurrences: {time.time() - t0:.2f}s")
-    ctx.sampler_begin(1, n_new=n_new, r_inner=sp.r_inner, r_total=sp.r, headway=sp.headway, alpha=sp.alpha,
-                      temperature=sp.temperature, seed=sp.seed)
+    log(f"[bench] prefill of {n_seqs} x {wl.prompt_len - 1} positions x {sp.r} recurrences: {time.time() - t0:.2f}s")
+    sampler_kw = dict(r_inner=sp.r_inner, r_total=sp.r, headway=sp.headway, alpha=sp.alpha, w_max=sp.w_max,
+                      adaptive=sp.adaptive, eps=sp.eps, temperature=sp.temperature, seed=sp.seed,
+                      pad_token=sp.pad_token)
+    ctx.sampler_begin(n_seqs, n_new=n_new, **sampler_kw)
+    frozen = lambda: sum(ctx.read_tokens(q, 1)[1] for q in range(n_seqs))
     for _ in range(W):
         ctx.sample_step()
     torch.cuda.synchronize()
-    _, nf0 = ctx.read_tokens(0, 1)
+    nf0 = frozen()
     n_gu, k_gu = 2 * shape.mlp, shape.hidden
     per_step_launches = shape.n_prelude + sp.r_inner * shape.n_core + shape.n_coda     # one per layer pass
     ctx.profile_gemm_begin(n_gu, k_gu, K * per_step_launches)
@@ -159,12 +168,12 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     gemm_ms, gemm_launches = ctx.profile_gemm_read()
-    _, nf1 = ctx.read_tokens(0, 1)
+    nf1 = frozen()
     tokens = nf1 - nf0
     ms_per_step = dt / K * 1e3
 
-    # dominant kernel: gate/up projection, rows = window padded to 32
-    rows = -(-window // 32) * 32
+    # dominant kernel: gate/up projection over the rows of a step (each sequence's window padded to 32)
+    rows = n_seqs * (-(-window // 32) * 32)
     # weights once + the packed bf16 operand + the bf16 SwiGLU output (width F = n_gu / 2)
     algo_bytes = n_gu * k_gu * 2 + rows * k_gu * 2 + rows * (n_gu // 2) * 2
     achieved = algo_bytes / (gemm_ms * 1e-3) / 1e9 if gemm_ms > 0 else 0.0
@@ -175,28 +184,51 @@ def main():
             traffic = json.load(open(tpath)).get(f"gemm_gu_{args.workload}")
         except Exception:
             traffic = None
-    core_ms = ctx.time_core_step(0, wl.prompt_len, window, 20)
+    core_ms = ctx.time_core_step(0, wl.prompt_len, min(window, max_rows), 20)
     h, F, V = shape.hidden, shape.mlp, shape.vocab
     layer_b = (4 * h * h + 3 * h * F) * 2
     core_bytes = shape.n_core * layer_b + 2 * h * h * 2
     step_bytes = shape.n_layers * layer_b + 2 * h * h * 2 + V * h * 2
 
+    # the same path run as the autoregressive sampler (r' = r: one token at a time, end of Sec. 3.3)
+    ar = None
+    if args.ar_tokens > 0 and not sp.adaptive:
+        ctx.set_tokens(0, prompts[0])          # caches of the prompt prefix are still in place
+        ar_kw = dict(sampler_kw, r_inner=sp.r, headway=1, w_max=0)
+        ctx.sampler_begin(1, n_new=args.ar_tokens + 2, **ar_kw)
+        ctx.sample_step()
+        ctx.sample_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.ar_tokens):
+            ctx.sample_step()
+        torch.cuda.synchronize()
+        ar_dt = time.perf_counter() - t0
+        ar = {"value": args.ar_tokens / ar_dt, "unit": "tokens/s", "tokens_timed": args.ar_tokens,
+              "speedup_of_diffusion_forcing": (tokens / dt) / (args.ar_tokens / ar_dt),
+              "note": "autoregressive sampling (r' = r) through the same library; the paper reports 4.4-4.8x "
+                      "for r'=4 on A100-40GB"}
+
     out = {
-        "metric": "generated tokens/sec @batch1 (3.5B-shaped)" if args.workload == "cfg3" else "generated tokens/sec @batch1",
+        "metric": "generated tokens/sec @batch1 (3.5B-shaped)" if args.workload == "cfg3" else f"generated tokens/sec ({args.workload})",
         "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {h}x{shape.n_heads}x{shape.head_dim}, mlp {F}, vocab {V}, "
                                f"P{shape.n_prelude}/R{shape.n_core}/C{shape.n_coda}, prompt {wl.prompt_len}, "
-                               f"r={sp.r}, r'={sp.r_inner}, window {window}, batch 1, greedy",
+                               f"r={sp.r}, r'={sp.r_inner}, window {window}, batch {n_seqs}, "
+                               + ("greedy" if sp.temperature == 0 else f"temperature {sp.temperature}")
+                               + (f", adaptive exit eps={sp.eps}" if sp.adaptive else "")
+                               + (f", headway {sp.headway}" if sp.headway > 1 else ""),
                    "tokens_in_timed_region": int(tokens), "context_at_end": int(nf1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "gemm_bf16_k (gate/up projection with fused SwiGLU, [2F x h] weights, 32 rows)",
+                     "kernel": f"gemm_bf16_k (gate/up projection with fused SwiGLU, [2F x h] weights, {rows} rows)",
                      "bytes_per_launch": algo_bytes, "avg_ms_per_launch": gemm_ms, "launches_timed": gemm_launches},
         "whole_step": {"weight_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "core_step": {"ms": core_ms, "weight_bytes": core_bytes, "GBps": core_bytes / (core_ms * 1e-3) / 1e9},
+        "autoregressive_same_path": ar,
     }
     ctx.close()
     torch.cuda.empty_cache()
