@@ -32,11 +32,32 @@ struct GemmArgs {
 // Epilogue helpers ---------------------------------------------------------------------------
 __device__ inline float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 
+// Column of the canonical [rows][N] output that row f (0..31) of packed weight block `blk` is.
+//   WL_NATURAL: 32 consecutive output features per block.
+//   WL_GU16 (gate/up, N = 2F): block j holds gate features [16j, 16j+16) in rows 0..15 and the up
+//     features of the same indices in rows 16..31, so a SwiGLU pair sits in one accumulator lane.
+//   WL_ROPE (q | k | v, N = 3h): in the q and k sections block j' of a head holds head dims
+//     [16j', 16j'+16) and their rotate-half partners [d/2 + 16j', d/2 + 16j' + 16); v is natural.
+__host__ __device__ inline int canon_col(int layout, int blk, int f, int N, int n_heads, int head_dim) {
+    if (layout == WL_GU16) {
+        const int F = N >> 1;
+        return (f < 16 ? 0 : F) + 16 * blk + (f & 15);
+    }
+    if (layout == WL_ROPE) {
+        const int h = n_heads * head_dim, hb = h >> 5, sec = blk / hb, r = blk - sec * hb;
+        if (sec == 2) return blk * 32 + f;
+        const int per = head_dim >> 5, head = r / per, j = r - head * per;
+        return sec * h + head * head_dim + (f < 16 ? 0 : (head_dim >> 1)) + 16 * j + (f & 15);
+    }
+    return blk * 32 + f;
+}
+
 template <int MT, int NB, int WAVES, int U, int EPI>
 __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     extern __shared__ float red[];                 // [WAVES][NB*MT*16][64]
-    __shared__ float cand_v[WAVES > 1 ? WAVES : 1][MT][32];
-    __shared__ int cand_i[WAVES > 1 ? WAVES : 1][MT][32];
+    constexpr int CW = (EPI == EPI_ARGMAX && WAVES > 1) ? WAVES : 1;
+    __shared__ float cand_v[CW][MT][32];
+    __shared__ int cand_i[CW][MT][32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int bid = blockIdx.x;
     const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
@@ -58,8 +79,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    // feature blocks of this workgroup: NB consecutive ones (the gate/up matrix is stored with gate
-    // block j and up block j adjacent, so the SwiGLU epilogue finds its pair in blocks 2j, 2j+1)
     int blk[NB];
     const bf16x8* wbase[NB];
     const bf16x8* xbase[MT];
@@ -126,8 +145,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
         }
     }
 
-    // cross-wave sum in a fixed order: every wave deposits its accumulators, then wave w finishes
-    // the register quads (b, q) with (b*4+q) % WAVES == w, for all feature blocks a
+    // Cross-wave sum in a fixed order: every wave deposits its accumulators; the finishing work is
+    // dealt to the waves in units of one register quad (4 consecutive features of a block for
+    // the lane's row) -- or, for the epilogues that pair row f of a block with row f + 16 (SwiGLU,
+    // RoPE), of quad q together with quad q + 2.
     constexpr int REGS = NB * MT * 16;
     if (WAVES > 1) {
 #pragma unroll
@@ -138,83 +159,38 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
                 for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
         __syncthreads();
     }
-    const int col = lane & 31, g = lane >> 5;
-    if constexpr (EPI == EPI_ROPE_KV) {
-        // The workgroup holds one whole head (NB*32 = head_dim features) of q, k or v for MT row
-        // tiles.  RoPE pairs feature u with u +- d/2: that is the same lane, register quad
-        // q +- (d/2 % 32)/8 of another (or the same) block.  The (block, quad) units are dealt round
-        // robin to the waves; a wave sums its unit and the partner unit from the deposited partials.
-        constexpr int D = NB * 32, HALF = D / 2, UNITS = NB * 4;
-        const int H = A.epi.n_heads, h = H * D;
-        const int section = grp / H, head = grp - section * H;      // 0 = q, 1 = k, 2 = v
-        const float2* __restrict__ table = reinterpret_cast<const float2*>(A.epi.rope_table);
-        auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
+    auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (a * MT + b) * 16 + q * 4 + i;
-                if (WAVES > 1) {
-                    float sum = 0.f;
+        for (int i = 0; i < 4; ++i) {
+            const int r = (a * MT + b) * 16 + q * 4 + i;
+            if (WAVES > 1) {
+                float sum = 0.f;
 #pragma unroll
-                    for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
-                    o[i] = sum;
-                } else {
-                    o[i] = acc[a][b][q * 4 + i];
-                }
-            }
-        };
-#pragma unroll
-        for (int b = 0; b < MT; ++b) {
-            const int t = t0 + b;
-            if (t >= n_tiles) continue;
-            const TileDesc td = A.epi.tiles[t];
-            const size_t row = (size_t)t * 32 + col;
-            const int pos = td.pos0 + col;
-            const bool valid = col < td.n_valid;
-            float sc = 1.0f;
-            if (A.epi.row_ssq) {
-                float ssq = 0.f;
-                for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
-                sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
-            }
-#pragma unroll
-            for (int unit = 0; unit < UNITS; ++unit) {
-                if (WAVES > 1 && unit % WAVES != wave) continue;
-                const int a = unit >> 2, q = unit & 3;
-                const int ub = 32 * a + 8 * q;                    // head dim of the quad without the lane's 4g
-                const int u0 = ub + 4 * g;
-                float x[4];
-                quad_sum(a, b, q, x);
-                if (section == 2) {
-                    if (valid) {
-                        uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td.seq * A.epi.seq_stride +
-                                       (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) Vt[(size_t)i * 32] = f32_to_bf16(x[i] * sc);
-                    }
-                    continue;
-                }
-                const int pb = (ub + HALF) % D;                   // partner quad: compile-time per unit
-                float p[4];
-                quad_sum(pb >> 5, b, (pb & 31) >> 3, p);
-                float2 cs[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) cs[i] = table[row * HALF + (u0 + i) % HALF];
-                ushort4 pk;
-                uint16_t* pkp = reinterpret_cast<uint16_t*>(&pk);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float xv = x[i] * sc, pv = p[i] * sc;
-                    pkp[i] = f32_to_bf16(ub < HALF ? xv * cs[i].x - pv * cs[i].y : xv * cs[i].x + pv * cs[i].y);
-                }
-                if (section == 0) {
-                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0) = pk;
-                } else if (valid) {
-                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td.seq * A.epi.seq_stride +
-                                                (size_t)pos * h + head * D + u0) = pk;
-                }
+                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
+                o[i] = sum;
+            } else {
+                o[i] = acc[a][b][q * 4 + i];
             }
         }
-        return;
+    };
+    const int col = lane & 31, g = lane >> 5;
+    constexpr bool PAIRED = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV);
+    constexpr int UQ = PAIRED ? 2 : 4;
+
+    // per row tile: deferred RMSNorm factor of the lane's row, tile descriptor
+    float sc[MT];
+    TileDesc td[MT];
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+        sc[b] = 1.0f;
+        const int t = min(t0 + b, n_tiles - 1);
+        if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = A.epi.tiles[t];
+        if (A.epi.row_ssq) {
+            const size_t row = (size_t)t * 32 + col;
+            float ssq = 0.f;
+            for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
+            sc[b] = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+        }
     }
     float best_v[MT];
     int best_i[MT];
@@ -222,91 +198,95 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     for (int b = 0; b < MT; ++b) { best_v[b] = -INFINITY; best_i[b] = 0x7fffffff; }
 
 #pragma unroll
-    for (int b = 0; b < MT; ++b) {
+    for (int unit = 0; unit < NB * MT * UQ; ++unit) {
+        const int a = unit / (MT * UQ), b = (unit / UQ) % MT, q = unit % UQ;
+        if (WAVES > 1 && unit % WAVES != wave) continue;
         const int t = t0 + b;
+        if (t >= n_tiles || blk[a] >= nblk) continue;
+        const size_t row = (size_t)t * 32 + col;
+        // accumulator register 4q+i of lane (col, g) is row 8q + 4g + i of the weight block, for row `col`
+        const int f0 = q * 8 + g * 4;
+        float lo[4], hi[4];
+        quad_sum(a, b, q, lo);
+        if (PAIRED) quad_sum(a, b, q + 2, hi);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (WAVES > 1 && (b * 4 + q) % WAVES != wave) continue;
-            if (t >= n_tiles) continue;
-            float v[NB][4];
-#pragma unroll
-            for (int a = 0; a < NB; ++a)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = (a * MT + b) * 16 + q * 4 + i;
-                    if (WAVES > 1) {
-                        float s = 0.f;
-#pragma unroll
-                        for (int w = 0; w < WAVES; ++w) s += red[((size_t)w * REGS + r) * 64 + lane];
-                        v[a][i] = s;
-                    } else {
-                        v[a][i] = acc[a][b][q * 4 + i];
-                    }
-                }
-            // accumulator register q*4+i of lane (col, g) is feature 8q + 4g + i of its block, row `col`
-            const size_t row = (size_t)t * 32 + col;
-            const int foff = q * 8 + g * 4;
-            if (A.epi.row_ssq) {                   // deferred RMSNorm factor of this output row
-                float ssq = 0.f;
-                for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
-                const float sc = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) v[a][i] *= sc;
-            }
-            if (EPI == EPI_F32) {
-                float* o = A.out + (size_t)ks * A.part_stride;
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-                    if (blk[a] < nblk) {
-                        // pair-interleaved weights (gate/up): block 2j is column block j, 2j+1 is nblk/2 + j
-                        const int cb = A.epi.pair_interleaved ? (blk[a] & 1) * (nblk >> 1) + (blk[a] >> 1) : blk[a];
-                        *reinterpret_cast<float4*>(o + row * A.N + cb * 32 + foff) =
-                            make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
-                    }
-            } else if (EPI == EPI_SWIGLU) {
-                // blocks (2p, 2p+1) = (gate, up) of the same 32 features: act = silu(gate) * up, stored
-                // as a packed bf16 activation of width F = N/2
-                const int F = A.N >> 1;
-#pragma unroll
-                for (int a = 0; a + 1 < NB; a += 2) {
-                    if (blk[a] >= nblk) continue;
-                    ushort4 pk;
-                    pk.x = f32_to_bf16(silu_f(v[a][0]) * v[a + 1][0]);
-                    pk.y = f32_to_bf16(silu_f(v[a][1]) * v[a + 1][1]);
-                    pk.z = f32_to_bf16(silu_f(v[a][2]) * v[a + 1][2]);
-                    pk.w = f32_to_bf16(silu_f(v[a][3]) * v[a + 1][3]);
-                    *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.act) +
-                                                packed_off((int)row, (blk[a] >> 1) * 32 + foff, F)) = pk;
-                }
-            } else {   // EPI_ARGMAX
-                const TileDesc td = A.epi.tiles[t];
-#pragma unroll
-                for (int a = 0; a < NB; ++a) {
-                    if (blk[a] >= nblk) continue;
-                    const int f0 = blk[a] * 32 + foff;
-                    if (A.out)
-                        *reinterpret_cast<float4*>(A.out + row * A.N + f0) = make_float4(v[a][0], v[a][1], v[a][2], v[a][3]);
-                    float gn[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (A.epi.temperature > 0.f) {
-                        uint32_t x[4];
-                        philox4x32_10(f0 >> 2, td.pos0 + col, td.seq, ((uint32_t)A.epi.step << 4) | TAG_SAMPLE,
-                                      A.epi.k0, A.epi.k1, x);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));
-                    }
+        for (int i = 0; i < 4; ++i) { lo[i] *= sc[b]; if (PAIRED) hi[i] *= sc[b]; }
+
+        if constexpr (EPI == EPI_F32) {
+            float* o = A.out + (size_t)ks * A.part_stride;
+            const int c0 = canon_col(A.epi.layout, blk[a], f0, A.N, A.epi.n_heads, A.epi.head_dim);
+            *reinterpret_cast<float4*>(o + row * A.N + c0) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+        } else if constexpr (EPI == EPI_SWIGLU) {
+            // rows f0.. are gate features 16 blk + f0.., rows 16 + f0.. the up features of the same index
+            const int F = A.N >> 1;
+            ushort4 pk;
+            pk.x = f32_to_bf16(silu_f(lo[0]) * hi[0]);
+            pk.y = f32_to_bf16(silu_f(lo[1]) * hi[1]);
+            pk.z = f32_to_bf16(silu_f(lo[2]) * hi[2]);
+            pk.w = f32_to_bf16(silu_f(lo[3]) * hi[3]);
+            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.act) +
+                                        packed_off((int)row, blk[a] * 16 + f0, F)) = pk;
+        } else if constexpr (EPI == EPI_ROPE_KV) {
+            // q, k: rotate (u, u + d/2) by the row's angle table, q -> bf16 rows for the attention
+            // kernel, k -> the layer's cache at the row's position; v -> transposed cache
+            const int D = A.epi.head_dim, HALF = D >> 1, H = A.epi.n_heads, h = H * D;
+            const int hb = h >> 5, sec = blk[a] / hb, r = blk[a] - sec * hb, per = D >> 5;
+            const int head = r / per, j = r - head * per;
+            const int pos = td[b].pos0 + col;
+            const bool valid = col < td[b].n_valid;
+            if (sec == 2) {
+                if (valid) {
+                    const int u0 = 32 * j + f0;
+                    uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td[b].seq * A.epi.seq_stride +
+                                   (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        float sc = v[a][i];
-                        if (A.epi.temperature > 0.f) sc = sc / A.epi.temperature + gn[i];
-                        if (sc > best_v[b] || (sc == best_v[b] && f0 + i < best_i[b])) { best_v[b] = sc; best_i[b] = f0 + i; }
+                        Vt[(size_t)i * 32] = f32_to_bf16(lo[i]);
+                        Vt[(size_t)(16 + i) * 32] = f32_to_bf16(hi[i]);
                     }
                 }
+            } else {
+                const int u0 = 16 * j + f0;                  // < HALF; partner u0 + HALF
+                const float2* __restrict__ table = reinterpret_cast<const float2*>(A.epi.rope_table);
+                ushort4 p0, p1;
+                uint16_t* p0p = reinterpret_cast<uint16_t*>(&p0);
+                uint16_t* p1p = reinterpret_cast<uint16_t*>(&p1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float2 cs = table[row * HALF + u0 + i];
+                    p0p[i] = f32_to_bf16(lo[i] * cs.x - hi[i] * cs.y);
+                    p1p[i] = f32_to_bf16(hi[i] * cs.x + lo[i] * cs.y);
+                }
+                uint16_t* dst = nullptr;
+                if (sec == 0) dst = reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0;
+                else if (valid)
+                    dst = reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td[b].seq * A.epi.seq_stride + (size_t)pos * h +
+                          head * D + u0;
+                if (dst) {
+                    *reinterpret_cast<ushort4*>(dst) = p0;
+                    *reinterpret_cast<ushort4*>(dst + HALF) = p1;
+                }
+            }
+        } else {   // EPI_ARGMAX
+            const int c0 = blk[a] * 32 + f0;
+            if (A.out) *reinterpret_cast<float4*>(A.out + row * A.N + c0) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+            float gn[4] = {0.f, 0.f, 0.f, 0.f};
+            if (A.epi.temperature > 0.f) {
+                uint32_t x[4];
+                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].seq, ((uint32_t)A.epi.step << 4) | TAG_SAMPLE, A.epi.k0,
+                              A.epi.k1, x);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float s = lo[i];
+                if (A.epi.temperature > 0.f) s = s / A.epi.temperature + gn[i];
+                if (s > best_v[b] || (s == best_v[b] && c0 + i < best_i[b])) { best_v[b] = s; best_i[b] = c0 + i; }
             }
         }
     }
-    if (EPI == EPI_ARGMAX) {
+    if constexpr (EPI == EPI_ARGMAX) {
         // best over the two half-waves, then over the waves; one candidate per (group, row)
 #pragma unroll
         for (int b = 0; b < MT; ++b) {
@@ -411,31 +391,30 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
         if (epi.kind == EPI_ARGMAX)                                                                              \
             return launch_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
                                                             max_tiles, st);                                      \
-        if constexpr (NB_ == 2 || NB_ == 4)                                                                      \
-            if (epi.kind == EPI_SWIGLU)                                                                          \
-                return launch_cfg<MT_, NB_, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles, \
-                                                                max_tiles, st);                                  \
-        if constexpr (NB_ <= 3)                                                                                  \
-            if (epi.kind == EPI_ROPE_KV && NB_ * 32 == epi.head_dim)                                             \
-                return launch_cfg<MT_, NB_, W_, U_, EPI_ROPE_KV>(xp, wp, out, N, K, part_stride, 1, epi,         \
-                                                                 n_tiles, max_tiles, st);                        \
+        if (epi.kind == EPI_SWIGLU)                                                                              \
+            return launch_cfg<MT_, NB_, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,     \
+                                                            max_tiles, st);                                      \
+        if (epi.kind == EPI_ROPE_KV)                                                                             \
+            return launch_cfg<MT_, NB_, W_, U_, EPI_ROPE_KV>(xp, wp, out, N, K, part_stride, 1, epi, n_tiles,    \
+                                                             max_tiles, st);                                     \
         return false;                                                                                            \
     }
-    RDLM_CASE(1, 1, 4, 4) RDLM_CASE(1, 1, 4, 8) RDLM_CASE(1, 1, 8, 4) RDLM_CASE(1, 1, 8, 8) RDLM_CASE(1, 1, 2, 8)
-    RDLM_CASE(1, 2, 4, 2) RDLM_CASE(1, 2, 4, 4) RDLM_CASE(1, 2, 4, 8) RDLM_CASE(1, 2, 8, 4) RDLM_CASE(1, 2, 2, 4)
-    RDLM_CASE(1, 2, 2, 8) RDLM_CASE(1, 2, 8, 2)
-    RDLM_CASE(1, 3, 4, 2) RDLM_CASE(1, 3, 4, 4) RDLM_CASE(1, 3, 2, 4) RDLM_CASE(1, 3, 8, 2) RDLM_CASE(1, 3, 2, 8)
-    RDLM_CASE(1, 3, 8, 1)
-    RDLM_CASE(1, 4, 4, 2) RDLM_CASE(1, 4, 4, 4) RDLM_CASE(1, 4, 2, 4) RDLM_CASE(1, 4, 2, 2) RDLM_CASE(1, 4, 8, 2)
+#define RDLM_ROW(NB_)                                                                                            \
+    RDLM_CASE(1, NB_, 2, 4) RDLM_CASE(1, NB_, 2, 8) RDLM_CASE(1, NB_, 4, 2) RDLM_CASE(1, NB_, 4, 4)              \
+    RDLM_CASE(1, NB_, 8, 1) RDLM_CASE(1, NB_, 8, 2)
+    RDLM_ROW(1) RDLM_ROW(2) RDLM_ROW(3) RDLM_ROW(4) RDLM_ROW(5)
     RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8) RDLM_CASE(2, 3, 4, 2)
-    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2) RDLM_CASE(4, 3, 2, 2)
+    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2)
+#undef RDLM_ROW
 #undef RDLM_CASE
     return false;
 }
 
-// canonical bf16 [N][K] -> MFMA-ordered tiles [N/32][K/16][64 lanes][8]; source block nb lands at
-// packed block nb * blk_stride + blk_off (used to interleave the gate and up matrices)
-__global__ void pack_weight_k(const uint16_t* w, uint16_t* wp, int N, int K, int blk_stride, int blk_off) {
+// canonical bf16 rows -> MFMA-ordered tiles [N/32][K/16][64 lanes][8].  Row f of packed block b is
+// canonical row canon_col(layout, b, f); canonical rows below `split` come from w0, the others
+// from w1 (the gate and up matrices are separate tensors).
+__global__ void pack_weight_k(const uint16_t* w0, const uint16_t* w1, int split, uint16_t* wp, int N, int K,
+                              int layout, int n_heads, int head_dim) {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;       // one lane-vector (8 elements) each
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
     if (idx >= total) return;
@@ -443,15 +422,16 @@ __global__ void pack_weight_k(const uint16_t* w, uint16_t* wp, int N, int K, int
     size_t tile = idx >> 6;
     int kt = (int)(tile % (K / 16));
     int nb = (int)(tile / (K / 16));
-    const uint16_t* src = w + ((size_t)nb * 32 + (lane & 31)) * K + kt * 16 + (lane >> 5) * 8;
+    int n = canon_col(layout, nb, lane & 31, N, n_heads, head_dim);
+    const uint16_t* src = (n < split ? w0 + (size_t)n * K : w1 + (size_t)(n - split) * K) + kt * 16 + (lane >> 5) * 8;
     uint4 v = *reinterpret_cast<const uint4*>(src);
-    size_t dst = (((size_t)nb * blk_stride + blk_off) * (K / 16) + kt) * 64 + lane;
-    *reinterpret_cast<uint4*>(wp + dst * 8) = v;
+    *reinterpret_cast<uint4*>(wp + idx * 8) = v;
 }
-void launch_pack_weight(const void* w, void* wp, int N, int K, int blk_stride, int blk_off, hipStream_t st) {
+void launch_pack_weight(const void* w0, const void* w1, int split, void* wp, int N, int K, int layout, int n_heads,
+                        int head_dim, hipStream_t st) {
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
-    hipLaunchKernelGGL(pack_weight_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t*)w,
-                       (uint16_t*)wp, N, K, blk_stride, blk_off);
+    hipLaunchKernelGGL(pack_weight_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t*)w0,
+                       (const uint16_t*)w1, split, (uint16_t*)wp, N, K, layout, n_heads, head_dim);
 }
 
 // f32 rows [rows][K] -> packed bf16 activation tiles (rows rounded up to 32 must be allocated)

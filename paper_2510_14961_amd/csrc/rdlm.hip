@@ -162,11 +162,11 @@ extern "C" int rdlm_destroy(rdlm_ctx* ctx) {
 }
 
 // copy (f32) or re-tile (bf16) a matrix [N,K] into library memory
-static int take_matrix(rdlm_ctx* ctx, const void* src, int N, int K, void** dst) {
+static int take_matrix(rdlm_ctx* ctx, const void* src, int N, int K, void** dst, int layout = WL_NATURAL) {
     size_t bytes = (size_t)N * K * ctx->esz;
     DALLOC(*dst, bytes, false);
     if (ctx->m.dtype == RDLM_F32) HIPCHK(hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, ctx->st));
-    else launch_pack_weight(src, *dst, N, K, 1, 0, ctx->st);
+    else launch_pack_weight(src, src, N, *dst, N, K, layout, ctx->m.n_heads, ctx->m.head_dim, ctx->st);
     return check_launch(ctx);
 }
 static int take_gain(rdlm_ctx* ctx, const void* src, int h, float** dst) {
@@ -192,19 +192,19 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     for (int l = 0; l < nl; ++l) {
         Layer& L = ctx->layers[l];
         if ((rc = take_gain(ctx, wp[wi++], h, &L.g1))) return rc;
-        if ((rc = take_matrix(ctx, wp[wi++], 3 * h, h, &L.wqkv))) return rc;
+        if ((rc = take_matrix(ctx, wp[wi++], 3 * h, h, &L.wqkv, WL_ROPE))) return rc;
         if ((rc = take_matrix(ctx, wp[wi++], h, h, &L.wo))) return rc;
         if ((rc = take_gain(ctx, wp[wi++], h, &L.g2))) return rc;
-        // gate and up as one [2F, h] matrix
+        // gate and up as one [2F, h] matrix (bf16: 16 gate rows and their 16 up rows per block)
         DALLOC(L.wgu, (size_t)2 * F * h * esz, false);
-        for (int part = 0; part < 2; ++part) {
-            char* dst = reinterpret_cast<char*>(L.wgu) + (size_t)part * F * h * esz;
-            if (m.dtype == RDLM_F32)
-                HIPCHK(hipMemcpyAsync(dst, wp[wi], (size_t)F * h * esz, hipMemcpyDeviceToDevice, ctx->st));
-            else
-                launch_pack_weight(wp[wi], L.wgu, F, h, 2, part, ctx->st);   // gate block j, up block j adjacent
-            ++wi;
+        if (m.dtype == RDLM_F32) {
+            for (int part = 0; part < 2; ++part)
+                HIPCHK(hipMemcpyAsync(reinterpret_cast<char*>(L.wgu) + (size_t)part * F * h * esz, wp[wi + part],
+                                      (size_t)F * h * esz, hipMemcpyDeviceToDevice, ctx->st));
+        } else {
+            launch_pack_weight(wp[wi], wp[wi + 1], F, L.wgu, 2 * F, h, WL_GU16, m.n_heads, m.head_dim, ctx->st);
         }
+        wi += 2;
         if ((rc = take_matrix(ctx, wp[wi++], h, F, &L.wd))) return rc;
         DALLOC(L.kc, cache_elems * esz, true);
         DALLOC(L.vc, cache_elems * esz, true);
@@ -308,10 +308,10 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     const bool split_ok = proj == PROJ_O || proj == PROJ_D || proj == PROJ_A;
     if (T == 1) {
         switch (proj) {
-            case PROJ_GU: g = {1, 2, 8, 2, 1}; break;
+            case PROJ_GU: g = {1, 5, 4, 2, 1}; break;
             case PROJ_HEAD: g = {1, 4, 4, 2, 1}; break;
             case PROJ_QKV: g = {1, 2, 2, 4, 1}; break;
-            case PROJ_D: g = {1, 4, 2, 2, 4}; break;
+            case PROJ_D: g = {1, 2, 8, 2, 3}; break;
             default: g = {1, 2, 2, 4, 8}; break;       // O, A
         }
         if (const char* p = getenv(kProjEnv[proj])) {
@@ -323,7 +323,6 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     } else {
         g = {4, proj == PROJ_GU ? 2 : 1, 4, 2, 4};
     }
-    if (proj == PROJ_GU && g.nb != 4) g.nb = 2;
     if (!split_ok) g.ksplit = 1;
     if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
         int kmax = std::max(1, (K / 16) / (g.waves * 4));
@@ -371,29 +370,18 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
     }
     GemmPlan g = plan_for(ctx, proj, N, K, T);
     GemmEpilogue epi;
+    epi.n_heads = m.n_heads; epi.head_dim = m.head_dim;
+    if (proj == PROJ_GU) epi.layout = WL_GU16;
+    if (proj == PROJ_QKV) epi.layout = WL_ROPE;
     if (!plain && proj == PROJ_GU) {
         epi.kind = EPI_SWIGLU;
         epi.act = ctx->abuf;
-    } else if (proj == PROJ_GU) {
-        epi.pair_interleaved = 1;
     } else if (!plain && proj == PROJ_QKV && rope_layer && !getenv("RDLM_NO_ROPE_FUSION")) {
-        // one workgroup per head: RoPE and the cache writes happen in the GEMM epilogue
+        // RoPE and the cache writes happen in the GEMM epilogue
         epi.kind = EPI_ROPE_KV;
         epi.q_out = ctx->q; epi.kc = rope_layer->kc; epi.vc = rope_layer->vc; epi.rope_table = ctx->rope_tab;
-        epi.n_heads = m.n_heads; epi.head_dim = m.head_dim; epi.seq_stride = (size_t)ctx->ctx_pad * h;
+        epi.seq_stride = (size_t)ctx->ctx_pad * h;
         epi.tiles = ctx->tiles;
-        const int nb = m.head_dim / 32;
-        if (T == 1) {
-            g = {1, nb, nb == 3 ? 8 : 4, nb == 1 ? 8 : (nb == 2 ? 4 : 1), 1};
-            if (const char* p = getenv("RDLM_PLAN_QKVR")) {
-                GemmPlan o = {1, nb, 0, 0, 1};
-                if (sscanf(p, "%d,%d", &o.waves, &o.unroll) == 2) g = o;
-            }
-        } else if (T <= 3) {
-            g = {2, nb, 4, nb == 1 ? 4 : 2, 1};
-        } else {
-            g = {4, nb, nb == 3 ? 2 : 4, 2, 1};
-        }
     } else if (!plain && proj == PROJ_HEAD && sa) {
         epi.kind = EPI_ARGMAX;
         epi.cand_val = ctx->cand_val; epi.cand_idx = ctx->cand_idx; epi.cand_stride = ctx->rows_pad;
@@ -414,9 +402,8 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
     }
     if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
-        g = {g.mt, epi.kind == EPI_SWIGLU ? 2 : 1, 4, 4, g.ksplit};
+        g = {g.mt, 1, 4, 4, g.ksplit};
         if (g.mt == 4) g.unroll = 2;
-        if (g.mt == 2 && g.nb == 2) g.unroll = 2;
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
         if (!ok) {
             fprintf(stderr, "rdlm: no GEMM kernel instance for plan {%d,%d,%d,%d} epilogue %d\n", g.mt, g.nb, g.waves,

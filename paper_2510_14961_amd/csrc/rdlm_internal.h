@@ -110,8 +110,11 @@ struct GemmPlan { int mt, nb, waves, unroll, ksplit; };
 
 // What the GEMM does with a finished output tile.
 enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3 };
+// Order of the output features inside the packed weight blocks (see canon_col in kernels_gemm.hip).
+enum { WL_NATURAL = 0, WL_GU16 = 1, WL_ROPE = 2 };
 struct GemmEpilogue {
     int kind = EPI_F32;
+    int layout = WL_NATURAL;          // weight block layout; EPI_F32 writes canonical columns
     void* act = nullptr;              // EPI_SWIGLU: packed bf16 activation [rows][F]
     float* cand_val = nullptr;        // EPI_ARGMAX: best score / token per (feature group, row)
     int32_t* cand_idx = nullptr;
@@ -120,15 +123,14 @@ struct GemmEpilogue {
     uint32_t k0 = 0, k1 = 0;
     int step = 0;
     const TileDesc* tiles = nullptr;
-    // EPI_ROPE_KV (QKV projection, one workgroup per head): rotate q and k, store q (bf16 rows),
-    // k and v into the layer's cache at the rows' positions
+    // EPI_ROPE_KV (QKV projection, WL_ROPE blocks): rotate q and k, store q (bf16 rows), k and v
+    // into the layer's cache at the rows' positions
     void* q_out = nullptr;
     void* kc = nullptr;
     void* vc = nullptr;
     const float* rope_table = nullptr;   // [rows][d/2] (cos, sin)
     int n_heads = 0, head_dim = 0;
     size_t seq_stride = 0;
-    int pair_interleaved = 0;         // EPI_F32 on the gate/up matrix: undo the block interleave in the output
     // Deferred RMSNorm: when row_ssq is set, the input rows were stored as x * gain without the
     // 1/rms factor; every output row is multiplied by 1/sqrt(sum_c row_ssq[row][c] / h + eps).
     const float* row_ssq = nullptr;
@@ -205,8 +207,9 @@ void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_g
 // f32: x [rows][K], w [N][K], out [rows][N]
 void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
-void launch_pack_weight(const void* w_canon /*bf16 [N][K]*/, void* w_packed, int N, int K, int blk_stride,
-                        int blk_off, hipStream_t st);
+// canonical bf16 rows [N][K] (rows < split from w0, the rest from w1) -> packed blocks in `layout`
+void launch_pack_weight(const void* w0, const void* w1, int split, void* w_packed, int N, int K, int layout,
+                        int n_heads, int head_dim, hipStream_t st);
 void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st);   // f32 rows -> packed bf16
 
 // attention -----------------------------------------------------------------------------------
