@@ -52,127 +52,17 @@ __host__ __device__ inline int canon_col(int layout, int blk, int f, int N, int 
     return blk * 32 + f;
 }
 
-template <int MT, int NB, int WAVES, int U, int EPI>
-__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
-    extern __shared__ float red[];                 // [WAVES][NB*MT*16][64]
-    constexpr int CW = (EPI == EPI_ARGMAX && WAVES > 1) ? WAVES : 1;
-    __shared__ float cand_v[CW][MT][32];
-    __shared__ int cand_i[CW][MT][32];
+// Finishing work of a workgroup that holds the sums of NB feature blocks x MT row tiles.
+// quad_sum(a, b, q, out[4]) returns accumulator registers 4q..4q+3 of (block a, row tile b) for this
+// lane: rows 8q + 4g + i of the weight block against activation row `col`.  The work is cut into
+// units of one register quad -- or, for the epilogues that pair row f of a block with row f + 16
+// (SwiGLU on WL_GU16 blocks, RoPE on WL_ROPE blocks), of quad q together with quad q + 2 -- and
+// wave w of the DEAL waves that share the sums takes the units u with u % DEAL == w.
+template <int MT, int NB, int WAVES, int DEAL, int EPI, class QuadSum, class CV, class CI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk)[NB], int t0, int n_tiles, int ks,
+                                              int grp, QuadSum quad_sum, CV& cand_v, CI& cand_i) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int bid = blockIdx.x;
-    const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
-    const int ks = bid % A.ksplit;
-    const int grp = bid / A.ksplit;
-    const int n_tiles = *A.n_tiles;
-    const int t0 = mc * MT;
-    if (t0 >= n_tiles) return;
-    const int nblk = A.N >> 5, K16 = A.K16;
-    // K range of this wave: K16 tiles split evenly over ksplit * WAVES slices
-    const int slices = A.ksplit * WAVES, sl = ks * WAVES + wave;
-    const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
-
-    f32x16 acc[NB][MT];
-#pragma unroll
-    for (int a = 0; a < NB; ++a)
-#pragma unroll
-        for (int b = 0; b < MT; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-    int blk[NB];
-    const bf16x8* wbase[NB];
-    const bf16x8* xbase[MT];
-#pragma unroll
-    for (int a = 0; a < NB; ++a) {
-        blk[a] = grp * NB + a;
-        int nb = min(blk[a], nblk - 1);             // a ragged last group re-reads a valid block
-        wbase[a] = A.wp + ((size_t)nb * K16) * 64 + lane;
-    }
-#pragma unroll
-    for (int b = 0; b < MT; ++b) {
-        int t = min(t0 + b, n_tiles - 1);
-        xbase[b] = A.xp + ((size_t)t * K16) * 64 + lane;
-    }
-
-    bf16x8 wa[U][NB], xa[U][MT], wb[U][NB], xb[U][MT];
-    auto load = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT], int kt) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int a = 0; a < NB; ++a) wv[u][a] = __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64);
-#pragma unroll
-            for (int b = 0; b < MT; ++b) xv[u][b] = xbase[b][(size_t)(kt + u) * 64];
-        }
-        __builtin_amdgcn_sched_barrier(0);          // all loads of the batch are issued before any MFMA
-    };
-    auto compute = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int a = 0; a < NB; ++a)
-#pragma unroll
-                for (int b = 0; b < MT; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv[u][b], acc[a][b], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    int kt = kbeg;
-    int batches = (kend - kbeg) / U;
-    if (batches > 0) {                              // double-buffered: one batch in flight while one is consumed
-        load(wa, xa, kt); kt += U;
-        int rem = batches - 1;
-        while (rem >= 2) {
-            load(wb, xb, kt); kt += U;
-            compute(wa, xa);
-            load(wa, xa, kt); kt += U;
-            compute(wb, xb);
-            rem -= 2;
-        }
-        if (rem == 1) {
-            load(wb, xb, kt); kt += U;
-            compute(wa, xa);
-            compute(wb, xb);
-        } else {
-            compute(wa, xa);
-        }
-    }
-    for (; kt < kend; ++kt) {
-#pragma unroll
-        for (int a = 0; a < NB; ++a) {
-            bf16x8 w = __builtin_nontemporal_load(wbase[a] + (size_t)kt * 64);
-#pragma unroll
-            for (int b = 0; b < MT; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xbase[b][(size_t)kt * 64], acc[a][b], 0, 0, 0);
-        }
-    }
-
-    // Cross-wave sum in a fixed order: every wave deposits its accumulators; the finishing work is
-    // dealt to the waves in units of one register quad (4 consecutive features of a block for
-    // the lane's row) -- or, for the epilogues that pair row f of a block with row f + 16 (SwiGLU,
-    // RoPE), of quad q together with quad q + 2.
-    constexpr int REGS = NB * MT * 16;
-    if (WAVES > 1) {
-#pragma unroll
-        for (int a = 0; a < NB; ++a)
-#pragma unroll
-            for (int b = 0; b < MT; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
-        __syncthreads();
-    }
-    auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (a * MT + b) * 16 + q * 4 + i;
-            if (WAVES > 1) {
-                float sum = 0.f;
-#pragma unroll
-                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
-                o[i] = sum;
-            } else {
-                o[i] = acc[a][b][q * 4 + i];
-            }
-        }
-    };
+    const int nblk = A.N >> 5;
     const int col = lane & 31, g = lane >> 5;
     constexpr bool PAIRED = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV);
     constexpr int UQ = PAIRED ? 2 : 4;
@@ -200,11 +90,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 #pragma unroll
     for (int unit = 0; unit < NB * MT * UQ; ++unit) {
         const int a = unit / (MT * UQ), b = (unit / UQ) % MT, q = unit % UQ;
-        if (WAVES > 1 && unit % WAVES != wave) continue;
+        if (DEAL > 1 && unit % DEAL != wave) continue;
         const int t = t0 + b;
         if (t >= n_tiles || blk[a] >= nblk) continue;
         const size_t row = (size_t)t * 32 + col;
-        // accumulator register 4q+i of lane (col, g) is row 8q + 4g + i of the weight block, for row `col`
         const int f0 = q * 8 + g * 4;
         float lo[4], hi[4];
         quad_sum(a, b, q, lo);
@@ -316,6 +205,256 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     }
 }
 
+template <int MT, int NB, int WAVES, int U, int EPI>
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
+    extern __shared__ float red[];                 // [WAVES][NB*MT*16][64]
+    constexpr int CW = (EPI == EPI_ARGMAX && WAVES > 1) ? WAVES : 1;
+    __shared__ float cand_v[CW][MT][32];
+    __shared__ int cand_i[CW][MT][32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int bid = blockIdx.x;
+    const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
+    const int ks = bid % A.ksplit;
+    const int grp = bid / A.ksplit;
+    const int n_tiles = *A.n_tiles;
+    const int t0 = mc * MT;
+    if (t0 >= n_tiles) return;
+    const int nblk = A.N >> 5, K16 = A.K16;
+    // K range of this wave: K16 tiles split evenly over ksplit * WAVES slices
+    const int slices = A.ksplit * WAVES, sl = ks * WAVES + wave;
+    const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
+
+    f32x16 acc[NB][MT];
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    int blk[NB];
+    const bf16x8* wbase[NB];
+    const bf16x8* xbase[MT];
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+        blk[a] = grp * NB + a;
+        int nb = min(blk[a], nblk - 1);             // a ragged last group re-reads a valid block
+        wbase[a] = A.wp + ((size_t)nb * K16) * 64 + lane;
+    }
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+        int t = min(t0 + b, n_tiles - 1);
+        xbase[b] = A.xp + ((size_t)t * K16) * 64 + lane;
+    }
+
+    bf16x8 wa[U][NB], xa[U][MT], wb[U][NB], xb[U][MT];
+    auto load = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT], int kt) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int a = 0; a < NB; ++a) wv[u][a] = __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64);
+#pragma unroll
+            for (int b = 0; b < MT; ++b) xv[u][b] = xbase[b][(size_t)(kt + u) * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);          // all loads of the batch are issued before any MFMA
+    };
+    auto compute = [&](bf16x8(&wv)[U][NB], bf16x8(&xv)[U][MT]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv[u][b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = kbeg;
+    int batches = (kend - kbeg) / U;
+    if (batches > 0) {                              // double-buffered: one batch in flight while one is consumed
+        load(wa, xa, kt); kt += U;
+        int rem = batches - 1;
+        while (rem >= 2) {
+            load(wb, xb, kt); kt += U;
+            compute(wa, xa);
+            load(wa, xa, kt); kt += U;
+            compute(wb, xb);
+            rem -= 2;
+        }
+        if (rem == 1) {
+            load(wb, xb, kt); kt += U;
+            compute(wa, xa);
+            compute(wb, xb);
+        } else {
+            compute(wa, xa);
+        }
+    }
+    for (; kt < kend; ++kt) {
+#pragma unroll
+        for (int a = 0; a < NB; ++a) {
+            bf16x8 w = __builtin_nontemporal_load(wbase[a] + (size_t)kt * 64);
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xbase[b][(size_t)kt * 64], acc[a][b], 0, 0, 0);
+        }
+    }
+
+    // Cross-wave sum in a fixed order: every wave deposits its accumulators; the finishing work is
+    // dealt to the waves in units of one register quad (see gemm_epilogue).
+    constexpr int REGS = NB * MT * 16;
+    if (WAVES > 1) {
+#pragma unroll
+        for (int a = 0; a < NB; ++a)
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
+        __syncthreads();
+    }
+    auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = (a * MT + b) * 16 + q * 4 + i;
+            if (WAVES > 1) {
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
+                o[i] = sum;
+            } else {
+                o[i] = acc[a][b][q * 4 + i];
+            }
+        }
+    };
+    gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, quad_sum, cand_v, cand_i);
+}
+
+// Row-tile-sharing variant for steps with several row tiles (wide windows, ragged batches,
+// prefill).  The waves of a workgroup own different feature blocks (NB each) over the same K range
+// and the same MT row tiles; the activation tiles of a K step are staged once per workgroup in
+// LDS (three stages, 1 KiB per tile, read back with conflict-free 16-byte reads), so the
+// activation traffic per weight byte drops by the number of waves, and every wave streams its own
+// weights straight into registers.  No cross-wave reduction: a wave finishes its own blocks.
+// Workgroups of one (feature group, K split) that cover different row chunks get ids that land on
+// the same XCD one after the other, so the weights they share are served by that XCD's L2.
+template <int MT, int NB, int WAVES, int KU, int EPI>
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
+    extern __shared__ float red[];                 // activation stages: [3][KU * MT][64] x 16 bytes
+    bf16x8* xs = reinterpret_cast<bf16x8*>(red);
+    constexpr int CW = EPI == EPI_ARGMAX ? WAVES : 1;
+    __shared__ float cand_v[CW][MT][32];
+    __shared__ int cand_i[CW][MT][32];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // id = xcd + 8 * (row chunk + m_chunks * j): (group, split) index gk = 8 j + xcd
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int mc = rest % A.m_chunks, gk = (rest / A.m_chunks) * 8 + xcd;
+    if (gk >= A.n_groups * A.ksplit) return;
+    const int ks = gk % A.ksplit, grp = gk / A.ksplit;
+    const int n_tiles = *A.n_tiles;
+    const int t0 = mc * MT;
+    if (t0 >= n_tiles) return;
+    const int nblk = A.N >> 5, K16 = A.K16;
+    const int kbeg = (int)(((long long)K16 * ks) / A.ksplit), kend = (int)(((long long)K16 * (ks + 1)) / A.ksplit);
+
+    f32x16 acc[NB][MT];
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    int blk[NB];
+    const bf16x8* wbase[NB];
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+        blk[a] = (grp * WAVES + wave) * NB + a;
+        wbase[a] = A.wp + ((size_t)min(blk[a], nblk - 1) * K16) * 64 + lane;
+    }
+    // staging: tile ti = u * MT + b of a K step; thread slot i covers tile wave + i * WAVES
+    constexpr int XL = (KU * MT + WAVES - 1) / WAVES;
+    const bf16x8* xsrc[XL];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {
+        const int ti = wave + i * WAVES, u = ti / MT, b = ti - u * MT;
+        const int t = min(t0 + b, n_tiles - 1);
+        xsrc[i] = A.xp + ((size_t)t * K16 + u) * 64 + lane;
+    }
+    const bool stream_w = A.m_chunks == 1;          // weights used once: keep them out of the caches
+
+    bf16x8 w0[KU][NB], w1[KU][NB], w2[KU][NB], xr[XL];
+    // activations first: the staging store then waits for them only, and the weight loads issued
+    // after them stay in flight (the memory counter retires loads in issue order)
+    auto load = [&](bf16x8(&wv)[KU][NB], int kt) {  // activations and weights of the K step at kt
+        const int kc = min(KU, kend - kt);
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int ti = wave + i * WAVES;
+            if (ti < KU * MT && ti / MT < kc) xr[i] = xsrc[i][(size_t)kt * 64];
+        }
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            if (u < kc) {
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    wv[u][a] = stream_w ? __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64)
+                                        : wbase[a][(size_t)(kt + u) * 64];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int ti = wave + i * WAVES;
+            if (ti < KU * MT) xs[((size_t)buf * KU * MT + ti) * 64 + lane] = xr[i];
+        }
+    };
+    auto compute = [&](bf16x8(&wv)[KU][NB], int buf, int kt) {
+        const int kc = min(KU, kend - kt);
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            if (u < kc) {
+#pragma unroll
+                for (int b = 0; b < MT; ++b) {
+                    const bf16x8 xv = xs[((size_t)buf * KU * MT + u * MT + b) * 64 + lane];
+#pragma unroll
+                    for (int a = 0; a < NB; ++a)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv, acc[a][b], 0, 0, 0);
+                }
+            }
+        }
+    };
+    // K step s uses weight registers s % 3 and stage buffer s % 3.  Its loads are issued at the top
+    // of step s - 2; its activation tiles go from registers to LDS at the top of step s - 1 (that
+    // buffer was last read in step s - 3, which every wave has left two barriers ago) and are read
+    // after the barrier that ends step s - 1.
+    auto step = [&](bf16x8(&wcur)[KU][NB], bf16x8(&wnext)[KU][NB], int bcur, int kt) {
+        if (kt + KU < kend) stage(bcur == 2 ? 0 : bcur + 1);
+        if (kt + 2 * KU < kend) load(wnext, kt + 2 * KU);
+        compute(wcur, bcur, kt);
+        __syncthreads();
+    };
+    int kt = kbeg;
+    if (kt < kend) {
+        load(w0, kt);
+        stage(0);
+        if (kt + KU < kend) load(w1, kt + KU);
+        __syncthreads();
+        while (true) {
+            step(w0, w2, 0, kt); kt += KU;
+            if (kt >= kend) break;
+            step(w1, w0, 1, kt); kt += KU;
+            if (kt >= kend) break;
+            step(w2, w1, 2, kt); kt += KU;
+            if (kt >= kend) break;
+        }
+    }
+    auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = acc[a][b][q * 4 + i];
+    };
+    gemm_epilogue<MT, NB, WAVES, 1, EPI>(A, blk, t0, n_tiles, ks, grp, quad_sum, cand_v, cand_i);
+}
+
 // one candidate (score, token) per (feature group, row) -> the row's token; lowest id wins ties
 __global__ void argmax_final_k(const float* cand_val, const int32_t* cand_idx, int n_groups, size_t cand_stride,
                                int32_t* tok_out, const int32_t* n_tiles) {
@@ -375,14 +514,69 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
     return true;
 }
 
+template <int MT, int NB, int WAVES, int KU, int EPI>
+static bool launch_rows_cfg(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride, int ksplit,
+                            const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    const int nblk = N / 32;
+    const int groups = (nblk + NB * WAVES - 1) / (NB * WAVES);
+    const int m_chunks = (max_tiles + MT - 1) / MT;
+    const size_t lds = (size_t)3 * KU * MT * 1024;
+    auto kern = gemm_bf16_rows_k<MT, NB, WAVES, KU, EPI>;
+    if (lds > 64 * 1024) {
+        static bool raised = false, ok = false;
+        if (!raised) {
+            raised = true;
+            ok = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)lds) == hipSuccess;
+            if (!ok) (void)hipGetLastError();
+        }
+        if (!ok) return false;
+    }
+    GemmArgs a;
+    a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
+    a.m_chunks = m_chunks; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
+    const int gk8 = (groups * ksplit + 7) / 8 * 8;
+    hipLaunchKernelGGL(kern, dim3(gk8 * m_chunks), dim3(WAVES * 64), lds, st, a);
+    return true;
+}
+
 int gemm_groups(int N, const GemmPlan& plan, int epi_kind) {
     const int nblk = N / 32;
     (void)epi_kind;
-    return (nblk + plan.nb - 1) / plan.nb;
+    const int per = plan.kind == GEMM_ROWS ? plan.nb * plan.waves : plan.nb;
+    return (nblk + per - 1) / per;
+}
+
+static bool launch_gemm_rows(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
+                             GemmPlan plan, const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles,
+                             hipStream_t st) {
+#define RDLM_RCASE(MT_, NB_, W_, U_)                                                                             \
+    if (plan.mt == MT_ && plan.nb == NB_ && plan.waves == W_ && plan.unroll == U_) {                             \
+        if (epi.kind == EPI_F32)                                                                                 \
+            return launch_rows_cfg<MT_, NB_, W_, U_, EPI_F32>(xp, wp, out, N, K, part_stride, plan.ksplit, epi,  \
+                                                              n_tiles, max_tiles, st);                           \
+        if (epi.kind == EPI_ARGMAX)                                                                              \
+            return launch_rows_cfg<MT_, NB_, W_, U_, EPI_ARGMAX>(xp, wp, out, N, K, part_stride, 1, epi,         \
+                                                                 n_tiles, max_tiles, st);                        \
+        if (epi.kind == EPI_SWIGLU)                                                                              \
+            return launch_rows_cfg<MT_, NB_, W_, U_, EPI_SWIGLU>(xp, wp, out, N, K, part_stride, 1, epi,         \
+                                                                 n_tiles, max_tiles, st);                        \
+        if (epi.kind == EPI_ROPE_KV)                                                                             \
+            return launch_rows_cfg<MT_, NB_, W_, U_, EPI_ROPE_KV>(xp, wp, out, N, K, part_stride, 1, epi,        \
+                                                                  n_tiles, max_tiles, st);                       \
+        return false;                                                                                            \
+    }
+    RDLM_RCASE(2, 1, 4, 8) RDLM_RCASE(2, 1, 4, 4) RDLM_RCASE(2, 2, 4, 4) RDLM_RCASE(2, 2, 4, 2) RDLM_RCASE(2, 1, 8, 4)
+    RDLM_RCASE(4, 1, 4, 4) RDLM_RCASE(4, 1, 4, 2) RDLM_RCASE(4, 2, 4, 4) RDLM_RCASE(4, 2, 4, 2) RDLM_RCASE(4, 1, 8, 4)
+    RDLM_RCASE(8, 1, 4, 4) RDLM_RCASE(8, 1, 4, 2) RDLM_RCASE(8, 2, 4, 4) RDLM_RCASE(8, 2, 4, 2) RDLM_RCASE(8, 1, 8, 2)
+#undef RDLM_RCASE
+    return false;
 }
 
 bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
                       GemmPlan plan, const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    if (plan.kind == GEMM_ROWS)
+        return launch_gemm_rows(xp, wp, out, N, K, part_stride, plan, epi, n_tiles, max_tiles, st);
 #define RDLM_CASE(MT_, NB_, W_, U_)                                                                              \
     if (plan.mt == MT_ && plan.nb == NB_ && plan.waves == W_ && plan.unroll == U_) {                             \
         if (epi.kind == EPI_F32)                                                                                 \
@@ -403,8 +597,6 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
     RDLM_CASE(1, NB_, 2, 4) RDLM_CASE(1, NB_, 2, 8) RDLM_CASE(1, NB_, 4, 2) RDLM_CASE(1, NB_, 4, 4)              \
     RDLM_CASE(1, NB_, 8, 1) RDLM_CASE(1, NB_, 8, 2)
     RDLM_ROW(1) RDLM_ROW(2) RDLM_ROW(3) RDLM_ROW(4) RDLM_ROW(5)
-    RDLM_CASE(2, 1, 4, 4) RDLM_CASE(2, 2, 4, 2) RDLM_CASE(2, 2, 4, 4) RDLM_CASE(2, 1, 4, 8) RDLM_CASE(2, 3, 4, 2)
-    RDLM_CASE(4, 1, 4, 2) RDLM_CASE(4, 1, 4, 4) RDLM_CASE(4, 2, 4, 2) RDLM_CASE(4, 2, 2, 2)
 #undef RDLM_ROW
 #undef RDLM_CASE
     return false;

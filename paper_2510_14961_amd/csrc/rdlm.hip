@@ -298,11 +298,14 @@ extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, 
 enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT };
 static const char* kProjEnv[PROJ_COUNT] = {"RDLM_PLAN_QKV", "RDLM_PLAN_O", "RDLM_PLAN_GU",
                                            "RDLM_PLAN_D", "RDLM_PLAN_A", "RDLM_PLAN_HEAD"};
+static const char* kProjEnvRows[PROJ_COUNT] = {"RDLM_PLANR_QKV", "RDLM_PLANR_O", "RDLM_PLANR_GU",
+                                               "RDLM_PLANR_D", "RDLM_PLANR_A", "RDLM_PLANR_HEAD"};
 
 // Launch shape of a projection for T row tiles: {row tiles per workgroup, feature blocks per
-// workgroup, waves, k tiles fetched per batch, split of K across workgroups}.  The defaults come
-// from sweeps on MI355X at the 3.5B shape; RDLM_PLAN_<proj>="nb,waves,unroll,ksplit" overrides the
-// one-tile case (tuning aid).
+// workgroup (per wave for the row-sharing kernel), waves, k tiles fetched per batch, split of K
+// across workgroups, kernel kind}.  The defaults come from sweeps on MI355X at the 3.5B shape;
+// RDLM_PLAN_<proj>="nb,waves,unroll,ksplit" overrides the one-tile case and
+// RDLM_PLANR_<proj>="mt,nb,waves,unroll,ksplit" the several-tile case (tuning aids).
 static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     GemmPlan g;
     const bool split_ok = proj == PROJ_O || proj == PROJ_D || proj == PROJ_A;
@@ -318,14 +321,25 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             GemmPlan o = {1, 0, 0, 0, 0};
             if (sscanf(p, "%d,%d,%d,%d", &o.nb, &o.waves, &o.unroll, &o.ksplit) == 4) g = o;
         }
-    } else if (T <= 3) {
-        g = {2, proj == PROJ_GU ? 2 : 1, 4, proj == PROJ_GU ? 2 : 4, 4};
     } else {
-        g = {4, proj == PROJ_GU ? 2 : 1, 4, 2, 4};
+        // several row tiles: the row-sharing kernel.  Shapes from sweeps at 64..4096 rows: small
+        // row chunks win while the step is bound by weight streaming (more workgroups in flight;
+        // chunks of one feature group run back to back on one XCD and share the weights in its L2)
+        if (T <= 2) g = {2, 1, 4, 8, 8, GEMM_ROWS};
+        else if (T <= 4) g = {proj == PROJ_HEAD ? 4 : 2, 1, 4, proj == PROJ_QKV ? 8 : 4, 8, GEMM_ROWS};
+        else if (T <= 8 && proj == PROJ_QKV) g = {2, 1, 4, 8, 1, GEMM_ROWS};
+        else g = {4, 1, 4, 4, 1, GEMM_ROWS};
+        if (const char* p = getenv(kProjEnvRows[proj])) {
+            GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
+            if (sscanf(p, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) g = o;
+        } else if (split_ok && T > 4) {
+            const int groups = gemm_groups(N, g, EPI_F32) * ((T + g.mt - 1) / g.mt);
+            g.ksplit = std::max(1, std::min(8, (640 + groups - 1) / groups));
+        }
     }
     if (!split_ok) g.ksplit = 1;
     if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
-        int kmax = std::max(1, (K / 16) / (g.waves * 4));
+        int kmax = std::max(1, (K / 16) / ((g.kind == GEMM_ROWS ? 1 : g.waves) * 4));
         g.ksplit = std::max(1, std::min(std::min(g.ksplit, 8), kmax));
     }
     return g;
@@ -402,8 +416,8 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
     }
     if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
-        g = {g.mt, 1, 4, 4, g.ksplit};
-        if (g.mt == 4) g.unroll = 2;
+        if (g.mt > 1) g = {g.mt, 1, 4, g.mt == 2 ? 8 : 4, 1, GEMM_ROWS};
+        else g = {1, 1, 4, 4, g.ksplit};
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
         if (!ok) {
             fprintf(stderr, "rdlm: no GEMM kernel instance for plan {%d,%d,%d,%d} epilogue %d\n", g.mt, g.nb, g.waves,

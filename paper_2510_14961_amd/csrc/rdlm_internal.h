@@ -106,7 +106,10 @@ __host__ __device__ inline float u24_open(uint32_t x) {
 // ---------------------------------------------------------------------------------------------
 // Launchers (defined in the kernel sources).  All enqueue on `st`; none synchronises.
 
-struct GemmPlan { int mt, nb, waves, unroll, ksplit; };
+// kind GEMM_STREAM: the waves of a workgroup split K (one row-tile group, weights streamed once);
+// kind GEMM_ROWS: the waves own different feature blocks and share the activation tiles through LDS.
+enum { GEMM_STREAM = 0, GEMM_ROWS = 1 };
+struct GemmPlan { int mt, nb, waves, unroll, ksplit, kind = GEMM_STREAM; };
 
 // What the GEMM does with a finished output tile.
 enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3 };
