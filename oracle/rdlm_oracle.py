@@ -324,6 +324,32 @@ class Trace:
         self.deltas: List[np.ndarray] = []
 
 
+def noise_level(beta: float, steps_done: int, n_steps: int) -> float:
+    """beta_t of Eq. 2, scheduled linearly in the sampler steps a position has already received
+    (Sec. 3.4: "the latter steps are naturally less noisy"): beta on a position's first step,
+    falling by beta / n_steps per step, where n_steps = ceil(r / r') is the number of steps a
+    position stays in flight under the fixed exit rule (the cap, for the adaptive rule)."""
+    return beta * max(0.0, 1.0 - steps_done / float(n_steps))
+
+
+def mix_noise(z: np.ndarray, level: float, position: int, seq: int, step: int, alpha: float,
+              seed: int) -> np.ndarray:
+    """z' = (1 - beta_t) z + beta_t z_noise, z_noise = InitState(1, alpha) drawn afresh at every
+    sampler step (Eq. 2; Alg. 1 lines 6-7): counter (., position, seq, step) tagged TAG_NOISE."""
+    if level == 0.0:
+        return z
+    noise = init_state(z.shape[0], position, seq, alpha, seed, step=step, tag=TAG_NOISE)
+    return (1.0 - level) * z + level * noise
+
+
+def momentum(e_new: np.ndarray, e_prev: Optional[np.ndarray], eta: float) -> np.ndarray:
+    """e = eta e_prev + (1 - eta) P(y_current) (Eq. 1).  A position that has no previous
+    conditioning yet (its first sampler step) takes P(y_current) as it is."""
+    if e_prev is None or eta == 0.0:
+        return e_new
+    return eta * e_prev + (1.0 - eta) * e_new
+
+
 def generate_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray, n_new: int, r: int,
                             alpha: float = 1.0, temperature: float = 0.0, seed: int = 1,
                             seq: int = 0, r_prefill: Optional[int] = None) -> Trace:
@@ -389,8 +415,10 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
                                r_inner: int, r: int, alpha: float = 1.0,
                                temperature: float = 0.0, seed: int = 1, seq: int = 0,
                                headway: int = 1, pad_token: int = 0, T: Optional[int] = None,
-                               r_prefill: Optional[int] = None, hook=None) -> Trace:
-    """Alg. 1: diffusion-forcing sampler with the fixed exit rule (beta_t = 0, eta = 0).
+                               r_prefill: Optional[int] = None, hook=None, eta: float = 0.0,
+                               beta: float = 0.0) -> Trace:
+    """Alg. 1: diffusion-forcing sampler with the fixed exit rule; optional momentum on the
+    conditioning (Eq. 1, eta) and scheduled state noise (Eq. 2, beta).
 
     y_current is kept as one array over absolute positions: frozen tokens, then the drafts of the
     in-flight positions, then pad tokens for headway positions that have no draft yet.  The
@@ -408,6 +436,8 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
     z_pos: List[int] = [L - 1]
     z: List[np.ndarray] = [init_state(model.h, L - 1, seq, alpha, seed)]
     count: List[int] = [0]
+    e_prev: Dict[int, np.ndarray] = {}
+    n_steps = -(-r // r_inner)
     tr = Trace()
     t = 0
     while T is None or t < T:
@@ -415,7 +445,12 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
         pos = np.asarray(z_pos)
         tr.window_sizes.append(len(z_pos))
         e = model.prelude(y[pos], pos, cache)                # e <- P(y_current)
-        zz = np.stack(z)
+        e = np.stack([momentum(e[i], e_prev.get(p), eta) for i, p in enumerate(z_pos)])
+        for i, p in enumerate(z_pos):
+            e_prev[p] = e[i]
+        # z <- (1 - beta_t) z + beta_t z_noise
+        zz = np.stack([mix_noise(z[i], noise_level(beta, count[i], n_steps), p, seq, t, alpha, seed)
+                       for i, p in enumerate(z_pos)])
         for _ in range(r_inner):                             # inner recurrence
             zz = model.core(e, zz, pos, cache)
         count = [c + 1 for c in count]
@@ -424,7 +459,7 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
             y[p + 1] = sample(logits[i], temperature, p, seq, t, seed)
         z = [zz[i] for i in range(len(z_pos))]
         if hook is not None:
-            hook(t, list(z_pos), zz, logits, y.copy())
+            hook(t, list(z_pos), zz, logits, y.copy(), e)
         # freeze completed tokens: states that have had r recurrences (always a prefix)
         k = 0
         while k < len(z_pos) and count[k] * r_inner >= r:
@@ -454,8 +489,11 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
                                         alpha: float = 1.0, temperature: float = 0.0,
                                         seed: int = 1, seq: int = 0, headway: int = 1,
                                         pad_token: int = 0, T: Optional[int] = None,
-                                        r_prefill: Optional[int] = None, hook=None) -> Trace:
-    """Alg. 2: diffusion-forcing sampler with latent-difference freezing and a wavefront limit.
+                                        r_prefill: Optional[int] = None, hook=None,
+                                        eta: float = 0.0, beta: float = 0.0) -> Trace:
+    """Alg. 2: diffusion-forcing sampler with latent-difference freezing and a wavefront limit;
+    optional momentum (Eq. 1) and scheduled state noise (Eq. 2; delta_i still compares the state
+    after the recurrences with the state the previous step ended on, before any noise).
 
     After the r' recurrences of a step, delta_i compares each state with what it was at the end of
     the previous step (a new state's previous value is its random initialisation).  The longest
@@ -473,6 +511,8 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
     z: List[np.ndarray] = [init_state(model.h, L - 1, seq, alpha, seed)]
     z_prev: List[np.ndarray] = [z[0]]
     count: List[int] = [0]
+    e_prev: Dict[int, np.ndarray] = {}
+    n_steps = -(-r_cap // r_inner)
     tr = Trace()
     t = 0
     while T is None or t < T:
@@ -480,7 +520,11 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
         pos = np.asarray(z_pos)
         tr.window_sizes.append(len(z_pos))
         e = model.prelude(y[pos], pos, cache)
-        zz = np.stack(z)
+        e = np.stack([momentum(e[i], e_prev.get(p), eta) for i, p in enumerate(z_pos)])
+        for i, p in enumerate(z_pos):
+            e_prev[p] = e[i]
+        zz = np.stack([mix_noise(z[i], noise_level(beta, count[i], n_steps), p, seq, t, alpha, seed)
+                       for i, p in enumerate(z_pos)])
         for _ in range(r_inner):
             zz = model.core(e, zz, pos, cache)
         count = [c + 1 for c in count]
@@ -491,7 +535,7 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
         tr.deltas.append(d)
         z = [zz[i] for i in range(len(z_pos))]
         if hook is not None:
-            hook(t, list(z_pos), zz, logits, y.copy())
+            hook(t, list(z_pos), zz, logits, y.copy(), e)
         k = k_star(freezable_flags(d, count, r_inner, eps, r_cap))
         for i in range(k):
             tr.final_states[z_pos[i]] = z[i]

@@ -178,3 +178,116 @@ def test_streams_are_not_degenerate(tiny):
     p2[3] = (p2[3] + 1) % 256
     tr2 = O.generate_diffusion_forcing(m, p2, 32, 1, 4)
     assert (tr.tokens[16:] != tr2.tokens[16:]).sum() >= 2
+
+
+# ---------------------------------------------------------------------------------------------
+# Stabilising components (Sec. 3.4): momentum on the conditioning (Eq. 1), state noise (Eq. 2)
+
+def test_noise_schedule_is_linear_and_ends_low():
+    """Sec. 3.4: beta_t falls linearly with the steps a position has received."""
+    levels = [O.noise_level(0.5, c, 8) for c in range(8)]
+    assert levels[0] == 0.5
+    assert np.allclose(np.diff(levels), -0.5 / 8)
+    assert all(l > 0 for l in levels) and O.noise_level(0.5, 8, 8) == 0.0 and O.noise_level(0.5, 11, 8) == 0.0
+    assert O.noise_level(0.0, 0, 8) == 0.0
+
+
+def test_mix_noise_is_the_convex_combination_of_eq_2():
+    z = np.linspace(-1, 1, 128)
+    zn = O.init_state(128, 9, 2, 0.7, 5, step=3, tag=O.TAG_NOISE)
+    out = O.mix_noise(z, 0.25, 9, 2, 3, 0.7, 5)
+    assert np.allclose(out, 0.75 * z + 0.25 * zn, rtol=0, atol=1e-15)
+    assert O.mix_noise(z, 0.0, 9, 2, 3, 0.7, 5) is z
+    assert np.array_equal(O.mix_noise(z, 1.0, 9, 2, 3, 0.7, 5), zn)
+    # the noise stream is its own: not the InitState draw of the same position, and new every step
+    assert not np.allclose(zn, O.init_state(128, 9, 2, 0.7, 5))
+    assert not np.allclose(zn, O.init_state(128, 9, 2, 0.7, 5, step=4, tag=O.TAG_NOISE))
+
+
+def test_momentum_is_an_exponential_average_of_the_preludes(tiny):
+    """Eq. 1 unrolled: e_k = eta^k P_0 + (1 - eta) sum_{j=1..k} eta^(k-j) P_j over the steps a
+    position has been in flight (P_j = its raw prelude output at step j)."""
+    eta = 0.3
+    rng = np.random.default_rng(0)
+    P = rng.standard_normal((5, 16))
+    e = None
+    for k in range(5):
+        e = O.momentum(P[k], e, eta)
+        want = eta ** k * P[0] + (1 - eta) * sum(eta ** (k - j) * P[j] for j in range(1, k + 1))
+        assert np.allclose(e, want, rtol=0, atol=1e-14)
+    assert np.array_equal(O.momentum(P[1], P[0], 0.0), P[1])
+    # in the sampler: the first state reads the last prompt token, which never changes, so its
+    # conditioning stays P(token) for any eta; later positions see changing drafts and do move
+    _, m, prompt = tiny
+    seen = {}
+
+    def hook(t, z_pos, zz, logits, y, e):
+        for i, p in enumerate(z_pos):
+            seen.setdefault(p, []).append(e[i].copy())
+
+    O.generate_diffusion_forcing(m, prompt, 6, 1, 4, seed=2, eta=eta, hook=hook)
+    first = seen[len(prompt) - 1]
+    assert len(first) == 4
+    for k in range(1, len(first)):
+        assert np.allclose(first[k], first[0], rtol=0, atol=1e-12)
+    plain = {}
+
+    def hook0(t, z_pos, zz, logits, y, e):
+        for i, p in enumerate(z_pos):
+            plain.setdefault(p, []).append(e[i].copy())
+
+    O.generate_diffusion_forcing(m, prompt, 6, 1, 4, seed=2, eta=0.0, hook=hook0)
+    later = len(prompt) + 1
+    assert np.allclose(seen[later][0], plain[later][0])          # first step of a position: no memory
+    assert any(not np.allclose(a, b) for a, b in zip(seen[later][1:], plain[later][1:]))
+
+
+def test_eta_and_beta_zero_change_nothing(tiny):
+    _, m, prompt = tiny
+    a = O.generate_diffusion_forcing(m, prompt, 8, 1, 4, seed=2)
+    b = O.generate_diffusion_forcing(m, prompt, 8, 1, 4, seed=2, eta=0.0, beta=0.0)
+    _same_run(a, b)
+
+
+def test_momentum_and_noise_change_the_run_but_not_its_shape(tiny):
+    _, m, prompt = tiny
+    base = O.generate_diffusion_forcing(m, prompt, 8, 1, 4, seed=2)
+    for kw in (dict(eta=0.5), dict(beta=0.5), dict(eta=0.1, beta=0.3)):
+        tr = O.generate_diffusion_forcing(m, prompt, 8, 1, 4, seed=2, **kw)
+        assert tr.steps == base.steps and tr.window_sizes == base.window_sizes
+        assert any(not np.allclose(tr.final_states[p], base.final_states[p]) for p in base.final_states)
+
+
+def test_full_noise_with_window_one_is_autoregressive_from_the_noise_draw(tiny):
+    """r' = r (window 1, one step per position) with beta = 1: the state a position starts from is
+    exactly the TAG_NOISE draw of that step, so the run equals an autoregressive loop seeded with
+    those draws."""
+    _, m, prompt = tiny
+    r, n_new, seed = 3, 5, 7
+    tr = O.generate_diffusion_forcing(m, prompt, n_new, r, r, seed=seed, beta=1.0)
+    L = len(prompt)
+    cache = m.new_cache(L + n_new + 4)
+    y = list(int(t) for t in prompt)
+    m.prefill(np.asarray(y[: L - 1]), r, 1.0, seed, 0, cache)
+    for t in range(1, n_new + 1):
+        p = len(y) - 1
+        pos = np.array([p])
+        s = O.init_state(m.h, p, 0, 1.0, seed, step=t, tag=O.TAG_NOISE)[None, :]
+        e = m.prelude(np.array([y[p]]), pos, cache)
+        for _ in range(r):
+            s = m.core(e, s, pos, cache)
+        y.append(O.sample(m.coda(s, pos, cache)[0], 0.0, p, 0, t, seed))
+        assert np.allclose(tr.final_states[p], s[0], rtol=0, atol=1e-12)
+    assert np.array_equal(tr.tokens, np.asarray(y))
+
+
+def test_adaptive_sampler_takes_momentum_and_noise(tiny_conditioned):
+    """Alg. 2 with eta, beta: delta_i still compares against the noise-free end of the previous
+    step, so with beta > 0 a state needs more steps to pass the threshold (or runs to the cap)."""
+    _, m, prompt = tiny_conditioned
+    kw = dict(r_inner=1, r_cap=12, eps=0.05, w_max=6, seed=4)
+    a = O.generate_diffusion_forcing_adaptive(m, prompt, 6, **kw)
+    b = O.generate_diffusion_forcing_adaptive(m, prompt, 6, beta=0.5, **kw)
+    assert sum(b.recurrences.values()) > sum(a.recurrences.values())
+    c = O.generate_diffusion_forcing_adaptive(m, prompt, 6, eta=0.0, beta=0.0, **kw)
+    _same_run(a, c)
