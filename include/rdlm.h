@@ -62,7 +62,14 @@ typedef struct {
  * r_total recurrences, is frozen, and states are appended only while fewer than w_max are in
  * flight (Alg. 2, Eq. 3).  headway states are appended per step (Sec. 4.2); those beyond the
  * first read pad_token until a draft exists.  temperature 0 = greedy (lowest id wins ties),
- * otherwise Gumbel-max sampling from softmax(logits / temperature). */
+ * otherwise Gumbel-max sampling from softmax(logits / temperature).
+ * Stabilising components (Sec. 3.4), both off at 0:
+ *   eta  -- momentum on the conditioning, e = eta e_prev + (1 - eta) P(y_current) (Eq. 1), per
+ *           position; a position's first step takes P(y_current) as it is.
+ *   beta -- state noise before the inner recurrences, z <- (1 - b) z + b z_noise (Eq. 2) with
+ *           z_noise = InitState(1, alpha) drawn afresh each step (generator tag 3, counter
+ *           includes the step) and b = beta * max(0, 1 - c / ceil(r_total / r_inner)) for a
+ *           position that has had c sampler steps (linear schedule, later steps less noisy). */
 typedef struct {
     int32_t n_new;        /* N: tokens to generate per sequence                                   */
     int32_t r_inner;      /* r'                                                                   */
@@ -74,7 +81,9 @@ typedef struct {
     float alpha;          /* init scale of InitState                                              */
     float temperature;
     int32_t pad_token;
-    uint64_t seed;        /* key of the counter-based generator (state init, Gumbel noise)        */
+    float beta;           /* state-noise level of a position's first step, in [0, 1]              */
+    float eta;            /* momentum of the conditioning, in [0, 1)                              */
+    uint64_t seed;        /* key of the counter-based generator (state init, Gumbel, state noise) */
 } rdlm_sampler;
 
 /* Number of weight tensors rdlm_create expects, and their order:

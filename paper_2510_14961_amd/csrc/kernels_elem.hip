@@ -371,9 +371,9 @@ __global__ void swiglu_k(const float* gu, int S, size_t part_stride, void* act, 
 // ---------------------------------------------------------------------------------------------
 // InitState: four normals per Philox block through two Box-Muller pairs.
 __device__ inline void gauss4(uint32_t blk, uint32_t pos, uint32_t seq, uint32_t k0, uint32_t k1, float alpha,
-                              float out[4]) {
+                              float out[4], uint32_t c3 = TAG_INIT_STATE) {
     uint32_t x[4];
-    philox4x32_10(blk, pos, seq, TAG_INIT_STATE, k0, k1, x);
+    philox4x32_10(blk, pos, seq, c3, k0, k1, x);
     for (int p = 0; p < 2; ++p) {
         float ua = u24_open(x[2 * p]), ub = u24_open(x[2 * p + 1]);
         float rad = sqrtf(-2.0f * logf(ua));
@@ -412,6 +412,47 @@ __global__ void init_state_new_k(float* z, float* z_prev, int h, const SeqState*
         size_t o = ((size_t)s * max_positions + pos) * h + blk * 4 + i;
         z[o] = g[i];
         z_prev[o] = g[i];
+    }
+}
+
+// Momentum on the conditioning (Eq. 1), one workgroup per row.
+__global__ void momentum_k(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
+                           const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    if (j >= d.n_valid) return;
+    const size_t srow = (size_t)d.zrow0 + j;               // (sequence, position) row of the stores
+    const bool first = counts[srow] == 0;                   // no previous conditioning yet
+    float* er = e + ((size_t)d.erow0 + j) * h;
+    float* pr = e_store + srow * h;
+    for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+        float4 v = ld4(er + k);
+        if (!first) {
+            float4 p = ld4(pr + k);
+            v.x = eta * p.x + (1.0f - eta) * v.x; v.y = eta * p.y + (1.0f - eta) * v.y;
+            v.z = eta * p.z + (1.0f - eta) * v.z; v.w = eta * p.w + (1.0f - eta) * v.w;
+            *reinterpret_cast<float4*>(er + k) = v;
+        }
+        *reinterpret_cast<float4*>(pr + k) = v;
+    }
+}
+
+// Scheduled state noise (Eq. 2), one workgroup per row, in place on the latent store.
+__global__ void noise_mix_k(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
+                            uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles) {
+    int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    TileDesc d = tiles[t];
+    if (j >= d.n_valid) return;
+    const size_t srow = (size_t)d.zrow0 + j;
+    const float b = beta * fmaxf(0.0f, 1.0f - (float)counts[srow] / (float)n_steps);
+    if (b == 0.0f) return;
+    float* zr = z + srow * h;
+    for (int blk = threadIdx.x; blk * 4 < h; blk += blockDim.x) {
+        float g[4];
+        gauss4(blk, d.pos0 + j, d.seq, k0, k1, alpha, g, ((uint32_t)step << 4) | TAG_NOISE);
+        for (int i = 0; i < 4 && blk * 4 + i < h; ++i) zr[blk * 4 + i] = (1.0f - b) * zr[blk * 4 + i] + b * g[i];
     }
 }
 
@@ -640,6 +681,16 @@ void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs,
     int nb = (h + 3) / 4;
     hipLaunchKernelGGL(init_state_new_k, dim3((nb + 255) / 256, n_seqs * headway), dim3(256), 0, st, z, z_prev, h,
                        seqs, max_positions, headway, alpha, k0, k1);
+}
+void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
+                     const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(momentum_k, dim3(max_tiles * 32), dim3(256), 0, st, e, e_store, counts, eta, h, tiles, n_tiles);
+}
+void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
+                      uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                      hipStream_t st) {
+    hipLaunchKernelGGL(noise_mix_k, dim3(max_tiles * 32), dim3(256), 0, st, z, counts, beta, n_steps, alpha, k0, k1,
+                       step, h, tiles, n_tiles);
 }
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
                    int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,

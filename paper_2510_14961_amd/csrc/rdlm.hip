@@ -49,7 +49,7 @@ struct rdlm_ctx {
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
     int32_t* counts = nullptr;
-    float *z_store = nullptr, *z_prev = nullptr;
+    float *z_store = nullptr, *z_prev = nullptr, *e_store = nullptr;
     int32_t* n_active = nullptr;
     int32_t* n_active_host = nullptr;    // pinned
     SamplerParams sp;
@@ -252,6 +252,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->counts, (SP + 64) * 4, true);
     DALLOC(ctx->z_store, SP * h * 4, true);
     DALLOC(ctx->z_prev, SP * h * 4, true);
+    DALLOC(ctx->e_store, SP * h * 4, true);
     DALLOC(ctx->n_active, 64, true);
     HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&ctx->n_active_host), 64, hipHostMallocDefault));
     ctx->prompt_len.assign(ctx->max_seqs, 0);
@@ -649,7 +650,8 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     if (!ctx || !s || n_seqs < 1) return RDLM_EINVAL;
     if (n_seqs > ctx->max_seqs) return RDLM_ECAPACITY;
     if (s->n_new < 1 || s->r_inner < 1 || s->r_total < 1 || s->headway < 1 || !(s->temperature >= 0.f) ||
-        !(s->eps >= 0.f) || s->pad_token < 0 || s->pad_token >= ctx->m.vocab)
+        !(s->eps >= 0.f) || s->pad_token < 0 || s->pad_token >= ctx->m.vocab || !(s->beta >= 0.f && s->beta <= 1.f) ||
+        !(s->eta >= 0.f && s->eta < 1.f))
         return RDLM_EINVAL;
     rdlm_sampler sp = *s;
     const int wave = (sp.r_total + sp.r_inner - 1) / sp.r_inner;
@@ -680,6 +682,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     ctx->sp.headway = sp.headway; ctx->sp.adaptive = sp.adaptive; ctx->sp.eps = sp.eps; ctx->sp.alpha = sp.alpha;
     ctx->sp.temperature = sp.temperature; ctx->sp.pad_token = sp.pad_token;
     ctx->sp.seed_lo = (uint32_t)sp.seed; ctx->sp.seed_hi = (uint32_t)(sp.seed >> 32);
+    ctx->sp.beta = sp.beta; ctx->sp.eta = sp.eta;
     ctx->samp_seqs = n_seqs;
     ctx->step = 0;
     ctx->sampler_on = true;
@@ -704,6 +707,11 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys);                       // e <- P(y_current)
+    if (s.eta > 0.f)                                                             // Eq. 1
+        launch_momentum(ctx->e, ctx->e_store, ctx->counts, s.eta, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    if (s.beta > 0.f)                                                            // Eq. 2
+        launch_noise_mix(ctx->z_store, ctx->counts, s.beta, (s.r_total + s.r_inner - 1) / s.r_inner, s.alpha,
+                         ctx->sp.seed_lo, ctx->sp.seed_hi, t, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
     for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
         bool last = i == s.r_inner - 1;
         core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,

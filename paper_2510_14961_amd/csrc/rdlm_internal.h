@@ -49,6 +49,7 @@ struct SamplerParams {
     float eps, alpha, temperature;
     int32_t pad_token;
     uint32_t seed_lo, seed_hi;
+    float beta, eta;
 };
 
 enum ActFmt { ACT_F32 = 0, ACT_BF16P = 1 };
@@ -187,6 +188,15 @@ void launch_init_state_rows(float* z, float* z_prev, int h, int seq, int pos0, i
 void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs, int n_seqs,
                            int max_positions, int headway, float alpha, uint32_t k0, uint32_t k1,
                            hipStream_t st);
+// Eq. 1 on the rows of the step: e <- eta e_prev + (1 - eta) e for positions that have been in
+// flight before (counts > 0); e_store keeps the result per (sequence, position).
+void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
+                     const int32_t* n_tiles, int max_tiles, hipStream_t st);
+// Eq. 2 on the rows of the step, in place on the latent store: z <- (1 - b) z + b z_noise with
+// b = beta * max(0, 1 - counts / n_steps) and z_noise drawn at (position, seq, step).
+void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
+                      uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                      hipStream_t st);
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
                    int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
                    hipStream_t st);

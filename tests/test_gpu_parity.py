@@ -222,6 +222,69 @@ def test_adaptive_exit_fp32_matches_oracle_decisions():
     ctx.close()
 
 
+@pytest.mark.parametrize("r,r_inner,eta,beta,temp", [(4, 1, 0.1, 0.0, 0.0), (4, 1, 0.0, 0.5, 0.0),
+                                                     (8, 4, 0.1, 0.3, 0.0), (6, 2, 0.5, 1.0, 1.0)])
+def test_momentum_and_state_noise_fp32(r, r_inner, eta, beta, temp):
+    """Sec. 3.4: momentum on the conditioning (Eq. 1) and scheduled state noise (Eq. 2) in the
+    fixed-exit sampler, including the paper's default r' = 4, eta = 0.1."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=2, max_positions=96, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 12, 3)
+    n_new = 10
+    ref = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=temp, seed=5, eta=eta, beta=beta)
+    base = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=temp, seed=5)
+    assert any(not np.allclose(ref.final_states[p], base.final_states[p]) for p in base.final_states)
+    steps = _run_gpu_sampler(ctx, [prompt], dict(n_new=n_new, r_inner=r_inner, r_total=r, temperature=temp, seed=5,
+                                                 eta=eta, beta=beta))
+    toks, n_frozen = ctx.read_tokens(0)
+    assert steps == ref.steps
+    assert np.array_equal(toks[: 12 + n_new], ref.tokens)
+    for p, s in ref.final_states.items():
+        assert rel_l2(ctx.read_states(0, p, 1)[0], s) < 1e-4
+    ctx.close()
+
+
+def test_momentum_and_state_noise_adaptive_fp32():
+    """Alg. 2 with eta and beta: delta_i is taken against the noise-free end of the previous step."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=1, gain_jitter=0.0, emb_mul=6.0, max_positions=128, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 16, 1)
+    kw = dict(r_inner=1, r_cap=24, eps=0.05, w_max=8)
+    ref = O.generate_diffusion_forcing_adaptive(m, prompt, 8, seed=4, eta=0.1, beta=0.2, **kw)
+    flat = np.concatenate(ref.deltas)
+    assert np.min(np.abs(flat - 0.05)) > 1e-4
+    steps = _run_gpu_sampler(ctx, [prompt], dict(n_new=8, r_inner=1, r_total=24, eps=0.05, w_max=8, adaptive=True,
+                                                 seed=4, eta=0.1, beta=0.2), r_prefill=24)
+    toks, _ = ctx.read_tokens(0)
+    assert steps == ref.steps
+    assert np.array_equal(toks[:24], ref.tokens)
+    cnt = ctx.read_counts(0, 15, 8)
+    assert np.array_equal(cnt, [ref.recurrences[p] for p in range(15, 23)])
+    ctx.close()
+
+
+def test_momentum_and_state_noise_bf16_first_steps():
+    """bf16 path: the first sampler steps with eta, beta against the oracle (teacher-forced by
+    construction: until a draft differs both sides see the same inputs)."""
+    shape = SMALL_BF16_D96
+    ctx, m, _ = make_pair(shape, seed=4, max_positions=96, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 20, 2)
+    states = {}
+
+    def hook(t, z_pos, zz, logits, y, e):
+        states[t] = (list(z_pos), zz.copy())
+
+    O.generate_diffusion_forcing(m, prompt, 6, 1, 4, seed=3, eta=0.2, beta=0.4, T=2, hook=hook)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, 19, 4, 1.0, 3)
+    ctx.sampler_begin(1, n_new=6, r_inner=1, r_total=4, seed=3, eta=0.2, beta=0.4)
+    ctx.sample_step()
+    z_pos, zz = states[1]
+    got = ctx.read_states(0, z_pos[0], len(z_pos))
+    assert rel_l2(got, zz) < tol_latent(shape)
+    ctx.close()
+
+
 def test_batch_of_ragged_sequences_equals_independent_runs():
     """Several sequences with different prompt lengths in one ragged step give what each gives
     alone (sequences never interact)."""
