@@ -10,6 +10,9 @@
 // [position block][head][dim][32 positions], with the 32 positions of a block stored in the
 // order the score accumulator presents them (vt_slot), so both operands are 16-byte loads.
 // Waves are merged through LDS; KV splits write (max, sum, O) partials merged by a second kernel.
+// Steps with several row tiles per sequence: consecutive tiles of one sequence form groups of up
+// to ATT_GROUP (tile descriptor field `group`) served by one workgroup that stages each K / V
+// block in LDS once for all of them (attn_group_k).
 #include "rdlm_internal.h"
 
 namespace rdlm {
@@ -26,7 +29,8 @@ size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit) {
     return (size_t)max_tiles * H * nsplit * att_rec_floats(d);
 }
 
-template <int D>
+// One row tile per workgroup (MTQ = 1): narrow windows, ragged batches of short windows.
+template <int D, int MTQ>
 __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ kc,
                                                                const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
@@ -39,150 +43,355 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
     const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
     if (t >= *n_tiles) return;
     const TileDesc td = tiles[t];
+    int ng = 1;
+    if (MTQ > 1) {
+        ng = min(td.group, MTQ);
+        if (ng <= 0) return;                                  // served by its group leader
+    }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int h = H * D;
-    const int n_keys = td.pos0 + td.n_valid;                 // keys 0..n_keys-1 are visible to the tile
+    int n_valid_last = td.n_valid;
+    if (MTQ > 1 && ng > 1) n_valid_last = tiles[t + ng - 1].n_valid;
+    const int n_keys = td.pos0 + 32 * (ng - 1) + n_valid_last;   // keys 0..n_keys-1 are visible to the group
     const int nkb = (n_keys + 31) >> 5;
     const int kb_lo = (int)(((long long)nkb * sp) / nsplit), kb_hi = (int)(((long long)nkb * (sp + 1)) / nsplit);
     const uint16_t* K = kc + (size_t)td.seq * seq_stride;
     const uint16_t* Vt = vc + (size_t)td.seq * seq_stride;
     const float scale = 1.0f / sqrtf((float)D);
-    const int qpos = td.pos0 + col;                           // position of this lane's query
+
+    bf16x8 qv[MTQ][DK];
+    f32x16 o[MTQ][DB];
+    float m_run[MTQ], l_run[MTQ];                             // l_run: this half-wave's share of the sum
+#pragma unroll
+    for (int b = 0; b < MTQ; ++b) {
+        const uint16_t* qr = q + ((size_t)(t + min(b, ng - 1)) * 32 + col) * h + hd * D + g * 8;
+#pragma unroll
+        for (int i = 0; i < DK; ++i) qv[b][i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[b][d][i] = 0.f;
+        m_run[b] = -INFINITY; l_run[b] = 0.f;
+    }
+
+    bf16x8 kA[DK], vA[2 * DB], kB[DK], vB[2 * DB];
+    auto load = [&](bf16x8(&kv)[DK], bf16x8(&vv)[2 * DB], int kb) {
+        const uint16_t* kr = K + ((size_t)(kb * 32 + col) * H + hd) * D + g * 8;
+#pragma unroll
+        for (int i = 0; i < DK; ++i) kv[i] = *reinterpret_cast<const bf16x8*>(kr + i * 16);
+        const uint16_t* vr = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)col * 32 + g * 8;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+            vv[2 * d] = *reinterpret_cast<const bf16x8*>(vr + (size_t)d * 32 * 32);
+            vv[2 * d + 1] = *reinterpret_cast<const bf16x8*>(vr + (size_t)d * 32 * 32 + 16);
+        }
+    };
+    auto block = [&](bf16x8(&kv)[DK], bf16x8(&vv)[2 * DB], int kb) {
+#pragma unroll
+        for (int b = 0; b < MTQ; ++b) {
+            if (b >= ng) continue;
+            const int qpos = td.pos0 + 32 * b + col;          // position of this lane's query
+            if (kb * 32 > td.pos0 + 32 * b + 31) continue;    // the whole block lies after the tile
+            f32x16 sacc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+            for (int i = 0; i < DK; ++i) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv[i], qv[b][i], sacc, 0, 0, 0);
+            // register r of lane (col, g) is key kb*32 + 8*(r/4) + 4g + r%4 against query `col`
+            float bm = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
+                sacc[r] = v;
+                bm = fmaxf(bm, v);
+            }
+            bm = fmaxf(bm, __shfl_xor(bm, 32));
+            float m_new = fmaxf(m_run[b], bm);
+            float m_use = (m_new == -INFINITY) ? 0.f : m_new; // nothing visible yet: all p become 0
+            float alpha = __expf(m_run[b] - m_use);           // m_run = -inf gives 0
+            float psum = 0.f;
+            bf16x8 p0, p1;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
+                psum += a + c;
+                p0[r] = (__bf16)a;
+                p1[r] = (__bf16)c;
+            }
+            l_run[b] = l_run[b] * alpha + psum;
+            m_run[b] = m_new;
+#pragma unroll
+            for (int d = 0; d < DB; ++d) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[b][d][i] *= alpha;
+                o[b][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[2 * d], p0, o[b][d], 0, 0, 0);
+                o[b][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[2 * d + 1], p1, o[b][d], 0, 0, 0);
+            }
+        }
+    };
+    // the wave's key blocks kb_lo + wave, + ATT_WAVES, ...: the next block's K and V are in flight
+    // while the current one is used
+    int kb = kb_lo + wave;
+    if (kb < kb_hi) {
+        load(kA, vA, kb);
+        while (true) {
+            const int k1 = kb + ATT_WAVES;
+            if (k1 < kb_hi) load(kB, vB, k1);
+            block(kA, vA, kb);
+            if (k1 >= kb_hi) break;
+            const int k2 = k1 + ATT_WAVES;
+            if (k2 < kb_hi) load(kA, vA, k2);
+            block(kB, vB, k1);
+            if (k2 >= kb_hi) break;
+            kb = k2;
+        }
+    }
+    // merge the waves, one row tile at a time: common max, rescaled sums
+#pragma unroll
+    for (int b = 0; b < MTQ; ++b) {
+        if (b >= ng) continue;                                // uniform over the workgroup
+        if (b > 0) __syncthreads();
+        float lr = l_run[b] + __shfl_xor(l_run[b], 32);
+        if (g == 0) { sm[wave][0][col] = m_run[b]; sm[wave][1][col] = lr; }
+        __syncthreads();
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) M = fmaxf(M, sm[w][0][col]);
+        float Muse = (M == -INFINITY) ? 0.f : M;
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATT_WAVES; ++w) L += sm[w][1][col] * __expf(sm[w][0][col] - Muse);
+        float mine = __expf(m_run[b] - Muse);
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) so[wave][d * 16 + i][lane] = o[b][d][i] * mine;
+        __syncthreads();
+        // wave w finishes the register quads with quad % ATT_WAVES == w; register (d, i) of lane
+        // (col, g) is dim 32d + 8*(i/4) + 4g + i%4 of query `col`
+        const int row = (t + b) * 32 + col;
+        float* rec = ws + (((size_t)(t + b) * H + hd) * nsplit + sp) * att_rec_floats(D);
+        for (int quad = wave; quad < DB * 4; quad += ATT_WAVES) {
+            float v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float acc = 0.f;
+#pragma unroll
+                for (int w = 0; w < ATT_WAVES; ++w) acc += so[w][quad * 4 + i][lane];
+                v[i] = acc;
+            }
+            int d = quad >> 2, qd = quad & 3;
+            int dim = 32 * d + 8 * qd + 4 * g;
+            if (nsplit == 1) {
+                float inv = L > 0.f ? 1.0f / L : 0.f;
+                ushort4 pk;
+                pk.x = f32_to_bf16(v[0] * inv); pk.y = f32_to_bf16(v[1] * inv);
+                pk.z = f32_to_bf16(v[2] * inv); pk.w = f32_to_bf16(v[3] * inv);
+                *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
+            } else {
+                *reinterpret_cast<float4*>(rec + 64 + (size_t)col * D + dim) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+        }
+        if (nsplit > 1 && wave == 0 && g == 0) {
+            rec[col] = M;
+            rec[32 + col] = L;
+        }
+    }
+}
+
+// Several row tiles per sequence (wide windows, prefill): one workgroup per (head, group of up to
+// ATT_GROUP consecutive tiles, KV split).  Every K / V block of the split is fetched once per
+// workgroup and staged in LDS in MFMA operand order (double-buffered; the next block's global
+// loads are in flight while the current block is used); wave w serves row tile w of the group
+// against the staged block, so no cross-wave merge is needed.
+template <int D>
+__global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* __restrict__ q,
+                                                                const uint16_t* __restrict__ kc,
+                                                                const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
+                                                                int H, size_t seq_stride, int nsplit, float* __restrict__ ws,
+                                                                const TileDesc* tiles, const int32_t* n_tiles) {
+    constexpr int DK = D / 16, DB = D / 32;
+    constexpr int SLOTS = (DK + 2 * DB) * 64;               // 16-byte slots of one staged K + V block
+    constexpr int PER = (SLOTS + ATT_GROUP * 64 - 1) / (ATT_GROUP * 64);
+    __shared__ bf16x8 stage[2][SLOTS];
+    const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
+    if (t >= *n_tiles) return;
+    const TileDesc td = tiles[t];
+    const int ng = min(td.group, ATT_GROUP);
+    if (ng <= 0) return;                                      // served by its group leader
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int h = H * D;
+    const int n_keys = td.pos0 + 32 * (ng - 1) + tiles[t + ng - 1].n_valid;
+    const int nkb = (n_keys + 31) >> 5;
+    const int kb_lo = (int)(((long long)nkb * sp) / nsplit), kb_hi = (int)(((long long)nkb * (sp + 1)) / nsplit);
+    const uint16_t* K = kc + (size_t)td.seq * seq_stride;
+    const uint16_t* Vt = vc + (size_t)td.seq * seq_stride;
+    const float scale = 1.0f / sqrtf((float)D);
+    const bool active = wave < ng;
+    const int tq = t + (active ? wave : 0);                   // this wave's row tile
+    const int pos0 = td.pos0 + 32 * (active ? wave : 0);
+    const int qpos = pos0 + col;
 
     bf16x8 qv[DK];
     {
-        const uint16_t* qr = q + ((size_t)t * 32 + col) * h + hd * D + g * 8;
+        const uint16_t* qr = q + ((size_t)tq * 32 + col) * h + hd * D + g * 8;
 #pragma unroll
         for (int i = 0; i < DK; ++i) qv[i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
     }
     f32x16 o[DB];
 #pragma unroll
-    for (int b = 0; b < DB; ++b)
+    for (int d = 0; d < DB; ++d)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[b][i] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;                     // l_run: this half-wave's share of the sum
+        for (int i = 0; i < 16; ++i) o[d][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
 
-    for (int kb = kb_lo + wave; kb < kb_hi; kb += ATT_WAVES) {
-        f32x16 s;
+    // slot s < DK*64: K operand (k step s/64, lane s%64); then V operand (j = (s - DK*64)/64)
+    bf16x8 fetch[PER];
+    auto load = [&](int kb) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s[i] = 0.f;
-        const uint16_t* kr = K + ((size_t)(kb * 32 + col) * H + hd) * D + g * 8;
-#pragma unroll
-        for (int i = 0; i < DK; ++i) {
-            bf16x8 kv = *reinterpret_cast<const bf16x8*>(kr + i * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qv[i], s, 0, 0, 0);
+        for (int p = 0; p < PER; ++p) {
+            const int s = threadIdx.x + p * ATT_GROUP * 64;
+            if (s < SLOTS) {
+                const int ln = s & 63, c = ln & 31, gg = ln >> 5, i = s >> 6;
+                const uint16_t* src;
+                if (i < DK) src = K + ((size_t)(kb * 32 + c) * H + hd) * D + gg * 8 + i * 16;
+                else {
+                    const int j = i - DK;
+                    src = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
+                }
+                fetch[p] = *reinterpret_cast<const bf16x8*>(src);
+            }
         }
-        // register r of lane (col, g) is key kb*32 + 8*(r/4) + 4g + r%4 against query `col`
-        float bm = -INFINITY;
+    };
+    auto put = [&](int buf) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            float v = (key <= qpos) ? s[r] * scale : -INFINITY;
-            s[r] = v;
-            bm = fmaxf(bm, v);
+        for (int p = 0; p < PER; ++p) {
+            const int s = threadIdx.x + p * ATT_GROUP * 64;
+            if (s < SLOTS) stage[buf][s] = fetch[p];
         }
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
-        float m_new = fmaxf(m_run, bm);
-        float m_use = (m_new == -INFINITY) ? 0.f : m_new;     // nothing visible yet: all p become 0
-        float alpha = __expf(m_run - m_use);                  // m_run = -inf gives 0
-        float psum = 0.f;
-        bf16x8 p0, p1;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            float a = __expf(s[r] - m_use), b = __expf(s[r + 8] - m_use);
-            psum += a + b;
-            p0[r] = (__bf16)a;
-            p1[r] = (__bf16)b;
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-        const uint16_t* vr = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)col * 32 + g * 8;
-#pragma unroll
-        for (int b = 0; b < DB; ++b) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[b][i] *= alpha;
-            bf16x8 v0 = *reinterpret_cast<const bf16x8*>(vr + (size_t)b * 32 * 32);
-            bf16x8 v1 = *reinterpret_cast<const bf16x8*>(vr + (size_t)b * 32 * 32 + 16);
-            o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v0, p0, o[b], 0, 0, 0);
-            o[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v1, p1, o[b], 0, 0, 0);
-        }
+    };
+    int cur = 0;
+    if (kb_lo < kb_hi) {
+        load(kb_lo);
+        put(0);
+        __syncthreads();
     }
-    // merge the waves: common max, rescaled sums
-    l_run += __shfl_xor(l_run, 32);
-    if (g == 0) { sm[wave][0][col] = m_run; sm[wave][1][col] = l_run; }
-    __syncthreads();
-    float M = -INFINITY;
+    for (int kb = kb_lo; kb < kb_hi; ++kb) {
+        if (kb + 1 < kb_hi) load(kb + 1);
+        if (active && kb * 32 <= pos0 + 31) {                 // else the whole block lies after the tile
+            f32x16 sacc;
 #pragma unroll
-    for (int w = 0; w < ATT_WAVES; ++w) M = fmaxf(M, sm[w][0][col]);
-    float Muse = (M == -INFINITY) ? 0.f : M;
-    float L = 0.f;
+            for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-    for (int w = 0; w < ATT_WAVES; ++w) L += sm[w][1][col] * __expf(sm[w][0][col] - Muse);
-    float mine = __expf(m_run - Muse);
+            for (int i = 0; i < DK; ++i)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][i * 64 + lane], qv[i], sacc, 0, 0, 0);
+            float bm = -INFINITY;
 #pragma unroll
-    for (int b = 0; b < DB; ++b)
+            for (int r = 0; r < 16; ++r) {
+                int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
+                sacc[r] = v;
+                bm = fmaxf(bm, v);
+            }
+            bm = fmaxf(bm, __shfl_xor(bm, 32));
+            float m_new = fmaxf(m_run, bm);
+            float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            float alpha = __expf(m_run - m_use);
+            float psum = 0.f;
+            bf16x8 p0, p1;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) so[wave][b * 16 + i][lane] = o[b][i] * mine;
-    __syncthreads();
-    // wave w finishes the registers r with r % ATT_WAVES == w; register (b, i) of lane (col, g) is
-    // dim 32b + 8*(i/4) + 4g + i%4 of query `col`; four consecutive i are four consecutive dims
-    for (int quad = wave; quad < DB * 4; quad += ATT_WAVES) {
-        float v[4];
+            for (int r = 0; r < 8; ++r) {
+                float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
+                psum += a + c;
+                p0[r] = (__bf16)a;
+                p1[r] = (__bf16)c;
+            }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float acc = 0.f;
+            for (int d = 0; d < DB; ++d) {
 #pragma unroll
-            for (int w = 0; w < ATT_WAVES; ++w) acc += so[w][quad * 4 + i][lane];
-            v[i] = acc;
+                for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d) * 64 + lane], p0, o[d], 0, 0, 0);
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d + 1) * 64 + lane], p1, o[d], 0, 0, 0);
+            }
         }
-        int b = quad >> 2, qd = quad & 3;
-        int dim = 32 * b + 8 * qd + 4 * g;
-        int row = t * 32 + col;
-        if (nsplit == 1) {
-            float inv = L > 0.f ? 1.0f / L : 0.f;
-            ushort4 pk;
-            pk.x = f32_to_bf16(v[0] * inv); pk.y = f32_to_bf16(v[1] * inv);
-            pk.z = f32_to_bf16(v[2] * inv); pk.w = f32_to_bf16(v[3] * inv);
-            *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
-        } else {
-            float* rec = ws + (((size_t)t * H + hd) * nsplit + sp) * att_rec_floats(D);
-            *reinterpret_cast<float4*>(rec + 64 + (size_t)col * D + dim) = make_float4(v[0], v[1], v[2], v[3]);
-        }
+        if (kb + 1 < kb_hi) put(cur ^ 1);                     // last read one block ago, before the barrier
+        __syncthreads();
+        cur ^= 1;
     }
-    if (nsplit > 1 && wave == 0 && g == 0) {
-        float* rec = ws + (((size_t)t * H + hd) * nsplit + sp) * att_rec_floats(D);
-        rec[col] = M;
+    if (!active) return;
+    const float L = l_run + __shfl_xor(l_run, 32);
+    const int row = tq * 32 + col;
+    float* rec = ws + (((size_t)tq * H + hd) * nsplit + sp) * att_rec_floats(D);
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int dim = 32 * d + 8 * qd + 4 * g;
+            const float v0 = o[d][qd * 4], v1 = o[d][qd * 4 + 1], v2 = o[d][qd * 4 + 2], v3 = o[d][qd * 4 + 3];
+            if (nsplit == 1) {
+                ushort4 pk;
+                pk.x = f32_to_bf16(v0 * inv); pk.y = f32_to_bf16(v1 * inv);
+                pk.z = f32_to_bf16(v2 * inv); pk.w = f32_to_bf16(v3 * inv);
+                *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
+            } else {
+                *reinterpret_cast<float4*>(rec + 64 + (size_t)col * D + dim) = make_float4(v0, v1, v2, v3);
+            }
+        }
+    if (nsplit > 1 && g == 0) {
+        rec[col] = m_run;
         rec[32 + col] = L;
     }
 }
 
+// Combine the KV-split partials of a (tile, head): one thread per (query, 4 dims); all loads of
+// the thread are issued before the first use.
+constexpr int ATT_MAX_SPLIT = 8;
 template <int D>
-__global__ void attn_merge_k(const float* __restrict__ ws, uint16_t* __restrict__ out, int H, int nsplit,
-                             const int32_t* n_tiles) {
+__global__ __launch_bounds__(256) void attn_merge_k(const float* __restrict__ ws, uint16_t* __restrict__ out, int H,
+                                                     int nsplit, const int32_t* n_tiles) {
     const int hd = blockIdx.x, t = blockIdx.y;
     if (t >= *n_tiles) return;
+    const int idx = blockIdx.z * blockDim.x + threadIdx.x;
+    if (idx >= 32 * (D / 4)) return;
     const float* base = ws + ((size_t)t * H + hd) * nsplit * att_rec_floats(D);
-    for (int idx = threadIdx.x; idx < 32 * (D / 4); idx += blockDim.x) {
-        int col = idx / (D / 4), dim = (idx % (D / 4)) * 4;
-        float M = -INFINITY;
-        for (int s = 0; s < nsplit; ++s) M = fmaxf(M, base[s * att_rec_floats(D) + col]);
-        float Muse = (M == -INFINITY) ? 0.f : M;
-        float L = 0.f;
-        float4 acc = make_float4(0, 0, 0, 0);
-        for (int s = 0; s < nsplit; ++s) {
+    const int col = idx / (D / 4), dim = (idx % (D / 4)) * 4;
+    float m[ATT_MAX_SPLIT], l[ATT_MAX_SPLIT];
+    float4 v[ATT_MAX_SPLIT];
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
+        if (s < nsplit) {
             const float* rec = base + s * att_rec_floats(D);
-            float w = __expf(rec[col] - Muse);
-            L += rec[32 + col] * w;
-            float4 v = *reinterpret_cast<const float4*>(rec + 64 + (size_t)col * D + dim);
-            acc.x += v.x * w; acc.y += v.y * w; acc.z += v.z * w; acc.w += v.w * w;
+            m[s] = rec[col];
+            l[s] = rec[32 + col];
+            v[s] = *reinterpret_cast<const float4*>(rec + 64 + (size_t)col * D + dim);
         }
-        float inv = L > 0.f ? 1.0f / L : 0.f;
-        ushort4 pk;
-        pk.x = f32_to_bf16(acc.x * inv); pk.y = f32_to_bf16(acc.y * inv);
-        pk.z = f32_to_bf16(acc.z * inv); pk.w = f32_to_bf16(acc.w * inv);
-        *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + col, hd * D + dim, H * D)) = pk;
     }
+    float M = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLIT; ++s)
+        if (s < nsplit) M = fmaxf(M, m[s]);
+    const float Muse = (M == -INFINITY) ? 0.f : M;
+    float L = 0.f;
+    float4 acc = make_float4(0, 0, 0, 0);
+#pragma unroll
+    for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
+        if (s < nsplit) {
+            const float w = __expf(m[s] - Muse);
+            L += l[s] * w;
+            acc.x += v[s].x * w; acc.y += v[s].y * w; acc.z += v[s].z * w; acc.w += v[s].w * w;
+        }
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    ushort4 pk;
+    pk.x = f32_to_bf16(acc.x * inv); pk.y = f32_to_bf16(acc.y * inv);
+    pk.z = f32_to_bf16(acc.z * inv); pk.w = f32_to_bf16(acc.w * inv);
+    *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + col, hd * D + dim, H * D)) = pk;
 }
 
 // f32 path: one workgroup per (row, head); scores kept in LDS.
@@ -238,7 +447,7 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
 }
 
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, float* ws, const TileDesc* tiles,
+                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, const TileDesc* tiles,
                       const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     if (dtype == 0) {
         hipLaunchKernelGGL(attn_f32_k, dim3(max_tiles * 32, H), dim3(256), 0, st, (const float*)q, (const float*)kc,
@@ -246,14 +455,20 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
         return;
     }
     dim3 grid(H, max_tiles, nsplit);
+    if (nsplit > ATT_MAX_SPLIT) nsplit = ATT_MAX_SPLIT;
 #define RDLM_ATT(D_)                                                                                              \
     if (d == D_) {                                                                                                \
-        hipLaunchKernelGGL(attn_bf16_k<D_>, grid, dim3(ATT_WAVES * 64), 0, st, (const uint16_t*)q,                \
-                           (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems, nsplit, \
-                           ws, tiles, n_tiles);                                                                   \
+        if (!grouped)                                                                                             \
+            hipLaunchKernelGGL((attn_bf16_k<D_, 1>), grid, dim3(ATT_WAVES * 64), 0, st, (const uint16_t*)q,       \
+                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \
+                               nsplit, ws, tiles, n_tiles);                                                       \
+        else                                                                                                      \
+            hipLaunchKernelGGL(attn_group_k<D_>, grid, dim3(ATT_GROUP * 64), 0, st, (const uint16_t*)q,           \
+                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \
+                               nsplit, ws, tiles, n_tiles);                                                       \
         if (nsplit > 1)                                                                                           \
-            hipLaunchKernelGGL(attn_merge_k<D_>, dim3(H, max_tiles), dim3(256), 0, st, ws, (uint16_t*)out, H,     \
-                               nsplit, n_tiles);                                                                  \
+            hipLaunchKernelGGL(attn_merge_k<D_>, dim3(H, max_tiles, (32 * (D_ / 4) + 255) / 256), dim3(256), 0,   \
+                               st, ws, (uint16_t*)out, H, nsplit, n_tiles);                                       \
         return;                                                                                                   \
     }
     RDLM_ATT(32) RDLM_ATT(64) RDLM_ATT(96) RDLM_ATT(128)

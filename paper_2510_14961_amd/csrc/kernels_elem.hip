@@ -51,7 +51,8 @@ __global__ void build_tiles_api_k(SeqWindows w, int mode, int max_positions, Til
                 d.erow0 = t * TILE_ROWS;
             }
             d.crow0 = c + off;
-            d.pad_ = 0;
+            const int k = off / TILE_ROWS, left = (w.rows[i] - off + TILE_ROWS - 1) / TILE_ROWS;
+            d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
             tiles[t++] = d;
         }
         c += w.rows[i];
@@ -77,7 +78,8 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positi
             d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
             d.erow0 = t * TILE_ROWS;
             d.crow0 = c + off;
-            d.pad_ = 0;
+            const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
+            d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
             tiles[t++] = d;
         }
         c += rows;

@@ -64,6 +64,7 @@ struct rdlm_ctx {
     float* cand_val = nullptr;
     int32_t* cand_idx = nullptr;
     int forced_att_split = 0;
+    bool grouped = false;           // current step: some sequence has several row tiles (grouped attention)
     // per-launch GEMM timing
     int prof_n = 0, prof_k = 0, prof_used = 0;
     std::vector<hipEvent_t> prof_ev;
@@ -437,7 +438,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
 static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
     if (ctx->m.dtype == RDLM_F32) return 1;
     if (ctx->forced_att_split > 0) return std::min(ctx->forced_att_split, ctx->att_max_split);
-    int wgs = ctx->m.n_heads * T;
+    int wgs = ctx->m.n_heads * (ctx->grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
     int kb = (max_keys + 31) / 32;
     int s = 1;
     while (s < ctx->att_max_split && wgs * s < 512 && kb / (s * 2) >= 8) s *= 2;
@@ -471,7 +472,7 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
-                     att_split_for(ctx, T, max_keys), ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
+                     att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
     run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S);
     dn = norm_operand(ctx, ctx->x, ctx->x, S, L.g2, ctx->xn, T);
     run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S, nullptr, false, dn);   // leaves silu(gate) * up in abuf
@@ -548,6 +549,9 @@ static int check_rows(const rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, c
     }
     if (rows > ctx->max_rows || tiles > ctx->max_tiles) return RDLM_ECAPACITY;
     *T = tiles; *M = rows; *max_keys = mk;
+    bool grouped = false;
+    for (int i = 0; i < n_seqs; ++i) grouped = grouped || n_rows[i] > TILE_ROWS;
+    const_cast<rdlm_ctx*>(ctx)->grouped = grouped;
     return RDLM_OK;
 }
 
@@ -574,6 +578,7 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     SeqWindows w;
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
+    ctx->grouped = T > 1;
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
@@ -701,6 +706,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     long long grow = 1 + (long long)(t - 1) * s.headway;
     int wmax_now = (int)std::min<long long>(s.w_max, grow);
     const int T = n * ((wmax_now + 31) / 32);
+    ctx->grouped = wmax_now > TILE_ROWS;
     int max_keys = 0;
     for (int q = 0; q < n; ++q)
         max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
@@ -955,6 +961,7 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
     SeqWindows w;
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
+    ctx->grouped = T > 1;
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;

@@ -17,8 +17,10 @@ struct TileDesc {
     int32_t erow0;    // row of the tile's first conditioning vector e
     int32_t yrow0;    // index of the tile's first input token in the token array it reads
     int32_t crow0;    // compact row index (rows of all tiles concatenated without padding)
-    int32_t pad_;
+    int32_t group;    // attention: tiles t..t+group-1 (same sequence, consecutive positions) are served
+                      // together by the workgroup of tile t; 0 = served by an earlier tile's workgroup
 };
+constexpr int ATT_GROUP = 4;
 
 constexpr int TILE_ROWS = 32;
 constexpr int MAX_API_SEQS = 64;      // sequences per API call (descriptor passed as a kernel argument)
@@ -229,7 +231,7 @@ void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st)
 // q: f32 [rows][H*d] (RDLM_F32) or bf16 [rows][H*d]; caches per the model dtype; out: activation
 // format of the model dtype, width H*d.  ws: split-KV partials.
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, float* ws, const TileDesc* tiles,
+                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, const TileDesc* tiles,
                       const int32_t* n_tiles, int max_tiles, hipStream_t st);
 size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);
 
