@@ -132,20 +132,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
         }
     };
     // the wave's key blocks kb_lo + wave, + ATT_WAVES, ...: the next block's K and V are in flight
-    // while the current one is used
-    int kb = kb_lo + wave;
-    if (kb < kb_hi) {
-        load(kA, vA, kb);
-        while (true) {
-            const int k1 = kb + ATT_WAVES;
-            if (k1 < kb_hi) load(kB, vB, k1);
-            block(kA, vA, kb);
-            if (k1 >= kb_hi) break;
-            const int k2 = k1 + ATT_WAVES;
-            if (k2 < kb_hi) load(kA, vA, k2);
-            block(kB, vB, k1);
-            if (k2 >= kb_hi) break;
-            kb = k2;
+    // while the current one is used (loads are issued unconditionally, clamped to the last block)
+    {
+        const int last = max(kb_hi - 1, 0);
+        int kb = kb_lo + wave;
+        if (kb < kb_hi) {
+            load(kA, vA, kb);
+            for (; kb < kb_hi; kb += 2 * ATT_WAVES) {
+                load(kB, vB, min(kb + ATT_WAVES, last));
+                block(kA, vA, kb);
+                load(kA, vA, min(kb + 2 * ATT_WAVES, last));
+                if (kb + ATT_WAVES < kb_hi) block(kB, vB, kb + ATT_WAVES);
+            }
         }
     }
     // merge the waves, one row tile at a time: common max, rescaled sums
@@ -248,80 +246,88 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
         for (int i = 0; i < 16; ++i) o[d][i] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // slot s < DK*64: K operand (k step s/64, lane s%64); then V operand (j = (s - DK*64)/64)
-    bf16x8 fetch[PER];
-    auto load = [&](int kb) {
+    // slot s < DK*64: K operand (k step s/64, lane s%64); then V operand (j = (s - DK*64)/64).
+    // Both advance by 32*H*D elements per key block, so a slot's address is base + kb * stride.
+    static_assert(SLOTS % (ATT_GROUP * 64) == 0, "every thread stages the same number of slots");
+    const size_t kb_stride = (size_t)32 * H * D;
+    const uint16_t* fbase[PER];
 #pragma unroll
-        for (int p = 0; p < PER; ++p) {
-            const int s = threadIdx.x + p * ATT_GROUP * 64;
-            if (s < SLOTS) {
-                const int ln = s & 63, c = ln & 31, gg = ln >> 5, i = s >> 6;
-                const uint16_t* src;
-                if (i < DK) src = K + ((size_t)(kb * 32 + c) * H + hd) * D + gg * 8 + i * 16;
-                else {
-                    const int j = i - DK;
-                    src = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
-                }
-                fetch[p] = *reinterpret_cast<const bf16x8*>(src);
-            }
-        }
-    };
-    auto put = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PER; ++p) {
-            const int s = threadIdx.x + p * ATT_GROUP * 64;
-            if (s < SLOTS) stage[buf][s] = fetch[p];
-        }
-    };
-    int cur = 0;
-    if (kb_lo < kb_hi) {
-        load(kb_lo);
-        put(0);
-        __syncthreads();
+    for (int p = 0; p < PER; ++p) {
+        const int s = threadIdx.x + p * ATT_GROUP * 64;
+        const int ln = s & 63, c = ln & 31, gg = ln >> 5, i = s >> 6, j = i - DK;
+        const uint16_t* sk = K + ((size_t)c * H + hd) * D + gg * 8 + i * 16;
+        const uint16_t* sv = Vt + (size_t)hd * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
+        fbase[p] = i < DK ? sk : sv;
     }
-    for (int kb = kb_lo; kb < kb_hi; ++kb) {
-        if (kb + 1 < kb_hi) load(kb + 1);
-        if (active && kb * 32 <= pos0 + 31) {                 // else the whole block lies after the tile
-            f32x16 sacc;
+    bf16x8 fetch0[PER], fetch1[PER];
+    auto load = [&](bf16x8(&fetch)[PER], int kb) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+        for (int p = 0; p < PER; ++p) fetch[p] = *reinterpret_cast<const bf16x8*>(fbase[p] + (size_t)kb * kb_stride);
+    };
+    auto put = [&](bf16x8(&fetch)[PER], int buf) {
 #pragma unroll
-            for (int i = 0; i < DK; ++i)
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][i * 64 + lane], qv[i], sacc, 0, 0, 0);
-            float bm = -INFINITY;
+        for (int p = 0; p < PER; ++p) stage[buf][threadIdx.x + p * ATT_GROUP * 64] = fetch[p];
+    };
+    auto block = [&](int cur, int kb) {
+        // nothing to do past the split's end, or when the whole block lies after the tile
+        if (!(active && kb < kb_hi && kb * 32 <= pos0 + 31)) return;
+        f32x16 sacc;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
-                sacc[r] = v;
-                bm = fmaxf(bm, v);
-            }
-            bm = fmaxf(bm, __shfl_xor(bm, 32));
-            float m_new = fmaxf(m_run, bm);
-            float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            float alpha = __expf(m_run - m_use);
-            float psum = 0.f;
-            bf16x8 p0, p1;
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
-                psum += a + c;
-                p0[r] = (__bf16)a;
-                p1[r] = (__bf16)c;
-            }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
+        for (int i = 0; i < DK; ++i)
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][i * 64 + lane], qv[i], sacc, 0, 0, 0);
+        float bm = -INFINITY;
 #pragma unroll
-            for (int d = 0; d < DB; ++d) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d) * 64 + lane], p0, o[d], 0, 0, 0);
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d + 1) * 64 + lane], p1, o[d], 0, 0, 0);
-            }
+        for (int r = 0; r < 16; ++r) {
+            int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
+            sacc[r] = v;
+            bm = fmaxf(bm, v);
         }
-        if (kb + 1 < kb_hi) put(cur ^ 1);                     // last read one block ago, before the barrier
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        float m_new = fmaxf(m_run, bm);
+        float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        float alpha = __expf(m_run - m_use);
+        float psum = 0.f;
+        bf16x8 p0, p1;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
+            psum += a + c;
+            p0[r] = (__bf16)a;
+            p1[r] = (__bf16)c;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d) * 64 + lane], p0, o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d + 1) * 64 + lane], p1, o[d], 0, 0, 0);
+        }
+    };
+    // Block j of the split (kb = kb_lo + j) is fetched into register set j % 2 two blocks ahead,
+    // staged into LDS buffer j % 2 one block ahead (that buffer was last read two blocks ago, before
+    // the previous barrier) and used after the barrier that follows.  Every iteration issues the
+    // same loads and stores (block indices clamped to the split), so the wait before the staging
+    // store covers the older fetch only and the newer one stays in flight.
+    auto one = [&](bf16x8(&mine)[PER], bf16x8(&next)[PER], int cur, int kb) {
+        load(mine, min(kb + 2, kb_hi - 1));                   // `mine` held block kb, already staged
+        block(cur, kb);
+        put(next, cur ^ 1);
         __syncthreads();
-        cur ^= 1;
+    };
+    if (kb_lo < kb_hi) {
+        load(fetch0, kb_lo);
+        load(fetch1, min(kb_lo + 1, kb_hi - 1));
+        put(fetch0, 0);
+        __syncthreads();
+        for (int kb = kb_lo; kb < kb_hi; kb += 2) {
+            one(fetch0, fetch1, 0, kb);
+            one(fetch1, fetch0, 1, kb + 1);
+        }
     }
     if (!active) return;
     const float L = l_run + __shfl_xor(l_run, 32);

@@ -381,32 +381,28 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     const bool stream_w = A.m_chunks == 1;          // weights used once: keep them out of the caches
 
     bf16x8 w0[KU][NB], w1[KU][NB], w2[KU][NB], xr[XL];
-    // activations first: the staging store then waits for them only, and the weight loads issued
-    // after them stay in flight (the memory counter retires loads in issue order)
+    // Every K step issues the same loads and stores (k indices clamped to the range), so the
+    // compiler can count them: activations first -- the staging store then waits for them only, and
+    // the weight loads issued after them stay in flight (the memory counter retires in issue order).
+    static_assert((KU * MT) % WAVES == 0, "every wave stages the same number of tiles");
     auto load = [&](bf16x8(&wv)[KU][NB], int kt) {  // activations and weights of the K step at kt
-        const int kc = min(KU, kend - kt);
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
-            const int ti = wave + i * WAVES;
-            if (ti < KU * MT && ti / MT < kc) xr[i] = xsrc[i][(size_t)kt * 64];
+            const int u = (wave + i * WAVES) / MT;
+            xr[i] = xsrc[i][(size_t)(min(kt + u, kend - 1) - u) * 64];
         }
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
-            if (u < kc) {
+            const size_t k = (size_t)min(kt + u, kend - 1);
 #pragma unroll
-                for (int a = 0; a < NB; ++a)
-                    wv[u][a] = stream_w ? __builtin_nontemporal_load(wbase[a] + (size_t)(kt + u) * 64)
-                                        : wbase[a][(size_t)(kt + u) * 64];
-            }
+            for (int a = 0; a < NB; ++a)
+                wv[u][a] = stream_w ? __builtin_nontemporal_load(wbase[a] + k * 64) : wbase[a][k * 64];
         }
         __builtin_amdgcn_sched_barrier(0);
     };
     auto stage = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < XL; ++i) {
-            const int ti = wave + i * WAVES;
-            if (ti < KU * MT) xs[((size_t)buf * KU * MT + ti) * 64 + lane] = xr[i];
-        }
+        for (int i = 0; i < XL; ++i) xs[((size_t)buf * KU * MT + wave + i * WAVES) * 64 + lane] = xr[i];
     };
     auto compute = [&](bf16x8(&wv)[KU][NB], int buf, int kt) {
         const int kc = min(KU, kend - kt);
@@ -428,8 +424,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     // buffer was last read in step s - 3, which every wave has left two barriers ago) and are read
     // after the barrier that ends step s - 1.
     auto step = [&](bf16x8(&wcur)[KU][NB], bf16x8(&wnext)[KU][NB], int bcur, int kt) {
-        if (kt + KU < kend) stage(bcur == 2 ? 0 : bcur + 1);
-        if (kt + 2 * KU < kend) load(wnext, kt + 2 * KU);
+        stage(bcur == 2 ? 0 : bcur + 1);
+        load(wnext, min(kt + 2 * KU, kend - 1));
         compute(wcur, bcur, kt);
         __syncthreads();
     };
@@ -437,7 +433,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     if (kt < kend) {
         load(w0, kt);
         stage(0);
-        if (kt + KU < kend) load(w1, kt + KU);
+        load(w1, min(kt + KU, kend - 1));
         __syncthreads();
         while (true) {
             step(w0, w2, 0, kt); kt += KU;

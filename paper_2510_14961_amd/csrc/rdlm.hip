@@ -256,6 +256,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->e_store, SP * h * 4, true);
     DALLOC(ctx->n_active, 64, true);
     HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&ctx->n_active_host), 64, hipHostMallocDefault));
+    memset(ctx->n_active_host, 0, 64);
     ctx->prompt_len.assign(ctx->max_seqs, 0);
     HIPCHK(hipStreamSynchronize(ctx->st));
     return RDLM_OK;
@@ -324,19 +325,23 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             if (sscanf(p, "%d,%d,%d,%d", &o.nb, &o.waves, &o.unroll, &o.ksplit) == 4) g = o;
         }
     } else {
-        // several row tiles: the row-sharing kernel.  Shapes from sweeps at 64..4096 rows: small
-        // row chunks win while the step is bound by weight streaming (more workgroups in flight;
-        // chunks of one feature group run back to back on one XCD and share the weights in its L2)
-        if (T <= 2) g = {2, 1, 4, 8, 8, GEMM_ROWS};
-        else if (T <= 4) g = {proj == PROJ_HEAD ? 4 : 2, 1, 4, proj == PROJ_QKV ? 8 : 4, 8, GEMM_ROWS};
-        else if (T <= 8 && proj == PROJ_QKV) g = {2, 1, 4, 8, 1, GEMM_ROWS};
-        else g = {4, 1, 4, 4, 1, GEMM_ROWS};
+        // several row tiles: the row-sharing kernel.  Shapes from sweeps at 64..4096 rows.  While the
+        // step is bound by weight streaming, small row chunks with many workgroups in flight win
+        // (chunks of one feature group run back to back on one XCD and share the weights in its
+        // L2); from a few hundred rows on, 256-row chunks feed the matrix cores.
+        const bool wide = proj == PROJ_GU || proj == PROJ_HEAD;       // many feature blocks
+        const bool deep = proj == PROJ_D || proj == PROJ_A;           // long K, few feature blocks
+        if (T <= 2) g = (wide || deep) ? GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
+        else if (T <= 4) g = wide ? GemmPlan{4, 1, 8, 4, 1, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, deep ? 8 : 4, GEMM_ROWS};
+        else if (T <= 8)
+            g = (wide || proj == PROJ_D) ? GemmPlan{8, 1, 8, 2, 8, GEMM_ROWS}
+                : proj == PROJ_A         ? GemmPlan{4, 1, 4, 2, 8, GEMM_ROWS}
+                                         : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
+        else if (T <= 24) g = proj == PROJ_HEAD ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS} : GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS};
+        else g = (proj == PROJ_GU || deep) ? GemmPlan{8, 2, 4, 2, 2, GEMM_ROWS} : GemmPlan{8, 1, 8, 2, 2, GEMM_ROWS};
         if (const char* p = getenv(kProjEnvRows[proj])) {
             GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
             if (sscanf(p, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) g = o;
-        } else if (split_ok && T > 4) {
-            const int groups = gemm_groups(N, g, EPI_F32) * ((T + g.mt - 1) / g.mt);
-            g.ksplit = std::max(1, std::min(8, (640 + groups - 1) / groups));
         }
     }
     if (!split_ok) g.ksplit = 1;
