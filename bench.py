@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 import synth_inputs as S  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def log(*a):
@@ -103,6 +104,8 @@ def main():
     ap.add_argument("--ar-tokens", type=int, default=8,
                     help="tokens of the autoregressive (r' = r) run timed for comparison; 0 = skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--large-window-rows", type=int, default=4095,
+                    help="rows of the large-window core step timed against the MFMA peak (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
     ap.add_argument("--threads", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
@@ -138,7 +141,9 @@ def main():
     dev, w64 = build_weights(shape, wl.weight_seed, want_cpu, args.threads)
     t0 = time.time()
     ctx = R.Context(shape, dev, n_seqs, max_positions, max_rows)
-    del dev
+    want_large = args.large_window_rows > 0 and args.workload == "cfg3"
+    if not want_large:
+        del dev
     torch.cuda.empty_cache()
     log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 2**30:.1f} GiB on device")
 
@@ -232,6 +237,21 @@ def main():
     }
     ctx.close()
     torch.cuda.empty_cache()
+    if want_large:
+        # the same core step over a prefill-sized window: every GEMM runs many row tiles per weight
+        # tile, the regime bounded by the matrix cores (algorithmic flops: the GEMMs only)
+        rows = args.large_window_rows
+        ctx2 = R.Context(shape, dev, 1, rows + 64, rows)
+        del dev
+        ms = ctx2.time_core_step(0, 0, rows, 3)
+        core_params = shape.n_core * (4 * h * h + 3 * h * F) + 2 * h * h
+        flops = 2.0 * core_params * rows
+        out["core_step_large_window"] = {"rows": rows, "ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+                                         "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                                         "frac_of_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                         "flops_counted": "2 x core weights x rows (attention not counted)"}
+        ctx2.close()
+        torch.cuda.empty_cache()
     if want_cpu:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(shape, w64, wl.prompt_len, window)
