@@ -201,6 +201,27 @@ __global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, 
     }
 }
 
+// End of the prelude on the bf16 path: e = x + sum part (f32, padded rows) and the adapter operand
+// concat(e, z) as packed bf16 in one pass; a row is cut into `chunks` pieces like fold_k.
+__global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const float* part, int S, size_t part_stride,
+                                                      float* e_out, const float* z, void* cat, int h, int chunks,
+                                                      const TileDesc* tiles, const int32_t* n_tiles) {
+    const int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    const TileDesc d = tiles[t];
+    const bool valid = j < d.n_valid;
+    const int cw = h / chunks;
+    const int k = c * cw + threadIdx.x * 4;
+    if ((int)threadIdx.x * 4 >= cw) return;
+    float4 v = row_value(xin, part, S, part_stride, (size_t)r * h + k);
+    *reinterpret_cast<float4*>(e_out + (size_t)r * h + k) = v;
+    float4 zz = make_float4(0, 0, 0, 0);
+    if (valid) zz = ld4(z + ((size_t)d.zrow0 + j) * h + k);
+    else v = make_float4(0, 0, 0, 0);
+    act_store4<ACT_BF16P>(cat, 2 * h, r, k, v.x, v.y, v.z, v.w);
+    act_store4<ACT_BF16P>(cat, 2 * h, r, h + k, zz.x, zz.y, zz.z, zz.w);
+}
+
 // Residual add + split-K fold with the RMS factor left to the consumer: a row is cut into
 // `chunks` pieces handled by different workgroups; each writes x_out, bf16(x_out * gain) in the
 // packed operand layout and its piece of the row's sum of squares.
@@ -230,8 +251,8 @@ __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, con
 // delta = ||z' - z_prev|| / ||z'|| (Eq. 3) and z_prev <- z'.
 __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
                                                      const float* gain, int h, float eps, float* z, float* z_prev,
-                                                     int update_prev, float* delta, const TileDesc* tiles,
-                                                     const int32_t* n_tiles) {
+                                                     int update_prev, float* delta, float* xcopy,
+                                                     const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sh[8];
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
@@ -254,6 +275,7 @@ __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const floa
 #pragma unroll
     for (int i = 0; i < ROW_VEC; ++i) {
         int k = (threadIdx.x + i * 256) * 4;
+        if (k < h && !valid && xcopy) *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = make_float4(0, 0, 0, 0);
         if (k < h && valid) {
             float4 g = ld4(gain + k);
             float4 o = make_float4(v[i].x * inv * g.x, v[i].y * inv * g.y, v[i].z * inv * g.z, v[i].w * inv * g.w);
@@ -265,6 +287,7 @@ __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const floa
             }
             den += o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
             *reinterpret_cast<float4*>(z + zr * h + k) = o;
+            if (xcopy) *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = o;
         }
     }
     if (delta) {
@@ -639,11 +662,18 @@ void launch_fold(const float* xin, float* xout, const float* part, int S, size_t
     hipLaunchKernelGGL(fold_k, dim3(c, max_tiles * 32), dim3(256), 0, st, xin, xout, part, S, part_stride, gain, xg,
                        ssq, h, c, n_tiles);
 }
+void launch_prelude_end(const float* xin, const float* part, int S, size_t part_stride, float* e_out, const float* z,
+                        void* cat, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                        hipStream_t st) {
+    const int c = fold_chunks(h);
+    hipLaunchKernelGGL(prelude_end_k, dim3(c, max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, e_out, z,
+                       cat, h, c, tiles, n_tiles);
+}
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
-                       int h, float eps, float* z, float* z_prev, int update_prev, float* delta,
+                       int h, float eps, float* z, float* z_prev, int update_prev, float* delta, float* xcopy,
                        const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     hipLaunchKernelGGL(final_norm_k, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain, h,
-                       eps, z, z_prev, update_prev, delta, tiles, n_tiles);
+                       eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
 }
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
                        int max_tiles, hipStream_t st) {

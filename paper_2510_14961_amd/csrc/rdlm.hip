@@ -318,7 +318,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             case PROJ_HEAD: g = {1, 4, 4, 2, 1}; break;
             case PROJ_QKV: g = {1, 2, 2, 4, 1}; break;
             case PROJ_D: g = {1, 2, 8, 2, 3}; break;
-            default: g = {1, 2, 2, 4, 8}; break;       // O, A
+            default: g = {1, 2, 8, 1, 3}; break;       // O, A
         }
         if (const char* p = getenv(kProjEnv[proj])) {
             GemmPlan o = {1, 0, 0, 0, 0};
@@ -485,29 +485,41 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
 }
 
 // e = P(tokens): embedding gather (scaled) and the prelude layers; result in e_out rows (erow0).
-static void prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys) {
+// With z_cat (bf16 path, internal e buffer): the closing pass also writes the adapter operand
+// concat(e, z) for the recurrence that follows, and the function returns true.
+static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys,
+                            const float* z_cat = nullptr) {
     const rdlm_model& m = ctx->m;
     launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->tiles, ctx->n_tiles,
                  T, ctx->st);
     int S = 0;
     for (int l = 0; l < m.n_prelude; ++l) layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S);
+    const size_t pst = (size_t)ctx->rows_pad * m.hidden;
+    if (z_cat && e_which < 0 && m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
+        launch_prelude_end(ctx->x, ctx->part, S, pst, e_out, z_cat, ctx->abuf, m.hidden, ctx->tiles, ctx->n_tiles, T,
+                           ctx->st);
+        return true;
+    }
     // fold the pending partial sums: x <- x + sum part (no norm output needed)
-    launch_addnorm(ctx->x, ctx->x, ctx->part, S, (size_t)ctx->rows_pad * m.hidden, ctx->gf, nullptr, ctx->fmt,
-                   m.hidden, m.rms_eps, ctx->n_tiles, T, ctx->st);
+    launch_addnorm(ctx->x, ctx->x, ctx->part, S, pst, ctx->gf, nullptr, ctx->fmt, m.hidden, m.rms_eps, ctx->n_tiles, T,
+                   ctx->st);
     if (e_out != ctx->x) {
         if (e_which < 0)   // internal e buffer is indexed by padded row: plain copy
             (void)hipMemcpyAsync(e_out, ctx->x, (size_t)T * 32 * m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st);
         else
             launch_copy_rows_out(ctx->x, e_out, m.hidden, e_which, ctx->tiles, ctx->n_tiles, T, ctx->st);
     }
+    return false;
 }
 
 // z <- R(z, e): adapter on concat(e, z), the core layers, closing norm; optional delta vs z_prev.
+// cat_ready: the adapter operand was already written (by the prelude's closing pass); x_for_coda:
+// also leave z' in the residual buffer, where the coda starts from.
 static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev, int update_prev, float* delta,
-                         int T, int max_keys) {
+                         int T, int max_keys, bool cat_ready = false, bool x_for_coda = false) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
-    launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    if (!cat_ready) launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S;
     run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S);
     bool x_valid = false;
@@ -516,14 +528,15 @@ static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev,
         x_valid = true;
     }
     launch_final_norm(ctx->x, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gf, h, m.rms_eps, z, z_prev, update_prev,
-                      delta, ctx->tiles, ctx->n_tiles, T, ctx->st);
+                      delta, x_for_coda ? ctx->x : nullptr, ctx->tiles, ctx->n_tiles, T, ctx->st);
 }
 
 // C: coda layers on z; with sa: final norm, tied LM head and Sample -> ctx->drafts (+ logits).
-static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int T, int max_keys) {
+static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int T, int max_keys,
+                         bool x_ready = false) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
-    launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    if (!x_ready) launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
     for (int l = 0; l < m.n_coda; ++l)
         layer_forward(ctx, ctx->layers[m.n_prelude + m.n_core + l], T, max_keys, true, S, &S);
@@ -717,7 +730,9 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
         max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
     launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
-    prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys);                       // e <- P(y_current)
+    // e <- P(y_current); without momentum or noise the closing pass of P also writes concat(e, z)
+    const bool plain = !(s.eta > 0.f) && !(s.beta > 0.f);
+    bool cat_ready = prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys, plain ? ctx->z_store : nullptr);
     if (s.eta > 0.f)                                                             // Eq. 1
         launch_momentum(ctx->e, ctx->e_store, ctx->counts, s.eta, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (s.beta > 0.f)                                                            // Eq. 2
@@ -726,10 +741,10 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
         bool last = i == s.r_inner - 1;
         core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
-                     last ? ctx->delta : nullptr, T, max_keys);
+                     last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
     }
     SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false};
-    coda_forward(ctx, ctx->z_store, &sa, T, max_keys);                           // p <- C(z); y_hat <- Sample(p)
+    coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
     launch_bookkeep(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
                     ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);        // freeze, append
     launch_init_state_new(ctx->z_store, ctx->z_prev, m.hidden, ctx->seqs, n, ctx->max_positions, s.headway, s.alpha,

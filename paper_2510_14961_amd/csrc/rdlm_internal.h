@@ -175,8 +175,13 @@ void launch_fold(const float* xin, float* xout, const float* part, int S, size_t
                  hipStream_t st);
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride,
                        const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
-                       float* delta, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
-                       hipStream_t st);
+                       float* delta, float* xcopy /* padded-row copy of z for the coda, or null */,
+                       const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+// bf16 path, end of the prelude: e_out (f32, padded rows) = xin + sum part, and the packed adapter
+// operand cat = concat(e, z) with z read from the latent store rows of the tiles
+void launch_prelude_end(const float* xin, const float* part, int S, size_t part_stride, float* e_out, const float* z,
+                        void* cat, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                        hipStream_t st);
 // table: [rows][d/2] (cos, sin) pairs written by launch_rope_table for the current tiles
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles,
                        const int32_t* n_tiles, int max_tiles, hipStream_t st);
