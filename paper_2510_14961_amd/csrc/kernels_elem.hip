@@ -8,7 +8,7 @@
 namespace rdlm {
 
 // ---------------------------------------------------------------------------------------------
-__device__ inline float block_sum(float v, float* sh) {          // 256 threads
+__device__ inline float block_sum(float v, float* sh) {          // up to 1024 threads, sh[16]
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     int w = threadIdx.x >> 6;
     __syncthreads();
@@ -66,10 +66,9 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positi
     int t = 0, c = 0;
     for (int s = 0; s < n_seqs; ++s) {
         SeqState& q = seqs[s];
-        q.pad_[0] = t;                                  // first tile of this sequence
         int rows = q.done ? 0 : q.win_n;
-        q.last_rows = rows;
-        q.last_pos0 = q.win_pos0;
+        q.cur_tile0 = t;                                // first tile of this sequence
+        q.cur_rows = rows;
         for (int off = 0; off < rows; off += TILE_ROWS) {
             TileDesc d;
             d.seq = s;
@@ -88,22 +87,33 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positi
 }
 
 // ---------------------------------------------------------------------------------------------
+// Embedding gather, a row cut into `chunks` workgroups; chunk 0 also writes the row's RoPE table.
 template <typename T>
-__global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float* x, int h, int V,
-                        const TileDesc* tiles, const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
+__global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float* x, int h, int V, int chunks,
+                        float2* rope_table, const float* theta, int half, const TileDesc* tiles,
+                        const int32_t* n_tiles) {
+    int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
     bool valid = j < d.n_valid;
     int tok = valid ? tokens[d.yrow0 + j] : 0;
     tok = min(max(tok, 0), V - 1);
-    for (int k = threadIdx.x; k < h; k += blockDim.x) {
+    const int cw = (h + chunks - 1) / chunks;
+    for (int k = c * cw + threadIdx.x; k < min(h, (c + 1) * cw); k += blockDim.x) {
         float v = 0.f;
         if (valid) {
             if (sizeof(T) == 2) v = bf16_to_f32(reinterpret_cast<const uint16_t*>(emb)[(size_t)tok * h + k]);
             else v = reinterpret_cast<const float*>(emb)[(size_t)tok * h + k];
         }
         x[(size_t)r * h + k] = v * scale;
+    }
+    if (rope_table && c == 0) {
+        const int pos = d.pos0 + j;
+        for (int i = threadIdx.x; i < half; i += blockDim.x) {
+            float sn, cs;
+            sincosf((float)pos * theta[i], &sn, &cs);
+            rope_table[(size_t)r * half + i] = make_float2(cs, sn);
+        }
     }
 }
 
@@ -172,7 +182,7 @@ template <int FMT>
 __global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, const float* part, int S,
                                                   size_t part_stride, const float* gain, void* xn, int h, float eps,
                                                   const int32_t* n_tiles) {
-    __shared__ float sh[8];
+    __shared__ float sh[16];
     int r = blockIdx.x;
     if ((r >> 5) >= *n_tiles) return;
     float4 v[ROW_VEC];
@@ -228,7 +238,7 @@ __global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const flo
 __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, const float* part, int S,
                                                size_t part_stride, const float* gain, void* xg, float* ssq, int h,
                                                int chunks, const int32_t* n_tiles) {
-    __shared__ float sh[8];
+    __shared__ float sh[16];
     const int r = blockIdx.y, c = blockIdx.x;
     if ((r >> 5) >= *n_tiles) return;
     const int cw = h / chunks;
@@ -253,7 +263,7 @@ __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const floa
                                                      const float* gain, int h, float eps, float* z, float* z_prev,
                                                      int update_prev, float* delta, float* xcopy,
                                                      const TileDesc* tiles, const int32_t* n_tiles) {
-    __shared__ float sh[8];
+    __shared__ float sh[16];
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
@@ -423,23 +433,6 @@ __global__ void init_state_rows_k(float* z, float* z_prev, int h, int seq, int p
     }
 }
 
-__global__ void init_state_new_k(float* z, float* z_prev, int h, const SeqState* seqs, int max_positions,
-                                 int headway, float alpha, uint32_t k0, uint32_t k1) {
-    int s = blockIdx.y / headway, a = blockIdx.y % headway;
-    SeqState q = seqs[s];
-    if (a >= q.new_n) return;
-    int blk = blockIdx.x * blockDim.x + threadIdx.x;
-    if (blk * 4 >= h) return;
-    int pos = q.new_pos0 + a;
-    float g[4];
-    gauss4(blk, pos, s, k0, k1, alpha, g);
-    for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
-        size_t o = ((size_t)s * max_positions + pos) * h + blk * 4 + i;
-        z[o] = g[i];
-        z_prev[o] = g[i];
-    }
-}
-
 // Momentum on the conditioning (Eq. 1), one workgroup per row.
 __global__ void momentum_k(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
                            const int32_t* n_tiles) {
@@ -520,58 +513,103 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
     if (threadIdx.x == 0) tok_out[r] = (si[0] == 0x7fffffff) ? 0 : si[0];
 }
 
-// Alg. 1 lines 13-16 / Alg. 2 freeze and append, one thread per sequence.
-__global__ void bookkeep_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
-                           int max_positions, const int32_t* drafts, const float* delta, int32_t* n_active,
-                           int step) {
-    int s = threadIdx.x;
+// End of a sampler step, one workgroup: for every sequence (in turn; its rows in parallel) the
+// drafts become y_current and the step counters advance (Alg. 1 line 13), the longest freezable
+// prefix k* is frozen (Alg. 1 line 14 / Eq. 3), new states are appended unless the wavefront is
+// full (Alg. 1 line 16, Alg. 2) and drawn (InitState); then the tile list of the next step is
+// built from the updated windows.
+__global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y,
+                                                   int32_t* counts, int max_positions, const int32_t* drafts,
+                                                   const float* delta, float* z, float* z_prev, int h,
+                                                   TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step) {
+    __shared__ int first_open;                       // first row of the window that is not freezable
+    __shared__ SeqState cur;
+    const int tid = threadIdx.x;
     int active = 0;
-    if (s < n_seqs) {
-        SeqState q = seqs[s];
-        int rows = q.last_rows;                     // rows this sequence had in the step just run
+    for (int s = 0; s < n_seqs; ++s) {
+        if (tid == 0) { cur = seqs[s]; first_open = 0x7fffffff; }
+        __syncthreads();
+        SeqState q = cur;
+        const int rows = q.cur_rows;                 // rows this sequence had in the step just run
+        const size_t base = (size_t)s * max_positions;
         if (!q.done && rows > 0) {
-            int row0 = q.pad_[0] * TILE_ROWS;       // its rows are contiguous in padded row space
-            size_t base = (size_t)s * max_positions;
-            for (int i = 0; i < rows; ++i) {        // y_current <- [y_frozen, y_hat]
-                int pos = q.win_pos0 + i;
-                y[base + pos + 1] = drafts[row0 + i];
-                counts[base + pos] += 1;
+            const int row0 = q.cur_tile0 * TILE_ROWS;   // its rows are contiguous in padded row space
+            for (int i = tid; i < rows; i += blockDim.x) {
+                const int pos = q.win_pos0 + i;
+                y[base + pos + 1] = drafts[row0 + i];                    // y_current <- [y_frozen, y_hat]
+                const int c = counts[base + pos] + 1;
+                counts[base + pos] = c;
+                const float dl = delta[row0 + i];
+                const bool conv = p.adaptive && (dl == dl) && fabsf(dl) != INFINITY && dl < p.eps;
+                const bool cap = c * p.r_inner >= p.r_total;
+                if (!(conv || cap)) atomicMin(&first_open, i);
             }
-            int k = 0;                              // longest freezable prefix
-            for (; k < rows; ++k) {
-                int pos = q.win_pos0 + k;
-                float dl = delta[row0 + k];
-                bool conv = p.adaptive && (dl == dl) && fabsf(dl) != INFINITY && dl < p.eps;
-                bool cap = counts[base + pos] * p.r_inner >= p.r_total;
-                if (!(conv || cap)) break;
+            __syncthreads();
+            if (tid == 0) {
+                const int k = min(first_open, rows);                     // longest freezable prefix
+                q.last_rows = rows; q.last_pos0 = q.win_pos0; q.last_tile0 = q.cur_tile0;
+                q.n_frozen += k; q.win_pos0 += k; q.win_n -= k;
+                q.new_n = 0;
+                if (q.n_frozen - q.prompt_len >= p.n_new) {
+                    q.done = 1; q.win_n = 0;
+                } else {
+                    const int n_app = min(p.headway, p.w_max - q.win_n);
+                    if (n_app > 0) {
+                        const int start = q.win_n > 0 ? q.win_pos0 + q.win_n : q.n_frozen - 1;
+                        if (q.win_n == 0) q.win_pos0 = start;
+                        q.new_pos0 = start; q.new_n = n_app;
+                        for (int a = 0; a < n_app; ++a) counts[base + start + a] = 0;
+                        q.win_n += n_app;
+                    }
+                }
+                cur = q;
             }
-            q.n_frozen += k; q.win_pos0 += k; q.win_n -= k;
-            q.new_n = 0;
-            if (q.n_frozen - q.prompt_len >= p.n_new) {
-                q.done = 1; q.win_n = 0;
-            } else {
-                int n_app = min(p.headway, p.w_max - q.win_n);
-                if (n_app > 0) {
-                    int start = q.win_n > 0 ? q.win_pos0 + q.win_n : q.n_frozen - 1;
-                    if (q.win_n == 0) q.win_pos0 = start;
-                    q.new_pos0 = start; q.new_n = n_app;
-                    for (int a = 0; a < n_app; ++a) counts[base + start + a] = 0;
-                    q.win_n += n_app;
+            __syncthreads();
+            q = cur;
+            // InitState for the appended positions
+            const int nb = (h + 3) / 4;
+            for (int idx = tid; idx < q.new_n * nb; idx += blockDim.x) {
+                const int a = idx / nb, blk = idx - a * nb, pos = q.new_pos0 + a;
+                float g[4];
+                gauss4(blk, pos, s, p.seed_lo, p.seed_hi, p.alpha, g);
+                for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
+                    const size_t o = (base + pos) * h + blk * 4 + i;
+                    z[o] = g[i];
+                    z_prev[o] = g[i];
                 }
             }
-            seqs[s] = q;
         }
-        active = q.done ? 0 : 1;
+        if (!q.done) active++;
+        __syncthreads();
+        if (tid == 0) seqs[s] = cur;
+        __syncthreads();
     }
-    __shared__ int tot;
-    if (threadIdx.x == 0) tot = 0;
-    __syncthreads();
-    if (active) atomicAdd(&tot, 1);
-    __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         // n_active[1] remembers the step at which the last sequence finished (0 = still running)
-        if (tot == 0 && n_active[0] != 0) n_active[1] = step;
-        n_active[0] = tot;
+        if (active == 0 && n_active[0] != 0) n_active[1] = step;
+        n_active[0] = active;
+        // tile list of the next step
+        int t = 0, c = 0;
+        for (int s = 0; s < n_seqs; ++s) {
+            SeqState& q = seqs[s];
+            const int rows = q.done ? 0 : q.win_n;
+            q.cur_tile0 = t;
+            q.cur_rows = rows;
+            for (int off = 0; off < rows; off += TILE_ROWS) {
+                TileDesc d;
+                d.seq = s;
+                d.pos0 = q.win_pos0 + off;
+                d.n_valid = min(TILE_ROWS, rows - off);
+                d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
+                d.erow0 = t * TILE_ROWS;
+                d.crow0 = c + off;
+                const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
+                d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
+                tiles[t++] = d;
+            }
+            c += rows;
+        }
+        *n_tiles = t;
     }
 }
 
@@ -612,13 +650,17 @@ void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positi
                        max_positions, tiles, n_tiles);
 }
 void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
-                  const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+                  float* rope_table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
+                  int max_tiles, hipStream_t st) {
+    const int chunks = h >= 2048 ? 8 : 1;
+    dim3 grid(chunks, max_tiles * 32);
+    float2* tab = reinterpret_cast<float2*>(rope_table);
     if (dtype == 0)
-        hipLaunchKernelGGL(embed_k<float>, dim3(max_tiles * 32), dim3(256), 0, st, (const float*)emb, tokens, scale,
-                           x, h, V, tiles, n_tiles);
+        hipLaunchKernelGGL(embed_k<float>, grid, dim3(256), 0, st, (const float*)emb, tokens, scale, x, h, V, chunks,
+                           tab, theta, half, tiles, n_tiles);
     else
-        hipLaunchKernelGGL(embed_k<uint16_t>, dim3(max_tiles * 32), dim3(256), 0, st, (const uint16_t*)emb, tokens,
-                           scale, x, h, V, tiles, n_tiles);
+        hipLaunchKernelGGL(embed_k<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)emb, tokens, scale, x, h, V,
+                           chunks, tab, theta, half, tiles, n_tiles);
 }
 void launch_copy_rows_in(const float* src, float* x, int h, int which, const TileDesc* tiles,
                          const int32_t* n_tiles, int max_tiles, hipStream_t st) {
@@ -707,13 +749,6 @@ void launch_init_state_rows(float* z, float* z_prev, int h, int seq, int pos0, i
     hipLaunchKernelGGL(init_state_rows_k, dim3((nb + 255) / 256, n), dim3(256), 0, st, z, z_prev, h, seq, pos0, n,
                        zrow0, alpha, k0, k1);
 }
-void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs, int n_seqs,
-                           int max_positions, int headway, float alpha, uint32_t k0, uint32_t k1,
-                           hipStream_t st) {
-    int nb = (h + 3) / 4;
-    hipLaunchKernelGGL(init_state_new_k, dim3((nb + 255) / 256, n_seqs * headway), dim3(256), 0, st, z, z_prev, h,
-                       seqs, max_positions, headway, alpha, k0, k1);
-}
 void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
                      const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     hipLaunchKernelGGL(momentum_k, dim3(max_tiles * 32), dim3(256), 0, st, e, e_store, counts, eta, h, tiles, n_tiles);
@@ -730,12 +765,11 @@ void launch_sample(const float* logits, int V, float temperature, uint32_t k0, u
     hipLaunchKernelGGL(sample_k, dim3(max_tiles * 32), dim3(256), 0, st, logits, V, temperature, k0, k1, step,
                        tok_out, tiles, n_tiles);
 }
-void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
-                     int max_positions, const int32_t* drafts, const float* delta, const TileDesc* tiles,
-                     const int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st) {
-    (void)tiles; (void)n_tiles;
-    hipLaunchKernelGGL(bookkeep_k, dim3(1), dim3(64), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts,
-                       delta, n_active, step);
+void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
+                     const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
+                     int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st) {
+    hipLaunchKernelGGL(step_end_k, dim3(1), dim3(256), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts, delta,
+                       z, z_prev, h, tiles, n_tiles, n_active, step);
 }
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
     if (!n) return;

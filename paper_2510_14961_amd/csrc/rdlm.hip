@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <utility>
 #include <vector>
 
 using namespace rdlm;
@@ -40,6 +41,8 @@ struct rdlm_ctx {
     // workspace
     TileDesc* tiles = nullptr;
     int32_t* n_tiles = nullptr;
+    TileDesc* tiles_samp = nullptr;      // the sampler's own tile list (built at the end of each step for the next)
+    int32_t* n_tiles_samp = nullptr;
     float *x = nullptr, *e = nullptr, *qkv = nullptr, *gu = nullptr, *part = nullptr, *logits = nullptr;
     float *delta = nullptr, *zp_api = nullptr, *att_ws = nullptr;
     void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
@@ -227,6 +230,8 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     const size_t wide = (size_t)std::max(2 * h, F);
     DALLOC(ctx->tiles, sizeof(TileDesc) * ctx->max_tiles, true);
     DALLOC(ctx->n_tiles, 64, true);
+    DALLOC(ctx->tiles_samp, sizeof(TileDesc) * ctx->max_tiles, true);
+    DALLOC(ctx->n_tiles_samp, 64, true);
     DALLOC(ctx->x, R * h * 4, true);
     DALLOC(ctx->e, R * h * 4, true);
     DALLOC(ctx->qkv, R * 3 * h * 4, true);
@@ -490,8 +495,9 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
 static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys,
                             const float* z_cat = nullptr) {
     const rdlm_model& m = ctx->m;
-    launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->tiles, ctx->n_tiles,
-                 T, ctx->st);
+    // the gather also writes the RoPE table of the step's rows
+    launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->rope_tab, ctx->theta,
+                 m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
     for (int l = 0; l < m.n_prelude; ++l) layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S);
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
@@ -598,7 +604,6 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
-    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
                            (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
     prelude_forward(ctx, ctx->y, ctx->e, -1, T, n);
@@ -623,7 +628,6 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
-    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     prelude_forward(ctx, tokens_dev, e_out, 1, T, mk);
     return check_launch(ctx);
 }
@@ -698,6 +702,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
                                (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
     }
     HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * n_seqs, hipMemcpyHostToDevice));
+    launch_build_tiles_sampler(ctx->seqs, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
     int32_t act[2] = {n_seqs, 0};
     HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
     ctx->sampler = sp;
@@ -728,8 +733,9 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     int max_keys = 0;
     for (int q = 0; q < n; ++q)
         max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
-    launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
-    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    // the tile list of this step was built by sampler_begin or by the end of the previous step
+    std::swap(ctx->tiles, ctx->tiles_samp);
+    std::swap(ctx->n_tiles, ctx->n_tiles_samp);
     // e <- P(y_current); without momentum or noise the closing pass of P also writes concat(e, z)
     const bool plain = !(s.eta > 0.f) && !(s.beta > 0.f);
     bool cat_ready = prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys, plain ? ctx->z_store : nullptr);
@@ -745,10 +751,11 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     }
     SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false};
     coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
-    launch_bookkeep(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
-                    ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);        // freeze, append
-    launch_init_state_new(ctx->z_store, ctx->z_prev, m.hidden, ctx->seqs, n, ctx->max_positions, s.headway, s.alpha,
-                          ctx->sp.seed_lo, ctx->sp.seed_hi, ctx->st);
+    // freeze, append, InitState of the appended positions, tile list of the next step
+    launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
+                    ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);
+    std::swap(ctx->tiles, ctx->tiles_samp);
+    std::swap(ctx->n_tiles, ctx->n_tiles_samp);
     return check_launch(ctx);
 }
 
@@ -824,7 +831,7 @@ extern "C" int rdlm_read_deltas(rdlm_ctx* ctx, int32_t seq, float* delta_host, i
     HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
     int n = std::min(cap, q.last_rows);
     if (n > 0)
-        HIPCHK(hipMemcpy(delta_host, ctx->delta + (size_t)q.pad_[0] * 32, (size_t)n * 4, hipMemcpyDeviceToHost));
+        HIPCHK(hipMemcpy(delta_host, ctx->delta + (size_t)q.last_tile0 * 32, (size_t)n * 4, hipMemcpyDeviceToHost));
     *n_out = q.last_rows;
     return RDLM_OK;
 }

@@ -43,7 +43,9 @@ struct SeqState {
     int32_t last_pos0;
     int32_t new_pos0;     // states appended by the last bookkeeping pass: [new_pos0, new_pos0+new_n)
     int32_t new_n;
-    int32_t pad_[3];
+    int32_t last_tile0;   // first row tile the sequence had in the last step
+    int32_t cur_rows;     // rows / first row tile of the sequence in the tile list built for the next step
+    int32_t cur_tile0;
 };
 
 struct SamplerParams {
@@ -153,8 +155,10 @@ void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* 
                               hipStream_t st);
 void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions,
                                 TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+// x[row] = scale * emb[token of the row]; with rope_table: also the (cos, sin) table of the rows
 void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
-                  const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
+                  float* rope_table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
+                  int max_tiles, hipStream_t st);
 void launch_copy_rows_in(const float* src, float* x, int h, int which /*0=z,1=e*/,
                          const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_copy_rows_out(const float* x, float* dst, int width, int which /*0=z,1=e,2=compact*/,
@@ -192,9 +196,6 @@ void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fm
                    const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_init_state_rows(float* z, float* z_prev, int h, int seq, int pos0, int n, size_t zrow0,
                             float alpha, uint32_t k0, uint32_t k1, hipStream_t st);
-void launch_init_state_new(float* z, float* z_prev, int h, const SeqState* seqs, int n_seqs,
-                           int max_positions, int headway, float alpha, uint32_t k0, uint32_t k1,
-                           hipStream_t st);
 // Eq. 1 on the rows of the step: e <- eta e_prev + (1 - eta) e for positions that have been in
 // flight before (counts > 0); e_store keeps the result per (sequence, position).
 void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
@@ -207,10 +208,12 @@ void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, 
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
                    int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
                    hipStream_t st);
-void launch_bookkeep(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
-                     int max_positions, const int32_t* drafts, const float* delta,
-                     const TileDesc* tiles, const int32_t* n_tiles, int32_t* n_active, int step,
-                     hipStream_t st);
+// End of a sampler step in one launch: drafts -> y_current, step counters, k*, freeze, append
+// (Alg. 1 lines 13-16 / Alg. 2), Gaussian states of the appended positions, and the tile list of
+// the next step.
+void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
+                     const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
+                     int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n,
                     float* k_out, float* v_out, hipStream_t st);
