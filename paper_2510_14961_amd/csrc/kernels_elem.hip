@@ -259,7 +259,8 @@ __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, con
 
 // End of a recurrence: z' = RMSNorm(x + sum part) * gain, stored to the latent array; optionally
 // delta = ||z' - z_prev|| / ||z'|| (Eq. 3) and z_prev <- z'.
-__global__ __launch_bounds__(256) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
+template <int NT>
+__global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
                                                      const float* gain, int h, float eps, float* z, float* z_prev,
                                                      int update_prev, float* delta, float* xcopy,
                                                      const TileDesc* tiles, const int32_t* n_tiles) {
@@ -268,11 +269,12 @@ __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const floa
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
     bool valid = j < d.n_valid;
-    float4 v[ROW_VEC];
+    constexpr int RV = ROW_VEC * 256 / NT;          // float4 per thread: h <= 8192
+    float4 v[RV];
     float ss = 0.f;
 #pragma unroll
-    for (int i = 0; i < ROW_VEC; ++i) {
-        int k = (threadIdx.x + i * 256) * 4;
+    for (int i = 0; i < RV; ++i) {
+        int k = (threadIdx.x + i * NT) * 4;
         if (k < h) {
             v[i] = row_value(xin, part, S, part_stride, (size_t)r * h + k);
             ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
@@ -283,8 +285,8 @@ __global__ __launch_bounds__(256) void final_norm_k(const float* xin, const floa
     float num = 0.f, den = 0.f;
     size_t zr = (size_t)d.zrow0 + j;
 #pragma unroll
-    for (int i = 0; i < ROW_VEC; ++i) {
-        int k = (threadIdx.x + i * 256) * 4;
+    for (int i = 0; i < RV; ++i) {
+        int k = (threadIdx.x + i * NT) * 4;
         if (k < h && !valid && xcopy) *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = make_float4(0, 0, 0, 0);
         if (k < h && valid) {
             float4 g = ld4(gain + k);
@@ -714,8 +716,12 @@ void launch_prelude_end(const float* xin, const float* part, int S, size_t part_
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
                        int h, float eps, float* z, float* z_prev, int update_prev, float* delta, float* xcopy,
                        const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(final_norm_k, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain, h,
-                       eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
+    if (h > 2048)     // long rows: more loads in flight per row
+        hipLaunchKernelGGL(final_norm_k<1024>, dim3(max_tiles * 32), dim3(1024), 0, st, xin, part, S, part_stride,
+                           gain, h, eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
+    else
+        hipLaunchKernelGGL(final_norm_k<256>, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain,
+                           h, eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
 }
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
                        int max_tiles, hipStream_t st) {

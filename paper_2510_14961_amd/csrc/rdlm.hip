@@ -451,7 +451,7 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
     int wgs = ctx->m.n_heads * (ctx->grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
     int kb = (max_keys + 31) / 32;
     int s = 1;
-    while (s < ctx->att_max_split && wgs * s < 512 && kb / (s * 2) >= 8) s *= 2;
+    while (s < ctx->att_max_split && wgs * s < 512 && kb / (s * 2) >= 16) s *= 2;
     return s;
 }
 
