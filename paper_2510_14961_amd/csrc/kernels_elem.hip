@@ -236,8 +236,8 @@ __global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const flo
 // `chunks` pieces handled by different workgroups; each writes x_out, bf16(x_out * gain) in the
 // packed operand layout and its piece of the row's sum of squares.
 __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, const float* part, int S,
-                                               size_t part_stride, const float* gain, void* xg, float* ssq, int h,
-                                               int chunks, const int32_t* n_tiles) {
+                                               size_t part_stride, const float* gain, void* xg, float* ssq,
+                                               size_t ssq_stride, int h, int chunks, const int32_t* n_tiles) {
     __shared__ float sh[16];
     const int r = blockIdx.y, c = blockIdx.x;
     if ((r >> 5) >= *n_tiles) return;
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, con
         }
     }
     ss = block_sum(ss, sh);
-    if (threadIdx.x == 0 && ssq) ssq[(size_t)r * SSQ_MAX_CHUNKS + c] = ss;
+    if (threadIdx.x == 0 && ssq) ssq[(size_t)c * ssq_stride + r] = ss;
 }
 
 // End of a recurrence: z' = RMSNorm(x + sum part) * gain, stored to the latent array; optionally
@@ -701,10 +701,11 @@ int fold_chunks(int h) {
     return h <= 1024 ? 1 : 0;
 }
 void launch_fold(const float* xin, float* xout, const float* part, int S, size_t part_stride, const float* gain,
-                 void* xg, float* ssq, int h, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+                 void* xg, float* ssq, size_t ssq_stride, int h, const int32_t* n_tiles, int max_tiles,
+                 hipStream_t st) {
     const int c = fold_chunks(h);
     hipLaunchKernelGGL(fold_k, dim3(c, max_tiles * 32), dim3(256), 0, st, xin, xout, part, S, part_stride, gain, xg,
-                       ssq, h, c, n_tiles);
+                       ssq, ssq_stride, h, c, n_tiles);
 }
 void launch_prelude_end(const float* xin, const float* part, int S, size_t part_stride, float* e_out, const float* z,
                         void* cat, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,

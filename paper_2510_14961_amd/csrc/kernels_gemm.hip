@@ -52,6 +52,123 @@ __host__ __device__ inline int canon_col(int layout, int blk, int f, int N, int 
     return blk * 32 + f;
 }
 
+// Deferred RMSNorm: 1 / sqrt(mean(x^2) + eps) of the lane's row in each of the workgroup's row tiles,
+// from the per-slot sums of squares the producer of the operand left (slot-major, so a wave reads 32
+// consecutive floats per slot).  Called before the K loop: the loads overlap the weight stream.
+template <int MT>
+__device__ __forceinline__ void gemm_row_scales(const GemmArgs& A, int t0, int n_tiles, float (&sc)[MT]) {
+    const int col = threadIdx.x & 31;
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+        sc[b] = 1.0f;
+        if (A.epi.row_ssq) {
+            const size_t row = (size_t)min(t0 + b, n_tiles - 1) * 32 + col;
+            float ssq = 0.f;
+            for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[(size_t)c * A.epi.ssq_stride + row];
+            sc[b] = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
+        }
+    }
+}
+
+// Fold of the split-K partial sums by the last workgroup of a feature group to arrive (see
+// GemmEpilogue::fold_counter).  No device-scope fence: the partial sums are written and read with
+// system-scope accesses (write-through stores, cache-bypassing loads), every wave waits for its
+// stores to be acknowledged before the workgroup takes its ticket, and the ticket is a
+// system-scope atomic -- so whoever draws the last ticket finds all partial sums in memory.
+// Which workgroup that is does not matter: it adds the S partial sums in split order.
+template <int NB, int THREADS>
+__device__ __forceinline__ void gemm_fold_tail(const GemmArgs& A, int grp, int t0) {
+    static_assert(NB == 1 || NB == 2 || NB == 4, "a row's columns of the group sit in 8, 16 or 32 adjacent lanes");
+    __shared__ uint32_t ticket;
+    __builtin_amdgcn_s_waitcnt(0);                 // this wave's stores have been acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0)
+        ticket = __hip_atomic_fetch_add(A.epi.fold_counter + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    if (ticket != (uint32_t)A.ksplit - 1) return;
+    // one thread per (register quad u of the group, lane): 4 consecutive columns of one row, read
+    // back in the order they were written (coalesced)
+    constexpr int UNITS = NB * 4;
+    __shared__ float unit_ss[UNITS][64];
+    const int N = A.N;
+    for (int slot = threadIdx.x; slot < UNITS * 64; slot += THREADS) {
+        const int u = slot >> 6, ln = slot & 63;
+        const int col = grp * NB * 32 + (u >> 2) * 32 + (u & 3) * 8 + (ln >> 5) * 4;
+        const size_t row = (size_t)t0 * 32 + (ln & 31);
+        float ss = 0.f;
+        if (col < N) {
+            const size_t off = row * N + col;
+            float4 v = A.epi.fold_xin ? *reinterpret_cast<const float4*>(A.epi.fold_xin + off) : make_float4(0, 0, 0, 0);
+            // all loads of a batch of up to 4 splits are issued before the first add
+            for (int s0 = 0; s0 < A.ksplit; s0 += 4) {
+                float p[4][4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float* pp = A.out + (((size_t)grp * A.ksplit + min(s0 + j, A.ksplit - 1)) * (NB * 16) + u * 4) * 64 + ln;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        p[j][i] = __hip_atomic_load(pp + i * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (s0 + j < A.ksplit) { v.x += p[j][0]; v.y += p[j][1]; v.z += p[j][2]; v.w += p[j][3]; }
+                }
+            }
+            ss = v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            *reinterpret_cast<float4*>(A.epi.fold_xout + off) = v;
+            const float4 g = *reinterpret_cast<const float4*>(A.epi.fold_gain + col);
+            ushort4 pk;
+            pk.x = f32_to_bf16(v.x * g.x); pk.y = f32_to_bf16(v.y * g.y);
+            pk.z = f32_to_bf16(v.z * g.z); pk.w = f32_to_bf16(v.w * g.w);
+            *reinterpret_cast<ushort4*>(reinterpret_cast<uint16_t*>(A.epi.fold_xg) + packed_off((int)row, col, N)) = pk;
+        }
+        unit_ss[u][ln] = ss;
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {                        // the group's share of each row's sum of squares
+        float ss = 0.f;
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) ss += unit_ss[u][threadIdx.x] + unit_ss[u][threadIdx.x + 32];
+        __hip_atomic_store(A.epi.fold_ssq + (size_t)grp * A.epi.ssq_stride + (size_t)t0 * 32 + threadIdx.x, ss,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(A.epi.fold_counter + grp, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    // second level, same protocol: the last group to finish adds the groups' shares of every row's
+    // sum of squares (in group order) and leaves one value per row for the consumer
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    uint32_t* total = A.epi.fold_counter + SSQ_MAX_CHUNKS;
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(total, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    if (ticket != (uint32_t)A.n_groups - 1) return;
+    __shared__ float part_ss[THREADS / 32][32];
+    {
+        constexpr int PARTS = THREADS / 32;
+        const int rt = threadIdx.x & 31, pt = threadIdx.x >> 5;
+        const size_t row = (size_t)t0 * 32 + rt;
+        float acc = 0.f;
+        for (int c0 = pt; c0 < A.n_groups; c0 += 8 * PARTS) {           // batches of 8 loads in flight
+            float v8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                v8[j] = __hip_atomic_load(A.epi.fold_ssq + (size_t)min(c0 + j * PARTS, A.n_groups - 1) * A.epi.ssq_stride + row,
+                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (c0 + j * PARTS < A.n_groups) acc += v8[j];
+        }
+        part_ss[pt][rt] = acc;
+        __syncthreads();
+        if (pt == 0) {
+            float tot = 0.f;
+#pragma unroll
+            for (int q = 0; q < PARTS; ++q) tot += part_ss[q][rt];
+            A.epi.fold_ssq[(size_t)SSQ_MAX_CHUNKS * A.epi.ssq_stride + row] = tot;
+        }
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(total, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // Finishing work of a workgroup that holds the sums of NB feature blocks x MT row tiles.
 // quad_sum(a, b, q, out[4]) returns accumulator registers 4q..4q+3 of (block a, row tile b) for this
 // lane: rows 8q + 4g + i of the weight block against activation row `col`.  The work is cut into
@@ -60,27 +177,20 @@ __host__ __device__ inline int canon_col(int layout, int blk, int f, int N, int 
 // wave w of the DEAL waves that share the sums takes the units u with u % DEAL == w.
 template <int MT, int NB, int WAVES, int DEAL, int EPI, class QuadSum, class CV, class CI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk)[NB], int t0, int n_tiles, int ks,
-                                              int grp, QuadSum quad_sum, CV& cand_v, CI& cand_i) {
+                                              int grp, const float (&sc)[MT], QuadSum quad_sum, CV& cand_v,
+                                              CI& cand_i) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nblk = A.N >> 5;
     const int col = lane & 31, g = lane >> 5;
     constexpr bool PAIRED = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV);
     constexpr int UQ = PAIRED ? 2 : 4;
 
-    // per row tile: deferred RMSNorm factor of the lane's row, tile descriptor
-    float sc[MT];
+    // per row tile: tile descriptor (sc: deferred RMSNorm factor of the lane's row)
     TileDesc td[MT];
 #pragma unroll
     for (int b = 0; b < MT; ++b) {
-        sc[b] = 1.0f;
         const int t = min(t0 + b, n_tiles - 1);
         if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = A.epi.tiles[t];
-        if (A.epi.row_ssq) {
-            const size_t row = (size_t)t * 32 + col;
-            float ssq = 0.f;
-            for (int c = 0; c < A.epi.ssq_chunks; ++c) ssq += A.epi.row_ssq[row * SSQ_MAX_CHUNKS + c];
-            sc[b] = 1.0f / sqrtf(ssq / (float)A.epi.norm_h + A.epi.norm_eps);
-        }
     }
     float best_v[MT];
     int best_i[MT];
@@ -104,7 +214,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
         if constexpr (EPI == EPI_F32) {
             float* o = A.out + (size_t)ks * A.part_stride;
             const int c0 = canon_col(A.epi.layout, blk[a], f0, A.N, A.epi.n_heads, A.epi.head_dim);
-            *reinterpret_cast<float4*>(o + row * A.N + c0) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+            if (A.epi.fold_counter) {
+                // another workgroup reads these: written through to memory, in accumulator order
+                // [group][split][register][lane] so that a wave writes 256 contiguous bytes
+                float* pf = A.out + (((size_t)grp * A.ksplit + ks) * (NB * 16) + (a * 4 + q) * 4) * 64 + lane;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(pf + i * 64, lo[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            } else {
+                *reinterpret_cast<float4*>(o + row * A.N + c0) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+            }
         } else if constexpr (EPI == EPI_SWIGLU) {
             // rows f0.. are gate features 16 blk + f0.., rows 16 + f0.. the up features of the same index
             const int F = A.N >> 1;
@@ -223,6 +342,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     // K range of this wave: K16 tiles split evenly over ksplit * WAVES slices
     const int slices = A.ksplit * WAVES, sl = ks * WAVES + wave;
     const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
+    float sc[MT];
+    gemm_row_scales<MT>(A, t0, n_tiles, sc);
 
     f32x16 acc[NB][MT];
 #pragma unroll
@@ -324,7 +445,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
             }
         }
     };
-    gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, quad_sum, cand_v, cand_i);
+    gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i);
+    if constexpr (EPI == EPI_F32 && MT == 1 && (NB == 1 || NB == 2 || NB == 4))
+        if (A.epi.fold_counter) gemm_fold_tail<NB, WAVES * 64>(A, grp, t0);
 }
 
 // Row-tile-sharing variant for steps with several row tiles (wide windows, ragged batches,
@@ -353,6 +476,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     if (t0 >= n_tiles) return;
     const int nblk = A.N >> 5, K16 = A.K16;
     const int kbeg = (int)(((long long)K16 * ks) / A.ksplit), kend = (int)(((long long)K16 * (ks + 1)) / A.ksplit);
+    float sc[MT];
+    gemm_row_scales<MT>(A, t0, n_tiles, sc);
 
     f32x16 acc[NB][MT];
 #pragma unroll
@@ -448,7 +573,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = acc[a][b][q * 4 + i];
     };
-    gemm_epilogue<MT, NB, WAVES, 1, EPI>(A, blk, t0, n_tiles, ks, grp, quad_sum, cand_v, cand_i);
+    gemm_epilogue<MT, NB, WAVES, 1, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i);
 }
 
 // one candidate (score, token) per (feature group, row) -> the row's token; lowest id wins ties

@@ -36,7 +36,9 @@ struct rdlm_ctx {
     float* gf = nullptr;
     float* gout = nullptr;
     float* theta = nullptr;
-    float* ssq = nullptr;           // [rows_pad][8] partial sums of squares of the folded rows
+    float* ssq = nullptr;           // [rows_pad][SSQ_MAX_CHUNKS] partial sums of squares of the folded rows
+    int ssq_count = 0;              // slots per row the last producer of the normalised operand filled
+    uint32_t* fold_counter = nullptr;   // tickets of the folding GEMMs, one per feature group, zero between launches
     float* rope_tab = nullptr;      // [rows_pad][d/2] (cos, sin) of the current step's rows
     // workspace
     TileDesc* tiles = nullptr;
@@ -245,7 +247,8 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->q, R * h * esz, true);
     DALLOC(ctx->att, R * h * esz, true);
     DALLOC(ctx->drafts, R * 4, true);
-    DALLOC(ctx->ssq, R * SSQ_MAX_CHUNKS * 4, true);
+    DALLOC(ctx->ssq, R * (SSQ_MAX_CHUNKS + 1) * 4, true);      // + one slot: row totals left by a folding GEMM
+    DALLOC(ctx->fold_counter, (SSQ_MAX_CHUNKS + 1) * 4, true);
     DALLOC(ctx->rope_tab, R * (m.head_dim / 2) * 8, true);
     DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
     DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
@@ -368,9 +371,18 @@ struct SampleArgs {
 //   QKV -> ctx->qkv (f32), O / D / A -> ctx->part ([S] partial sums, *S_out = S),
 //   GU -> ctx->abuf (SwiGLU applied; bf16 path fuses it into the GEMM), HEAD -> ctx->drafts
 //   (sampled tokens; logits in ctx->logits when asked for, always on the f32 path).
+// fold (O, D, A on the one-tile bf16 path): the GEMM itself folds its split-K partial sums into
+// the residual rows and prepares the next normalised operand (see GemmEpilogue::fold_counter);
+// *folded tells whether it did, in which case no partial sums are pending (*S_out = 0).
+struct FoldSpec {
+    const float* xin;     // residual rows before the projection (null: none)
+    float* xout;
+    const float* gain;    // gain of the RMSNorm that follows
+};
 static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int T, int* S_out,
                     const SampleArgs* sa = nullptr, bool plain = false, bool deferred_norm = false,
-                    const Layer* rope_layer = nullptr, bool* rope_fused = nullptr) {
+                    const Layer* rope_layer = nullptr, bool* rope_fused = nullptr, const FoldSpec* fold = nullptr,
+                    bool* folded = nullptr) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden, F = m.mlp;
     int N, K;
@@ -396,6 +408,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
     }
     GemmPlan g = plan_for(ctx, proj, N, K, T);
     GemmEpilogue epi;
+    epi.ssq_stride = ctx->rows_pad;
     epi.n_heads = m.n_heads; epi.head_dim = m.head_dim;
     if (proj == PROJ_GU) epi.layout = WL_GU16;
     if (proj == PROJ_QKV) epi.layout = WL_ROPE;
@@ -416,7 +429,17 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         if (!sa->want_logits) out = nullptr;
     }
     if (deferred_norm) {
-        epi.row_ssq = ctx->ssq; epi.ssq_chunks = fold_chunks(h); epi.norm_h = h; epi.norm_eps = m.rms_eps;
+        // ssq_count 0: a folding GEMM left the row totals in the last slot
+        epi.row_ssq = ctx->ssq_count ? ctx->ssq : ctx->ssq + (size_t)SSQ_MAX_CHUNKS * ctx->rows_pad;
+        epi.ssq_chunks = ctx->ssq_count ? ctx->ssq_count : 1; epi.norm_h = h; epi.norm_eps = m.rms_eps;
+    }
+    if (folded) *folded = false;
+    const bool do_fold = fold && !plain && T == 1 && epi.kind == EPI_F32 && g.kind == GEMM_STREAM && g.mt == 1 &&
+                         (g.nb == 1 || g.nb == 2 || g.nb == 4) && gemm_groups(N, g, EPI_F32) <= SSQ_MAX_CHUNKS &&
+                         !getenv("RDLM_NO_FOLD_FUSION");
+    if (do_fold) {
+        epi.fold_counter = ctx->fold_counter; epi.fold_xin = fold->xin; epi.fold_xout = fold->xout;
+        epi.fold_gain = fold->gain; epi.fold_xg = ctx->xn; epi.fold_ssq = ctx->ssq;
     }
     const bool prof = ctx->prof_n == N && ctx->prof_k == K && (size_t)ctx->prof_used + 2 <= ctx->prof_ev.size();
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
@@ -442,6 +465,11 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         launch_argmax_final(ctx->cand_val, ctx->cand_idx, gemm_groups(N, g, EPI_ARGMAX), ctx->rows_pad, ctx->drafts,
                             ctx->n_tiles, T, ctx->st);
     if (S_out) *S_out = g.ksplit;
+    if (do_fold && epi.fold_counter) {      // (a fallback plan above would have dropped the fold with the epilogue)
+        ctx->ssq_count = 0;
+        if (S_out) *S_out = 0;
+        if (folded) *folded = true;
+    }
     return RDLM_OK;
 }
 
@@ -461,7 +489,8 @@ static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, co
     const rdlm_model& m = ctx->m;
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
     if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
-        launch_fold(xin, xout, ctx->part, S, pst, gain, xn, ctx->ssq, m.hidden, ctx->n_tiles, T, ctx->st);
+        launch_fold(xin, xout, ctx->part, S, pst, gain, xn, ctx->ssq, ctx->rows_pad, m.hidden, ctx->n_tiles, T, ctx->st);
+        ctx->ssq_count = fold_chunks(m.hidden);
         return true;
     }
     launch_addnorm(xin, xout, ctx->part, S, pst, gain, xn, ctx->fmt, m.hidden, m.rms_eps, ctx->n_tiles, T, ctx->st);
@@ -469,13 +498,18 @@ static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, co
 }
 
 // One transformer layer over the current tiles.  On entry the residual stream is
-// x (+ the S_in partial sums in part, if any); on exit it is x + the *S_out partials in part.
-static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out) {
+// x (+ the S_in partial sums in part, if any) -- or, with xn_ready, x is complete and its
+// normalised operand (gain g1) is already in xn.  On exit it is x + the *S_out partials in part;
+// with next_gain the down projection may fold them itself and prepare the operand of the norm with
+// that gain (*next_ready).
+static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out,
+                          bool xn_ready = false, const float* next_gain = nullptr, bool* next_ready = nullptr) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
     hipStream_t st = ctx->st;
     int S;
-    bool dn = norm_operand(ctx, x_valid ? ctx->x : nullptr, ctx->x, S_in, L.g1, ctx->xn, T);
+    bool dn = true;
+    if (!xn_ready) dn = norm_operand(ctx, x_valid ? ctx->x : nullptr, ctx->x, S_in, L.g1, ctx->xn, T);
     bool rope_done = false;
     run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S, nullptr, false, dn, &L, &rope_done);
     if (!rope_done)
@@ -483,10 +517,16 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
                        (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
                      att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
-    run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S);
-    dn = norm_operand(ctx, ctx->x, ctx->x, S, L.g2, ctx->xn, T);
+    const FoldSpec fo = {ctx->x, ctx->x, L.g2};
+    bool folded = false;
+    run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded);
+    dn = folded ? true : norm_operand(ctx, ctx->x, ctx->x, S, L.g2, ctx->xn, T);
     run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S, nullptr, false, dn);   // leaves silu(gate) * up in abuf
-    run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out);
+    const FoldSpec fd = {ctx->x, ctx->x, next_gain};
+    folded = false;
+    run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out, nullptr, false, false, nullptr, nullptr,
+             next_gain ? &fd : nullptr, &folded);
+    if (next_ready) *next_ready = folded;
 }
 
 // e = P(tokens): embedding gather (scaled) and the prelude layers; result in e_out rows (erow0).
@@ -499,7 +539,10 @@ static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, 
     launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->rope_tab, ctx->theta,
                  m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
-    for (int l = 0; l < m.n_prelude; ++l) layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S);
+    bool ready = false;
+    for (int l = 0; l < m.n_prelude; ++l)
+        layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S, ready,
+                      l + 1 < m.n_prelude ? ctx->layers[l + 1].g1 : nullptr, &ready);
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
     if (z_cat && e_which < 0 && m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
         launch_prelude_end(ctx->x, ctx->part, S, pst, e_out, z_cat, ctx->abuf, m.hidden, ctx->tiles, ctx->n_tiles, T,
@@ -527,10 +570,13 @@ static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev,
     const int h = m.hidden;
     if (!cat_ready) launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S;
-    run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S);
-    bool x_valid = false;
+    const FoldSpec fa = {nullptr, ctx->x, ctx->layers[m.n_prelude].g1};
+    bool ready = false;
+    run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S, nullptr, false, false, nullptr, nullptr, &fa, &ready);
+    bool x_valid = ready;
     for (int l = 0; l < m.n_core; ++l) {
-        layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S);
+        layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S, ready,
+                      l + 1 < m.n_core ? ctx->layers[m.n_prelude + l + 1].g1 : nullptr, &ready);
         x_valid = true;
     }
     launch_final_norm(ctx->x, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gf, h, m.rms_eps, z, z_prev, update_prev,
@@ -544,10 +590,13 @@ static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, in
     const int h = m.hidden;
     if (!x_ready) launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
+    bool ready = false;
+    const int l0 = m.n_prelude + m.n_core;
     for (int l = 0; l < m.n_coda; ++l)
-        layer_forward(ctx, ctx->layers[m.n_prelude + m.n_core + l], T, max_keys, true, S, &S);
+        layer_forward(ctx, ctx->layers[l0 + l], T, max_keys, true, S, &S, ready,
+                      l + 1 < m.n_coda ? ctx->layers[l0 + l + 1].g1 : (sa ? ctx->gout : nullptr), &ready);
     if (!sa) return;
-    bool dn = norm_operand(ctx, ctx->x, nullptr, S, ctx->gout, ctx->xn, T);
+    bool dn = ready ? true : norm_operand(ctx, ctx->x, nullptr, S, ctx->gout, ctx->xn, T);
     run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa, false, dn);
 }
 

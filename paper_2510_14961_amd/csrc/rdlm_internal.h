@@ -141,12 +141,24 @@ struct GemmEpilogue {
     size_t seq_stride = 0;
     // Deferred RMSNorm: when row_ssq is set, the input rows were stored as x * gain without the
     // 1/rms factor; every output row is multiplied by 1/sqrt(sum_c row_ssq[row][c] / h + eps).
-    const float* row_ssq = nullptr;
+    const float* row_ssq = nullptr;      // [slot][ssq_stride rows]
     int ssq_chunks = 0;
+    size_t ssq_stride = 0;
+    // EPI_F32 with fold_counter set (one row tile, WL_NATURAL, 1, 2 or 4 blocks per workgroup): the
+    // split-K partial sums are written through to memory; the last workgroup of a feature group to
+    // arrive (ticket in fold_counter[group], left at zero again) adds them in split order to the
+    // residual rows, and writes x_out, bf16(x_out * gain) as packed operand and the group's share
+    // of each row's sum of squares (slot = group) -- what fold_k would do in a launch of its own.
+    uint32_t* fold_counter = nullptr;
+    const float* fold_xin = nullptr;
+    float* fold_xout = nullptr;
+    const float* fold_gain = nullptr;
+    void* fold_xg = nullptr;
+    float* fold_ssq = nullptr;
     int norm_h = 0;
     float norm_eps = 0.f;
 };
-constexpr int SSQ_MAX_CHUNKS = 8;
+constexpr int SSQ_MAX_CHUNKS = 256;   // slots per row: chunks of fold_k, or feature groups of a folding GEMM
 
 // elementwise / row kernels ------------------------------------------------------------------
 void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
@@ -175,8 +187,8 @@ void launch_addnorm(const float* xin, float* xout, const float* part, int S, siz
 // row is split over `chunks` workgroups, so a 32-row step still fills the chip.
 int fold_chunks(int h);
 void launch_fold(const float* xin, float* xout, const float* part, int S, size_t part_stride,
-                 const float* gain, void* xg, float* ssq, int h, const int32_t* n_tiles, int max_tiles,
-                 hipStream_t st);
+                 const float* gain, void* xg, float* ssq, size_t ssq_stride, int h, const int32_t* n_tiles,
+                 int max_tiles, hipStream_t st);
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride,
                        const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
                        float* delta, float* xcopy /* padded-row copy of z for the coda, or null */,
