@@ -90,8 +90,9 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positi
 // Embedding gather, a row cut into `chunks` workgroups; chunk 0 also writes the row's RoPE table.
 template <typename T>
 __global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float* x, int h, int V, int chunks,
-                        float2* rope_table, const float* theta, int half, const TileDesc* tiles,
-                        const int32_t* n_tiles) {
+                        float2* rope_table, const float* theta, int half, const float* gain, void* xg, float* ssq,
+                        size_t ssq_stride, const TileDesc* tiles, const int32_t* n_tiles) {
+    __shared__ float sh[16];
     int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
@@ -99,13 +100,23 @@ __global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float*
     int tok = valid ? tokens[d.yrow0 + j] : 0;
     tok = min(max(tok, 0), V - 1);
     const int cw = (h + chunks - 1) / chunks;
+    float ss = 0.f;
     for (int k = c * cw + threadIdx.x; k < min(h, (c + 1) * cw); k += blockDim.x) {
         float v = 0.f;
         if (valid) {
             if (sizeof(T) == 2) v = bf16_to_f32(reinterpret_cast<const uint16_t*>(emb)[(size_t)tok * h + k]);
             else v = reinterpret_cast<const float*>(emb)[(size_t)tok * h + k];
         }
-        x[(size_t)r * h + k] = v * scale;
+        v *= scale;
+        x[(size_t)r * h + k] = v;
+        if (xg) {                 // operand of the first layer's norm, 1/rms left to the consuming GEMM
+            reinterpret_cast<uint16_t*>(xg)[packed_off(r, k, h)] = f32_to_bf16(v * gain[k]);
+            ss += v * v;
+        }
+    }
+    if (xg) {
+        ss = block_sum(ss, sh);
+        if (threadIdx.x == 0) ssq[(size_t)c * ssq_stride + r] = ss;
     }
     if (rope_table && c == 0) {
         const int pos = d.pos0 + j;
@@ -262,8 +273,9 @@ __global__ __launch_bounds__(256) void fold_k(const float* xin, float* xout, con
 template <int NT>
 __global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float* part, int S, size_t part_stride,
                                                      const float* gain, int h, float eps, float* z, float* z_prev,
-                                                     int update_prev, float* delta, float* xcopy,
-                                                     const TileDesc* tiles, const int32_t* n_tiles) {
+                                                     int update_prev, float* delta, float* xcopy, const float* gain2,
+                                                     void* xg, float* ssq_tot, const TileDesc* tiles,
+                                                     const int32_t* n_tiles) {
     __shared__ float sh[16];
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
@@ -287,7 +299,10 @@ __global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float
 #pragma unroll
     for (int i = 0; i < RV; ++i) {
         int k = (threadIdx.x + i * NT) * 4;
-        if (k < h && !valid && xcopy) *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = make_float4(0, 0, 0, 0);
+        if (k < h && !valid && xcopy) {
+            *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = make_float4(0, 0, 0, 0);
+            if (xg) act_store4<ACT_BF16P>(xg, h, r, k, 0.f, 0.f, 0.f, 0.f);
+        }
         if (k < h && valid) {
             float4 g = ld4(gain + k);
             float4 o = make_float4(v[i].x * inv * g.x, v[i].y * inv * g.y, v[i].z * inv * g.z, v[i].w * inv * g.w);
@@ -300,12 +315,19 @@ __global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float
             den += o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
             *reinterpret_cast<float4*>(z + zr * h + k) = o;
             if (xcopy) *reinterpret_cast<float4*>(xcopy + (size_t)r * h + k) = o;
+            if (xg) {             // operand of the coda's first norm (gain2), 1/rms left to the consuming GEMM
+                float4 g2 = ld4(gain2 + k);
+                act_store4<ACT_BF16P>(xg, h, r, k, o.x * g2.x, o.y * g2.y, o.z * g2.z, o.w * g2.w);
+            }
         }
     }
-    if (delta) {
+    if (delta || xg) {
         num = block_sum(num, sh);
         den = block_sum(den, sh);
-        if (threadIdx.x == 0) delta[r] = valid ? sqrtf(num) / sqrtf(den) : 0.f;
+        if (threadIdx.x == 0) {
+            if (delta) delta[r] = valid ? sqrtf(num) / sqrtf(den) : 0.f;
+            if (xg) ssq_tot[r] = den;                       // sum of z'^2 over the row (0 for padding rows)
+        }
     }
 }
 
@@ -652,17 +674,17 @@ void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positi
                        max_positions, tiles, n_tiles);
 }
 void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
-                  float* rope_table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
-                  int max_tiles, hipStream_t st) {
-    const int chunks = h >= 2048 ? 8 : 1;
+                  float* rope_table, const float* theta, int half, const float* gain, void* xg, float* ssq,
+                  size_t ssq_stride, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    const int chunks = xg ? fold_chunks(h) : (h >= 2048 ? 8 : 1);
     dim3 grid(chunks, max_tiles * 32);
     float2* tab = reinterpret_cast<float2*>(rope_table);
     if (dtype == 0)
         hipLaunchKernelGGL(embed_k<float>, grid, dim3(256), 0, st, (const float*)emb, tokens, scale, x, h, V, chunks,
-                           tab, theta, half, tiles, n_tiles);
+                           tab, theta, half, gain, xg, ssq, ssq_stride, tiles, n_tiles);
     else
         hipLaunchKernelGGL(embed_k<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)emb, tokens, scale, x, h, V,
-                           chunks, tab, theta, half, tiles, n_tiles);
+                           chunks, tab, theta, half, gain, xg, ssq, ssq_stride, tiles, n_tiles);
 }
 void launch_copy_rows_in(const float* src, float* x, int h, int which, const TileDesc* tiles,
                          const int32_t* n_tiles, int max_tiles, hipStream_t st) {
@@ -716,13 +738,14 @@ void launch_prelude_end(const float* xin, const float* part, int S, size_t part_
 }
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
                        int h, float eps, float* z, float* z_prev, int update_prev, float* delta, float* xcopy,
-                       const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+                       const float* gain2, void* xg, float* ssq_tot, const TileDesc* tiles, const int32_t* n_tiles,
+                       int max_tiles, hipStream_t st) {
     if (h > 2048)     // long rows: more loads in flight per row
         hipLaunchKernelGGL(final_norm_k<1024>, dim3(max_tiles * 32), dim3(1024), 0, st, xin, part, S, part_stride,
-                           gain, h, eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
+                           gain, h, eps, z, z_prev, update_prev, delta, xcopy, gain2, xg, ssq_tot, tiles, n_tiles);
     else
         hipLaunchKernelGGL(final_norm_k<256>, dim3(max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, gain,
-                           h, eps, z, z_prev, update_prev, delta, xcopy, tiles, n_tiles);
+                           h, eps, z, z_prev, update_prev, delta, xcopy, gain2, xg, ssq_tot, tiles, n_tiles);
 }
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
                        int max_tiles, hipStream_t st) {

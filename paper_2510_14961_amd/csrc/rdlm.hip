@@ -69,6 +69,7 @@ struct rdlm_ctx {
     float* cand_val = nullptr;
     int32_t* cand_idx = nullptr;
     int forced_att_split = 0;
+    bool coda_ready = false;        // the closing norm of the recurrence left the coda's first operand in xn
     bool grouped = false;           // current step: some sequence has several row tiles (grouped attention)
     // per-launch GEMM timing
     int prof_n = 0, prof_k = 0, prof_used = 0;
@@ -535,11 +536,15 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
 static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys,
                             const float* z_cat = nullptr) {
     const rdlm_model& m = ctx->m;
-    // the gather also writes the RoPE table of the step's rows
+    // the gather also writes the RoPE table of the step's rows and, on the bf16 path, the operand
+    // of the first layer's norm
+    const bool prep = m.dtype == RDLM_BF16 && m.n_prelude > 0 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD");
     launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->rope_tab, ctx->theta,
-                 m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+                 m.head_dim / 2, prep ? ctx->layers[0].g1 : nullptr, prep ? ctx->xn : nullptr, ctx->ssq, ctx->rows_pad,
+                 ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
-    bool ready = false;
+    bool ready = prep;
+    if (prep) ctx->ssq_count = fold_chunks(m.hidden);
     for (int l = 0; l < m.n_prelude; ++l)
         layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S, ready,
                       l + 1 < m.n_prelude ? ctx->layers[l + 1].g1 : nullptr, &ready);
@@ -579,8 +584,15 @@ static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev,
                       l + 1 < m.n_core ? ctx->layers[m.n_prelude + l + 1].g1 : nullptr, &ready);
         x_valid = true;
     }
+    // before the coda: also leave z' in the residual buffer and, on the bf16 path, the operand of the
+    // coda's first norm with the row totals of z'^2
+    const bool prep = x_for_coda && m.dtype == RDLM_BF16 && m.n_coda > 0 && !getenv("RDLM_NO_FOLD");
     launch_final_norm(ctx->x, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gf, h, m.rms_eps, z, z_prev, update_prev,
-                      delta, x_for_coda ? ctx->x : nullptr, ctx->tiles, ctx->n_tiles, T, ctx->st);
+                      delta, x_for_coda ? ctx->x : nullptr, prep ? ctx->layers[m.n_prelude + m.n_core].g1 : nullptr,
+                      prep ? ctx->xn : nullptr, ctx->ssq + (size_t)SSQ_MAX_CHUNKS * ctx->rows_pad, ctx->tiles,
+                      ctx->n_tiles, T, ctx->st);
+    if (prep) ctx->ssq_count = 0;
+    ctx->coda_ready = prep;
 }
 
 // C: coda layers on z; with sa: final norm, tied LM head and Sample -> ctx->drafts (+ logits).
@@ -590,7 +602,8 @@ static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, in
     const int h = m.hidden;
     if (!x_ready) launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S = 0;
-    bool ready = false;
+    bool ready = x_ready && ctx->coda_ready;
+    ctx->coda_ready = false;
     const int l0 = m.n_prelude + m.n_core;
     for (int l = 0; l < m.n_coda; ++l)
         layer_forward(ctx, ctx->layers[l0 + l], T, max_keys, true, S, &S, ready,

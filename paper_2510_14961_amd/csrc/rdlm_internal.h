@@ -167,10 +167,12 @@ void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* 
                               hipStream_t st);
 void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions,
                                 TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
-// x[row] = scale * emb[token of the row]; with rope_table: also the (cos, sin) table of the rows
+// x[row] = scale * emb[token of the row]; with rope_table: also the (cos, sin) table of the rows;
+// with xg (bf16 path): also bf16(x * gain) as packed operand and the fold_chunks(h) per-chunk sums of
+// squares of each row (what fold_k would leave for the first layer's norm)
 void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
-                  float* rope_table, const float* theta, int half, const TileDesc* tiles, const int32_t* n_tiles,
-                  int max_tiles, hipStream_t st);
+                  float* rope_table, const float* theta, int half, const float* gain, void* xg, float* ssq,
+                  size_t ssq_stride, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_copy_rows_in(const float* src, float* x, int h, int which /*0=z,1=e*/,
                          const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_copy_rows_out(const float* x, float* dst, int width, int which /*0=z,1=e,2=compact*/,
@@ -192,6 +194,8 @@ void launch_fold(const float* xin, float* xout, const float* part, int S, size_t
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride,
                        const float* gain, int h, float eps, float* z, float* z_prev, int update_prev,
                        float* delta, float* xcopy /* padded-row copy of z for the coda, or null */,
+                       const float* gain2, void* xg /* with xcopy: packed bf16(z' * gain2), or null */,
+                       float* ssq_tot /* with xg: sum of z'^2 per row */,
                        const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 // bf16 path, end of the prelude: e_out (f32, padded rows) = xin + sum part, and the packed adapter
 // operand cat = concat(e, z) with z read from the latent store rows of the tiles
