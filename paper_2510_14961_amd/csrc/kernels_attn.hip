@@ -21,6 +21,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int ATT_WAVES = 4;
+constexpr int ATT_MAX_SPLIT = 8;
 
 // partial record per (tile, head, split): m[32], l[32], O[32][D]
 __host__ __device__ inline size_t att_rec_floats(int D) { return 64 + 32 * (size_t)D; }
@@ -35,6 +36,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
                                                                const uint16_t* __restrict__ kc,
                                                                const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
                                                                int H, size_t seq_stride, int nsplit, float* __restrict__ ws,
+                                                               uint32_t* __restrict__ tickets,
                                                                const TileDesc* tiles, const int32_t* n_tiles) {
     constexpr int DK = D / 16;      // k steps of the score contraction
     constexpr int DB = D / 32;      // 32-row blocks of O^T
@@ -170,6 +172,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
         // wave w finishes the register quads with quad % ATT_WAVES == w; register (d, i) of lane
         // (col, g) is dim 32d + 8*(i/4) + 4g + i%4 of query `col`
         const int row = (t + b) * 32 + col;
+        // split partials: [m[32], l[32], O in accumulator order [quad][i][lane]] (a wave writes 256
+        // contiguous bytes), written through to memory when another workgroup will merge them
         float* rec = ws + (((size_t)(t + b) * H + hd) * nsplit + sp) * att_rec_floats(D);
         for (int quad = wave; quad < DB * 4; quad += ATT_WAVES) {
             float v[4];
@@ -189,14 +193,65 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
                 pk.z = f32_to_bf16(v[2] * inv); pk.w = f32_to_bf16(v[3] * inv);
                 *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
             } else {
-                *reinterpret_cast<float4*>(rec + 64 + (size_t)col * D + dim) = make_float4(v[0], v[1], v[2], v[3]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    __hip_atomic_store(rec + 64 + (size_t)(quad * 4 + i) * 64 + lane, v[i], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_SYSTEM);
             }
         }
         if (nsplit > 1 && wave == 0 && g == 0) {
-            rec[col] = M;
-            rec[32 + col] = L;
+            __hip_atomic_store(rec + col, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(rec + 32 + col, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
+    if (nsplit == 1) return;
+    // The last split of this (tile, head) to arrive merges all of them.  No device-scope fence:
+    // partials are written and read with system-scope accesses, every wave waits for its stores to
+    // be acknowledged before the workgroup draws its ticket (a system-scope atomic).
+    __shared__ uint32_t ticket;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    uint32_t* tk = tickets + (size_t)t * H + hd;
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    if (ticket != (uint32_t)nsplit - 1) return;
+    const float* base = ws + ((size_t)t * H + hd) * nsplit * att_rec_floats(D);
+    for (int item = threadIdx.x; item < DB * 4 * 64; item += ATT_WAVES * 64) {
+        const int quad = item >> 6, ln = item & 63, c = ln & 31, gg = ln >> 5;
+        float m[ATT_MAX_SPLIT], l[ATT_MAX_SPLIT], v[ATT_MAX_SPLIT][4];
+#pragma unroll
+        for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
+            const float* r = base + (size_t)min(s, nsplit - 1) * att_rec_floats(D);
+            m[s] = __hip_atomic_load(r + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            l[s] = __hip_atomic_load(r + 32 + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                v[s][i] = __hip_atomic_load(r + 64 + (size_t)(quad * 4 + i) * 64 + ln, __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        float Mx = -INFINITY;
+#pragma unroll
+        for (int s = 0; s < ATT_MAX_SPLIT; ++s)
+            if (s < nsplit) Mx = fmaxf(Mx, m[s]);
+        const float Muse = (Mx == -INFINITY) ? 0.f : Mx;
+        float Ls = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
+            if (s < nsplit) {
+                const float w = __expf(m[s] - Muse);
+                Ls += l[s] * w;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] += v[s][i] * w;
+            }
+        }
+        const float inv = Ls > 0.f ? 1.0f / Ls : 0.f;
+        ushort4 pk;
+        pk.x = f32_to_bf16(acc[0] * inv); pk.y = f32_to_bf16(acc[1] * inv);
+        pk.z = f32_to_bf16(acc[2] * inv); pk.w = f32_to_bf16(acc[3] * inv);
+        const int dim = 32 * (quad >> 2) + 8 * (quad & 3) + 4 * gg;
+        *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + c, hd * D + dim, h)) = pk;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Several row tiles per sequence (wide windows, prefill): one workgroup per (head, group of up to
@@ -357,7 +412,6 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
 
 // Combine the KV-split partials of a (tile, head): one thread per (query, 4 dims); all loads of
 // the thread are issued before the first use.
-constexpr int ATT_MAX_SPLIT = 8;
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_k(const float* __restrict__ ws, uint16_t* __restrict__ out, int H,
                                                      int nsplit, const int32_t* n_tiles) {
@@ -453,8 +507,8 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
 }
 
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, const TileDesc* tiles,
-                      const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, uint32_t* tickets,
+                      const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     if (dtype == 0) {
         hipLaunchKernelGGL(attn_f32_k, dim3(max_tiles * 32, H), dim3(256), 0, st, (const float*)q, (const float*)kc,
                            (const float*)vc, (float*)out, H, d, seq_stride_elems, tiles, n_tiles);
@@ -464,10 +518,12 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
     if (nsplit > ATT_MAX_SPLIT) nsplit = ATT_MAX_SPLIT;
 #define RDLM_ATT(D_)                                                                                              \
     if (d == D_) {                                                                                                \
-        if (!grouped)                                                                                             \
+        if (!grouped) {         /* merges its KV splits itself */                                                 \
             hipLaunchKernelGGL((attn_bf16_k<D_, 1>), grid, dim3(ATT_WAVES * 64), 0, st, (const uint16_t*)q,       \
                                (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \
-                               nsplit, ws, tiles, n_tiles);                                                       \
+                               nsplit, ws, tickets, tiles, n_tiles);                                              \
+            return;                                                                                               \
+        }                                                                                                         \
         else                                                                                                      \
             hipLaunchKernelGGL(attn_group_k<D_>, grid, dim3(ATT_GROUP * 64), 0, st, (const uint16_t*)q,           \
                                (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \

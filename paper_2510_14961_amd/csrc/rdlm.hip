@@ -50,6 +50,7 @@ struct rdlm_ctx {
     void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
     int32_t* drafts = nullptr;
     int att_max_split = 8;
+    uint32_t* att_tickets = nullptr;     // [max_tiles][heads], zero between launches
     // sampler state
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
@@ -253,6 +254,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->rope_tab, R * (m.head_dim / 2) * 8, true);
     DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
     DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
+    DALLOC(ctx->att_tickets, (size_t)ctx->max_tiles * m.n_heads * 4, true);
     if (m.dtype == RDLM_BF16)
         DALLOC(ctx->att_ws, attention_ws_floats(ctx->max_tiles, m.n_heads, m.head_dim, ctx->att_max_split) * 4, false);
     // sampler state
@@ -517,7 +519,8 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
-                     att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->tiles, ctx->n_tiles, T, st);
+                     att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
+                     ctx->n_tiles, T, st);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
     bool folded = false;
     run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded);

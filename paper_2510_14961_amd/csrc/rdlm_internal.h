@@ -255,7 +255,8 @@ void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st)
 // q: f32 [rows][H*d] (RDLM_F32) or bf16 [rows][H*d]; caches per the model dtype; out: activation
 // format of the model dtype, width H*d.  ws: split-KV partials.
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, const TileDesc* tiles,
+                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws,
+                      uint32_t* tickets /* [max_tiles][H], zero between launches */, const TileDesc* tiles,
                       const int32_t* n_tiles, int max_tiles, hipStream_t st);
 size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);
 
