@@ -145,3 +145,39 @@ def test_big_shape_wide_window_and_ragged_batch(big_pair):
     print(f"[big] ragged batch: worst row rel-L2 {max(errs):.4f}", flush=True)
     assert max(errs) < tol
     ctx.close()
+
+
+def _run_steps(ctx, prompt, n_steps, seed=3):
+    """Prefill a short prompt, run n_steps sampler steps at window 32, return tokens and states."""
+    L = len(prompt)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, L - 1, 2, 1.0, seed)
+    ctx.sampler_begin(1, n_new=100, r_inner=1, r_total=32, seed=seed)
+    for _ in range(n_steps):
+        ctx.sample_step()
+    toks, _ = ctx.read_tokens(0)
+    z = ctx.read_states(0, L - 1, n_steps)
+    return toks[: L + n_steps].copy(), z
+
+
+def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_kernels(big_pair, monkeypatch):
+    """The one-tile path folds split-K partial sums and KV-split partials inside the producing
+    kernel: the last workgroup to arrive reads what the others wrote.  A read that came too
+    early would see the previous launch's values, so (a) two runs of 40 full-shape steps (about
+    4000 such hand-overs each) must agree bit for bit, and (b) they must agree with the path that
+    folds in separate kernels up to the order of a few float32 additions."""
+    shape, ctx, m = big_pair
+    prompt = S.make_prompt(shape.vocab, 12, 21)
+    t1, z1 = _run_steps(ctx, prompt, 40)
+    t2, z2 = _run_steps(ctx, prompt, 40)
+    assert np.array_equal(t1, t2)
+    assert np.array_equal(z1, z2)
+    # (b) one step of each path from the same start: the states differ by float32 summation order and
+    # the bf16 roundings that flips (measured 4e-3, the size of the path's bf16 error); one stale
+    # 64-column group alone would be an error of sqrt(64 / 5280) = 0.11
+    t4, z4 = _run_steps(ctx, prompt, 1)
+    monkeypatch.setenv("RDLM_NO_FOLD_FUSION", "1")
+    t3, z3 = _run_steps(ctx, prompt, 1)
+    monkeypatch.delenv("RDLM_NO_FOLD_FUSION")
+    assert np.array_equal(t4, t3)
+    assert rel_l2(z4[0], z3[0]) < 2e-2
