@@ -103,6 +103,9 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--ar-tokens", type=int, default=8,
                     help="tokens of the autoregressive (r' = r) run timed for comparison; 0 = skip")
+    ap.add_argument("--headway", type=int, default=0,
+                    help="override the workload's headway (states appended per step, Sec. 4.2): the window "
+                         "becomes r/r' x headway; 0 = the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-window-rows", type=int, default=4095,
                     help="rows of the large-window core step timed against the MFMA peak (0 = skip)")
@@ -121,6 +124,9 @@ def main():
     torch.cuda.set_device(0)
     wl = S.WORKLOADS[args.workload]
     shape, sp = wl.shape, wl.sampler
+    if args.headway > 0:
+        import dataclasses
+        sp = dataclasses.replace(sp, headway=args.headway)
     K, W = args.steps, args.warmup
     wave = -(-sp.r // sp.r_inner) * sp.headway
     window = sp.w_max if (sp.adaptive and sp.w_max > 0) else wave

@@ -63,12 +63,12 @@ def test_init_state_ragged_width():
 @pytest.mark.parametrize("shape", ALL_SHAPES, ids=IDS)
 def test_every_projection_against_the_oracle_matmul(shape):
     """y = x W^T for each weight matrix through the kernel the model path uses, at row counts that
-    leave a ragged tile and span several tiles."""
+    leave a ragged tile and reach every launch-plan tier (1, 2, 3-4, 5-8, 9-24 and more row tiles)."""
     torch = _torch()
-    ctx, m, w = make_pair(shape, max_rows=128)
+    ctx, m, w = make_pair(shape, max_rows=832)
     names = __import__("paper_2510_14961_amd").weight_names(shape)
     tol = 2e-6 if shape.dtype == "f32" else 6e-3           # bf16 rounding of x: ~2^-9 per element
-    for rows in (1, 31, 70):
+    for rows in (1, 31, 64, 70, 200, 300, 830):
         for wname in ("emb", "R0.wqkv", "R1.wo" if shape.n_core > 1 else "R0.wo", "C0.wg", "P0.wd", "wa"):
             idx = names.index(wname)
             W = w[wname].astype(np.float64)
@@ -282,6 +282,26 @@ def test_momentum_and_state_noise_bf16_first_steps():
     z_pos, zz = states[1]
     got = ctx.read_states(0, z_pos[0], len(z_pos))
     assert rel_l2(got, zz) < tol_latent(shape)
+    ctx.close()
+
+
+def test_wavefront_of_one_is_adaptive_compute_autoregression_fp32():
+    """Sec. 3.5: Alg. 2 with a wavefront of one token is the token-per-token adaptive-compute
+    sampler; the GPU path at w_max = 1 against the oracle's separately written loop."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=1, gain_jitter=0.0, emb_mul=6.0, max_positions=128, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 16, 1)
+    ref = O.generate_adaptive_autoregressive(m, prompt, 8, r_inner=2, r_cap=24, eps=0.05, temperature=1.0, seed=4)
+    steps = _run_gpu_sampler(ctx, [prompt], dict(n_new=8, r_inner=2, r_total=24, eps=0.05, w_max=1, adaptive=True,
+                                                 temperature=1.0, seed=4), r_prefill=24)
+    toks, _ = ctx.read_tokens(0)
+    assert steps == ref.steps
+    assert np.array_equal(toks[:24], ref.tokens)
+    cnt = ctx.read_counts(0, 15, 8) * 2
+    assert np.array_equal(cnt, [ref.recurrences[p] for p in range(15, 23)])
+    assert min(cnt) < 24
+    for p, s in ref.final_states.items():
+        assert rel_l2(ctx.read_states(0, p, 1)[0], s) < 1e-4
     ctx.close()
 
 
