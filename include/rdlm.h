@@ -110,7 +110,8 @@ size_t rdlm_device_bytes(const rdlm_ctx* ctx);
 
 /* ---- sequence text ------------------------------------------------------------------------ */
 /* Set the known tokens of a sequence (y_frozen = y_current = x, Alg. 1 lines 1-2); tokens_host
- * [n] int32 in [0, vocab).  Clears the sequence's sampler state. */
+ * [n] int32 in [0, vocab).  Synchronises the stream.  If a sampler is running, the sequence leaves
+ * it (its slot contributes no rows) until rdlm_sampler_join puts it back. */
 int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens_host, int32_t n);
 
 /* Parallel prefill (Sec. 3.3): positions 0..n-1 of the sequence at once: e = P(x), fresh states
@@ -152,6 +153,16 @@ int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, cons
  * (Alg. 1 line 3).  Needs L + n_new + w_max + headway <= max_positions and
  * n_seqs * roundup32(w_max) <= max_rows. */
 int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t n_seqs);
+
+/* Continuous batching (App. "Larger batch sizes": slots whose occupants come and go while the
+ * sampler runs).  Put sequence slot seq -- tokens set with rdlm_set_tokens, first L-1 positions
+ * prefilled, in a slot that never ran or whose sequence has finished -- into the sampler started by
+ * rdlm_sampler_begin, with one fresh state at position L-1 and the running sampler's
+ * hyper-parameters.  The sequence counts its sampler steps (generator counters of Sample and of
+ * the state noise) from the step it joins at, so its tokens and states are those of a run of its
+ * own.  Enqueued on the stream, no synchronisation.  Same capacity rules as rdlm_sampler_begin,
+ * with n_seqs = the highest slot in use + 1. */
+int rdlm_sampler_join(rdlm_ctx* ctx, int32_t seq);
 
 /* One iteration of Alg. 1 / Alg. 2 for all sequences that are not finished, entirely on the
  * device (no host synchronisation): P on the in-flight tokens, r' x R, C, Sample, drafts written

@@ -17,7 +17,7 @@ _LIB = None
 EXPORTED_SYMBOLS = [
     "rdlm_num_weights", "rdlm_create", "rdlm_destroy", "rdlm_strerror", "rdlm_last_hip_error",
     "rdlm_device_bytes", "rdlm_set_tokens", "rdlm_prefill", "rdlm_init_state", "rdlm_prelude",
-    "rdlm_core_step", "rdlm_coda_decode", "rdlm_sampler_begin", "rdlm_sample_step", "rdlm_generate",
+    "rdlm_core_step", "rdlm_coda_decode", "rdlm_sampler_begin", "rdlm_sampler_join", "rdlm_sample_step", "rdlm_generate",
     "rdlm_read_tokens", "rdlm_read_states", "rdlm_read_counts", "rdlm_read_deltas", "rdlm_read_kv",
     "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
     "rdlm_profile_gemm_read",
@@ -73,6 +73,7 @@ def load_library():
         "rdlm_core_step": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, vp, i32, vp]),
         "rdlm_coda_decode": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, f32, u64, i32, vp, vp]),
         "rdlm_sampler_begin": (C.c_int, [vp, C.POINTER(_Sampler), i32]),
+        "rdlm_sampler_join": (C.c_int, [vp, i32]),
         "rdlm_sample_step": (C.c_int, [vp]),
         "rdlm_generate": (C.c_int, [vp, i32, pi32]),
         "rdlm_read_tokens": (C.c_int, [vp, i32, pi32, i32, pi32]),
@@ -216,6 +217,9 @@ class Context:
         s = _Sampler(n_new, r_inner, r_total, w_max, headway, int(adaptive), eps, alpha, temperature, pad_token,
                      beta, eta, seed)
         self._chk(self.lib.rdlm_sampler_begin(self.ctx, C.byref(s), n_seqs), "rdlm_sampler_begin")
+
+    def sampler_join(self, seq: int):
+        self._chk(self.lib.rdlm_sampler_join(self.ctx, seq), "rdlm_sampler_join")
 
     def sample_step(self):
         self._chk(self.lib.rdlm_sample_step(self.ctx), "rdlm_sample_step")

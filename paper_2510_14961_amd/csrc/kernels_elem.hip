@@ -482,7 +482,8 @@ __global__ void momentum_k(float* e, float* e_store, const int32_t* counts, floa
 
 // Scheduled state noise (Eq. 2), one workgroup per row, in place on the latent store.
 __global__ void noise_mix_k(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
-                            uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles) {
+                            uint32_t k1, int step, const int32_t* seq_step0, int h, const TileDesc* tiles,
+                            const int32_t* n_tiles) {
     int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
@@ -490,17 +491,18 @@ __global__ void noise_mix_k(float* z, const int32_t* counts, float beta, int n_s
     const size_t srow = (size_t)d.zrow0 + j;
     const float b = beta * fmaxf(0.0f, 1.0f - (float)counts[srow] / (float)n_steps);
     if (b == 0.0f) return;
+    const int lstep = step - (seq_step0 ? seq_step0[d.seq] : 0);
     float* zr = z + srow * h;
     for (int blk = threadIdx.x; blk * 4 < h; blk += blockDim.x) {
         float g[4];
-        gauss4(blk, d.pos0 + j, d.seq, k0, k1, alpha, g, ((uint32_t)step << 4) | TAG_NOISE);
+        gauss4(blk, d.pos0 + j, d.seq, k0, k1, alpha, g, ((uint32_t)lstep << 4) | TAG_NOISE);
         for (int i = 0; i < 4 && blk * 4 + i < h; ++i) zr[blk * 4 + i] = (1.0f - b) * zr[blk * 4 + i] + b * g[i];
     }
 }
 
 // Sample: greedy or Gumbel-max, one workgroup per row; lowest token id wins ties.
 __global__ void sample_k(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
-                         int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles) {
+                         const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sv[256];
     __shared__ int si[256];
     int r = blockIdx.x, t = r >> 5, j = r & 31;
@@ -514,7 +516,7 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
         float g[4] = {0.f, 0.f, 0.f, 0.f};
         if (temperature > 0.f) {
             uint32_t x[4];
-            philox4x32_10(b, pos, d.seq, ((uint32_t)step << 4) | TAG_SAMPLE, k0, k1, x);
+            philox4x32_10(b, pos, d.seq, ((uint32_t)(step - (seq_step0 ? seq_step0[d.seq] : 0)) << 4) | TAG_SAMPLE, k0, k1, x);
             for (int i = 0; i < 4; ++i) g[i] = -logf(-logf(u24_open(x[i])));
         }
         for (int i = 0; i < 4 && b * 4 + i < V; ++i) {
@@ -635,6 +637,23 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
         }
         *n_tiles = t;
     }
+}
+
+// Continuous batching: a sequence (tokens set, first L-1 positions prefilled) enters a running
+// sampler with one fresh state at position L-1 and counts its steps from `step`; a retired slot
+// contributes no rows.
+__global__ void seq_join_k(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    SeqState q;
+    q.prompt_len = prompt_len; q.n_frozen = prompt_len; q.win_pos0 = prompt_len - 1; q.win_n = 1; q.done = 0;
+    q.last_rows = 0; q.last_pos0 = 0; q.new_pos0 = 0; q.new_n = 0; q.last_tile0 = 0; q.cur_rows = 0; q.cur_tile0 = 0;
+    seqs[seq] = q;
+    seq_step0[seq] = step;
+}
+__global__ void seq_retire_k(SeqState* seqs, int seq, int prompt_len) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    SeqState& q = seqs[seq];
+    q.done = 1; q.win_n = 0; q.cur_rows = 0; q.last_rows = 0; q.prompt_len = prompt_len; q.n_frozen = prompt_len;
 }
 
 __global__ void fill_i32_k(int32_t* p, int32_t v, size_t n) {
@@ -784,22 +803,28 @@ void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta,
     hipLaunchKernelGGL(momentum_k, dim3(max_tiles * 32), dim3(256), 0, st, e, e_store, counts, eta, h, tiles, n_tiles);
 }
 void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
-                      uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
-                      hipStream_t st) {
+                      uint32_t k1, int step, const int32_t* seq_step0, int h, const TileDesc* tiles,
+                      const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     hipLaunchKernelGGL(noise_mix_k, dim3(max_tiles * 32), dim3(256), 0, st, z, counts, beta, n_steps, alpha, k0, k1,
-                       step, h, tiles, n_tiles);
+                       step, seq_step0, h, tiles, n_tiles);
 }
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
-                   int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
-                   hipStream_t st) {
+                   const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles,
+                   int max_tiles, hipStream_t st) {
     hipLaunchKernelGGL(sample_k, dim3(max_tiles * 32), dim3(256), 0, st, logits, V, temperature, k0, k1, step,
-                       tok_out, tiles, n_tiles);
+                       seq_step0, tok_out, tiles, n_tiles);
 }
 void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
                      const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
                      int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st) {
     hipLaunchKernelGGL(step_end_k, dim3(1), dim3(256), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts, delta,
                        z, z_prev, h, tiles, n_tiles, n_active, step);
+}
+void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st) {
+    hipLaunchKernelGGL(seq_join_k, dim3(1), dim3(64), 0, st, seqs, seq_step0, seq, prompt_len, step);
+}
+void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st) {
+    hipLaunchKernelGGL(seq_retire_k, dim3(1), dim3(64), 0, st, seqs, seq, prompt_len);
 }
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
     if (!n) return;

@@ -281,7 +281,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
             float gn[4] = {0.f, 0.f, 0.f, 0.f};
             if (A.epi.temperature > 0.f) {
                 uint32_t x[4];
-                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].seq, ((uint32_t)A.epi.step << 4) | TAG_SAMPLE, A.epi.k0,
+                // a sequence counts its sampler steps from the step it joined at
+                const int lstep = A.epi.step - (A.epi.seq_step0 ? A.epi.seq_step0[td[b].seq] : 0);
+                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].seq, ((uint32_t)lstep << 4) | TAG_SAMPLE, A.epi.k0,
                               A.epi.k1, x);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));

@@ -55,6 +55,7 @@ struct rdlm_ctx {
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
     int32_t* counts = nullptr;
+    int32_t* seq_step0 = nullptr;    // [max_seqs] sampler step each sequence joined at
     float *z_store = nullptr, *z_prev = nullptr, *e_store = nullptr;
     int32_t* n_active = nullptr;
     int32_t* n_active_host = nullptr;    // pinned
@@ -63,6 +64,7 @@ struct rdlm_ctx {
     int samp_seqs = 0;
     int step = 0;
     bool sampler_on = false;
+    bool joined = false;             // a sequence joined the running sampler (windows no longer grow in lockstep)
     std::vector<int> prompt_len;
     int last_hip = 0;
     size_t bytes = 0;
@@ -260,6 +262,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     // sampler state
     const size_t SP = (size_t)ctx->max_seqs * ctx->max_positions;
     DALLOC(ctx->seqs, sizeof(SeqState) * ctx->max_seqs, true);
+    DALLOC(ctx->seq_step0, 4 * ctx->max_seqs + 64, true);
     DALLOC(ctx->y, (SP + 64) * 4, true);
     DALLOC(ctx->counts, (SP + 64) * 4, true);
     DALLOC(ctx->z_store, SP * h * 4, true);
@@ -368,6 +371,7 @@ struct SampleArgs {
     uint32_t k0, k1;
     int step;
     bool want_logits;
+    const int32_t* seq_step0 = nullptr;   // sampler: per-sequence step offsets (device)
 };
 
 // One projection of the model path.  Output by projection:
@@ -405,7 +409,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         if (plain) return RDLM_OK;
         if (proj == PROJ_GU) launch_swiglu(ctx->gu, 1, 0, ctx->abuf, ctx->fmt, F, ctx->n_tiles, T, ctx->st);
         if (proj == PROJ_HEAD && sa)
-            launch_sample(ctx->logits, m.vocab, sa->temperature, sa->k0, sa->k1, sa->step, ctx->drafts, ctx->tiles,
+            launch_sample(ctx->logits, m.vocab, sa->temperature, sa->k0, sa->k1, sa->step, sa->seq_step0, ctx->drafts, ctx->tiles,
                           ctx->n_tiles, T, ctx->st);
         return RDLM_OK;
     }
@@ -428,6 +432,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.kind = EPI_ARGMAX;
         epi.cand_val = ctx->cand_val; epi.cand_idx = ctx->cand_idx; epi.cand_stride = ctx->rows_pad;
         epi.temperature = sa->temperature; epi.k0 = sa->k0; epi.k1 = sa->k1; epi.step = sa->step;
+        epi.seq_step0 = sa->seq_step0;
         epi.tiles = ctx->tiles;
         if (!sa->want_logits) out = nullptr;
     }
@@ -656,8 +661,12 @@ extern "C" int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens
     HIPCHK(hipStreamSynchronize(ctx->st));
     HIPCHK(hipMemcpy(ctx->y + base, tokens_host, (size_t)n * 4, hipMemcpyHostToDevice));
     ctx->prompt_len[seq] = n;
-    ctx->sampler_on = false;
-    return RDLM_OK;
+    if (ctx->sampler_on) {          // the slot leaves the running sampler until it joins again
+        launch_seq_retire(ctx->seqs, seq, n, ctx->st);
+        launch_build_tiles_sampler(ctx->seqs, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp,
+                                   ctx->st);
+    }
+    return check_launch(ctx);
 }
 
 extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, float alpha, uint64_t seed) {
@@ -755,8 +764,9 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
         if ((long long)ctx->prompt_len[q] + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
     }
     HIPCHK(hipStreamSynchronize(ctx->st));
-    std::vector<SeqState> hs(n_seqs);
-    memset(hs.data(), 0, sizeof(SeqState) * n_seqs);
+    std::vector<SeqState> hs(ctx->max_seqs);            // slots beyond n_seqs: finished, no rows
+    memset(hs.data(), 0, sizeof(SeqState) * ctx->max_seqs);
+    for (int q = n_seqs; q < ctx->max_seqs; ++q) hs[q].done = 1;
     for (int q = 0; q < n_seqs; ++q) {
         const int L = ctx->prompt_len[q];
         hs[q].prompt_len = L; hs[q].n_frozen = L; hs[q].win_pos0 = L - 1; hs[q].win_n = 1;
@@ -766,7 +776,8 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
         launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, q, L - 1, 1, base + L - 1, sp.alpha,
                                (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
     }
-    HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * n_seqs, hipMemcpyHostToDevice));
+    launch_fill_i32(ctx->seq_step0, 0, ctx->max_seqs, ctx->st);
+    HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * ctx->max_seqs, hipMemcpyHostToDevice));
     launch_build_tiles_sampler(ctx->seqs, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
     int32_t act[2] = {n_seqs, 0};
     HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
@@ -778,8 +789,31 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     ctx->sp.beta = sp.beta; ctx->sp.eta = sp.eta;
     ctx->samp_seqs = n_seqs;
     ctx->step = 0;
+    ctx->joined = false;
     ctx->sampler_on = true;
     HIPCHK(hipStreamSynchronize(ctx->st));
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_sampler_join(rdlm_ctx* ctx, int32_t seq) {
+    if (!ctx || seq < 0) return RDLM_EINVAL;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    const rdlm_sampler& sp = ctx->sampler;
+    const int L = ctx->prompt_len[seq];
+    if (L < 1) return RDLM_ESTATE;
+    if ((long long)L + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
+    const int n = std::max(ctx->samp_seqs, seq + 1);
+    if (n * ((sp.w_max + 31) / 32) > ctx->max_tiles || n * sp.w_max > ctx->max_rows) return RDLM_ECAPACITY;
+    const size_t base = (size_t)seq * ctx->max_positions;
+    launch_fill_i32(ctx->y + base + L, sp.pad_token, ctx->max_positions - L, ctx->st);
+    launch_fill_i32(ctx->counts + base, 0, ctx->max_positions, ctx->st);
+    launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, seq, L - 1, 1, base + L - 1, sp.alpha,
+                           (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
+    launch_seq_join(ctx->seqs, ctx->seq_step0, seq, L, ctx->step, ctx->st);
+    ctx->samp_seqs = n;
+    ctx->joined = true;
+    launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
     return check_launch(ctx);
 }
 
@@ -792,7 +826,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     const int n = ctx->samp_seqs;
     // upper bound of the wave size at this step (it grows by at most `headway` per step)
     long long grow = 1 + (long long)(t - 1) * s.headway;
-    int wmax_now = (int)std::min<long long>(s.w_max, grow);
+    int wmax_now = (int)std::min<long long>(s.w_max, grow);      // (a joined sequence restarts at 1: still a bound)
     const int T = n * ((wmax_now + 31) / 32);
     ctx->grouped = wmax_now > TILE_ROWS;
     int max_keys = 0;
@@ -808,13 +842,14 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
         launch_momentum(ctx->e, ctx->e_store, ctx->counts, s.eta, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (s.beta > 0.f)                                                            // Eq. 2
         launch_noise_mix(ctx->z_store, ctx->counts, s.beta, (s.r_total + s.r_inner - 1) / s.r_inner, s.alpha,
-                         ctx->sp.seed_lo, ctx->sp.seed_hi, t, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
+                         ctx->sp.seed_lo, ctx->sp.seed_hi, t, ctx->seq_step0, m.hidden, ctx->tiles, ctx->n_tiles, T,
+                         ctx->st);
     for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
         bool last = i == s.r_inner - 1;
         core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
                      last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
     }
-    SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false};
+    SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false, ctx->seq_step0};
     coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
     // freeze, append, InitState of the appended positions, tile list of the next step
     launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,

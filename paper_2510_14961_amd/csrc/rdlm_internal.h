@@ -130,6 +130,7 @@ struct GemmEpilogue {
     float temperature = 0.f;          // > 0: Gumbel-max on logits / temperature
     uint32_t k0 = 0, k1 = 0;
     int step = 0;
+    const int32_t* seq_step0 = nullptr;   // per sequence: sampler step it joined at (its own steps count from there)
     const TileDesc* tiles = nullptr;
     // EPI_ROPE_KV (QKV projection, WL_ROPE blocks): rotate q and k, store q (bf16 rows), k and v
     // into the layer's cache at the rows' positions
@@ -219,11 +220,14 @@ void launch_momentum(float* e, float* e_store, const int32_t* counts, float eta,
 // Eq. 2 on the rows of the step, in place on the latent store: z <- (1 - b) z + b z_noise with
 // b = beta * max(0, 1 - counts / n_steps) and z_noise drawn at (position, seq, step).
 void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
-                      uint32_t k1, int step, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
-                      hipStream_t st);
+                      uint32_t k1, int step, const int32_t* seq_step0, int h, const TileDesc* tiles,
+                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
-                   int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
-                   hipStream_t st);
+                   const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles,
+                   int max_tiles, hipStream_t st);
+// Continuous batching: put a sequence into (join) or take it out of (retire) a running sampler.
+void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st);
+void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st);
 // End of a sampler step in one launch: drafts -> y_current, step counters, k*, freeze, append
 // (Alg. 1 lines 13-16 / Alg. 2), Gaussian states of the appended positions, and the tile list of
 // the next step.

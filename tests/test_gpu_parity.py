@@ -321,6 +321,55 @@ def test_batch_of_ragged_sequences_equals_independent_runs():
     ctx.close()
 
 
+@pytest.mark.parametrize("temp,beta", [(0.0, 0.0), (0.8, 0.3)])
+def test_continuous_batching_join_and_slot_reuse(temp, beta):
+    """App. "Larger batch sizes": sequences join a running sampler and reuse the slot of a finished
+    one.  Sequences never interact, and a sequence counts its steps from the step it joins at, so
+    each must come out exactly as a run of its own (tokens, and states to the fp32 bar)."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=3, max_seqs=3, max_positions=96, max_rows=96)
+    pa = S.make_prompt(shape.vocab, 9, 31, seq=0)
+    pb = S.make_prompt(shape.vocab, 14, 32, seq=1)
+    pc = S.make_prompt(shape.vocab, 6, 33, seq=0)
+    spec = dict(n_new=7, r_inner=1, r_total=4, temperature=temp, seed=9, beta=beta)
+    kw = dict(temperature=temp, seed=9, beta=beta)
+    # sequence A starts alone in slot 0
+    ctx.set_tokens(0, pa)
+    ctx.prefill(0, len(pa) - 1, 4, 1.0, 9)
+    ctx.sampler_begin(1, **spec)
+    for _ in range(3):
+        ctx.sample_step()
+    # B joins in slot 1 while A is in flight
+    ctx.set_tokens(1, pb)
+    ctx.prefill(1, len(pb) - 1, 4, 1.0, 9)
+    ctx.sampler_join(1)
+    for _ in range(8):                    # A needs 7 + 3 steps in all: it finishes in here
+        ctx.sample_step()
+    ref_a = O.generate_diffusion_forcing(m, pa, 7, 1, 4, seq=0, **kw)
+    toks, nf = ctx.read_tokens(0)
+    assert nf == len(pa) + 7
+    assert np.array_equal(toks[:nf], ref_a.tokens)
+    for p, st in ref_a.final_states.items():
+        assert rel_l2(ctx.read_states(0, p, 1)[0], st) < 1e-4
+    # C takes over slot 0 while B is still running
+    ctx.set_tokens(0, pc)
+    ctx.prefill(0, len(pc) - 1, 4, 1.0, 9)
+    ctx.sampler_join(0)
+    steps = ctx.generate(100)
+    for q, prompt in ((1, pb), (0, pc)):
+        ref = O.generate_diffusion_forcing(m, prompt, 7, 1, 4, seq=q, **kw)
+        toks, nf = ctx.read_tokens(q)
+        assert nf == len(prompt) + 7, q
+        assert np.array_equal(toks[:nf], ref.tokens), q
+        for p, st in ref.final_states.items():
+            assert rel_l2(ctx.read_states(q, p, 1)[0], st) < 1e-4, (q, p)
+    # joining needs a running sampler and a slot within capacity
+    import paper_2510_14961_amd as R
+    with pytest.raises(R.RdlmError):
+        ctx.sampler_join(3)
+    ctx.close()
+
+
 @pytest.mark.parametrize("shape", [SMALL_BF16_D64, SMALL_BF16_D96], ids=["bf16_d64", "bf16_d96"])
 def test_bf16_sampler_steps_teacher_forced(shape):
     """bf16: drive the GPU sampler step by step and compare each step's latents with an oracle step
