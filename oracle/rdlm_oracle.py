@@ -108,12 +108,31 @@ def gumbel_noise(vocab: int, position: int, seq: int, step: int, seed: int) -> n
     return -np.log(-np.log(u))
 
 
+def nucleus(logits: np.ndarray, temperature: float, top_p: float) -> np.ndarray:
+    """Top-p filter (the paper's runs sample at temperature 0.2 with top-p 0.95, App. "Dataset
+    details"): boolean mask of the smallest set of tokens, taken in order of decreasing probability
+    under softmax(logits / T), whose total probability reaches top_p.  Tokens exactly as probable
+    as the last one taken are all kept, so the set depends on the probabilities only."""
+    if not (0.0 < top_p < 1.0):
+        return np.ones(logits.shape[0], dtype=bool)
+    s = logits / temperature
+    p = np.exp(s - np.max(s))
+    p = p / np.sum(p)
+    order = np.argsort(-p, kind="stable")
+    c = np.cumsum(p[order])
+    k = int(np.searchsorted(c, top_p, side="left"))        # first prefix with mass >= top_p
+    k = min(k, len(order) - 1)
+    return p >= p[order[k]]
+
+
 def sample(logits: np.ndarray, temperature: float, position: int, seq: int, step: int,
-           seed: int) -> int:
+           seed: int, top_p: float = 1.0) -> int:
     """Sample(p) (Alg. 1): greedy at temperature 0, else Gumbel-max, which draws from
-    softmax(logits / T).  Ties go to the lowest token id."""
+    softmax(logits / T) -- restricted to the top-p set and renormalised when 0 < top_p < 1 (the
+    Gumbel race among the kept tokens draws from exactly that).  Ties go to the lowest token id."""
     if temperature > 0.0:
         score = logits / temperature + gumbel_noise(logits.shape[0], position, seq, step, seed)
+        score = np.where(nucleus(logits, temperature, top_p), score, -np.inf)
     else:
         score = logits
     return int(np.argmax(score))            # numpy returns the first maximum
@@ -352,7 +371,7 @@ def momentum(e_new: np.ndarray, e_prev: Optional[np.ndarray], eta: float) -> np.
 
 def generate_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray, n_new: int, r: int,
                             alpha: float = 1.0, temperature: float = 0.0, seed: int = 1,
-                            seq: int = 0, r_prefill: Optional[int] = None) -> Trace:
+                            seq: int = 0, r_prefill: Optional[int] = None, top_p: float = 1.0) -> Trace:
     """Baseline sampler (Sec. 1): one token at a time, r sequential recurrences per token."""
     L = len(prompt)
     cache = model.new_cache(L + n_new)
@@ -367,7 +386,7 @@ def generate_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray, n_new: 
         for _ in range(r):
             s = model.core(e, s, pos, cache)
         logits = model.coda(s, pos, cache)[0]
-        y.append(sample(logits, temperature, p, seq, t, seed))
+        y.append(sample(logits, temperature, p, seq, t, seed, top_p))
         tr.final_states[p] = s[0]
         tr.recurrences[p] = r
         tr.steps += 1
@@ -378,7 +397,7 @@ def generate_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray, n_new: 
 def generate_adaptive_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray, n_new: int,
                                      r_inner: int, r_cap: int, eps: float, alpha: float = 1.0,
                                      temperature: float = 0.0, seed: int = 1, seq: int = 0,
-                                     r_prefill: Optional[int] = None) -> Trace:
+                                     r_prefill: Optional[int] = None, top_p: float = 1.0) -> Trace:
     """Token-per-token adaptive-compute sampler (Sec. 4): recur on one position, r' recurrences
     at a time, until the latent's relative change drops below eps (or r_cap is reached)."""
     L = len(prompt)
@@ -403,7 +422,7 @@ def generate_adaptive_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray
             if (np.isfinite(d) and d < eps) or c * r_inner >= r_cap:
                 break
         logits = model.coda(s, pos, cache)[0]
-        y.append(sample(logits, temperature, p, seq, t, seed))
+        y.append(sample(logits, temperature, p, seq, t, seed, top_p))
         tr.final_states[p] = s[0]
         tr.recurrences[p] = c * r_inner
     tr.steps = t
@@ -416,7 +435,7 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
                                temperature: float = 0.0, seed: int = 1, seq: int = 0,
                                headway: int = 1, pad_token: int = 0, T: Optional[int] = None,
                                r_prefill: Optional[int] = None, hook=None, eta: float = 0.0,
-                               beta: float = 0.0) -> Trace:
+                               beta: float = 0.0, top_p: float = 1.0) -> Trace:
     """Alg. 1: diffusion-forcing sampler with the fixed exit rule; optional momentum on the
     conditioning (Eq. 1, eta) and scheduled state noise (Eq. 2, beta).
 
@@ -456,7 +475,7 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
         count = [c + 1 for c in count]
         logits = model.coda(zz, pos, cache)                  # p <- C(z)
         for i, p in enumerate(z_pos):                        # y_hat <- Sample(p)
-            y[p + 1] = sample(logits[i], temperature, p, seq, t, seed)
+            y[p + 1] = sample(logits[i], temperature, p, seq, t, seed, top_p)
         z = [zz[i] for i in range(len(z_pos))]
         if hook is not None:
             hook(t, list(z_pos), zz, logits, y.copy(), e)
@@ -490,7 +509,7 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
                                         seed: int = 1, seq: int = 0, headway: int = 1,
                                         pad_token: int = 0, T: Optional[int] = None,
                                         r_prefill: Optional[int] = None, hook=None,
-                                        eta: float = 0.0, beta: float = 0.0) -> Trace:
+                                        eta: float = 0.0, beta: float = 0.0, top_p: float = 1.0) -> Trace:
     """Alg. 2: diffusion-forcing sampler with latent-difference freezing and a wavefront limit;
     optional momentum (Eq. 1) and scheduled state noise (Eq. 2; delta_i still compares the state
     after the recurrences with the state the previous step ended on, before any noise).
@@ -530,7 +549,7 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
         count = [c + 1 for c in count]
         logits = model.coda(zz, pos, cache)
         for i, p in enumerate(z_pos):
-            y[p + 1] = sample(logits[i], temperature, p, seq, t, seed)
+            y[p + 1] = sample(logits[i], temperature, p, seq, t, seed, top_p)
         d = delta(zz, np.stack(z_prev))
         tr.deltas.append(d)
         z = [zz[i] for i in range(len(z_pos))]

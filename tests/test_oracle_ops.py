@@ -375,3 +375,51 @@ def test_k_star_is_the_longest_prefix():
     f = O.freezable_flags(np.array([0.5, 1e-4, np.nan, np.inf, 1e-4]), [9, 1, 1, 1, 1], 1, 1e-3, 9)
     assert f == [True, True, False, False, True]              # cap, converged, nan, inf, converged
     assert O.freezable_flags(np.array([np.nan]), [4], 2, 1e-3, 8) == [True]   # the cap still applies
+
+
+# ---------------------------------------------------------------------------------------------
+# Top-p (nucleus) filter of Sample
+
+def test_nucleus_is_the_smallest_descending_prefix_reaching_top_p():
+    rng = np.random.default_rng(3)
+    for trial in range(50):
+        v = int(rng.integers(2, 9))
+        logits = rng.standard_normal(v) * 2.0
+        T, top_p = float(rng.uniform(0.2, 1.5)), float(rng.uniform(0.05, 0.99))
+        keep = O.nucleus(logits, T, top_p)
+        p = np.exp(logits / T - np.max(logits / T))
+        p /= p.sum()
+        # brute force: over all subsets, the kept one is closed under "at least as probable as a
+        # member", reaches top_p, and dropping its least probable member falls below top_p
+        assert keep.any()
+        assert p[keep].min() >= p[~keep].max() if (~keep).any() else True
+        assert p[keep].sum() >= top_p - 1e-12
+        least = np.argmin(np.where(keep, p, np.inf))
+        assert p[keep].sum() - p[least] < top_p + 1e-12
+    assert O.nucleus(np.array([0.0, 1.0, 2.0]), 1.0, 1.0).all()
+    assert O.nucleus(np.array([0.0, 1.0, 2.0]), 1.0, 0.0).all()          # off
+    assert list(O.nucleus(np.array([0.0, 1.0, 5.0]), 1.0, 0.5)) == [False, False, True]
+    assert list(O.nucleus(np.array([1.0, 1.0, -9.0]), 1.0, 0.4)) == [True, True, False]   # equal probabilities stay together
+
+
+def test_top_p_sampling_draws_from_the_renormalised_nucleus():
+    """Gumbel-max restricted to the nucleus is sampling from the truncated, renormalised softmax
+    (chi-square on a small vocabulary), and never leaves the nucleus."""
+    logits = np.array([2.0, 1.0, 0.5, 0.0, -1.0, -3.0])
+    T, top_p = 0.7, 0.97
+    keep = O.nucleus(logits, T, top_p)
+    p = np.exp(logits / T)
+    p = np.where(keep, p, 0.0)
+    p /= p.sum()
+    n = 4000
+    counts = np.zeros(6)
+    for step in range(n):
+        counts[O.sample(logits, T, 3, 1, step, 11, top_p)] += 1
+    assert counts[~keep].sum() == 0
+    chi2 = np.sum((counts[keep] - n * p[keep]) ** 2 / (n * p[keep]))
+    assert chi2 < 16.27                                  # chi-square 0.999 quantile, 3 degrees of freedom
+    assert keep.sum() == 4
+    # top_p = 1 is plain temperature sampling, a tiny top_p is greedy
+    for step in range(20):
+        assert O.sample(logits, T, 3, 1, step, 11, 1.0) == O.sample(logits, T, 3, 1, step, 11)
+        assert O.sample(logits, T, 3, 1, step, 11, 1e-6) == 0
