@@ -83,6 +83,10 @@ typedef struct {
     int32_t pad_token;
     float beta;           /* state-noise level of a position's first step, in [0, 1]              */
     float eta;            /* momentum of the conditioning, in [0, 1)                              */
+    float top_p;          /* in (0, 1) with temperature > 0: sample from the smallest set of most */
+                          /* probable tokens whose mass reaches top_p; 0 or >= 1: off.  Needs      */
+                          /* vocab <= 65536 and vocab % 4 == 0                                     */
+    int32_t reserved_;
     uint64_t seed;        /* key of the counter-based generator (state init, Gumbel, state noise) */
 } rdlm_sampler;
 
@@ -142,11 +146,12 @@ int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const 
                    float* delta_out);
 
 /* C + Sample on every given row (Alg. 1 lines 11-12): coda layers (caches overwritten), final
- * norm, tied LM head, then greedy or Gumbel-max at (seed, step).  tokens_out: device int32 [M];
- * logits_out: device float32 [M, vocab] or NULL. */
+ * norm, tied LM head, then greedy or Gumbel-max at (seed, step), restricted to the top-p set when
+ * 0 < top_p < 1 (App. "Dataset details": the paper samples at temperature 0.2, top-p 0.95).
+ * tokens_out: device int32 [M]; logits_out: device float32 [M, vocab] or NULL. */
 int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
                      const int32_t* n_rows, const float* z, float temperature, uint64_t seed,
-                     int32_t step, int32_t* tokens_out, float* logits_out);
+                     int32_t step, int32_t* tokens_out, float* logits_out, float top_p);
 
 /* Start the sampler on sequences 0..n_seqs-1: each needs rdlm_set_tokens (L >= 1 tokens) and
  * rdlm_prefill of its first L-1 positions before.  Creates one fresh state at position L-1

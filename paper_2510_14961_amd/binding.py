@@ -38,7 +38,7 @@ class _Sampler(C.Structure):
     _fields_ = [("n_new", C.c_int32), ("r_inner", C.c_int32), ("r_total", C.c_int32), ("w_max", C.c_int32),
                 ("headway", C.c_int32), ("adaptive", C.c_int32), ("eps", C.c_float), ("alpha", C.c_float),
                 ("temperature", C.c_float), ("pad_token", C.c_int32), ("beta", C.c_float), ("eta", C.c_float),
-                ("seed", C.c_uint64)]
+                ("top_p", C.c_float), ("reserved_", C.c_int32), ("seed", C.c_uint64)]
 
 
 def library_path() -> str:
@@ -71,7 +71,7 @@ def load_library():
         "rdlm_init_state": (C.c_int, [vp, i32, i32, i32, f32, u64, vp]),
         "rdlm_prelude": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, vp]),
         "rdlm_core_step": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, vp, i32, vp]),
-        "rdlm_coda_decode": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, f32, u64, i32, vp, vp]),
+        "rdlm_coda_decode": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, f32, u64, i32, vp, vp, f32]),
         "rdlm_sampler_begin": (C.c_int, [vp, C.POINTER(_Sampler), i32]),
         "rdlm_sampler_join": (C.c_int, [vp, i32]),
         "rdlm_sample_step": (C.c_int, [vp]),
@@ -203,19 +203,19 @@ class Context:
                                           C.c_void_p(z_inout.data_ptr()), r_inner, d), "rdlm_core_step")
 
     def coda_decode(self, seq_ids, pos0, n_rows, z, temperature: float, seed: int, step: int, tokens_out,
-                    logits_out=None):
+                    logits_out=None, top_p: float = 0.0):
         s, p, n = self._rows(seq_ids, pos0, n_rows)
         lo = C.c_void_p(logits_out.data_ptr()) if logits_out is not None else C.c_void_p()
         self._chk(self.lib.rdlm_coda_decode(self.ctx, len(s), _iptr(s), _iptr(p), _iptr(n), C.c_void_p(z.data_ptr()),
-                                            temperature, seed, step, C.c_void_p(tokens_out.data_ptr()), lo),
+                                            temperature, seed, step, C.c_void_p(tokens_out.data_ptr()), lo, top_p),
                   "rdlm_coda_decode")
 
     def sampler_begin(self, n_seqs: int, *, n_new: int, r_inner: int, r_total: int, w_max: int = 0,
                       headway: int = 1, adaptive: bool = False, eps: float = 0.0, alpha: float = 1.0,
                       temperature: float = 0.0, pad_token: int = 0, seed: int = 1, beta: float = 0.0,
-                      eta: float = 0.0):
+                      eta: float = 0.0, top_p: float = 0.0):
         s = _Sampler(n_new, r_inner, r_total, w_max, headway, int(adaptive), eps, alpha, temperature, pad_token,
-                     beta, eta, seed)
+                     beta, eta, top_p, 0, seed)
         self._chk(self.lib.rdlm_sampler_begin(self.ctx, C.byref(s), n_seqs), "rdlm_sampler_begin")
 
     def sampler_join(self, seq: int):

@@ -539,6 +539,109 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
     if (threadIdx.x == 0) tok_out[r] = (si[0] == 0x7fffffff) ? 0 : si[0];
 }
 
+// Sample with a top-p filter (the paper's runs: temperature 0.2, top-p 0.95), one workgroup of
+// 1024 threads per row, up to 65536 classes held in registers as e_v = exp(logit_v / T - max).
+// The kept set is {v : e_v >= thr} with thr the largest value whose tail mass
+// sum_{e_v >= thr} e_v reaches top_p * sum_v e_v -- found by bisection on the bit pattern of thr
+// (the mass is a step function of thr that only changes at the e_v), every mass summed in a
+// fixed order.  The Gumbel race among the kept classes draws from the renormalised nucleus.
+constexpr int TOPP_THREADS = 1024, TOPP_VEC = 16;
+__device__ inline float block_max(float v, float* sh) {
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[w] = v;
+    __syncthreads();
+    float t = -INFINITY;
+    for (int i = 0; i < (int)(blockDim.x >> 6); ++i) t = fmaxf(t, sh[i]);
+    return t;
+}
+__global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logits, int V, float temperature,
+                                                                float top_p, uint32_t k0, uint32_t k1, int step,
+                                                                const int32_t* seq_step0, int32_t* tok_out,
+                                                                const TileDesc* tiles, const int32_t* n_tiles) {
+    __shared__ float sh[16];
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    const int r = blockIdx.x, t = r >> 5, j = r & 31;
+    if (t >= *n_tiles) return;
+    const TileDesc d = tiles[t];
+    const int pos = d.pos0 + j;
+    const float* lg = logits + (size_t)r * V;
+    const float invT = 1.0f / temperature;
+    float e[TOPP_VEC][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < TOPP_VEC; ++i) {
+        const int v0 = (i * TOPP_THREADS + threadIdx.x) * 4;
+        if (v0 < V) {
+            const float4 l = ld4(lg + v0);
+            e[i][0] = l.x * invT; e[i][1] = l.y * invT; e[i][2] = l.z * invT; e[i][3] = l.w * invT;
+        } else {
+            e[i][0] = e[i][1] = e[i][2] = e[i][3] = -INFINITY;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mx = fmaxf(mx, e[i][c]);
+    }
+    mx = block_max(mx, sh);
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < TOPP_VEC; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { e[i][c] = __expf(e[i][c] - mx); part += e[i][c]; }
+    const float target = top_p * block_sum(part, sh);
+    uint32_t lo = 0u, hi = 0x3f800001u;                    // mass(+0) = everything; e_v <= 1
+    while (hi - lo > 1u) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        const float thr = __uint_as_float(mid);
+        float m = 0.f;
+#pragma unroll
+        for (int i = 0; i < TOPP_VEC; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) m += e[i][c] >= thr ? e[i][c] : 0.f;
+        m = block_sum(m, sh);
+        if (m >= target) lo = mid; else hi = mid;
+    }
+    const float thr = __uint_as_float(lo);
+    const int lstep = step - (seq_step0 ? seq_step0[d.seq] : 0);
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int i = 0; i < TOPP_VEC; ++i) {
+        const int v0 = (i * TOPP_THREADS + threadIdx.x) * 4;
+        if (v0 >= V) continue;
+        bool any = false;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) any = any || e[i][c] >= thr;
+        if (!any) continue;
+        uint32_t x[4];
+        philox4x32_10(v0 >> 2, pos, d.seq, ((uint32_t)lstep << 4) | TAG_SAMPLE, k0, k1, x);
+        const float4 l = ld4(lg + v0);
+        const float lv[4] = {l.x, l.y, l.z, l.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (e[i][c] >= thr) {
+                const float sc = lv[c] / temperature + (-logf(-logf(u24_open(x[c]))));
+                if (sc > best) { best = sc; bi = v0 + c; }     // ascending ids: first maximum kept
+            }
+        }
+    }
+    // lowest id wins ties: reduce (value, id) over the workgroup
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < TOPP_THREADS / 64; ++w)
+            if (sv[w] > best || (sv[w] == best && si[w] < bi)) { best = sv[w]; bi = si[w]; }
+        tok_out[r] = bi == 0x7fffffff ? 0 : bi;
+    }
+}
+
 // End of a sampler step, one workgroup: for every sequence (in turn; its rows in parallel) the
 // drafts become y_current and the step counters advance (Alg. 1 line 13), the longest freezable
 // prefix k* is frozen (Alg. 1 line 14 / Eq. 3), new states are appended unless the wavefront is
@@ -813,6 +916,12 @@ void launch_sample(const float* logits, int V, float temperature, uint32_t k0, u
                    int max_tiles, hipStream_t st) {
     hipLaunchKernelGGL(sample_k, dim3(max_tiles * 32), dim3(256), 0, st, logits, V, temperature, k0, k1, step,
                        seq_step0, tok_out, tiles, n_tiles);
+}
+void launch_sample_top_p(const float* logits, int V, float temperature, float top_p, uint32_t k0, uint32_t k1,
+                         int step, const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles,
+                         const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(sample_top_p_k, dim3(max_tiles * 32), dim3(TOPP_THREADS), 0, st, logits, V, temperature, top_p,
+                       k0, k1, step, seq_step0, tok_out, tiles, n_tiles);
 }
 void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
                      const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,

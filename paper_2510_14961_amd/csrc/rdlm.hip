@@ -372,7 +372,9 @@ struct SampleArgs {
     int step;
     bool want_logits;
     const int32_t* seq_step0 = nullptr;   // sampler: per-sequence step offsets (device)
+    float top_p = 0.f;                    // in (0, 1): nucleus filter (needs temperature > 0)
 };
+static bool top_p_on(const SampleArgs* sa) { return sa && sa->temperature > 0.f && sa->top_p > 0.f && sa->top_p < 1.f; }
 
 // One projection of the model path.  Output by projection:
 //   QKV -> ctx->qkv (f32), O / D / A -> ctx->part ([S] partial sums, *S_out = S),
@@ -408,7 +410,10 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
                         ctx->n_tiles, T, ctx->st);
         if (plain) return RDLM_OK;
         if (proj == PROJ_GU) launch_swiglu(ctx->gu, 1, 0, ctx->abuf, ctx->fmt, F, ctx->n_tiles, T, ctx->st);
-        if (proj == PROJ_HEAD && sa)
+        if (proj == PROJ_HEAD && top_p_on(sa))
+            launch_sample_top_p(ctx->logits, m.vocab, sa->temperature, sa->top_p, sa->k0, sa->k1, sa->step,
+                                sa->seq_step0, ctx->drafts, ctx->tiles, ctx->n_tiles, T, ctx->st);
+        else if (proj == PROJ_HEAD && sa)
             launch_sample(ctx->logits, m.vocab, sa->temperature, sa->k0, sa->k1, sa->step, sa->seq_step0, ctx->drafts, ctx->tiles,
                           ctx->n_tiles, T, ctx->st);
         return RDLM_OK;
@@ -434,7 +439,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.temperature = sa->temperature; epi.k0 = sa->k0; epi.k1 = sa->k1; epi.step = sa->step;
         epi.seq_step0 = sa->seq_step0;
         epi.tiles = ctx->tiles;
-        if (!sa->want_logits) out = nullptr;
+        if (!sa->want_logits && !top_p_on(sa)) out = nullptr;      // the nucleus filter reads full logits
     }
     if (deferred_norm) {
         // ssq_count 0: a folding GEMM left the row totals in the last slot
@@ -469,7 +474,10 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         }
     }
     if (prof) (void)hipEventRecord(ctx->prof_ev[ctx->prof_used++], ctx->st);
-    if (epi.kind == EPI_ARGMAX)
+    if (epi.kind == EPI_ARGMAX && top_p_on(sa))
+        launch_sample_top_p(ctx->logits, m.vocab, sa->temperature, sa->top_p, sa->k0, sa->k1, sa->step, sa->seq_step0,
+                            ctx->drafts, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    else if (epi.kind == EPI_ARGMAX)
         launch_argmax_final(ctx->cand_val, ctx->cand_idx, gemm_groups(N, g, EPI_ARGMAX), ctx->rows_pad, ctx->drafts,
                             ctx->n_tiles, T, ctx->st);
     if (S_out) *S_out = g.ksplit;
@@ -729,15 +737,16 @@ extern "C" int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_
 
 extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
                                 const int32_t* n_rows, const float* z, float temperature, uint64_t seed,
-                                int32_t step, int32_t* tokens_out, float* logits_out) {
+                                int32_t step, int32_t* tokens_out, float* logits_out, float top_p) {
     SeqWindows w;
     int T, M, mk;
-    if (!z || !tokens_out || !(temperature >= 0.f) || step < 0) return RDLM_EINVAL;
+    if (!z || !tokens_out || !(temperature >= 0.f) || step < 0 || !(top_p >= 0.f)) return RDLM_EINVAL;
+    if (ctx && top_p > 0.f && top_p < 1.f && (ctx->m.vocab > TOPP_MAX_VOCAB || ctx->m.vocab % 4)) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
-    SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr};
+    SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr, nullptr, top_p};
     coda_forward(ctx, z, &sa, T, mk);
     launch_copy_i32_out(ctx->drafts, tokens_out, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (logits_out) launch_copy_rows_out(ctx->logits, logits_out, ctx->m.vocab, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
@@ -752,8 +761,9 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     if (n_seqs > ctx->max_seqs) return RDLM_ECAPACITY;
     if (s->n_new < 1 || s->r_inner < 1 || s->r_total < 1 || s->headway < 1 || !(s->temperature >= 0.f) ||
         !(s->eps >= 0.f) || s->pad_token < 0 || s->pad_token >= ctx->m.vocab || !(s->beta >= 0.f && s->beta <= 1.f) ||
-        !(s->eta >= 0.f && s->eta < 1.f))
+        !(s->eta >= 0.f && s->eta < 1.f) || !(s->top_p >= 0.f))
         return RDLM_EINVAL;
+    if (s->top_p > 0.f && s->top_p < 1.f && (ctx->m.vocab > TOPP_MAX_VOCAB || ctx->m.vocab % 4)) return RDLM_EINVAL;
     rdlm_sampler sp = *s;
     const int wave = (sp.r_total + sp.r_inner - 1) / sp.r_inner;
     if (sp.w_max <= 0 || !sp.adaptive) sp.w_max = wave * sp.headway;
@@ -849,7 +859,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
         core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
                      last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
     }
-    SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false, ctx->seq_step0};
+    SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false, ctx->seq_step0, s.top_p};
     coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
     // freeze, append, InitState of the appended positions, tile list of the next step
     launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,

@@ -225,6 +225,11 @@ void launch_noise_mix(float* z, const int32_t* counts, float beta, int n_steps, 
 void launch_sample(const float* logits, int V, float temperature, uint32_t k0, uint32_t k1, int step,
                    const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles,
                    int max_tiles, hipStream_t st);
+// Sample with a top-p filter from full logits [rows][V]; V % 4 == 0, V <= TOPP_MAX_VOCAB.
+constexpr int TOPP_MAX_VOCAB = 65536;
+void launch_sample_top_p(const float* logits, int V, float temperature, float top_p, uint32_t k0, uint32_t k1,
+                         int step, const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles,
+                         const int32_t* n_tiles, int max_tiles, hipStream_t st);
 // Continuous batching: put a sequence into (join) or take it out of (retire) a running sampler.
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st);
 void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st);

@@ -58,6 +58,30 @@ def tie_aware_token_check(gpu_tokens, oracle_scores, tau):
     return exact, ties
 
 
+def top_p_token_check(gpu_tokens, logits, temperature, top_p, positions, seq, step, seed, tau=1e-5, slack=1e-4):
+    """Tokens sampled with a top-p filter, judged on the logits the GPU itself returned (float32
+    values, exact in the oracle's float64), so both sides decide on the same numbers.  A token
+    is accepted iff it lies in the oracle's top-p set and its Gumbel score is within tau of the
+    best in that set -- for top_p itself or top_p (1 +- slack): the GPU sums probabilities in
+    float32, which can move a token sitting exactly on the boundary.
+    Returns (matches at the nominal top_p, tokens accepted otherwise); raises on a mismatch."""
+    exact = other = 0
+    for i, t in enumerate(gpu_tokens):
+        t = int(t)
+        lg = np.asarray(logits[i], dtype=np.float64)
+        if t == O.sample(lg, temperature, int(positions[i]), seq, step, seed, top_p):
+            exact += 1
+            continue
+        score = lg / temperature + O.gumbel_noise(lg.shape[0], int(positions[i]), seq, step, seed)
+        ok = False
+        for tp in (top_p, top_p * (1 - slack), min(top_p * (1 + slack), 1 - 1e-12)):
+            keep = O.nucleus(lg, temperature, tp)
+            ok = ok or (keep[t] and float(np.max(score[keep]) - score[t]) <= tau)
+        assert ok, f"row {i}: GPU token {t} is not the oracle's top-p sample (top_p {top_p})"
+        other += 1
+    return exact, other
+
+
 def teacher_forced_sampler_run(ctx, m, shape, prompt, r, n_new, seed, tol, max_positions):
     """Drive the GPU sampler (fixed exit, r' = 1) step by step; before each step read the GPU's own
     inputs (tokens, in-flight states), run the same step in the oracle from them, and compare the

@@ -11,7 +11,7 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import (SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, make_pair, rel_l2,
+from gpu_util import (top_p_token_check, SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, make_pair, rel_l2,
                       teacher_forced_sampler_run, tie_aware_token_check, tol_latent)
 
 pytestmark = pytest.mark.gpu
@@ -146,6 +146,17 @@ def test_single_step_blocks_teacher_forced(shape):
         if shape.dtype == "f32":
             assert ties == 0
         assert exact >= n // 2
+    # Sample with a top-p filter: a wide and a narrow nucleus, judged on the GPU's own logits
+    for temp, top_p, step in ((1.0, 0.9, 3), (0.5, 0.3, 4), (0.2, 0.95, 5)):
+        tok = torch.zeros(n, dtype=torch.int32, device="cuda")
+        lg = torch.zeros(n, shape.vocab, device="cuda")
+        ctx.coda_decode([0], [L], [n], _dev(z2.astype(np.float32)), temp, 77, step, tok, lg, top_p)
+        got = lg.cpu().numpy()
+        assert rel_l2(got, logits_ref) < tol
+        exact, other = top_p_token_check(tok.cpu().numpy(), got, temp, top_p, pos, 0, step, 77)
+        assert exact >= n - 2, (exact, other)
+        kept = [int(O.nucleus(got[i].astype(np.float64), temp, top_p).sum()) for i in range(n)]
+        assert min(kept) < shape.vocab                      # the filter really cut something
     ctx.close()
 
 
@@ -156,6 +167,50 @@ def _run_gpu_sampler(ctx, prompts, spec, r_prefill=None):
                     spec.get("seed", 1))
     ctx.sampler_begin(len(prompts), **spec)
     return ctx.generate(10000)
+
+
+@pytest.mark.parametrize("temp,top_p", [(1.0, 0.8), (0.2, 0.95)])
+def test_top_p_free_running_fp32(temp, top_p):
+    """Alg. 1 with Sample restricted to the top-p set (the paper's runs: temperature 0.2, top-p
+    0.95), float32 model: tokens identical to the oracle's, and different from the unfiltered
+    run's where the filter matters."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=2, max_positions=96, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 12, 3)
+    n_new, r, r_inner = 14, 4, 1
+    ref = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=temp, seed=6, top_p=top_p)
+    steps = _run_gpu_sampler(ctx, [prompt], dict(n_new=n_new, r_inner=r_inner, r_total=r, temperature=temp, seed=6,
+                                                 top_p=top_p))
+    toks, n_frozen = ctx.read_tokens(0)
+    assert steps == ref.steps and n_frozen == 12 + n_new
+    assert np.array_equal(toks[: n_frozen], ref.tokens)
+    if temp == 1.0:
+        base = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=temp, seed=6)
+        assert not np.array_equal(base.tokens, ref.tokens)
+    for p, s in ref.final_states.items():
+        assert rel_l2(ctx.read_states(0, p, 1)[0], s) < 1e-4
+    ctx.close()
+
+
+def test_top_p_rejects_unsupported_vocab_and_values():
+    """top_p < 0 is an error; top_p >= 1 or 0 switches the filter off (same tokens as without)."""
+    torch = _torch()
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=2, max_positions=64, max_rows=32)
+    prompt = S.make_prompt(shape.vocab, 10, 3)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, 9, 3, 1.0, 1)
+    with pytest.raises(RuntimeError):
+        ctx.sampler_begin(1, n_new=4, r_inner=1, r_total=3, temperature=1.0, top_p=-0.1)
+    outs = []
+    for tp in (0.0, 1.0, 1.5):
+        ctx.set_tokens(0, prompt)
+        ctx.prefill(0, 9, 3, 1.0, 1)
+        ctx.sampler_begin(1, n_new=4, r_inner=1, r_total=3, temperature=1.0, seed=2, top_p=tp)
+        ctx.generate(100)
+        outs.append(ctx.read_tokens(0)[0][:14].copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    ctx.close()
 
 
 def test_cfg1_free_running_tokens_and_latents():

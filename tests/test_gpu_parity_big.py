@@ -12,7 +12,7 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import rel_l2, teacher_forced_sampler_run, tie_aware_token_check
+from gpu_util import rel_l2, teacher_forced_sampler_run, tie_aware_token_check, top_p_token_check
 
 pytestmark = pytest.mark.gpu
 
@@ -85,6 +85,14 @@ def test_big_shape_single_step_blocks(big_pair):
     exact, ties = tie_aware_token_check(tok.cpu().numpy(), logits_ref, tau=4 * err + 1e-6)
     print(f"[big] logits max abs err {err:.4f}, tokens exact {exact}/{n}, near-ties {ties}", flush=True)
     assert exact >= n // 2
+    # Sample with the paper's temperature 0.2 / top-p 0.95 at the full vocabulary, and a hot,
+    # narrow nucleus; judged on the logits the GPU returned
+    for temp, top_p, step in ((0.2, 0.95, 2), (1.5, 0.5, 3)):
+        ctx.coda_decode([0], [L], [n], dev(z1.astype(np.float32)), temp, 11, step, tok, lg, top_p)
+        got_lg = lg.cpu().numpy()
+        exact, other = top_p_token_check(tok.cpu().numpy(), got_lg, temp, top_p, pos, 0, step, 11)
+        print(f"[big] top-p {top_p} T {temp}: exact {exact}/{n}, boundary cases {other}", flush=True)
+        assert exact >= n - 2
 
 
 def test_big_shape_sampler_steps_teacher_forced(big_pair):
