@@ -86,7 +86,9 @@ typedef struct {
     float top_p;          /* in (0, 1) with temperature > 0: sample from the smallest set of most */
                           /* probable tokens whose mass reaches top_p; 0 or >= 1: off.  Needs      */
                           /* vocab <= 65536 and vocab % 4 == 0                                     */
-    int32_t reserved_;
+    int32_t init_mode;    /* states of appended positions: 0 = InitState draws (Alg. 1); 1 = copies  */
+                          /* of the latest state of the position to the left (App., "continuous    */
+                          /* compute"); the first state of a sequence is always a draw              */
     uint64_t seed;        /* key of the counter-based generator (state init, Gumbel, state noise) */
 } rdlm_sampler;
 

@@ -430,14 +430,26 @@ def generate_adaptive_autoregressive(model: RecurrentDepthLM, prompt: np.ndarray
     return tr
 
 
+def appended_state(h: int, position: int, seq: int, alpha: float, seed: int,
+                   left_state: np.ndarray, continuous_compute: bool) -> np.ndarray:
+    """State of a position that enters the window: a random InitState draw (Alg. 1), or, with
+    "continuous compute" (App., additional hyperparameter sweeps), a copy of the latest state of
+    the position one step to its left."""
+    if continuous_compute:
+        return np.array(left_state, dtype=np.float64, copy=True)
+    return init_state(h, position, seq, alpha, seed)
+
+
 def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_new: int,
                                r_inner: int, r: int, alpha: float = 1.0,
                                temperature: float = 0.0, seed: int = 1, seq: int = 0,
                                headway: int = 1, pad_token: int = 0, T: Optional[int] = None,
                                r_prefill: Optional[int] = None, hook=None, eta: float = 0.0,
-                               beta: float = 0.0, top_p: float = 1.0) -> Trace:
+                               beta: float = 0.0, top_p: float = 1.0,
+                               continuous_compute: bool = False) -> Trace:
     """Alg. 1: diffusion-forcing sampler with the fixed exit rule; optional momentum on the
-    conditioning (Eq. 1, eta) and scheduled state noise (Eq. 2, beta).
+    conditioning (Eq. 1, eta), scheduled state noise (Eq. 2, beta) and continuous-compute
+    initialisation of appended states (the very first state is always a random draw).
 
     y_current is kept as one array over absolute positions: frozen tokens, then the drafts of the
     in-flight positions, then pad tokens for headway positions that have no draft yet.  The
@@ -488,15 +500,17 @@ def generate_diffusion_forcing(model: RecurrentDepthLM, prompt: np.ndarray, n_ne
             tr.recurrences[z_pos[i]] = count[i] * r_inner
         n_frozen += k
         tr.frozen_per_step.append(k)
+        left = z[-1]                                         # latest state at position nxt - 1 (see below)
         z_pos, z, count = z_pos[k:], z[k:], count[k:]
         if n_frozen - L >= n_new:
             break
         # the next state sits after the last in-flight one, or, when none is left, at the
-        # position of the newest frozen token (which it reads)
+        # position of the newest frozen token (which it reads); either way the position to its
+        # left is the last row of this step's window
         nxt = (z_pos[-1] + 1) if z_pos else n_frozen - 1
         for j in range(headway):                             # append new latent state(s)
             z_pos.append(nxt + j)
-            z.append(init_state(model.h, nxt + j, seq, alpha, seed))
+            z.append(appended_state(model.h, nxt + j, seq, alpha, seed, left, continuous_compute))
             count.append(0)
     tr.steps = t
     tr.tokens = y[: L + n_new].copy()
@@ -509,7 +523,8 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
                                         seed: int = 1, seq: int = 0, headway: int = 1,
                                         pad_token: int = 0, T: Optional[int] = None,
                                         r_prefill: Optional[int] = None, hook=None,
-                                        eta: float = 0.0, beta: float = 0.0, top_p: float = 1.0) -> Trace:
+                                        eta: float = 0.0, beta: float = 0.0, top_p: float = 1.0,
+                                        continuous_compute: bool = False) -> Trace:
     """Alg. 2: diffusion-forcing sampler with latent-difference freezing and a wavefront limit;
     optional momentum (Eq. 1) and scheduled state noise (Eq. 2; delta_i still compares the state
     after the recurrences with the state the previous step ended on, before any noise).
@@ -561,6 +576,7 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
             tr.recurrences[z_pos[i]] = count[i] * r_inner
         n_frozen += k
         tr.frozen_per_step.append(k)
+        left = z[-1]
         z_pos, z, count = z_pos[k:], z[k:], count[k:]
         if n_frozen - L >= n_new:
             break
@@ -568,7 +584,7 @@ def generate_diffusion_forcing_adaptive(model: RecurrentDepthLM, prompt: np.ndar
         nxt = (z_pos[-1] + 1) if z_pos else n_frozen - 1
         for j in range(max(0, n_app)):
             z_pos.append(nxt + j)
-            z.append(init_state(model.h, nxt + j, seq, alpha, seed))
+            z.append(appended_state(model.h, nxt + j, seq, alpha, seed, left, continuous_compute))
             count.append(0)
         z_prev = list(z)                                     # z_prev <- z
     tr.steps = t

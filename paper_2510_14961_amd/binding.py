@@ -38,7 +38,7 @@ class _Sampler(C.Structure):
     _fields_ = [("n_new", C.c_int32), ("r_inner", C.c_int32), ("r_total", C.c_int32), ("w_max", C.c_int32),
                 ("headway", C.c_int32), ("adaptive", C.c_int32), ("eps", C.c_float), ("alpha", C.c_float),
                 ("temperature", C.c_float), ("pad_token", C.c_int32), ("beta", C.c_float), ("eta", C.c_float),
-                ("top_p", C.c_float), ("reserved_", C.c_int32), ("seed", C.c_uint64)]
+                ("top_p", C.c_float), ("init_mode", C.c_int32), ("seed", C.c_uint64)]
 
 
 def library_path() -> str:
@@ -213,9 +213,9 @@ class Context:
     def sampler_begin(self, n_seqs: int, *, n_new: int, r_inner: int, r_total: int, w_max: int = 0,
                       headway: int = 1, adaptive: bool = False, eps: float = 0.0, alpha: float = 1.0,
                       temperature: float = 0.0, pad_token: int = 0, seed: int = 1, beta: float = 0.0,
-                      eta: float = 0.0, top_p: float = 0.0):
+                      eta: float = 0.0, top_p: float = 0.0, continuous_compute: bool = False):
         s = _Sampler(n_new, r_inner, r_total, w_max, headway, int(adaptive), eps, alpha, temperature, pad_token,
-                     beta, eta, top_p, 0, seed)
+                     beta, eta, top_p, int(continuous_compute), seed)
         self._chk(self.lib.rdlm_sampler_begin(self.ctx, C.byref(s), n_seqs), "rdlm_sampler_begin")
 
     def sampler_join(self, seq: int):

@@ -695,12 +695,19 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
             }
             __syncthreads();
             q = cur;
-            // InitState for the appended positions
+            // InitState for the appended positions: a random draw, or ("continuous compute", App.,
+            // additional hyperparameter sweeps) the latest state of the position one step to the
+            // left, which is the last row of the window this step ran on
             const int nb = (h + 3) / 4;
+            const size_t left = (base + q.new_pos0 - 1) * h;
             for (int idx = tid; idx < q.new_n * nb; idx += blockDim.x) {
                 const int a = idx / nb, blk = idx - a * nb, pos = q.new_pos0 + a;
                 float g[4];
-                gauss4(blk, pos, s, p.seed_lo, p.seed_hi, p.alpha, g);
+                if (p.init_mode == 1) {
+                    for (int i = 0; i < 4 && blk * 4 + i < h; ++i) g[i] = z[left + blk * 4 + i];
+                } else {
+                    gauss4(blk, pos, s, p.seed_lo, p.seed_hi, p.alpha, g);
+                }
                 for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
                     const size_t o = (base + pos) * h + blk * 4 + i;
                     z[o] = g[i];

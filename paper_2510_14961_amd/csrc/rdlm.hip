@@ -761,7 +761,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     if (n_seqs > ctx->max_seqs) return RDLM_ECAPACITY;
     if (s->n_new < 1 || s->r_inner < 1 || s->r_total < 1 || s->headway < 1 || !(s->temperature >= 0.f) ||
         !(s->eps >= 0.f) || s->pad_token < 0 || s->pad_token >= ctx->m.vocab || !(s->beta >= 0.f && s->beta <= 1.f) ||
-        !(s->eta >= 0.f && s->eta < 1.f) || !(s->top_p >= 0.f))
+        !(s->eta >= 0.f && s->eta < 1.f) || !(s->top_p >= 0.f) || (s->init_mode != 0 && s->init_mode != 1))
         return RDLM_EINVAL;
     if (s->top_p > 0.f && s->top_p < 1.f && (ctx->m.vocab > TOPP_MAX_VOCAB || ctx->m.vocab % 4)) return RDLM_EINVAL;
     rdlm_sampler sp = *s;
@@ -796,7 +796,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     ctx->sp.headway = sp.headway; ctx->sp.adaptive = sp.adaptive; ctx->sp.eps = sp.eps; ctx->sp.alpha = sp.alpha;
     ctx->sp.temperature = sp.temperature; ctx->sp.pad_token = sp.pad_token;
     ctx->sp.seed_lo = (uint32_t)sp.seed; ctx->sp.seed_hi = (uint32_t)(sp.seed >> 32);
-    ctx->sp.beta = sp.beta; ctx->sp.eta = sp.eta;
+    ctx->sp.beta = sp.beta; ctx->sp.eta = sp.eta; ctx->sp.init_mode = sp.init_mode;
     ctx->samp_seqs = n_seqs;
     ctx->step = 0;
     ctx->joined = false;

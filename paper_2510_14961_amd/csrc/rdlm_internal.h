@@ -54,6 +54,7 @@ struct SamplerParams {
     int32_t pad_token;
     uint32_t seed_lo, seed_hi;
     float beta, eta;
+    int32_t init_mode;      // 0: appended states are InitState draws; 1: copies of the left neighbour's latest state
 };
 
 enum ActFmt { ACT_F32 = 0, ACT_BF16P = 1 };

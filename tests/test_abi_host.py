@@ -33,7 +33,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(B._Model) == 12 * 4
     assert C.sizeof(B._Sampler) == 14 * 4 + 8
     assert B._Sampler.beta.offset == 40 and B._Sampler.eta.offset == 44
-    assert B._Sampler.top_p.offset == 48 and B._Sampler.seed.offset == 56
+    assert B._Sampler.top_p.offset == 48 and B._Sampler.init_mode.offset == 52 and B._Sampler.seed.offset == 56
 
 
 def _model(**kw):

@@ -192,6 +192,35 @@ def test_top_p_free_running_fp32(temp, top_p):
     ctx.close()
 
 
+@pytest.mark.parametrize("adaptive,r_inner,headway", [(False, 1, 1), (False, 2, 2), (True, 1, 1)])
+def test_continuous_compute_init_fp32(adaptive, r_inner, headway):
+    """Appended states start as copies of the left neighbour's latest state (App., additional
+    hyperparameter sweeps) instead of InitState draws: tokens and frozen latents as the oracle's."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=2, max_positions=96, max_rows=32, emb_mul=6.0 if adaptive else 1.0)
+    prompt = S.make_prompt(shape.vocab, 12, 3)
+    n_new, r = 12, 5
+    if adaptive:
+        ref = O.generate_diffusion_forcing_adaptive(m, prompt, n_new, r_inner, 24, 0.05, 6, temperature=1.0, seed=4,
+                                                    headway=headway, continuous_compute=True)
+        spec = dict(n_new=n_new, r_inner=r_inner, r_total=24, eps=0.05, w_max=6, adaptive=True, temperature=1.0,
+                    seed=4, headway=headway, continuous_compute=True)
+        r_prefill = 24
+    else:
+        ref = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=1.0, seed=4, headway=headway,
+                                           pad_token=3, continuous_compute=True)
+        spec = dict(n_new=n_new, r_inner=r_inner, r_total=r, temperature=1.0, seed=4, headway=headway, pad_token=3,
+                    continuous_compute=True)
+        r_prefill = r
+    steps = _run_gpu_sampler(ctx, [prompt], spec, r_prefill=r_prefill)
+    toks, n_frozen = ctx.read_tokens(0)
+    assert steps == ref.steps
+    assert np.array_equal(toks[: 12 + n_new], ref.tokens)
+    for p, s in ref.final_states.items():
+        assert rel_l2(ctx.read_states(0, p, 1)[0], s) < 1e-4
+    ctx.close()
+
+
 def test_top_p_rejects_unsupported_vocab_and_values():
     """top_p < 0 is an error; top_p >= 1 or 0 switches the filter off (same tokens as without)."""
     torch = _torch()

@@ -291,3 +291,58 @@ def test_adaptive_sampler_takes_momentum_and_noise(tiny_conditioned):
     assert sum(b.recurrences.values()) > sum(a.recurrences.values())
     c = O.generate_diffusion_forcing_adaptive(m, prompt, 6, eta=0.0, beta=0.0, **kw)
     _same_run(a, c)
+
+
+def test_continuous_compute_with_window_one_carries_the_state_across_tokens(tiny):
+    """App., additional hyperparameter sweeps: appended states start from the latest state of the
+    position to the left.  With r' = r (window 1) that is the plain token-by-token loop whose
+    state is never re-drawn -- written out here without the sampler's bookkeeping."""
+    _, m, prompt = tiny
+    r, n_new, seed = 3, 9, 5
+    df = O.generate_diffusion_forcing(m, prompt, n_new, r, r, temperature=1.0, seed=seed, continuous_compute=True)
+    L = len(prompt)
+    cache = m.new_cache(L + n_new)
+    y = [int(t) for t in prompt]
+    m.prefill(np.asarray(y[: L - 1]), r, 1.0, seed, 0, cache)
+    s = O.init_state(m.h, L - 1, 0, 1.0, seed)[None, :]          # drawn once
+    for t in range(1, n_new + 1):
+        p = len(y) - 1
+        e = m.prelude(np.array([y[p]]), np.array([p]), cache)
+        for _ in range(r):
+            s = m.core(e, s, np.array([p]), cache)
+        y.append(O.sample(m.coda(s, np.array([p]), cache)[0], 1.0, p, 0, t, seed))
+        assert np.array_equal(df.final_states[p], s[0])
+    assert np.array_equal(df.tokens, np.asarray(y))
+    plain = O.generate_diffusion_forcing(m, prompt, n_new, r, r, temperature=1.0, seed=seed)
+    assert np.array_equal(plain.final_states[L - 1], df.final_states[L - 1])      # the first state is a draw
+    assert not np.array_equal(plain.final_states[L], df.final_states[L])
+
+
+@pytest.mark.parametrize("headway", [1, 2])
+def test_continuous_compute_starts_from_the_left_neighbours_latest_state(tiny, headway):
+    """In a wavefront the copied state is the one the left neighbour ended the step on: the first
+    delta_i of an appended state (Eq. 3, against its initial value) must equal its distance to
+    that neighbour state, as recorded by the hook one step earlier."""
+    _, m, prompt = tiny
+    states = {}
+
+    def hook(t, z_pos, zz, logits, y, e):
+        states[t] = {p: zz[i].copy() for i, p in enumerate(z_pos)}
+
+    tr = O.generate_diffusion_forcing_adaptive(m, prompt, 8, 1, 4, 0.0, 16, seed=2, headway=headway,
+                                               continuous_compute=True, hook=hook)
+    checked = 0
+    for t in range(2, tr.steps + 1):
+        prev, cur = states[t - 1], states[t]
+        last_prev = max(prev)                                   # right-most position of the previous window
+        fresh = [p for p in cur if p not in prev]
+        assert all(p > last_prev for p in fresh)
+        pos = sorted(cur)
+        for p in fresh:
+            want = np.linalg.norm(cur[p] - prev[last_prev]) / np.linalg.norm(cur[p])
+            assert math.isclose(tr.deltas[t - 1][pos.index(p)], want, rel_tol=1e-12)
+            checked += 1
+    assert checked >= 6
+    base = O.generate_diffusion_forcing_adaptive(m, prompt, 8, 1, 4, 0.0, 16, seed=2, headway=headway)
+    assert base.steps == tr.steps and base.window_sizes == tr.window_sizes      # same wave, other values
+    assert not np.array_equal(base.final_states[len(prompt)], tr.final_states[len(prompt)])
