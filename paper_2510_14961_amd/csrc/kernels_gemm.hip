@@ -508,15 +508,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     const bool stream_w = A.m_chunks == 1;          // weights used once: keep them out of the caches
 
     bf16x8 w0[KU][NB], w1[KU][NB], w2[KU][NB], xr[XL];
-    // Every K step issues the same loads and stores (k indices clamped to the range), so the
-    // compiler can count them: activations first -- the staging store then waits for them only, and
-    // the weight loads issued after them stay in flight (the memory counter retires in issue order).
+    uint32_t xok = 0;                               // bit i: staged tile i of the loaded step lies inside the K range
+    // Every K step issues the same loads, stores and matrix instructions (k indices clamped to the
+    // range; activation tiles beyond it are staged as zeros), so the loop body is one straight
+    // path and the compiler can count the memory operations: activations first -- the staging
+    // store then waits for them only, and the weight loads issued after them stay in flight (the
+    // memory counter retires in issue order).
     static_assert((KU * MT) % WAVES == 0, "every wave stages the same number of tiles");
     auto load = [&](bf16x8(&wv)[KU][NB], int kt) {  // activations and weights of the K step at kt
+        xok = 0;
 #pragma unroll
         for (int i = 0; i < XL; ++i) {
             const int u = (wave + i * WAVES) / MT;
             xr[i] = xsrc[i][(size_t)(min(kt + u, kend - 1) - u) * 64];
+            xok |= (kt + u < kend ? 1u : 0u) << i;
         }
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
@@ -528,22 +533,30 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
         __builtin_amdgcn_sched_barrier(0);
     };
     auto stage = [&](int buf) {
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int i = 0; i < XL; ++i) xs[((size_t)buf * KU * MT + wave + i * WAVES) * 64 + lane] = xr[i];
+        for (int i = 0; i < XL; ++i)
+            xs[((size_t)buf * KU * MT + wave + i * WAVES) * 64 + lane] = ((xok >> i) & 1u) ? xr[i] : zero;
     };
-    auto compute = [&](bf16x8(&wv)[KU][NB], int buf, int kt) {
-        const int kc = min(KU, kend - kt);
+    // The activation tiles of K tile u + 1 are read from LDS while the matrix instructions of
+    // K tile u run (two register sets), so the wave does not sit out the LDS latency per tile.
+    auto compute = [&](bf16x8(&wv)[KU][NB], int buf) {
+        bf16x8 xv[2][MT];
+#pragma unroll
+        for (int b = 0; b < MT; ++b) xv[0][b] = xs[((size_t)buf * KU * MT + b) * 64 + lane];
 #pragma unroll
         for (int u = 0; u < KU; ++u) {
-            if (u < kc) {
+            if (u + 1 < KU) {
 #pragma unroll
-                for (int b = 0; b < MT; ++b) {
-                    const bf16x8 xv = xs[((size_t)buf * KU * MT + u * MT + b) * 64 + lane];
-#pragma unroll
-                    for (int a = 0; a < NB; ++a)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv, acc[a][b], 0, 0, 0);
-                }
+                for (int b = 0; b < MT; ++b)
+                    xv[(u + 1) & 1][b] = xs[((size_t)buf * KU * MT + (u + 1) * MT + b) * 64 + lane];
             }
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+#pragma unroll
+                for (int a = 0; a < NB; ++a)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[u][a], xv[u & 1][b], acc[a][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     // K step s uses weight registers s % 3 and stage buffer s % 3.  Its loads are issued at the top
@@ -553,22 +566,32 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     auto step = [&](bf16x8(&wcur)[KU][NB], bf16x8(&wnext)[KU][NB], int bcur, int kt) {
         stage(bcur == 2 ? 0 : bcur + 1);
         load(wnext, min(kt + 2 * KU, kend - 1));
-        compute(wcur, bcur, kt);
+        compute(wcur, bcur);
         __syncthreads();
     };
+    // The loop body is three steps (one turn of the register ring) without exits in between; the
+    // one or two steps left over run after it.
+    const int nsteps = (kend - kbeg + KU - 1) / KU;
     int kt = kbeg;
-    if (kt < kend) {
+    if (nsteps > 0) {
         load(w0, kt);
         stage(0);
         load(w1, min(kt + KU, kend - 1));
         __syncthreads();
-        while (true) {
+        int s3 = nsteps / 3;
+        for (; s3 > 0; --s3) {
             step(w0, w2, 0, kt); kt += KU;
-            if (kt >= kend) break;
             step(w1, w0, 1, kt); kt += KU;
-            if (kt >= kend) break;
             step(w2, w1, 2, kt); kt += KU;
-            if (kt >= kend) break;
+        }
+        const int rem = nsteps % 3;
+        if (rem >= 1) {
+            if (rem == 2) stage(1);
+            compute(w0, 0);
+            if (rem == 2) {
+                __syncthreads();
+                compute(w1, 1);
+            }
         }
     }
     auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
@@ -692,6 +715,8 @@ static bool launch_gemm_rows(const void* xp, const void* wp, float* out, int N, 
     RDLM_RCASE(2, 1, 4, 8) RDLM_RCASE(2, 1, 4, 4) RDLM_RCASE(2, 2, 4, 4) RDLM_RCASE(2, 2, 4, 2) RDLM_RCASE(2, 1, 8, 4)
     RDLM_RCASE(4, 1, 4, 4) RDLM_RCASE(4, 1, 4, 2) RDLM_RCASE(4, 2, 4, 4) RDLM_RCASE(4, 2, 4, 2) RDLM_RCASE(4, 1, 8, 4)
     RDLM_RCASE(8, 1, 4, 4) RDLM_RCASE(8, 1, 4, 2) RDLM_RCASE(8, 2, 4, 4) RDLM_RCASE(8, 2, 4, 2) RDLM_RCASE(8, 1, 8, 2)
+    // five waves: 1120 and 165 feature blocks (widths 35840 and 5280) split into equal workgroups
+    RDLM_RCASE(2, 1, 5, 5) RDLM_RCASE(4, 1, 5, 5)
 #undef RDLM_RCASE
     return false;
 }

@@ -343,15 +343,36 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
         // step is bound by weight streaming, small row chunks with many workgroups in flight win
         // (chunks of one feature group run back to back on one XCD and share the weights in its
         // L2); from a few hundred rows on, 256-row chunks feed the matrix cores.
-        const bool wide = proj == PROJ_GU || proj == PROJ_HEAD;       // many feature blocks
+        const bool wide = proj == PROJ_GU || proj == PROJ_HEAD;       // many feature blocks, no K split
         const bool deep = proj == PROJ_D || proj == PROJ_A;           // long K, few feature blocks
-        if (T <= 2) g = (wide || deep) ? GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
-        else if (T <= 4) g = wide ? GemmPlan{4, 1, 8, 4, 1, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, deep ? 8 : 4, GEMM_ROWS};
+        // waves per workgroup of a projection without K split: the count (4, 5 or 8 feature blocks
+        // per workgroup) that fills the 256 compute units most evenly, e.g. 5 for 1120 blocks
+        auto even_waves = [&](int mt) {
+            const int nblk = N / 32, chunks = (T + mt - 1) / mt;
+            int best = 8;
+            double best_u = 0.0;
+            for (int w : {8, 5, 4}) {
+                const int wgs = (nblk + w - 1) / w * chunks;
+                const double u = (double)nblk * chunks / ((double)((wgs + 255) / 256 * 256) * w);
+                if (u > best_u + 1e-9) { best_u = u; best = w; }
+            }
+            return best;
+        };
+        auto wide_plan = [&](int mt) {
+            const int w = even_waves(mt);
+            return GemmPlan{mt, 1, w, w == 5 ? 5 : 4, 1, GEMM_ROWS};
+        };
+        if (T <= 2) g = wide ? wide_plan(2) : deep ? GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
+        else if (T <= 4) g = wide ? wide_plan(4) : GemmPlan{2, 1, 4, 4, deep ? 8 : 3, GEMM_ROWS};
         else if (T <= 8)
-            g = (wide || proj == PROJ_D) ? GemmPlan{8, 1, 8, 2, 8, GEMM_ROWS}
-                : proj == PROJ_A         ? GemmPlan{4, 1, 4, 2, 8, GEMM_ROWS}
-                                         : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
-        else if (T <= 24) g = proj == PROJ_HEAD ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS} : GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS};
+            g = wide             ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS}
+                : proj == PROJ_A ? GemmPlan{4, 1, 4, 2, 8, GEMM_ROWS}
+                                 : GemmPlan{2, 1, 8, 4, 3, GEMM_ROWS};
+        else if (T <= 24)
+            g = proj == PROJ_HEAD ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS}
+                : proj == PROJ_GU ? GemmPlan{4, 1, 4, 4, 1, GEMM_ROWS}
+                : proj == PROJ_A  ? GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS}
+                                  : GemmPlan{4, 1, 8, 4, 3, GEMM_ROWS};
         else g = (proj == PROJ_GU || deep) ? GemmPlan{8, 2, 4, 2, 2, GEMM_ROWS} : GemmPlan{8, 1, 8, 2, 2, GEMM_ROWS};
         if (const char* p = getenv(kProjEnvRows[proj])) {
             GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
