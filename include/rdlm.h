@@ -205,7 +205,9 @@ int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_
  * Runs the same tiled kernel the model path uses (including its split-K reduction). */
 int rdlm_linear(rdlm_ctx* ctx, int32_t w_index, const float* x, int32_t m, float* y);
 /* Time `iters` launches of that GEMM alone with HIP events on the context's stream, inputs
- * resident; returns the average milliseconds per launch in ms_out (host). Synchronises. */
+ * resident; the launches go round the same projection of every layer (same shape, different
+ * weights), so that none finds its weights cached by the one before.  Returns the average
+ * milliseconds per launch in ms_out (host). Synchronises. */
 int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m, int32_t iters, float* ms_out);
 /* Time `iters` core steps (r_inner = 1) over one sequence window [pos0, pos0+n) with HIP events;
  * the cache content at those positions is overwritten.  Synchronises. */

@@ -328,10 +328,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
 
 template <int MT, int NB, int WAVES, int U, int EPI>
 __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
-    extern __shared__ float red[];                 // [WAVES][NB*MT*16][64]
+    // cross-wave sums: [WAVES][NB*MT*16][64] for one row tile; with several row tiles the waves
+    // finish one row tile at a time through [WAVES][NB*16][64]
+    extern __shared__ float red[];
+    constexpr bool PER_TILE = WAVES > 1 && MT > 1;
     constexpr int CW = (EPI == EPI_ARGMAX && WAVES > 1) ? WAVES : 1;
-    __shared__ float cand_v[CW][MT][32];
-    __shared__ int cand_i[CW][MT][32];
+    constexpr int CM = PER_TILE ? 1 : MT;
+    __shared__ float cand_v[CW][CM][32];
+    __shared__ int cand_i[CW][CM][32];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int bid = blockIdx.x;
     const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
@@ -423,31 +427,56 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 
     // Cross-wave sum in a fixed order: every wave deposits its accumulators; the finishing work is
     // dealt to the waves in units of one register quad (see gemm_epilogue).
-    constexpr int REGS = NB * MT * 16;
-    if (WAVES > 1) {
+    if constexpr (PER_TILE) {
+        constexpr int REGS = NB * 16;
 #pragma unroll
-        for (int a = 0; a < NB; ++a)
+        for (int b = 0; b < MT; ++b) {
+            if (b > 0) __syncthreads();            // the previous row tile's sums have been read
 #pragma unroll
-            for (int b = 0; b < MT; ++b)
+            for (int a = 0; a < NB; ++a)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
-        __syncthreads();
-    }
-    auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
+                for (int i = 0; i < 16; ++i) red[((size_t)wave * REGS + a * 16 + i) * 64 + lane] = acc[a][b][i];
+            __syncthreads();
+            auto quad_sum = [&](int a, int, int q, float (&o)[4]) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = (a * MT + b) * 16 + q * 4 + i;
-            if (WAVES > 1) {
-                float sum = 0.f;
+                for (int i = 0; i < 4; ++i) {
+                    float sum = 0.f;
 #pragma unroll
-                for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
-                o[i] = sum;
-            } else {
-                o[i] = acc[a][b][q * 4 + i];
-            }
+                    for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + a * 16 + q * 4 + i) * 64 + lane];
+                    o[i] = sum;
+                }
+            };
+            const float sc1[1] = {sc[b]};
+            gemm_epilogue<1, NB, WAVES, WAVES, EPI>(A, blk, t0 + b, n_tiles, ks, grp, sc1, quad_sum, cand_v, cand_i);
         }
-    };
-    gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i);
+    } else {
+        constexpr int REGS = NB * MT * 16;
+        if (WAVES > 1) {
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int b = 0; b < MT; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        red[((size_t)wave * REGS + (a * MT + b) * 16 + i) * 64 + lane] = acc[a][b][i];
+            __syncthreads();
+        }
+        auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = (a * MT + b) * 16 + q * 4 + i;
+                if (WAVES > 1) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w) sum += red[((size_t)w * REGS + r) * 64 + lane];
+                    o[i] = sum;
+                } else {
+                    o[i] = acc[a][b][q * 4 + i];
+                }
+            }
+        };
+        gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i);
+    }
     if constexpr (EPI == EPI_F32 && MT == 1 && (NB == 1 || NB == 2 || NB == 4))
         if (A.epi.fold_counter) gemm_fold_tail<NB, WAVES * 64>(A, grp, t0);
 }
@@ -641,7 +670,7 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
     const int nblk = N / 32;
     const int groups = (nblk + NB - 1) / NB;
     const int m_chunks = (max_tiles + MT - 1) / MT;
-    const size_t lds = WAVES > 1 ? (size_t)WAVES * NB * MT * 16 * 64 * sizeof(float) : 0;
+    const size_t lds = WAVES > 1 ? (size_t)WAVES * NB * 16 * 64 * sizeof(float) : 0;   // one row tile at a time
     auto kern = gemm_bf16_k<MT, NB, WAVES, U, EPI>;
     if (lds > 64 * 1024) {
         static bool raised = false, ok = false;
@@ -745,6 +774,10 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
     RDLM_CASE(1, NB_, 2, 4) RDLM_CASE(1, NB_, 2, 8) RDLM_CASE(1, NB_, 4, 2) RDLM_CASE(1, NB_, 4, 4)              \
     RDLM_CASE(1, NB_, 8, 1) RDLM_CASE(1, NB_, 8, 2)
     RDLM_ROW(1) RDLM_ROW(2) RDLM_ROW(3) RDLM_ROW(4) RDLM_ROW(5)
+    // two and four row tiles per workgroup (windows of 33..128 rows): the same shapes as above
+    RDLM_CASE(2, 2, 2, 4) RDLM_CASE(2, 2, 2, 2) RDLM_CASE(2, 2, 8, 1) RDLM_CASE(2, 2, 8, 2) RDLM_CASE(2, 5, 4, 2)
+    RDLM_CASE(2, 4, 4, 2)
+    RDLM_CASE(4, 2, 2, 4) RDLM_CASE(4, 2, 2, 2) RDLM_CASE(4, 2, 8, 1) RDLM_CASE(4, 2, 8, 2)
 #undef RDLM_ROW
 #undef RDLM_CASE
     return false;

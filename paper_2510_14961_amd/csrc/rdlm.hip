@@ -362,8 +362,23 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             const int w = even_waves(mt);
             return GemmPlan{mt, 1, w, w == 5 ? 5 : 4, 1, GEMM_ROWS};
         };
-        if (T <= 2) g = wide ? wide_plan(2) : deep ? GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS} : GemmPlan{2, 1, 4, 4, 4, GEMM_ROWS};
-        else if (T <= 4) g = wide ? wide_plan(4) : GemmPlan{2, 1, 4, 4, deep ? 8 : 3, GEMM_ROWS};
+        // Up to two row tiles (and four, where the accumulators still fit) the streaming kernel of
+        // the one-tile step carries over: no barrier in its K loop, and a weight tile in registers
+        // meets every row tile.
+        if (T <= 2) {
+            switch (proj) {
+                case PROJ_GU: g = {2, 5, 4, 2, 1}; break;
+                case PROJ_HEAD: g = {2, 4, 4, 2, 1}; break;
+                case PROJ_QKV: g = {2, 2, 2, 4, 1}; break;
+                case PROJ_A: g = GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS}; break;
+                default: g = {2, 2, 8, 1, 3}; break;       // O, D
+            }
+        } else if (T <= 4) {
+            g = wide               ? wide_plan(4)
+                : proj == PROJ_D   ? GemmPlan{4, 2, 8, 1, 3}
+                : proj == PROJ_QKV ? GemmPlan{4, 2, 2, 4, 1}
+                                   : GemmPlan{2, 1, 4, 4, deep ? 8 : 3, GEMM_ROWS};
+        }
         else if (T <= 8)
             g = wide             ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS}
                 : proj == PROJ_A ? GemmPlan{4, 1, 4, 2, 8, GEMM_ROWS}
@@ -377,6 +392,10 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
         if (const char* p = getenv(kProjEnvRows[proj])) {
             GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
             if (sscanf(p, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) g = o;
+            if (p[0] == 's' && sscanf(p + 1, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) {
+                o.kind = GEMM_STREAM;             // "s<mt>,<nb>,<waves>,<unroll>,<ksplit>": the streaming kernel
+                g = o;
+            }
         }
     }
     if (!split_ok) g.ksplit = 1;
@@ -1073,8 +1092,18 @@ extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, 
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     for (int i = 0; i < 3; ++i)
         if ((rc = run_proj(ctx, proj, xin, W, T, &S, &sa, false, false, rl, &fused))) return rc;
+    // the timed launches go round the same projection of every layer, as a model pass does, so
+    // that no launch finds its weights in a cache left by the one before
+    std::vector<const void*> ring;
+    if (w_index >= 1 && w_index < 1 + 7 * (int)ctx->layers.size())
+        for (int l = 0; l < (int)ctx->layers.size(); ++l) {
+            const void* Wl; int pj, n2, k2;
+            if (weight_by_index(ctx, 1 + 7 * l + (w_index - 1) % 7, &Wl, &pj, &n2, &k2) == RDLM_OK) ring.push_back(Wl);
+        }
+    if (ring.empty()) ring.push_back(W);
     HIPCHK(hipEventRecord(a, ctx->st));
-    for (int i = 0; i < iters; ++i) run_proj(ctx, proj, xin, W, T, &S, &sa, false, false, rl, &fused);
+    for (int i = 0; i < iters; ++i)
+        run_proj(ctx, proj, xin, ring[i % ring.size()], T, &S, &sa, false, false, rl, &fused);
     HIPCHK(hipEventRecord(b, ctx->st));
     HIPCHK(hipEventSynchronize(b));
     float ms = 0.f;
