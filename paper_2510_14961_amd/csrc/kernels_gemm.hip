@@ -777,7 +777,7 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
     // two and four row tiles per workgroup (windows of 33..128 rows): the same shapes as above
     RDLM_CASE(2, 2, 2, 4) RDLM_CASE(2, 2, 2, 2) RDLM_CASE(2, 2, 8, 1) RDLM_CASE(2, 2, 8, 2) RDLM_CASE(2, 5, 4, 2)
     RDLM_CASE(2, 4, 4, 2)
-    RDLM_CASE(4, 2, 2, 4) RDLM_CASE(4, 2, 2, 2) RDLM_CASE(4, 2, 8, 1) RDLM_CASE(4, 2, 8, 2)
+    RDLM_CASE(4, 2, 8, 1) RDLM_CASE(4, 2, 8, 2)
 #undef RDLM_ROW
 #undef RDLM_CASE
     return false;

@@ -374,10 +374,9 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                 default: g = {2, 2, 8, 1, 3}; break;       // O, D
             }
         } else if (T <= 4) {
-            g = wide               ? wide_plan(4)
-                : proj == PROJ_D   ? GemmPlan{4, 2, 8, 1, 3}
-                : proj == PROJ_QKV ? GemmPlan{4, 2, 2, 4, 1}
-                                   : GemmPlan{2, 1, 4, 4, deep ? 8 : 3, GEMM_ROWS};
+            g = wide             ? wide_plan(4)
+                : proj == PROJ_D ? GemmPlan{4, 2, 8, 1, 3}
+                                 : GemmPlan{2, 1, 4, 4, deep ? 8 : 3, GEMM_ROWS};
         }
         else if (T <= 8)
             g = wide             ? GemmPlan{8, 1, 8, 2, 1, GEMM_ROWS}
