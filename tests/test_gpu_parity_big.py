@@ -132,12 +132,23 @@ def test_big_shape_wide_window_and_ragged_batch(big_pair):
     got = z.cpu().numpy()
     assert max(rel_l2(got[i], z1[i]) for i in range(n)) < tol
     assert np.max(np.abs(d.cpu().numpy() - O.delta(z1, z0))) < 4 * tol
+    # (a2) 50 rows (two row tiles, the second ragged): the streaming kernel with two row tiles
+    n2 = 50
+    pos2 = np.arange(n2)
+    cache2 = m.new_cache(192)
+    e_2 = S.make_rows(n2, shape.hidden, 23, scale=3.0).astype(np.float64)
+    z0_2 = np.stack([O.init_state(shape.hidden, p, 2, 1.0, 8) for p in pos2])
+    z1_2 = m.core(e_2, z0_2, pos2, cache2)
+    z_2 = dev_t(z0_2.astype(np.float32))
+    ctx.core_step([2], [0], [n2], dev_t(e_2.astype(np.float32)), z_2, 1, None)
+    got2 = z_2.cpu().numpy()
+    assert max(rel_l2(got2[i], z1_2[i]) for i in range(n2)) < tol
     # (b) three sequences, windows of 40, 33 and 7 rows at different positions
     wins = [(1, 0, 40), (2, 5, 33), (0, 128, 7)]          # (seq, pos0, rows); seq 0 continues behind (a)
     rows = sum(wn for _, _, wn in wins)
     e2 = S.make_rows(rows, shape.hidden, 22, scale=3.0).astype(np.float64)
     zs, refs, off = [], [], 0
-    caches = {0: cache, 1: m.new_cache(192), 2: m.new_cache(192)}
+    caches = {0: cache, 1: m.new_cache(192), 2: cache2}           # seq 2 continues over the rows of (a2)
     for seq, p0, wn in wins:
         pp = np.arange(p0, p0 + wn)
         zi = np.stack([O.init_state(shape.hidden, p, seq, 1.0, 8) for p in pp])
