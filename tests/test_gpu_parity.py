@@ -347,6 +347,32 @@ def test_momentum_and_state_noise_adaptive_fp32():
     ctx.close()
 
 
+def test_all_sampler_options_together_batched_fp32():
+    """Three sequences of different prompt lengths through Alg. 2 with every option switched on at
+    once (inner recurrences, wavefront limit, headway, momentum, state noise, temperature with
+    top-p, continuous-compute initialisation): each sequence as in an oracle run of its own."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=3, gain_jitter=0.0, emb_mul=6.0, max_seqs=3, max_positions=128, max_rows=96)
+    prompts = [S.make_prompt(shape.vocab, L, 7, seq=q) for q, L in enumerate((9, 16, 12))]
+    kw = dict(temperature=0.8, seed=12, eta=0.1, beta=0.3, top_p=0.9, headway=2, continuous_compute=True)
+    spec = dict(n_new=9, r_inner=2, r_total=12, eps=0.1, w_max=5, adaptive=True, **kw)
+    steps = _run_gpu_sampler(ctx, prompts, spec, r_prefill=12)
+    worst = 0
+    for q, p in enumerate(prompts):
+        ref = O.generate_diffusion_forcing_adaptive(m, p, 9, 2, 12, 0.1, 5, seq=q, **kw)
+        flat = np.concatenate(ref.deltas)
+        assert np.min(np.abs(flat - 0.1)) > 1e-4, "an exit decision sits on the threshold: pick another seed"
+        toks, n_frozen = ctx.read_tokens(q)
+        assert n_frozen >= len(p) + 9
+        assert np.array_equal(toks[: len(p) + 9], ref.tokens)
+        for pos, st in ref.final_states.items():
+            if pos < len(p) - 1 + 9:
+                assert rel_l2(ctx.read_states(q, pos, 1)[0], st) < 1e-4
+        worst = max(worst, ref.steps)
+    assert steps == worst
+    ctx.close()
+
+
 def test_momentum_and_state_noise_bf16_first_steps():
     """bf16 path: the first sampler steps with eta, beta against the oracle (teacher-forced by
     construction: until a draft differs both sides see the same inputs)."""
