@@ -30,6 +30,52 @@ size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit) {
     return (size_t)max_tiles * H * nsplit * att_rec_floats(d);
 }
 
+// Online-softmax update of one 32-key block for a lane's query: sacc holds the 16 raw scores of
+// lane (col, g) (register r = key kb*32 + 8*(r/4) + 4g + r%4 against query `col`).  m_ref is the
+// reference the exponentials are taken against: it follows the running maximum lazily -- it only
+// moves when a block's maximum exceeds it by more than ATT_LAZY (so every p stays below
+// e^ATT_LAZY, far inside the float and bf16 ranges), because moving it costs a rescale of the
+// whole output tile, a trip through the accumulator registers for each of its elements.  The
+// final result does not depend on the reference: numerator and denominator carry the same factor.
+// Returns alpha, the factor for the running output (exactly 1 when the reference stays), and the
+// probabilities as the two B operands of O^T += V^T P^T.  `full` (uniform over the wave): every
+// key of the block is visible to every query of the tile, so the causal mask is skipped.
+constexpr float ATT_LAZY = 8.0f;
+__device__ __forceinline__ float att_block_probs(f32x16& sacc, int kb, int g, int qpos, bool full, float scale,
+                                                 float& m_ref, float& l_run, bf16x8& p0, bf16x8& p1) {
+    float bm = -INFINITY;
+    if (full) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            sacc[r] *= scale;
+            bm = fmaxf(bm, sacc[r]);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            const float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
+            sacc[r] = v;
+            bm = fmaxf(bm, v);
+        }
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float m_new = (bm > m_ref + ATT_LAZY) ? bm : m_ref; // also the first visible block: m_ref = -inf
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // nothing visible yet: all p become 0
+    const float alpha = (m_new == m_ref) ? 1.0f : __expf(m_ref - m_use);   // m_ref = -inf gives 0
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
+        psum += a + c;
+        p0[r] = (__bf16)a;
+        p1[r] = (__bf16)c;
+    }
+    l_run = l_run * alpha + psum;
+    m_ref = m_new;
+    return alpha;
+}
+
 // One row tile per workgroup (MTQ = 1): narrow windows, ragged batches of short windows.
 template <int D, int MTQ>
 __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __restrict__ q,
@@ -100,34 +146,16 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
             for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
             for (int i = 0; i < DK; ++i) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv[i], qv[b][i], sacc, 0, 0, 0);
-            // register r of lane (col, g) is key kb*32 + 8*(r/4) + 4g + r%4 against query `col`
-            float bm = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
-                sacc[r] = v;
-                bm = fmaxf(bm, v);
-            }
-            bm = fmaxf(bm, __shfl_xor(bm, 32));
-            float m_new = fmaxf(m_run[b], bm);
-            float m_use = (m_new == -INFINITY) ? 0.f : m_new; // nothing visible yet: all p become 0
-            float alpha = __expf(m_run[b] - m_use);           // m_run = -inf gives 0
-            float psum = 0.f;
             bf16x8 p0, p1;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
-                psum += a + c;
-                p0[r] = (__bf16)a;
-                p1[r] = (__bf16)c;
-            }
-            l_run[b] = l_run[b] * alpha + psum;
-            m_run[b] = m_new;
+            const float alpha = att_block_probs(sacc, kb, g, qpos, kb * 32 + 31 <= td.pos0 + 32 * b, scale, m_run[b],
+                                                l_run[b], p0, p1);
+            const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;   // some lane moved its reference
 #pragma unroll
             for (int d = 0; d < DB; ++d) {
+                if (rescale) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[b][d][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) o[b][d][i] *= alpha;
+                }
                 o[b][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[2 * d], p0, o[b][d], 0, 0, 0);
                 o[b][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv[2 * d + 1], p1, o[b][d], 0, 0, 0);
             }
@@ -332,33 +360,15 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
 #pragma unroll
         for (int i = 0; i < DK; ++i)
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][i * 64 + lane], qv[i], sacc, 0, 0, 0);
-        float bm = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int key = kb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            float v = (key <= qpos) ? sacc[r] * scale : -INFINITY;
-            sacc[r] = v;
-            bm = fmaxf(bm, v);
-        }
-        bm = fmaxf(bm, __shfl_xor(bm, 32));
-        float m_new = fmaxf(m_run, bm);
-        float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        float alpha = __expf(m_run - m_use);
-        float psum = 0.f;
         bf16x8 p0, p1;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            float a = __expf(sacc[r] - m_use), c = __expf(sacc[r + 8] - m_use);
-            psum += a + c;
-            p0[r] = (__bf16)a;
-            p1[r] = (__bf16)c;
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+        const float alpha = att_block_probs(sacc, kb, g, qpos, kb * 32 + 31 <= pos0, scale, m_run, l_run, p0, p1);
+        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0;   // some lane moved its reference
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
+            if (rescale) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+                for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+            }
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d) * 64 + lane], p0, o[d], 0, 0, 0);
             o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(stage[cur][(DK + 2 * d + 1) * 64 + lane], p1, o[d], 0, 0, 0);
         }
