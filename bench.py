@@ -65,7 +65,7 @@ def cpu_baseline(shape, w64, prompt_len, window, budget_s=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     m = O.RecurrentDepthLM(shape, w64)
-    max_steps = 8
+    max_steps = 24                       # about 15 s on the 16 host threads of a GPU machine
     cache = m.new_cache(prompt_len + window + max_steps + 2)
     rng = np.random.default_rng(0)
     for d in (cache.k, cache.v):
