@@ -873,9 +873,13 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     const rdlm_model& m = ctx->m;
     const int t = ++ctx->step;
     const int n = ctx->samp_seqs;
-    // upper bound of the wave size at this step (it grows by at most `headway` per step)
+    // upper bound of the wave size at this step: it grows by at most `headway` per step, and a
+    // state stays at most ceil(r / r') steps (then it and every older state are freezable), so no
+    // more than that many generations of `headway` states are in flight -- also under the
+    // adaptive exit rule, whatever the wavefront limit
     long long grow = 1 + (long long)(t - 1) * s.headway;
-    int wmax_now = (int)std::min<long long>(s.w_max, grow);      // (a joined sequence restarts at 1: still a bound)
+    const long long in_flight = (long long)((s.r_total + s.r_inner - 1) / s.r_inner) * s.headway;
+    int wmax_now = (int)std::min<long long>(std::min<long long>(s.w_max, in_flight), grow);   // (a joined sequence restarts at 1: still a bound)
     const int T = n * ((wmax_now + 31) / 32);
     ctx->grouped = wmax_now > TILE_ROWS;
     int max_keys = 0;

@@ -347,6 +347,29 @@ def test_momentum_and_state_noise_adaptive_fp32():
     ctx.close()
 
 
+@pytest.mark.parametrize("headway", [1, 3])
+def test_wavefront_limit_far_above_the_wave_fp32(headway):
+    """Alg. 2 with a wavefront limit (64) far above what can be in flight (ceil(r/r') generations of
+    `headway` states): the launch sizes follow the smaller bound; tokens and latents as the oracle's."""
+    shape = S.TINY
+    ctx, m, _ = make_pair(shape, seed=2, gain_jitter=0.0, emb_mul=6.0, max_positions=128, max_rows=64)
+    prompt = S.make_prompt(shape.vocab, 14, 5)
+    kw = dict(temperature=1.0, seed=6, headway=headway, pad_token=2)
+    ref = O.generate_diffusion_forcing_adaptive(m, prompt, 20, 2, 12, 0.02, 64, **kw)
+    assert max(ref.window_sizes) <= 6 * headway
+    flat = np.concatenate(ref.deltas)
+    assert np.min(np.abs(flat - 0.02)) > 1e-5
+    steps = _run_gpu_sampler(ctx, [prompt], dict(n_new=20, r_inner=2, r_total=12, eps=0.02, w_max=64, adaptive=True,
+                                                 **kw), r_prefill=12)
+    toks, n_frozen = ctx.read_tokens(0)
+    assert steps == ref.steps
+    assert np.array_equal(toks[: 14 + 20], ref.tokens)
+    for p, st in ref.final_states.items():
+        if p < 14 - 1 + 20:
+            assert rel_l2(ctx.read_states(0, p, 1)[0], st) < 1e-4
+    ctx.close()
+
+
 def test_all_sampler_options_together_batched_fp32():
     """Three sequences of different prompt lengths through Alg. 2 with every option switched on at
     once (inner recurrences, wavefront limit, headway, momentum, state noise, temperature with
