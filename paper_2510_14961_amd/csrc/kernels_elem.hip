@@ -545,7 +545,7 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
 // sum_{e_v >= thr} e_v reaches top_p * sum_v e_v -- found by bisection on the bit pattern of thr
 // (the mass is a step function of thr that only changes at the e_v), every mass summed in a
 // fixed order.  The Gumbel race among the kept classes draws from the renormalised nucleus.
-constexpr int TOPP_THREADS = 1024, TOPP_VEC = 16;
+constexpr int TOPP_THREADS = 1024, TOPP_VEC = 16, TOPP_CAND = 1024;
 __device__ inline float block_max(float v, float* sh) {
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
     int w = threadIdx.x >> 6;
@@ -563,6 +563,9 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
     __shared__ float sh[16];
     __shared__ float sv[16];
     __shared__ int si[16];
+    __shared__ int wtot[TOPP_THREADS / 64];
+    __shared__ float cand[TOPP_CAND];
+    __shared__ uint32_t thr_sh;
     const int r = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     const TileDesc d = tiles[t];
@@ -589,18 +592,76 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
     for (int i = 0; i < TOPP_VEC; ++i)
 #pragma unroll
         for (int c = 0; c < 4; ++c) { e[i][c] = __expf(e[i][c] - mx); part += e[i][c]; }
-    const float target = top_p * block_sum(part, sh);
-    uint32_t lo = 0u, hi = 0x3f800001u;                    // mass(+0) = everything; e_v <= 1
-    while (hi - lo > 1u) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
-        const float thr = __uint_as_float(mid);
-        float m = 0.f;
+    const float total = block_sum(part, sh);
+    const float target = top_p * total;
+    // The classes below floor = (1 - top_p) total / V hold less than (1 - top_p) total together,
+    // so the cut lies at or above it (half of it is used, to stay clear of rounding).  Usually only
+    // a few classes reach that: when no more than TOPP_CAND do, they are compacted (in a fixed
+    // order) into LDS and one wave runs the bisection over them with wave-level sums; otherwise
+    // the whole workgroup bisects over the values in registers.
+    const float floor_e = 0.5f * (1.0f - top_p) * total / (float)V;
+    int mine = 0;
+#pragma unroll
+    for (int i = 0; i < TOPP_VEC; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mine += e[i][c] >= floor_e ? 1 : 0;
+    // exclusive prefix sum of the per-thread counts (wave scan, then the waves' totals)
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if ((int)(threadIdx.x & 63) >= o) incl += up;
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 63) wtot[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    int before = 0, n_cand = 0;
+#pragma unroll
+    for (int w = 0; w < TOPP_THREADS / 64; ++w) {
+        if (w < (int)(threadIdx.x >> 6)) before += wtot[w];
+        n_cand += wtot[w];
+    }
+    uint32_t lo = __float_as_uint(floor_e) & 0x7fffffffu, hi = 0x3f800001u;   // mass(floor) >= target; e_v <= 1
+    if (n_cand > 0 && n_cand <= TOPP_CAND) {
+        int at = before + incl - mine;
 #pragma unroll
         for (int i = 0; i < TOPP_VEC; ++i)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) m += e[i][c] >= thr ? e[i][c] : 0.f;
-        m = block_sum(m, sh);
-        if (m >= target) lo = mid; else hi = mid;
+            for (int c = 0; c < 4; ++c)
+                if (e[i][c] >= floor_e) cand[at++] = e[i][c];
+        for (int q = n_cand + threadIdx.x; q < TOPP_CAND; q += TOPP_THREADS) cand[q] = 0.f;
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            float v[TOPP_CAND / 64];
+#pragma unroll
+            for (int q = 0; q < TOPP_CAND / 64; ++q) v[q] = cand[q * 64 + threadIdx.x];
+            while (hi - lo > 1u) {
+                const uint32_t mid = lo + ((hi - lo) >> 1);
+                const float thr = __uint_as_float(mid);
+                float m = 0.f;
+#pragma unroll
+                for (int q = 0; q < TOPP_CAND / 64; ++q) m += v[q] >= thr ? v[q] : 0.f;
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) m += __shfl_xor(m, o);    // every lane ends with the same sum
+                if (m >= target) lo = mid; else hi = mid;
+            }
+            if (threadIdx.x == 0) thr_sh = lo;
+        }
+        __syncthreads();
+        lo = thr_sh;
+    } else {
+        lo = n_cand > 0 ? lo : 0u;                         // nothing reached the floor (not finite): search from +0
+        while (hi - lo > 1u) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            const float thr = __uint_as_float(mid);
+            float m = 0.f;
+#pragma unroll
+            for (int i = 0; i < TOPP_VEC; ++i)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) m += e[i][c] >= thr ? e[i][c] : 0.f;
+            m = block_sum(m, sh);
+            if (m >= target) lo = mid; else hi = mid;
+        }
     }
     const float thr = __uint_as_float(lo);
     const int lstep = step - (seq_step0 ? seq_step0[d.seq] : 0);
