@@ -524,8 +524,9 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
                            (const float*)vc, (float*)out, H, d, seq_stride_elems, tiles, n_tiles);
         return;
     }
-    dim3 grid(H, max_tiles, nsplit);
     if (nsplit > ATT_MAX_SPLIT) nsplit = ATT_MAX_SPLIT;
+    if (nsplit < 1) nsplit = 1;
+    dim3 grid(H, max_tiles, nsplit);
 #define RDLM_ATT(D_)                                                                                              \
     if (d == D_) {                                                                                                \
         if (!grouped) {         /* merges its KV splits itself */                                                 \
