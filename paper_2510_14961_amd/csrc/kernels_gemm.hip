@@ -561,6 +561,23 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
         }
         __builtin_amdgcn_sched_barrier(0);
     };
+    // the same loads for a K step that lies inside the range as a whole: no clamping, no masks
+    auto load_in = [&](bf16x8(&wv)[KU][NB], int kt) {
+        const size_t off = (size_t)kt * 64;
+        xok = (1u << XL) - 1u;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) xr[i] = xsrc[i][off];
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+                wv[u][a] = stream_w ? __builtin_nontemporal_load(wbase[a] + off + (size_t)u * 64) : wbase[a][off + (size_t)u * 64];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto stage_in = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XL; ++i) xs[((size_t)buf * KU * MT + wave + i * WAVES) * 64 + lane] = xr[i];
+    };
     auto stage = [&](int buf) {
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -598,6 +615,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
         compute(wcur, bcur);
         __syncthreads();
     };
+    // a step whose staged tiles (K step s + 1) and loads (K step s + 2) all lie inside the range
+    auto step_in = [&](bf16x8(&wcur)[KU][NB], bf16x8(&wnext)[KU][NB], int bcur, int kt) {
+        stage_in(bcur == 2 ? 0 : bcur + 1);
+        load_in(wnext, kt + 2 * KU);
+        compute(wcur, bcur);
+        __syncthreads();
+    };
     // The loop body is three steps (one turn of the register ring) without exits in between; the
     // one or two steps left over run after it.
     const int nsteps = (kend - kbeg + KU - 1) / KU;
@@ -607,7 +631,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
         stage(0);
         load(w1, min(kt + KU, kend - 1));
         __syncthreads();
+        // turns of the ring in which every step is an inside step: step s qualifies while K steps
+        // s + 1 and s + 2 are whole, i.e. s + 3 <= (kend - kbeg) / KU
         int s3 = nsteps / 3;
+        int in3 = min(s3, max(0, ((kend - kbeg) / KU - 2) / 3));
+        s3 -= in3;
+        for (; in3 > 0; --in3) {
+            step_in(w0, w2, 0, kt); kt += KU;
+            step_in(w1, w0, 1, kt); kt += KU;
+            step_in(w2, w1, 2, kt); kt += KU;
+        }
         for (; s3 > 0; --s3) {
             step(w0, w2, 0, kt); kt += KU;
             step(w1, w0, 1, kt); kt += KU;

@@ -387,7 +387,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                 : proj == PROJ_GU ? GemmPlan{4, 1, 4, 4, 1, GEMM_ROWS}
                 : proj == PROJ_A  ? GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS}
                                   : GemmPlan{4, 1, 8, 4, 3, GEMM_ROWS};
-        else g = (proj == PROJ_GU || deep) ? GemmPlan{8, 2, 4, 2, 2, GEMM_ROWS} : GemmPlan{8, 1, 8, 2, 2, GEMM_ROWS};
+        else g = GemmPlan{8, 1, 8, 2, deep ? 3 : 2, GEMM_ROWS};
         if (const char* p = getenv(kProjEnvRows[proj])) {
             GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
             if (sscanf(p, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) g = o;
