@@ -78,7 +78,7 @@ __device__ __forceinline__ float att_block_probs(f32x16& sacc, int kb, int g, in
 
 // One row tile per workgroup (MTQ = 1): narrow windows, ragged batches of short windows.
 template <int D, int MTQ>
-__global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ kc,
                                                                const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
                                                                int H, size_t seq_stride, int nsplit, float* __restrict__ ws,
@@ -244,40 +244,62 @@ __global__ __launch_bounds__(ATT_WAVES * 64) void attn_bf16_k(const uint16_t* __
     __syncthreads();
     if (ticket != (uint32_t)nsplit - 1) return;
     const float* base = ws + ((size_t)t * H + hd) * nsplit * att_rec_floats(D);
-    for (int item = threadIdx.x; item < DB * 4 * 64; item += ATT_WAVES * 64) {
-        const int quad = item >> 6, ln = item & 63, c = ln & 31, gg = ln >> 5;
-        float m[ATT_MAX_SPLIT], l[ATT_MAX_SPLIT], v[ATT_MAX_SPLIT][4];
+    // Thread (wave, lane) merges accumulator quads wave, wave + ATT_WAVES, ... of query column
+    // `col`, two quads per round: the loads of a round are all issued before its first use, and
+    // the splits' maxima and sums, which depend on the column only, come with the first round.
+    constexpr int QPW = DB * 4 / ATT_WAVES;
+    static_assert(DB * 4 % ATT_WAVES == 0, "quads must divide over the waves");
+    float ms[ATT_MAX_SPLIT], ls[ATT_MAX_SPLIT], w[ATT_MAX_SPLIT], inv = 0.f;
+#pragma unroll
+    for (int k0 = 0; k0 < QPW; k0 += 2) {
+        float v[2][ATT_MAX_SPLIT][4];
 #pragma unroll
         for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
             const float* r = base + (size_t)min(s, nsplit - 1) * att_rec_floats(D);
-            m[s] = __hip_atomic_load(r + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-            l[s] = __hip_atomic_load(r + 32 + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                v[s][i] = __hip_atomic_load(r + 64 + (size_t)(quad * 4 + i) * 64 + ln, __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_SYSTEM);
-        }
-        float Mx = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < ATT_MAX_SPLIT; ++s)
-            if (s < nsplit) Mx = fmaxf(Mx, m[s]);
-        const float Muse = (Mx == -INFINITY) ? 0.f : Mx;
-        float Ls = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
-            if (s < nsplit) {
-                const float w = __expf(m[s] - Muse);
-                Ls += l[s] * w;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) acc[i] += v[s][i] * w;
+            if (k0 == 0) {
+                ms[s] = __hip_atomic_load(r + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                ls[s] = __hip_atomic_load(r + 32 + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (k0 + k < QPW)
+                        v[k][s][i] = __hip_atomic_load(r + 64 + (size_t)((wave + (k0 + k) * ATT_WAVES) * 4 + i) * 64 + lane,
+                                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
-        const float inv = Ls > 0.f ? 1.0f / Ls : 0.f;
-        ushort4 pk;
-        pk.x = f32_to_bf16(acc[0] * inv); pk.y = f32_to_bf16(acc[1] * inv);
-        pk.z = f32_to_bf16(acc[2] * inv); pk.w = f32_to_bf16(acc[3] * inv);
-        const int dim = 32 * (quad >> 2) + 8 * (quad & 3) + 4 * gg;
-        *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + c, hd * D + dim, h)) = pk;
+        if (k0 == 0) {
+            float Mx = -INFINITY;
+#pragma unroll
+            for (int s = 0; s < ATT_MAX_SPLIT; ++s)
+                if (s < nsplit) Mx = fmaxf(Mx, ms[s]);
+            const float Muse = (Mx == -INFINITY) ? 0.f : Mx;
+            float Ls = 0.f;
+#pragma unroll
+            for (int s = 0; s < ATT_MAX_SPLIT; ++s) {
+                w[s] = (s < nsplit) ? __expf(ms[s] - Muse) : 0.f;
+                Ls += (s < nsplit) ? ls[s] * w[s] : 0.f;
+            }
+            inv = Ls > 0.f ? 1.0f / Ls : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (k0 + k >= QPW) continue;
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < ATT_MAX_SPLIT; ++s)
+                if (s < nsplit) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[i] += v[k][s][i] * w[s];
+                }
+            ushort4 pk;
+            pk.x = f32_to_bf16(acc[0] * inv); pk.y = f32_to_bf16(acc[1] * inv);
+            pk.z = f32_to_bf16(acc[2] * inv); pk.w = f32_to_bf16(acc[3] * inv);
+            const int quad = wave + (k0 + k) * ATT_WAVES;
+            const int dim = 32 * (quad >> 2) + 8 * (quad & 3) + 4 * g;
+            *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + col, hd * D + dim, h)) = pk;
+        }
+        __builtin_amdgcn_sched_barrier(0);      // keep the next round's loads behind this round
     }
     if (threadIdx.x == 0) __hip_atomic_store(tk, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }

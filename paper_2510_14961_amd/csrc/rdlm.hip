@@ -533,6 +533,12 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
     if (ctx->forced_att_split > 0) return std::min(ctx->forced_att_split, ctx->att_max_split);
     int wgs = ctx->m.n_heads * (ctx->grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
     int kb = (max_keys + 31) / 32;
+    if (T == 1) {
+        // one tile: n_heads workgroups per split.  Measured at 55 heads x 96: four splits pay from
+        // about 1500 keys on, eight not before 6000
+        int s1 = kb >= 512 ? 8 : kb >= 48 ? 4 : kb >= 32 ? 2 : 1;
+        return std::min(s1, ctx->att_max_split);
+    }
     int s = 1;
     while (s < ctx->att_max_split && wgs * s < 512 && kb / (s * 2) >= 16) s *= 2;
     return s;
