@@ -125,9 +125,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
 
     bf16x8 kA[DK], vA[2 * DB], kB[DK], vB[2 * DB];
     auto load = [&](bf16x8(&kv)[DK], bf16x8(&vv)[2 * DB], int kb) {
-        const uint16_t* kr = K + ((size_t)(kb * 32 + col) * H + hd) * D + g * 8;
+        const uint16_t* kr = K + k_cache_off(kb * 32 + col, hd, g * 8, H, D);
 #pragma unroll
-        for (int i = 0; i < DK; ++i) kv[i] = *reinterpret_cast<const bf16x8*>(kr + i * 16);
+        for (int i = 0; i < DK; ++i) kv[i] = *reinterpret_cast<const bf16x8*>(kr + i * 512);
         const uint16_t* vr = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)col * 32 + g * 8;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     for (int p = 0; p < PER; ++p) {
         const int s = threadIdx.x + p * ATT_GROUP * 64;
         const int ln = s & 63, c = ln & 31, gg = ln >> 5, i = s >> 6, j = i - DK;
-        const uint16_t* sk = K + ((size_t)c * H + hd) * D + gg * 8 + i * 16;
+        const uint16_t* sk = K + k_cache_off(c, hd, gg * 8 + (i < DK ? i : 0) * 16, H, D);
         const uint16_t* sv = Vt + (size_t)hd * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
         fbase[p] = i < DK ? sk : sv;
     }

@@ -385,8 +385,9 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
             uint16_t* q = reinterpret_cast<uint16_t*>(qout);
             q[(size_t)r * h + c0] = f32_to_bf16(qa); q[(size_t)r * h + c1] = f32_to_bf16(qb);
             if (valid) {
-                uint16_t* K = reinterpret_cast<uint16_t*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
-                K[c0] = f32_to_bf16(ka); K[c1] = f32_to_bf16(kb);
+                uint16_t* K = reinterpret_cast<uint16_t*>(kc) + (size_t)ds.seq * seq_stride;
+                K[k_cache_off(pos, hd, i, H, d)] = f32_to_bf16(ka);
+                K[k_cache_off(pos, hd, i + half, H, d)] = f32_to_bf16(kb);
             }
         }
     }
@@ -841,7 +842,7 @@ __global__ void read_kv_k(const void* kc, const void* vc, int H, int d, int pos0
             v_out[(size_t)i * h + c] = reinterpret_cast<const float*>(vc)[(size_t)pos * h + c];
         } else {
             int hd = c / d, dd = c - hd * d;
-            k_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(kc)[(size_t)pos * h + c]);
+            k_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(kc)[k_cache_off(pos, hd, dd, H, d)]);
             v_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(vc)[
                 (((size_t)(pos >> 5) * H + hd) * d + dd) * 32 + vt_slot(pos & 31)]);
         }

@@ -265,14 +265,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                     p0p[i] = f32_to_bf16(lo[i] * cs.x - hi[i] * cs.y);
                     p1p[i] = f32_to_bf16(hi[i] * cs.x + lo[i] * cs.y);
                 }
-                uint16_t* dst = nullptr;
-                if (sec == 0) dst = reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0;
-                else if (valid)
-                    dst = reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td[b].seq * A.epi.seq_stride + (size_t)pos * h +
-                          head * D + u0;
-                if (dst) {
+                if (sec == 0) {
+                    uint16_t* dst = reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0;
                     *reinterpret_cast<ushort4*>(dst) = p0;
                     *reinterpret_cast<ushort4*>(dst + HALF) = p1;
+                } else if (valid) {
+                    uint16_t* Kc = reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td[b].seq * A.epi.seq_stride;
+                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos, head, u0, H, D)) = p0;
+                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos, head, u0 + HALF, H, D)) = p1;
                 }
             }
         } else {   // EPI_ARGMAX

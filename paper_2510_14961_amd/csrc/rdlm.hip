@@ -19,7 +19,7 @@ struct Layer {
     void* wo = nullptr;
     void* wgu = nullptr;     // gate rows then up rows: [2F, h]
     void* wd = nullptr;
-    void* kc = nullptr;      // K cache [max_seqs][ctx_pad][H][d]
+    void* kc = nullptr;      // K cache: f32 [max_seqs][ctx_pad][H][d]; bf16 per 32-position block in operand order (k_cache_off)
     void* vc = nullptr;      // V cache: f32 same layout; bf16 transposed per 32-position block
 };
 

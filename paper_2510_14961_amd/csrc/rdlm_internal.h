@@ -78,6 +78,15 @@ __host__ __device__ inline size_t packed_off(int row, int k, int K) {
     return (((size_t)t * (K >> 4) + kt) * 64 + m + 32 * (kk >> 3)) * 8 + (kk & 7);
 }
 
+// Offset of (position, head, dim) inside one sequence's bf16 K cache.  Keys are stored in blocks of
+// 32 positions per head, each block as the A operands of the score contraction S^T = K.Q^T:
+// [pos / 32][head][dim / 16][lane = 32 * (dim % 16 / 8) + pos % 32][dim % 8].  A wave's load of one
+// k step is 1 KiB contiguous and a (block, head) is 64 * D contiguous bytes, as in the V cache.
+__host__ __device__ inline size_t k_cache_off(int pos, int hd, int dim, int H, int D) {
+    return ((((size_t)(pos >> 5) * H + hd) * (D >> 4) + (dim >> 4)) * 64 + 32 * ((dim >> 3) & 1) + (pos & 31)) * 8 +
+           (dim & 7);
+}
+
 // Position of key `kappa` (0..31) inside a 32-position block of the transposed V cache.  The
 // order is the one in which the 32x32 score accumulator of the attention kernel hands its keys to
 // the P.V contraction, so that both operands of that contraction are plain 16-byte loads.
