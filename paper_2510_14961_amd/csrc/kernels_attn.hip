@@ -89,8 +89,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     __shared__ float sm[ATT_WAVES][2][32];
     __shared__ float so[ATT_WAVES][DB * 16][64];
     const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
-    if (t >= *n_tiles) return;
-    const TileDesc td = tiles[t];
+    const TileDesc td = tiles[t];                             // valid memory for every t of the grid; read
+    if (t >= *n_tiles) return;                                // together with the count, used only behind it
     int ng = 1;
     if (MTQ > 1) {
         ng = min(td.group, MTQ);
@@ -320,8 +320,8 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     constexpr int PER = (SLOTS + ATT_GROUP * 64 - 1) / (ATT_GROUP * 64);
     __shared__ bf16x8 stage[2][SLOTS];
     const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
+    const TileDesc td = tiles[t];                             // read together with the count
     if (t >= *n_tiles) return;
-    const TileDesc td = tiles[t];
     const int ng = min(td.group, ATT_GROUP);
     if (ng <= 0) return;                                      // served by its group leader
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

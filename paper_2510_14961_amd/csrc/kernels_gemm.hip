@@ -24,6 +24,7 @@ struct GemmArgs {
     const bf16x8* wp;
     float* out;             // EPI_F32: [ksplit][rows][N] partial sums; EPI_ARGMAX: logits [rows][N] or null
     int N, K16, n_groups, m_chunks, ksplit;
+    int max_tiles;          // the host's bound on the tile count (the launch covers that many)
     size_t part_stride;
     const int32_t* n_tiles;
     GemmEpilogue epi;
@@ -341,15 +342,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
     const int mc = bid % A.m_chunks; bid /= A.m_chunks;   // row chunk fastest: neighbours share weights
     const int ks = bid % A.ksplit;
     const int grp = bid / A.ksplit;
-    const int n_tiles = *A.n_tiles;
     const int t0 = mc * MT;
-    if (t0 >= n_tiles) return;
+    // The tile count lives in device memory.  A launch over a single row tile does not wait for
+    // it before its first weights are on their way: tile 0's operand is valid memory whatever
+    // the count is, and the count is looked at when the contraction is done.
+    const bool late_count = A.max_tiles == 1;
+    int n_tiles = 1;
+    if (!late_count) {
+        n_tiles = *A.n_tiles;
+        if (t0 >= n_tiles) return;
+    }
     const int nblk = A.N >> 5, K16 = A.K16;
     // K range of this wave: K16 tiles split evenly over ksplit * WAVES slices
     const int slices = A.ksplit * WAVES, sl = ks * WAVES + wave;
     const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
     float sc[MT];
-    gemm_row_scales<MT>(A, t0, n_tiles, sc);
+    gemm_row_scales<MT>(A, t0, n_tiles, sc);        // late_count: tile 0, as n_tiles = 1 stands in
 
     f32x16 acc[NB][MT];
 #pragma unroll
@@ -423,6 +431,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
             for (int b = 0; b < MT; ++b)
                 acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xbase[b][(size_t)kt * 64], acc[a][b], 0, 0, 0);
         }
+    }
+
+    if (late_count) {
+        n_tiles = *A.n_tiles;
+        if (n_tiles <= 0) return;
     }
 
     // Cross-wave sum in a fixed order: every wave deposits its accumulators; the finishing work is
@@ -502,9 +515,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
     const int mc = rest % A.m_chunks, gk = (rest / A.m_chunks) * 8 + xcd;
     if (gk >= A.n_groups * A.ksplit) return;
     const int ks = gk % A.ksplit, grp = gk / A.ksplit;
-    const int n_tiles = *A.n_tiles;
     const int t0 = mc * MT;
-    if (t0 >= n_tiles) return;
+    const bool late_count = A.max_tiles == 1;      // as in gemm_bf16_k: look at the count afterwards
+    int n_tiles = 1;
+    if (!late_count) {
+        n_tiles = *A.n_tiles;
+        if (t0 >= n_tiles) return;
+    }
     const int nblk = A.N >> 5, K16 = A.K16;
     const int kbeg = (int)(((long long)K16 * ks) / A.ksplit), kend = (int)(((long long)K16 * (ks + 1)) / A.ksplit);
     float sc[MT];
@@ -656,6 +673,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
             }
         }
     }
+    if (late_count) {
+        n_tiles = *A.n_tiles;
+        if (n_tiles <= 0) return;
+    }
     auto quad_sum = [&](int a, int b, int q, float (&o)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = acc[a][b][q * 4 + i];
@@ -717,7 +738,7 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
     }
     GemmArgs a;
     a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
-    a.m_chunks = m_chunks; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
+    a.m_chunks = m_chunks; a.max_tiles = max_tiles; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
     hipLaunchKernelGGL(kern, dim3(groups * ksplit * m_chunks), dim3(WAVES * 64), lds, st, a);
     return true;
 }
@@ -742,7 +763,7 @@ static bool launch_rows_cfg(const void* xp, const void* wp, float* out, int N, i
     }
     GemmArgs a;
     a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
-    a.m_chunks = m_chunks; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
+    a.m_chunks = m_chunks; a.max_tiles = max_tiles; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
     const int gk8 = (groups * ksplit + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(gk8 * m_chunks), dim3(WAVES * 64), lds, st, a);
     return true;
