@@ -12,7 +12,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librdlm.so")
 SOURCES = ["kernels_elem.hip", "kernels_gemm.hip", "kernels_attn.hip", "rdlm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _hipcc() -> str:

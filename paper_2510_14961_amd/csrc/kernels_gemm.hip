@@ -30,6 +30,20 @@ struct GemmArgs {
     GemmEpilogue epi;
 };
 
+// The GEMM kernels take the fields of GemmArgs that the K loop needs as leading scalar arguments,
+// in this order, so that they can be preloaded into scalar registers when the wave starts (the
+// first 16 dwords of the argument block); the epilogue's parameters follow as a struct.
+#define GEMM_KERNEL_PARAMS                                                                                      \
+    const bf16x8 *xp_, const bf16x8 *wp_, const int32_t *n_tiles_, float *out_, int N_, int K16_, int n_groups_, \
+        int m_chunks_, int ksplit_, int max_tiles_, size_t part_stride_, GemmEpilogue epi_
+#define GEMM_KERNEL_ARGS_STRUCT                                                                                 \
+    GemmArgs A;                                                                                                 \
+    A.xp = xp_; A.wp = wp_; A.n_tiles = n_tiles_; A.out = out_; A.N = N_; A.K16 = K16_; A.n_groups = n_groups_; \
+    A.m_chunks = m_chunks_; A.ksplit = ksplit_; A.max_tiles = max_tiles_; A.part_stride = part_stride_; A.epi = epi_
+#define GEMM_LAUNCH_ARGS(a)                                                                                     \
+    (a).xp, (a).wp, (a).n_tiles, (a).out, (a).N, (a).K16, (a).n_groups, (a).m_chunks, (a).ksplit, (a).max_tiles, \
+        (a).part_stride, (a).epi
+
 // Epilogue helpers ---------------------------------------------------------------------------
 __device__ inline float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 
@@ -328,7 +342,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
 }
 
 template <int MT, int NB, int WAVES, int U, int EPI>
-__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GEMM_KERNEL_PARAMS) {
+    GEMM_KERNEL_ARGS_STRUCT;
     // cross-wave sums: [WAVES][NB*MT*16][64] for one row tile; with several row tiles the waves
     // finish one row tile at a time through [WAVES][NB*16][64]
     extern __shared__ float red[];
@@ -503,7 +518,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GemmArgs A) {
 // Workgroups of one (feature group, K split) that cover different row chunks get ids that land on
 // the same XCD one after the other, so the weights they share are served by that XCD's L2.
 template <int MT, int NB, int WAVES, int KU, int EPI>
-__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GemmArgs A) {
+__global__ __launch_bounds__(WAVES * 64) void gemm_bf16_rows_k(GEMM_KERNEL_PARAMS) {
+    GEMM_KERNEL_ARGS_STRUCT;
     extern __shared__ float red[];                 // activation stages: [3][KU * MT][64] x 16 bytes
     bf16x8* xs = reinterpret_cast<bf16x8*>(red);
     constexpr int CW = EPI == EPI_ARGMAX ? WAVES : 1;
@@ -739,7 +755,7 @@ static bool launch_cfg(const void* xp, const void* wp, float* out, int N, int K,
     GemmArgs a;
     a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
     a.m_chunks = m_chunks; a.max_tiles = max_tiles; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
-    hipLaunchKernelGGL(kern, dim3(groups * ksplit * m_chunks), dim3(WAVES * 64), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(groups * ksplit * m_chunks), dim3(WAVES * 64), lds, st, GEMM_LAUNCH_ARGS(a));
     return true;
 }
 
@@ -765,7 +781,7 @@ static bool launch_rows_cfg(const void* xp, const void* wp, float* out, int N, i
     a.xp = (const bf16x8*)xp; a.wp = (const bf16x8*)wp; a.out = out; a.N = N; a.K16 = K / 16; a.n_groups = groups;
     a.m_chunks = m_chunks; a.max_tiles = max_tiles; a.ksplit = ksplit; a.part_stride = part_stride; a.n_tiles = n_tiles; a.epi = epi;
     const int gk8 = (groups * ksplit + 7) / 8 * 8;
-    hipLaunchKernelGGL(kern, dim3(gk8 * m_chunks), dim3(WAVES * 64), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(gk8 * m_chunks), dim3(WAVES * 64), lds, st, GEMM_LAUNCH_ARGS(a));
     return true;
 }
 
