@@ -570,6 +570,42 @@ def test_same_seed_twice_is_bitwise_identical():
     ctx.close()
 
 
+@pytest.mark.parametrize("shape_name,forced_split", [("d96", 0), ("d64", 8), ("d32", 0), ("d96", 2)])
+def test_one_tile_window_behind_long_context_kv_splits(shape_name, forced_split, monkeypatch):
+    """One ragged row tile behind 1600 cached positions: the one-tile attention kernel splits the keys
+    four ways by itself at this length (eight and two when forced), and the last workgroup of a
+    head to arrive merges the splits -- in rounds of two accumulator quads, of which head sizes
+    96, 64 and 32 have three, two and one per wave."""
+    torch = _torch()
+    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32}[shape_name]
+    if forced_split:
+        monkeypatch.setenv("RDLM_ATT_SPLIT", str(forced_split))      # read when the context is created
+    ctx, m, _ = make_pair(shape, max_positions=1700, max_rows=1632)
+    monkeypatch.delenv("RDLM_ATT_SPLIT", raising=False)
+    L, n = 1600, 21
+    tokens = S.make_prompt(shape.vocab, L + n, 14)
+    ctx.set_tokens(0, tokens[:L])
+    ctx.prefill(0, L, 1, 1.0, 5)
+    cache = m.new_cache(1700)
+    m.prefill(tokens[:L], 1, 1.0, 5, 0, cache)
+    tol = tol_latent(shape)
+    pos = np.arange(L, L + n)
+    e_ref = m.prelude(tokens[L:], pos, cache)
+    z0 = np.stack([O.init_state(shape.hidden, p, 0, 1.0, 5) for p in pos])
+    z1 = m.core(e_ref, z0, pos, cache)
+    e = torch.zeros(n, shape.hidden, device="cuda")
+    ctx.prelude([0], [L], [n], _dev(tokens[L:].astype(np.int32)), e)
+    assert rel_l2(e.cpu().numpy(), e_ref) < tol
+    z = _dev(z0.astype(np.float32))
+    ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z, 1, None)
+    assert max(rel_l2(a, b) for a, b in zip(z.cpu().numpy(), z1)) < tol
+    # the same step again: the tickets of the merge were reset, the result repeats bit for bit
+    z_again = _dev(z0.astype(np.float32))
+    ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z_again, 1, None)
+    assert torch.equal(z, z_again)
+    ctx.close()
+
+
 def test_long_context_attention_splits():
     """A context of more than a thousand positions (many key blocks, several KV splits merged) in
     front of a ragged window, head dim 96."""
