@@ -486,8 +486,13 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         epi.ssq_chunks = ctx->ssq_count ? ctx->ssq_count : 1; epi.norm_h = h; epi.norm_eps = m.rms_eps;
     }
     if (folded) *folded = false;
+    // (one row tile only: folding two to four tiles of one workgroup tile after tile in the same
+    // tail was measured -- 1115 -> 1123 tokens/s at a 64-row window, nothing at 128 rows -- and left out)
     const bool do_fold = fold && !plain && T == 1 && epi.kind == EPI_F32 && g.kind == GEMM_STREAM && g.mt == 1 &&
                          (g.nb == 1 || g.nb == 2 || g.nb == 4) && gemm_groups(N, g, EPI_F32) <= SSQ_MAX_CHUNKS &&
+                         // partial sums in accumulator order cover whole feature groups: they must fit
+                         (size_t)g.ksplit * T * 32 * gemm_groups(N, g, EPI_F32) * g.nb * 32 <=
+                             (size_t)8 * ctx->rows_pad * h &&
                          !getenv("RDLM_NO_FOLD_FUSION");
     if (do_fold) {
         epi.fold_counter = ctx->fold_counter; epi.fold_xin = fold->xin; epi.fold_xout = fold->xout;
@@ -503,7 +508,10 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
     }
     if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
-        if (g.mt > 1) g = {g.mt, 1, 4, g.mt == 2 ? 8 : 4, 1, GEMM_ROWS};
+        if (g.mt > 1) {
+            g = {g.mt, 1, 4, g.mt == 2 ? 8 : 4, 1, GEMM_ROWS};
+            epi.fold_counter = nullptr;         // the row-sharing kernel leaves plain partial sums
+        }
         else g = {1, 1, 4, 4, g.ksplit};
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
         if (!ok) {

@@ -166,17 +166,17 @@ def test_big_shape_wide_window_and_ragged_batch(big_pair):
     ctx.close()
 
 
-def _run_steps(ctx, prompt, n_steps, seed=3):
-    """Prefill a short prompt, run n_steps sampler steps at window 32, return tokens and states."""
+def _run_steps(ctx, prompt, n_steps, seed=3, headway=1, n_new=100):
+    """Prefill a short prompt, run n_steps sampler steps at window 32 * headway, return tokens and states."""
     L = len(prompt)
     ctx.set_tokens(0, prompt)
     ctx.prefill(0, L - 1, 2, 1.0, seed)
-    ctx.sampler_begin(1, n_new=100, r_inner=1, r_total=32, seed=seed)
+    ctx.sampler_begin(1, n_new=n_new, r_inner=1, r_total=32, seed=seed, headway=headway)
     for _ in range(n_steps):
         ctx.sample_step()
     toks, _ = ctx.read_tokens(0)
-    z = ctx.read_states(0, L - 1, n_steps)
-    return toks[: L + n_steps].copy(), z
+    z = ctx.read_states(0, L - 1, n_steps * headway)
+    return toks[: L + n_steps * headway].copy(), z
 
 
 def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_kernels(big_pair, monkeypatch):
@@ -200,3 +200,9 @@ def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_k
     monkeypatch.delenv("RDLM_NO_FOLD_FUSION")
     assert np.array_equal(t4, t3)
     assert rel_l2(z4[0], z3[0]) < 2e-2
+    # (c) two states appended per step: from step 17 on the window spans two row tiles (separate fold
+    # kernels, grouped attention); again repeatable bit for bit
+    t5, z5 = _run_steps(ctx, prompt, 30, headway=2, n_new=64)
+    t6, z6 = _run_steps(ctx, prompt, 30, headway=2, n_new=64)
+    assert np.array_equal(t5, t6)
+    assert np.array_equal(z5, z6)
