@@ -704,20 +704,24 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
     }
 }
 
-// End of a sampler step, one workgroup: for every sequence (in turn; its rows in parallel) the
-// drafts become y_current and the step counters advance (Alg. 1 line 13), the longest freezable
-// prefix k* is frozen (Alg. 1 line 14 / Eq. 3), new states are appended unless the wavefront is
-// full (Alg. 1 line 16, Alg. 2) and drawn (InitState); then the tile list of the next step is
-// built from the updated windows.
+// End of a sampler step, one workgroup per sequence (its rows in parallel): the drafts become
+// y_current and the step counters advance (Alg. 1 line 13), the longest freezable prefix k* is
+// frozen (Alg. 1 line 14 / Eq. 3), new states are appended unless the wavefront is full (Alg. 1
+// line 16, Alg. 2) and drawn (InitState).  The last workgroup to finish then builds the tile list
+// of the next step from all updated windows: the sequence records are handed over with
+// system-scope stores and loads around a ticket (no device-scope fence), as the GEMM folds are.
 __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y,
                                                    int32_t* counts, int max_positions, const int32_t* drafts,
                                                    const float* delta, float* z, float* z_prev, int h,
-                                                   TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step) {
+                                                   TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step,
+                                                   uint32_t* ticket_ctr) {
     __shared__ int first_open;                       // first row of the window that is not freezable
     __shared__ SeqState cur;
+    __shared__ uint32_t ticket;
+    constexpr int NF = sizeof(SeqState) / sizeof(int32_t);
     const int tid = threadIdx.x;
-    int active = 0;
-    for (int s = 0; s < n_seqs; ++s) {
+    const int s = blockIdx.x;
+    if (s < n_seqs) {
         if (tid == 0) { cur = seqs[s]; first_open = 0x7fffffff; }
         __syncthreads();
         SeqState q = cur;
@@ -754,6 +758,10 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
                     }
                 }
                 cur = q;
+                // the record goes to memory for the workgroup that builds the tile list
+                const int32_t* src = reinterpret_cast<const int32_t*>(&q);
+                int32_t* dst = reinterpret_cast<int32_t*>(&seqs[s]);
+                for (int f = 0; f < NF; ++f) __hip_atomic_store(dst + f, src[f], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             }
             __syncthreads();
             q = cur;
@@ -777,37 +785,58 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
                 }
             }
         }
-        if (!q.done) active++;
+    }
+    if (gridDim.x > 1) {
+        __builtin_amdgcn_s_waitcnt(0);               // the record's stores have been acknowledged
         __syncthreads();
-        if (tid == 0) seqs[s] = cur;
+        if (tid == 0) ticket = __hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __syncthreads();
+        if (ticket != gridDim.x - 1) return;
+    } else {
+        __syncthreads();
+    }
+    // tile list of the next step: the records of up to 256 sequences at a time are fetched in
+    // parallel, one thread lays the tiles out in sequence order
+    __shared__ int32_t s_done[256], s_win_n[256], s_pos0[256];
+    int t = 0, c = 0, active = 0;
+    for (int s0 = 0; s0 < n_seqs; s0 += 256) {
+        const int i = s0 + tid;
+        if (i < n_seqs) {
+            s_done[tid] = __hip_atomic_load(&seqs[i].done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            s_win_n[tid] = __hip_atomic_load(&seqs[i].win_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            s_pos0[tid] = __hip_atomic_load(&seqs[i].win_pos0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int j = 0; j < min(256, n_seqs - s0); ++j) {
+                const int sq = s0 + j;
+                if (!s_done[j]) active++;
+                const int rows = s_done[j] ? 0 : s_win_n[j];
+                seqs[sq].cur_tile0 = t;
+                seqs[sq].cur_rows = rows;
+                for (int off = 0; off < rows; off += TILE_ROWS) {
+                    TileDesc d;
+                    d.seq = sq;
+                    d.pos0 = s_pos0[j] + off;
+                    d.n_valid = min(TILE_ROWS, rows - off);
+                    d.zrow0 = d.yrow0 = sq * max_positions + d.pos0;
+                    d.erow0 = t * TILE_ROWS;
+                    d.crow0 = c + off;
+                    const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
+                    d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
+                    tiles[t++] = d;
+                }
+                c += rows;
+            }
+        }
         __syncthreads();
     }
     if (tid == 0) {
         // n_active[1] remembers the step at which the last sequence finished (0 = still running)
         if (active == 0 && n_active[0] != 0) n_active[1] = step;
         n_active[0] = active;
-        // tile list of the next step
-        int t = 0, c = 0;
-        for (int s = 0; s < n_seqs; ++s) {
-            SeqState& q = seqs[s];
-            const int rows = q.done ? 0 : q.win_n;
-            q.cur_tile0 = t;
-            q.cur_rows = rows;
-            for (int off = 0; off < rows; off += TILE_ROWS) {
-                TileDesc d;
-                d.seq = s;
-                d.pos0 = q.win_pos0 + off;
-                d.n_valid = min(TILE_ROWS, rows - off);
-                d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
-                d.erow0 = t * TILE_ROWS;
-                d.crow0 = c + off;
-                const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
-                d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
-                tiles[t++] = d;
-            }
-            c += rows;
-        }
         *n_tiles = t;
+        if (gridDim.x > 1) __hip_atomic_store(ticket_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -994,9 +1023,9 @@ void launch_sample_top_p(const float* logits, int V, float temperature, float to
 }
 void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
                      const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
-                     int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st) {
-    hipLaunchKernelGGL(step_end_k, dim3(1), dim3(256), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts, delta,
-                       z, z_prev, h, tiles, n_tiles, n_active, step);
+                     int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st) {
+    hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(256), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts,
+                       delta, z, z_prev, h, tiles, n_tiles, n_active, step, ticket);
 }
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st) {
     hipLaunchKernelGGL(seq_join_k, dim3(1), dim3(64), 0, st, seqs, seq_step0, seq, prompt_len, step);

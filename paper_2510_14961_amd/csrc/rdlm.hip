@@ -51,6 +51,7 @@ struct rdlm_ctx {
     int32_t* drafts = nullptr;
     int att_max_split = 8;
     uint32_t* att_tickets = nullptr;     // [max_tiles][heads], zero between launches
+    uint32_t* step_ticket = nullptr;     // step_end_k's arrival counter, zero between launches
     // sampler state
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
@@ -257,6 +258,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
     DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
     DALLOC(ctx->att_tickets, (size_t)ctx->max_tiles * m.n_heads * 4, true);
+    DALLOC(ctx->step_ticket, 64, true);
     if (m.dtype == RDLM_BF16)
         DALLOC(ctx->att_ws, attention_ws_floats(ctx->max_tiles, m.n_heads, m.head_dim, ctx->att_max_split) * 4, false);
     // sampler state
@@ -920,7 +922,8 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
     // freeze, append, InitState of the appended positions, tile list of the next step
     launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
-                    ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->st);
+                    ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->step_ticket,
+                    ctx->st);
     std::swap(ctx->tiles, ctx->tiles_samp);
     std::swap(ctx->n_tiles, ctx->n_tiles_samp);
     return check_launch(ctx);

@@ -243,12 +243,12 @@ void launch_sample_top_p(const float* logits, int V, float temperature, float to
 // Continuous batching: put a sequence into (join) or take it out of (retire) a running sampler.
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st);
 void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st);
-// End of a sampler step in one launch: drafts -> y_current, step counters, k*, freeze, append
-// (Alg. 1 lines 13-16 / Alg. 2), Gaussian states of the appended positions, and the tile list of
-// the next step.
+// End of a sampler step in one launch (one workgroup per sequence): drafts -> y_current, step
+// counters, k*, freeze, append (Alg. 1 lines 13-16 / Alg. 2), Gaussian states of the appended
+// positions, and the tile list of the next step.  ticket: one device word, zero between launches.
 void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
                      const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
-                     int32_t* n_tiles, int32_t* n_active, int step, hipStream_t st);
+                     int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n,
                     float* k_out, float* v_out, hipStream_t st);
