@@ -134,7 +134,11 @@ def main():
     wave = -(-sp.r // sp.r_inner) * sp.headway
     window = sp.w_max if (sp.adaptive and sp.w_max > 0) else wave
     n_seqs = wl.n_seqs
-    n_new = max(sp.n_new, (K + W + 1) * sp.headway)          # never finish inside the timed steps
+    # steps before the first freeze: ceil(r / r') under the fixed exit rule and, at worst (no state
+    # converges before the cap), under the adaptive one
+    fill_steps = -(-sp.r // sp.r_inner)
+    K2_max = 64
+    n_new = max(sp.n_new, (fill_steps + K + W + K2_max + 1) * sp.headway)   # never finish inside the timed steps
     max_positions = wl.prompt_len + n_new + window + sp.headway + 8
     max_rows = max(wl.prompt_len, n_seqs * (-(-window // 32) * 32))
     want_cpu = not args.no_cpu_baseline and args.workload in ("cfg2", "cfg3")
@@ -168,23 +172,39 @@ def main():
                       pad_token=sp.pad_token)
     ctx.sampler_begin(n_seqs, n_new=n_new, **sampler_kw)
     frozen = lambda: sum(ctx.read_tokens(q, 1)[1] for q in range(n_seqs))
+    # wave fill (untimed, not part of --warmup): a position stays in flight for ceil(r / r') steps, so
+    # nothing is frozen before that many steps have run; after them every step freezes tokens
+    for _ in range(fill_steps):
+        ctx.sample_step()
     for _ in range(W):
         ctx.sample_step()
     torch.cuda.synchronize()
     nf0 = frozen()
-    n_gu, k_gu = 2 * shape.mlp, shape.hidden
-    per_step_launches = shape.n_prelude + sp.r_inner * shape.n_core + shape.n_coda     # one per layer pass
-    ctx.profile_gemm_begin(n_gu, k_gu, K * per_step_launches)
-    torch.cuda.synchronize()
+    # headline: K steps, nothing but the sampler's own launches on the stream
     t0 = time.perf_counter()
     for _ in range(K):
         ctx.sample_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    gemm_ms, gemm_launches = ctx.profile_gemm_read()
     nf1 = frozen()
     tokens = nf1 - nf0
     ms_per_step = dt / K * 1e3
+    if tokens <= 0:
+        print(f"bench.py: no token was frozen in the {K} timed steps (fill {fill_steps}, warmup {W}): "
+              "the metric cannot be computed", file=sys.stderr)
+        sys.exit(3)
+    # roofline leg (second, short pass, not part of the headline): every launch of the gate/up
+    # projection bracketed by a HIP event pair on the library's stream
+    n_gu, k_gu = 2 * shape.mlp, shape.hidden
+    per_step_launches = shape.n_prelude + sp.r_inner * shape.n_core + shape.n_coda     # one per layer pass
+    K2 = min(K, 64)
+    ctx.profile_gemm_begin(n_gu, k_gu, K2 * per_step_launches)
+    torch.cuda.synchronize()
+    for _ in range(K2):
+        ctx.sample_step()
+    torch.cuda.synchronize()
+    gemm_ms, gemm_launches = ctx.profile_gemm_read()
+    nf2 = frozen()
 
     # dominant kernel: gate/up projection over the rows of a step (each sequence's window padded to 32)
     rows = n_seqs * (-(-window // 32) * 32)
@@ -281,9 +301,14 @@ def main():
                                + ("greedy" if sp.temperature == 0 else f"temperature {sp.temperature}")
                                + (f", adaptive exit eps={sp.eps}" if sp.adaptive else "")
                                + (f", headway {sp.headway}" if sp.headway > 1 else ""),
-                   "tokens_in_timed_region": int(tokens), "context_at_end": int(nf1)},
+                   "tokens_in_timed_region": int(tokens), "fill_steps": int(fill_steps),
+                   "context_at_end": int(nf2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier "
+                                       "run of this command, scaled by a 1 GiB copy; not measured by this run)"
+                                       if traffic is not None else None,
+                     "timing": f"HIP event pair around each launch, second pass of {K2} steps after the headline steps",
                      "kernel": f"gemm_bf16_k (gate/up projection with fused SwiGLU, [2F x h] weights, {rows} rows)",
                      "bytes_per_launch": algo_bytes, "avg_ms_per_launch": gemm_ms, "launches_timed": gemm_launches},
         "whole_step": {"weight_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -16,7 +16,10 @@
  *     "host" pointers are ordinary host memory.  No torch types cross this boundary.
  *   - All work is enqueued on the stream given to rdlm_create and is asynchronous, except the
  *     rdlm_read_* functions and rdlm_generate, which synchronise that stream.
- *   - After rdlm_create the library allocates no further memory.
+ *   - After rdlm_create the library allocates no further memory.  The step workspace is one slab:
+ *     the library's own, or the caller's (rdlm_workspace_bytes + rdlm_create_ws).  Weights (re-tiled
+ *     copies), the KV cache and the per-position sampler stores (latents, tokens, counters) are
+ *     always the library's: their layouts are internal (MFMA operand order).
  *   - Rows of a step are given per sequence as (seq id, first position, row count): row j of
  *     sequence entry i sits at absolute position pos0[i] + j; rows of all entries are
  *     concatenated in the order given ("M rows").  Row-major float32 [M, hidden] everywhere.
@@ -40,14 +43,19 @@ typedef enum {
     RDLM_ECAPACITY = -2,  /* more sequences, rows or positions than the context was created for   */
     RDLM_ENOMEM = -3,     /* device allocation failed in rdlm_create                              */
     RDLM_EHIP = -4,       /* a HIP call failed; see rdlm_last_hip_error                           */
-    RDLM_ESTATE = -5      /* call out of order (e.g. sample_step before sampler_begin)            */
+    RDLM_ESTATE = -5,     /* call out of order (e.g. sample_step before sampler_begin)            */
+    RDLM_ENUMERIC = -6    /* a non-finite delta_i (NaN / infinite latent, or ||z|| = 0) reached the  */
+                          /* exit rule of Eq. 3; such a state is never frozen by it                  */
 } rdlm_status;
 
 enum { RDLM_F32 = 0, RDLM_BF16 = 1 };
 
 /* Shape of the model.  dtype is the storage type of the matrices (and of the KV cache and GEMM
  * operands); accumulation, norms, softmax and the latent state are always float32.
- * RDLM_BF16 needs hidden % 32 == 0, mlp % 32 == 0, vocab % 32 == 0, head_dim % 32 == 0. */
+ * RDLM_BF16 needs hidden % 32 == 0, mlp % 32 == 0, vocab % 32 == 0 and head_dim 32, 64 or 96
+ * (the attention kernels for 128 are not covered by parity tests and stay switched off).
+ * Both types need hidden <= 8192 (row kernels keep a row in registers), mlp >= hidden (staging
+ * buffers are sized by mlp) and an even head_dim; anything else is RDLM_EINVAL from rdlm_create. */
 typedef struct {
     int32_t vocab, hidden, n_heads, head_dim, mlp;
     int32_t n_prelude, n_core, n_coda;
@@ -107,6 +115,15 @@ int32_t rdlm_num_weights(const rdlm_model* m);
 int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
                 int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out);
 int rdlm_destroy(rdlm_ctx* ctx);
+
+/* The same with the step workspace in caller-owned device memory: `workspace` (256-byte aligned)
+ * of at least rdlm_workspace_bytes(m, max_seqs, max_rows) bytes, which must stay valid until
+ * rdlm_destroy and is used by this context only.  workspace = NULL: the library allocates it.
+ * rdlm_workspace_bytes returns 0 for a model or sizes rdlm_create would refuse. */
+size_t rdlm_workspace_bytes(const rdlm_model* m, int32_t max_seqs, int32_t max_rows);
+int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                   int32_t max_positions, int32_t max_rows, void* hip_stream, void* workspace,
+                   size_t workspace_bytes, rdlm_ctx** out);
 
 const char* rdlm_strerror(int status);
 int rdlm_last_hip_error(const rdlm_ctx* ctx);   /* hipError_t of the last failed HIP call, or 0 */
@@ -179,10 +196,14 @@ int rdlm_sample_step(rdlm_ctx* ctx);
 /* Iterate rdlm_sample_step until every sequence has n_new frozen tokens or max_steps steps were
  * taken; synchronises.  The device is looked at only every few iterations (at the predicted last
  * one for the fixed exit rule); iterations enqueued after the finishing one do nothing.
- * steps_out (host, may be NULL) receives the number of iterations up to the finishing one. */
+ * steps_out (host, may be NULL) receives the number of iterations of this call up to the finishing
+ * one.  Returns RDLM_ENUMERIC (after stopping at the next look) if a non-finite delta_i was seen. */
 int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_out);
 
 /* ---- read-back (synchronise the stream) ------------------------------------------------- */
+/* State of the running sampler: sequences not yet finished, and whether any step since
+ * rdlm_sampler_begin saw a non-finite delta_i (either may be NULL). */
+int rdlm_sampler_status(rdlm_ctx* ctx, int32_t* n_active_out, int32_t* nonfinite_out);
 /* Tokens of a sequence: frozen ones first (prompt + generated); n_frozen_out = |y_frozen|.
  * Copies min(cap, max_positions) entries of y_current (frozen, then current drafts, then pad). */
 int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap,
@@ -200,6 +221,13 @@ int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_
                  float* k_host, float* v_host);
 
 /* ---- kernel-level entry points (measurement and unit tests) ------------------------------- */
+/* Tuning knobs of a context (launch shapes, fusion switches); the same names in upper case with
+ * the prefix RDLM_ are read from the environment once, by rdlm_create.  Names: "att_split" (forced
+ * number of KV splits, 0 = automatic), "no_rope_fusion", "no_fold_fusion", "no_fold" ("1" / "0"),
+ * "plan_<p>" = "nb,waves,unroll,ksplit" and "planr_<p>" = "[s]mt,nb,waves,unroll,ksplit" with <p> in
+ * qkv, o, gu, d, a, head ("" = default).  A launch shape without a kernel instance makes the calls
+ * that would use it return RDLM_EINVAL (and ends a running sampler: part of the step has run). */
+int rdlm_set_tuning(rdlm_ctx* ctx, const char* name, const char* value);
 /* y[M,N] = x[M,K] . W^T for weight tensor index w_index (as in the rdlm_create order; wg and wu
  * are one fused [2F,h] matrix reachable through wg's index).  x, y: device float32 row-major.
  * Runs the same tiled kernel the model path uses (including its split-K reduction). */

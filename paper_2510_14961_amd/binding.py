@@ -20,12 +20,17 @@ EXPORTED_SYMBOLS = [
     "rdlm_core_step", "rdlm_coda_decode", "rdlm_sampler_begin", "rdlm_sampler_join", "rdlm_sample_step", "rdlm_generate",
     "rdlm_read_tokens", "rdlm_read_states", "rdlm_read_counts", "rdlm_read_deltas", "rdlm_read_kv",
     "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
-    "rdlm_profile_gemm_read",
+    "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws",
+    "rdlm_sampler_status", "rdlm_set_tuning",
 ]
+
+STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
 
 
 class RdlmError(RuntimeError):
-    pass
+    def __init__(self, msg, status=None):
+        super().__init__(msg)
+        self.status = status
 
 
 class _Model(C.Structure):
@@ -86,6 +91,11 @@ def load_library():
         "rdlm_time_core_step": (C.c_int, [vp, i32, i32, i32, i32, C.POINTER(C.c_float)]),
         "rdlm_profile_gemm_begin": (C.c_int, [vp, i32, i32, i32]),
         "rdlm_profile_gemm_read": (C.c_int, [vp, C.POINTER(C.c_float), pi32]),
+        "rdlm_workspace_bytes": (C.c_size_t, [C.POINTER(_Model), i32, i32]),
+        "rdlm_create_ws": (C.c_int, [C.POINTER(_Model), C.POINTER(vp), i32, i32, i32, vp, vp, C.c_size_t,
+                                     C.POINTER(vp)]),
+        "rdlm_sampler_status": (C.c_int, [vp, pi32, pi32]),
+        "rdlm_set_tuning": (C.c_int, [vp, C.c_char_p, C.c_char_p]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -93,6 +103,18 @@ def load_library():
         fn.argtypes = args
     _LIB = lib
     return lib
+
+
+def _model_struct(shape) -> "_Model":
+    return _Model(shape.vocab, shape.hidden, shape.n_heads, shape.head_dim, shape.mlp, shape.n_prelude,
+                  shape.n_core, shape.n_coda, shape.rope_base, shape.rms_eps, shape.emb_scale,
+                  0 if shape.dtype == "f32" else 1)
+
+
+def workspace_bytes(shape, max_seqs: int, max_rows: int) -> int:
+    """rdlm_workspace_bytes: size of the step workspace a context of these limits needs (host only)."""
+    m = _model_struct(shape)
+    return int(load_library().rdlm_workspace_bytes(C.byref(m), max_seqs, max_rows))
 
 
 def weight_names(shape) -> List[str]:
@@ -125,14 +147,14 @@ class Context:
     """One rdlm_ctx.  Methods carry the names of the C functions without the prefix."""
 
     def __init__(self, shape, dev_weights: Dict[str, "object"], max_seqs: int, max_positions: int,
-                 max_rows: int, stream=None):
+                 max_rows: int, stream=None, workspace=None):
+        """workspace: None (the library allocates its step workspace) or a CUDA uint8 tensor of at
+        least workspace_bytes(shape, max_seqs, max_rows) bytes that the caller keeps alive."""
         import torch
         self.lib = load_library()
         self.shape = shape
         self.h, self.V = shape.hidden, shape.vocab
-        self.model = _Model(shape.vocab, shape.hidden, shape.n_heads, shape.head_dim, shape.mlp, shape.n_prelude,
-                            shape.n_core, shape.n_coda, shape.rope_base, shape.rms_eps, shape.emb_scale,
-                            0 if shape.dtype == "f32" else 1)
+        self.model = _model_struct(shape)
         names = weight_names(shape)
         assert self.lib.rdlm_num_weights(C.byref(self.model)) == len(names)
         want = torch.float32 if shape.dtype == "f32" else torch.bfloat16
@@ -144,10 +166,17 @@ class Context:
             ptrs[i] = t.data_ptr()
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         handle = C.c_void_p()
-        rc = self.lib.rdlm_create(C.byref(self.model), ptrs, max_seqs, max_positions, max_rows,
-                                  C.c_void_p(self.stream.cuda_stream), C.byref(handle))
+        if workspace is None:
+            rc = self.lib.rdlm_create(C.byref(self.model), ptrs, max_seqs, max_positions, max_rows,
+                                      C.c_void_p(self.stream.cuda_stream), C.byref(handle))
+        else:
+            assert workspace.is_cuda and workspace.is_contiguous() and workspace.element_size() == 1
+            self._workspace = workspace                 # keep it alive as long as the context
+            rc = self.lib.rdlm_create_ws(C.byref(self.model), ptrs, max_seqs, max_positions, max_rows,
+                                         C.c_void_p(self.stream.cuda_stream), C.c_void_p(workspace.data_ptr()),
+                                         workspace.numel(), C.byref(handle))
         if rc != 0:
-            raise RdlmError(f"rdlm_create: {self.lib.rdlm_strerror(rc).decode()} ({rc})")
+            raise RdlmError(f"rdlm_create: {self.lib.rdlm_strerror(rc).decode()} ({rc})", rc)
         self.ctx = handle
         self.max_positions = max_positions
 
@@ -155,7 +184,7 @@ class Context:
     def _chk(self, rc: int, what: str):
         if rc != 0:
             hip = self.lib.rdlm_last_hip_error(self.ctx)
-            raise RdlmError(f"{what}: {self.lib.rdlm_strerror(rc).decode()} ({rc}), hip={hip}")
+            raise RdlmError(f"{what}: {self.lib.rdlm_strerror(rc).decode()} ({rc}), hip={hip}", rc)
 
     @staticmethod
     def _rows(seq_ids, pos0, n_rows):
@@ -201,6 +230,14 @@ class Context:
         d = C.c_void_p(delta_out.data_ptr()) if delta_out is not None else C.c_void_p()
         self._chk(self.lib.rdlm_core_step(self.ctx, len(s), _iptr(s), _iptr(p), _iptr(n), C.c_void_p(e.data_ptr()),
                                           C.c_void_p(z_inout.data_ptr()), r_inner, d), "rdlm_core_step")
+
+    def set_tuning(self, name: str, value: str):
+        self._chk(self.lib.rdlm_set_tuning(self.ctx, name.encode(), str(value).encode()), "rdlm_set_tuning")
+
+    def sampler_status(self):
+        a, nf = C.c_int32(0), C.c_int32(0)
+        self._chk(self.lib.rdlm_sampler_status(self.ctx, C.byref(a), C.byref(nf)), "rdlm_sampler_status")
+        return a.value, bool(nf.value)
 
     def coda_decode(self, seq_ids, pos0, n_rows, z, temperature: float, seed: int, step: int, tokens_out,
                     logits_out=None, top_p: float = 0.0):

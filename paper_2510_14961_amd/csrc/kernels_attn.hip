@@ -237,12 +237,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     // partials are written and read with system-scope accesses, every wave waits for its stores to
     // be acknowledged before the workgroup draws its ticket (a system-scope atomic).
     __shared__ uint32_t ticket;
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
     uint32_t* tk = tickets + (size_t)t * H + hd;
-    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(tk, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    __syncthreads();
-    if (ticket != (uint32_t)nsplit - 1) return;
+    if (draw_ticket(tk, &ticket) != (uint32_t)nsplit - 1) return;
     const float* base = ws + ((size_t)t * H + hd) * nsplit * att_rec_floats(D);
     // Thread (wave, lane) merges accumulator quads wave, wave + ATT_WAVES, ... of query column
     // `col`, two quads per round: the loads of a round are all issued before its first use, and

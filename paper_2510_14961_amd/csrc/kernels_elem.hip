@@ -735,7 +735,11 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
                 const int c = counts[base + pos] + 1;
                 counts[base + pos] = c;
                 const float dl = delta[row0 + i];
-                const bool conv = p.adaptive && (dl == dl) && fabsf(dl) != INFINITY && dl < p.eps;
+                const bool finite = (dl == dl) && fabsf(dl) != INFINITY;
+                // a non-finite delta_i (NaN or infinite latent, or ||z|| = 0) never freezes a state; it is
+                // also reported: n_active[2] counts as "seen", every writer stores the same value
+                if (!finite) n_active[2] = 1;
+                const bool conv = p.adaptive && finite && dl < p.eps;
                 const bool cap = c * p.r_inner >= p.r_total;
                 if (!(conv || cap)) atomicMin(&first_open, i);
             }
@@ -787,11 +791,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
         }
     }
     if (gridDim.x > 1) {
-        __builtin_amdgcn_s_waitcnt(0);               // the record's stores have been acknowledged
-        __syncthreads();
-        if (tid == 0) ticket = __hip_atomic_fetch_add(ticket_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-        __syncthreads();
-        if (ticket != gridDim.x - 1) return;
+        if (draw_ticket(ticket_ctr, &ticket) != gridDim.x - 1) return;
     } else {
         __syncthreads();
     }

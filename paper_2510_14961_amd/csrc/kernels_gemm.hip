@@ -95,12 +95,7 @@ template <int NB, int THREADS>
 __device__ __forceinline__ void gemm_fold_tail(const GemmArgs& A, int grp, int t0) {
     static_assert(NB == 1 || NB == 2 || NB == 4, "a row's columns of the group sit in 8, 16 or 32 adjacent lanes");
     __shared__ uint32_t ticket;
-    __builtin_amdgcn_s_waitcnt(0);                 // this wave's stores have been acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0)
-        ticket = __hip_atomic_fetch_add(A.epi.fold_counter + grp, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    __syncthreads();
-    if (ticket != (uint32_t)A.ksplit - 1) return;
+    if (draw_ticket(A.epi.fold_counter + grp, &ticket) != (uint32_t)A.ksplit - 1) return;
     // one thread per (register quad u of the group, lane): 4 consecutive columns of one row, read
     // back in the order they were written (coalesced)
     constexpr int UNITS = NB * 4;
@@ -150,12 +145,8 @@ __device__ __forceinline__ void gemm_fold_tail(const GemmArgs& A, int grp, int t
     if (threadIdx.x == 0) __hip_atomic_store(A.epi.fold_counter + grp, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     // second level, same protocol: the last group to finish adds the groups' shares of every row's
     // sum of squares (in group order) and leaves one value per row for the consumer
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
     uint32_t* total = A.epi.fold_counter + SSQ_MAX_CHUNKS;
-    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(total, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    __syncthreads();
-    if (ticket != (uint32_t)A.n_groups - 1) return;
+    if (draw_ticket(total, &ticket) != (uint32_t)A.n_groups - 1) return;
     __shared__ float part_ss[THREADS / 32][32];
     {
         constexpr int PARTS = THREADS / 32;

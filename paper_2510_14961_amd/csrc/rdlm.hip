@@ -6,7 +6,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <cctype>
 #include <cstring>
+#include <strings.h>
 #include <utility>
 #include <vector>
 
@@ -23,9 +25,48 @@ struct Layer {
     void* vc = nullptr;      // V cache: f32 same layout; bf16 transposed per 32-position block
 };
 
-struct rdlm_ctx {
+enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT };
+
+// Tuning knobs (launch shapes, fusion switches).  Read from the environment once, in rdlm_create
+// (RDLM_<NAME> with NAME in upper case), or set on a context with rdlm_set_tuning; never looked up
+// inside a step.
+struct Knobs {
+    int att_split = 0;               // > 0: forced number of KV splits of the attention kernels
+    bool no_rope_fusion = false;     // RoPE + cache writes in a kernel of their own instead of the QKV epilogue
+    bool no_fold_fusion = false;     // split-K folds in fold_k launches instead of the producing GEMM
+    bool no_fold = false;            // full RMSNorm kernels instead of the deferred 1/rms factor
+    bool has_plan[PROJ_COUNT] = {}, has_plan_rows[PROJ_COUNT] = {};
+    GemmPlan plan[PROJ_COUNT], plan_rows[PROJ_COUNT];
+};
+
+// Scratch memory of a step: everything the kernels of one call write and read back, nothing that has
+// to survive the call except that the ticket words are zero between launches.  One slab, cut up by
+// carve_workspace: allocated by rdlm_create or handed in by the caller.
+struct Workspace {
+    int max_tiles = 0, rows_pad = 0;
+    TileDesc* tiles = nullptr;
+    int32_t* n_tiles = nullptr;
+    TileDesc* tiles_samp = nullptr;      // the sampler's own tile list (built at the end of each step for the next)
+    int32_t* n_tiles_samp = nullptr;
+    float *x = nullptr, *e = nullptr, *qkv = nullptr, *gu = nullptr, *part = nullptr, *logits = nullptr;
+    float *delta = nullptr, *zp_api = nullptr, *att_ws = nullptr;
+    void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
+    int32_t* drafts = nullptr;
+    float* ssq = nullptr;           // [SSQ_MAX_CHUNKS + 1][rows_pad] partial sums of squares of the folded rows
+    uint32_t* fold_counter = nullptr;   // tickets of the folding GEMMs, one per feature group, zero between launches
+    float* rope_tab = nullptr;      // [rows_pad][d/2] (cos, sin) of the current step's rows
+    float* cand_val = nullptr;
+    int32_t* cand_idx = nullptr;
+    uint32_t* att_tickets = nullptr;     // [max_tiles][heads], zero between launches
+    uint32_t* step_ticket = nullptr;     // step_end_k's arrival counter, zero between launches
+    // the ticket words, for clearing: [ticket_lo, ticket_lo + ticket_bytes)
+    void* ticket_lo = nullptr;
+    size_t ticket_bytes = 0;
+};
+
+struct rdlm_ctx : Workspace {
     rdlm_model m;
-    int max_seqs = 0, max_positions = 0, ctx_pad = 0, max_rows = 0, max_tiles = 0, rows_pad = 0;
+    int max_seqs = 0, max_positions = 0, ctx_pad = 0, max_rows = 0;
     hipStream_t st = nullptr;
     int fmt = ACT_F32;
     size_t esz = 4;
@@ -36,29 +77,15 @@ struct rdlm_ctx {
     float* gf = nullptr;
     float* gout = nullptr;
     float* theta = nullptr;
-    float* ssq = nullptr;           // [rows_pad][SSQ_MAX_CHUNKS] partial sums of squares of the folded rows
     int ssq_count = 0;              // slots per row the last producer of the normalised operand filled
-    uint32_t* fold_counter = nullptr;   // tickets of the folding GEMMs, one per feature group, zero between launches
-    float* rope_tab = nullptr;      // [rows_pad][d/2] (cos, sin) of the current step's rows
-    // workspace
-    TileDesc* tiles = nullptr;
-    int32_t* n_tiles = nullptr;
-    TileDesc* tiles_samp = nullptr;      // the sampler's own tile list (built at the end of each step for the next)
-    int32_t* n_tiles_samp = nullptr;
-    float *x = nullptr, *e = nullptr, *qkv = nullptr, *gu = nullptr, *part = nullptr, *logits = nullptr;
-    float *delta = nullptr, *zp_api = nullptr, *att_ws = nullptr;
-    void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
-    int32_t* drafts = nullptr;
     int att_max_split = 8;
-    uint32_t* att_tickets = nullptr;     // [max_tiles][heads], zero between launches
-    uint32_t* step_ticket = nullptr;     // step_end_k's arrival counter, zero between launches
     // sampler state
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
     int32_t* counts = nullptr;
     int32_t* seq_step0 = nullptr;    // [max_seqs] sampler step each sequence joined at
     float *z_store = nullptr, *z_prev = nullptr, *e_store = nullptr;
-    int32_t* n_active = nullptr;
+    int32_t* n_active = nullptr;     // [0] unfinished sequences, [1] step the last one finished at, [2] non-finite deltas seen
     int32_t* n_active_host = nullptr;    // pinned
     SamplerParams sp;
     rdlm_sampler sampler;
@@ -70,11 +97,9 @@ struct rdlm_ctx {
     int last_hip = 0;
     size_t bytes = 0;
     std::vector<void*> allocs;
-    float* cand_val = nullptr;
-    int32_t* cand_idx = nullptr;
-    int forced_att_split = 0;
     bool coda_ready = false;        // the closing norm of the recurrence left the coda's first operand in xn
     bool grouped = false;           // current step: some sequence has several row tiles (grouped attention)
+    Knobs knobs;
     // per-launch GEMM timing
     int prof_n = 0, prof_k = 0, prof_used = 0;
     std::vector<hipEvent_t> prof_ev;
@@ -131,6 +156,7 @@ extern "C" const char* rdlm_strerror(int s) {
         case RDLM_ENOMEM: return "device allocation failed";
         case RDLM_EHIP: return "HIP call failed";
         case RDLM_ESTATE: return "call out of order";
+        case RDLM_ENUMERIC: return "a non-finite latent reached the exit rule";
         default: return "unknown status";
     }
 }
@@ -186,7 +212,62 @@ static int take_gain(rdlm_ctx* ctx, const void* src, int h, float** dst) {
     return RDLM_OK;
 }
 
-static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
+// Cut a workspace for steps of up to max_tiles row tiles out of the slab at `base` (null: only
+// count).  Returns the bytes needed.  `full`: also what the prelude, the coda and the sampler use
+// (conditioning rows, logits, argmax candidates, drafts, the sampler's second tile list); without
+// it only what rdlm_core_step touches.
+static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, int max_tiles, int att_max_split,
+                              bool full) {
+    const int h = m.hidden, F = m.mlp, V = m.vocab;
+    const size_t esz = m.dtype == RDLM_F32 ? 4 : 2;
+    const size_t R = (size_t)max_tiles * 32;
+    const size_t wide = (size_t)std::max(2 * h, F);
+    size_t off = 0;
+    auto take = [&](size_t bytes) -> void* {
+        void* p = base ? static_cast<char*>(base) + off : nullptr;
+        off += (std::max<size_t>(bytes, 1) + 255) / 256 * 256;
+        return p;
+    };
+    Workspace w;
+    w.max_tiles = max_tiles; w.rows_pad = (int)R;
+    // ticket words first, contiguous: they are the only part that must read zero when a call starts
+    w.ticket_lo = take(0);
+    w.fold_counter = (uint32_t*)take((SSQ_MAX_CHUNKS + 1) * 4);
+    w.att_tickets = (uint32_t*)take((size_t)max_tiles * m.n_heads * 4);
+    w.step_ticket = (uint32_t*)take(64);
+    w.ticket_bytes = off;
+    w.tiles = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
+    w.n_tiles = (int32_t*)take(64);
+    w.x = (float*)take(R * h * 4);
+    w.qkv = (float*)take(R * 3 * h * 4);
+    // f32 gate/up sums: the f32 path's GEMM output, rdlm_linear's, and the staging area of rdlm_read_kv
+    if (full || m.dtype == RDLM_F32) w.gu = (float*)take(R * 2 * F * 4);
+    w.part = (float*)take(8 * R * h * 4);
+    w.delta = (float*)take(R * 4);
+    w.zp_api = (float*)take(R * h * 4);
+    w.xn = take(R * h * esz);
+    w.abuf = take(R * wide * esz);
+    w.q = take(R * h * esz);
+    w.att = take(R * h * esz);
+    w.ssq = (float*)take(R * (SSQ_MAX_CHUNKS + 1) * 4);       // + one slot: row totals left by a folding GEMM
+    w.rope_tab = (float*)take(R * (m.head_dim / 2) * 8);
+    if (m.dtype == RDLM_BF16) w.att_ws = (float*)take(attention_ws_floats(max_tiles, m.n_heads, m.head_dim, att_max_split) * 4);
+    if (full) {
+        w.tiles_samp = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
+        w.n_tiles_samp = (int32_t*)take(64);
+        w.e = (float*)take(R * h * 4);
+        w.logits = (float*)take(R * V * 4);
+        w.drafts = (int32_t*)take(R * 4);
+        w.cand_val = (float*)take((size_t)(V / 32 + 1) * R * 4);
+        w.cand_idx = (int32_t*)take((size_t)(V / 32 + 1) * R * 4);
+    }
+    if (ws) *ws = w;
+    return off;
+}
+
+static int tiles_for(int max_seqs, int max_rows) { return (max_rows + 31) / 32 + max_seqs; }
+
+static int create_impl(rdlm_ctx* ctx, const void* const* wp, void* workspace) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden, F = m.mlp, V = m.vocab;
     const size_t esz = ctx->esz;
@@ -233,34 +314,14 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
         DALLOC(ctx->theta, th.size() * 4, false);
         HIPCHK(hipMemcpy(ctx->theta, th.data(), th.size() * 4, hipMemcpyHostToDevice));
     }
-    const size_t R = ctx->rows_pad;
-    const size_t wide = (size_t)std::max(2 * h, F);
-    DALLOC(ctx->tiles, sizeof(TileDesc) * ctx->max_tiles, true);
-    DALLOC(ctx->n_tiles, 64, true);
-    DALLOC(ctx->tiles_samp, sizeof(TileDesc) * ctx->max_tiles, true);
-    DALLOC(ctx->n_tiles_samp, 64, true);
-    DALLOC(ctx->x, R * h * 4, true);
-    DALLOC(ctx->e, R * h * 4, true);
-    DALLOC(ctx->qkv, R * 3 * h * 4, true);
-    DALLOC(ctx->gu, R * 2 * F * 4, true);
-    DALLOC(ctx->part, 8 * R * h * 4, true);
-    DALLOC(ctx->logits, R * V * 4, true);
-    DALLOC(ctx->delta, R * 4, true);
-    DALLOC(ctx->zp_api, R * h * 4, true);
-    DALLOC(ctx->xn, R * h * esz, true);
-    DALLOC(ctx->abuf, R * wide * esz, true);
-    DALLOC(ctx->q, R * h * esz, true);
-    DALLOC(ctx->att, R * h * esz, true);
-    DALLOC(ctx->drafts, R * 4, true);
-    DALLOC(ctx->ssq, R * (SSQ_MAX_CHUNKS + 1) * 4, true);      // + one slot: row totals left by a folding GEMM
-    DALLOC(ctx->fold_counter, (SSQ_MAX_CHUNKS + 1) * 4, true);
-    DALLOC(ctx->rope_tab, R * (m.head_dim / 2) * 8, true);
-    DALLOC(ctx->cand_val, (size_t)(V / 32 + 1) * R * 4, true);
-    DALLOC(ctx->cand_idx, (size_t)(V / 32 + 1) * R * 4, true);
-    DALLOC(ctx->att_tickets, (size_t)ctx->max_tiles * m.n_heads * 4, true);
-    DALLOC(ctx->step_ticket, 64, true);
-    if (m.dtype == RDLM_BF16)
-        DALLOC(ctx->att_ws, attention_ws_floats(ctx->max_tiles, m.n_heads, m.head_dim, ctx->att_max_split) * 4, false);
+    // workspace: one slab (the caller's, or allocated here), cleared once with a fill kernel
+    {
+        const size_t need = carve_workspace(nullptr, nullptr, m, ctx->max_tiles, ctx->att_max_split, true);
+        void* slab = workspace;
+        if (!slab) DALLOC(slab, need, false);
+        carve_workspace(ctx, slab, m, ctx->max_tiles, ctx->att_max_split, true);
+        launch_fill_i32(reinterpret_cast<int32_t*>(slab), 0, need / 4, ctx->st);
+    }
     // sampler state
     const size_t SP = (size_t)ctx->max_seqs * ctx->max_positions;
     DALLOC(ctx->seqs, sizeof(SeqState) * ctx->max_seqs, true);
@@ -278,8 +339,76 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp) {
     return RDLM_OK;
 }
 
-extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
-                           int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out) {
+// ---------------------------------------------------------------------------------------------
+// tuning knobs
+
+static const char* kProjName[PROJ_COUNT] = {"qkv", "o", "gu", "d", "a", "head"};
+
+static int set_knob(Knobs* k, const char* name, const char* value) {
+    if (!name || !value) return RDLM_EINVAL;
+    auto is = [&](const char* n) { return strcasecmp(name, n) == 0; };
+    if (is("att_split")) { k->att_split = atoi(value); return RDLM_OK; }
+    if (is("no_rope_fusion")) { k->no_rope_fusion = atoi(value) != 0; return RDLM_OK; }
+    if (is("no_fold_fusion")) { k->no_fold_fusion = atoi(value) != 0; return RDLM_OK; }
+    if (is("no_fold")) { k->no_fold = atoi(value) != 0; return RDLM_OK; }
+    for (int pj = 0; pj < PROJ_COUNT; ++pj) {
+        char nm[32];
+        // plan_<proj> = "nb,waves,unroll,ksplit": the one-tile launch shape ("" = default again)
+        snprintf(nm, sizeof nm, "plan_%s", kProjName[pj]);
+        if (is(nm)) {
+            GemmPlan o = {1, 0, 0, 0, 0};
+            k->has_plan[pj] = sscanf(value, "%d,%d,%d,%d", &o.nb, &o.waves, &o.unroll, &o.ksplit) == 4;
+            if (k->has_plan[pj]) k->plan[pj] = o;
+            return (k->has_plan[pj] || !value[0]) ? RDLM_OK : RDLM_EINVAL;
+        }
+        // planr_<proj> = "mt,nb,waves,unroll,ksplit" (row-sharing kernel) or "s<the same>" (streaming
+        // kernel): the launch shape for several row tiles
+        snprintf(nm, sizeof nm, "planr_%s", kProjName[pj]);
+        if (is(nm)) {
+            GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
+            const bool stream = value[0] == 's';
+            k->has_plan_rows[pj] =
+                sscanf(value + (stream ? 1 : 0), "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5;
+            if (stream) o.kind = GEMM_STREAM;
+            if (k->has_plan_rows[pj]) k->plan_rows[pj] = o;
+            return (k->has_plan_rows[pj] || !value[0]) ? RDLM_OK : RDLM_EINVAL;
+        }
+    }
+    return RDLM_EINVAL;
+}
+
+static void knobs_from_env(Knobs* k) {
+    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold"};
+    auto env_of = [](const char* name) {
+        char buf[48] = "RDLM_";
+        size_t n = strlen(buf);
+        for (const char* c = name; *c && n + 1 < sizeof buf; ++c) buf[n++] = (char)toupper((unsigned char)*c);
+        buf[n] = 0;
+        return getenv(buf);
+    };
+    for (const char* nm : names)
+        if (const char* v = env_of(nm)) (void)set_knob(k, nm, v);
+    for (int pj = 0; pj < PROJ_COUNT; ++pj)
+        for (const char* pre : {"plan_", "planr_"}) {
+            char nm[32];
+            snprintf(nm, sizeof nm, "%s%s", pre, kProjName[pj]);
+            if (const char* v = env_of(nm)) (void)set_knob(k, nm, v);
+        }
+}
+
+extern "C" int rdlm_set_tuning(rdlm_ctx* ctx, const char* name, const char* value) {
+    if (!ctx) return RDLM_EINVAL;
+    return set_knob(&ctx->knobs, name, value);
+}
+
+extern "C" size_t rdlm_workspace_bytes(const rdlm_model* m, int32_t max_seqs, int32_t max_rows) {
+    if (!model_ok(m) || max_seqs < 1 || max_seqs > MAX_API_SEQS || max_rows < 1) return 0;
+    return carve_workspace(nullptr, nullptr, *m, tiles_for(max_seqs, max_rows), 8, true);
+}
+
+extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                              int32_t max_positions, int32_t max_rows, void* hip_stream, void* workspace,
+                              size_t workspace_bytes, rdlm_ctx** out) {
     if (!out) return RDLM_EINVAL;
     *out = nullptr;
     if (!model_ok(m) || !weight_ptrs) return RDLM_EINVAL;
@@ -287,21 +416,24 @@ extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, 
     if (m->dtype == RDLM_F32 && max_positions > 8192) return RDLM_EINVAL;   // f32 attention keeps scores in LDS
     for (int i = 0; i < rdlm_num_weights(m); ++i)
         if (!weight_ptrs[i]) return RDLM_EINVAL;
+    if (workspace) {
+        if (reinterpret_cast<uintptr_t>(workspace) % 256) return RDLM_EINVAL;
+        if (workspace_bytes < rdlm_workspace_bytes(m, max_seqs, max_rows)) return RDLM_ECAPACITY;
+    }
     rdlm_ctx* ctx = new rdlm_ctx();
     ctx->m = *m;
     ctx->max_seqs = max_seqs;
     ctx->max_positions = max_positions;
     ctx->ctx_pad = (max_positions + 31) / 32 * 32;
     ctx->max_rows = max_rows;
-    ctx->max_tiles = (max_rows + 31) / 32 + max_seqs;
+    ctx->max_tiles = tiles_for(max_seqs, max_rows);
     ctx->rows_pad = ctx->max_tiles * 32;
     ctx->st = reinterpret_cast<hipStream_t>(hip_stream);
     ctx->fmt = m->dtype == RDLM_F32 ? ACT_F32 : ACT_BF16P;
     ctx->esz = m->dtype == RDLM_F32 ? 4 : 2;
-    if (const char* p = getenv("RDLM_ATT_SPLIT")) ctx->forced_att_split = atoi(p);
-    int rc = create_impl(ctx, weight_ptrs);
+    knobs_from_env(&ctx->knobs);
+    int rc = create_impl(ctx, weight_ptrs, workspace);
     if (rc != RDLM_OK) {
-        // keep the HIP error readable through a static slot: the context is gone
         for (void* p : ctx->allocs) (void)hipFree(p);
         if (ctx->n_active_host) (void)hipHostFree(ctx->n_active_host);
         delete ctx;
@@ -311,20 +443,18 @@ extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, 
     return RDLM_OK;
 }
 
+extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                           int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out) {
+    return rdlm_create_ws(m, weight_ptrs, max_seqs, max_positions, max_rows, hip_stream, nullptr, 0, out);
+}
+
 // ---------------------------------------------------------------------------------------------
 // GEMM dispatch
-
-enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT };
-static const char* kProjEnv[PROJ_COUNT] = {"RDLM_PLAN_QKV", "RDLM_PLAN_O", "RDLM_PLAN_GU",
-                                           "RDLM_PLAN_D", "RDLM_PLAN_A", "RDLM_PLAN_HEAD"};
-static const char* kProjEnvRows[PROJ_COUNT] = {"RDLM_PLANR_QKV", "RDLM_PLANR_O", "RDLM_PLANR_GU",
-                                               "RDLM_PLANR_D", "RDLM_PLANR_A", "RDLM_PLANR_HEAD"};
 
 // Launch shape of a projection for T row tiles: {row tiles per workgroup, feature blocks per
 // workgroup (per wave for the row-sharing kernel), waves, k tiles fetched per batch, split of K
 // across workgroups, kernel kind}.  The defaults come from sweeps on MI355X at the 3.5B shape;
-// RDLM_PLAN_<proj>="nb,waves,unroll,ksplit" overrides the one-tile case and
-// RDLM_PLANR_<proj>="mt,nb,waves,unroll,ksplit" the several-tile case (tuning aids).
+// the knobs plan_<proj> and planr_<proj> override the one-tile and the several-tile case (tuning aids).
 static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     GemmPlan g;
     const bool split_ok = proj == PROJ_O || proj == PROJ_D || proj == PROJ_A;
@@ -336,10 +466,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             case PROJ_D: g = {1, 2, 8, 2, 3}; break;
             default: g = {1, 2, 8, 1, 3}; break;       // O, A
         }
-        if (const char* p = getenv(kProjEnv[proj])) {
-            GemmPlan o = {1, 0, 0, 0, 0};
-            if (sscanf(p, "%d,%d,%d,%d", &o.nb, &o.waves, &o.unroll, &o.ksplit) == 4) g = o;
-        }
+        if (ctx->knobs.has_plan[proj]) g = ctx->knobs.plan[proj];
     } else {
         // several row tiles: the row-sharing kernel.  Shapes from sweeps at 64..4096 rows.  While the
         // step is bound by weight streaming, small row chunks with many workgroups in flight win
@@ -390,14 +517,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                 : proj == PROJ_A  ? GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS}
                                   : GemmPlan{4, 1, 8, 4, 3, GEMM_ROWS};
         else g = GemmPlan{8, 1, 8, 2, deep ? 3 : 2, GEMM_ROWS};
-        if (const char* p = getenv(kProjEnvRows[proj])) {
-            GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
-            if (sscanf(p, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) g = o;
-            if (p[0] == 's' && sscanf(p + 1, "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5) {
-                o.kind = GEMM_STREAM;             // "s<mt>,<nb>,<waves>,<unroll>,<ksplit>": the streaming kernel
-                g = o;
-            }
-        }
+        if (ctx->knobs.has_plan_rows[proj]) g = ctx->knobs.plan_rows[proj];
     }
     if (!split_ok) g.ksplit = 1;
     if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
@@ -468,7 +588,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
     if (!plain && proj == PROJ_GU) {
         epi.kind = EPI_SWIGLU;
         epi.act = ctx->abuf;
-    } else if (!plain && proj == PROJ_QKV && rope_layer && !getenv("RDLM_NO_ROPE_FUSION")) {
+    } else if (!plain && proj == PROJ_QKV && rope_layer && !ctx->knobs.no_rope_fusion) {
         // RoPE and the cache writes happen in the GEMM epilogue
         epi.kind = EPI_ROPE_KV;
         epi.q_out = ctx->q; epi.kc = rope_layer->kc; epi.vc = rope_layer->vc; epi.rope_table = ctx->rope_tab;
@@ -495,7 +615,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
                          // partial sums in accumulator order cover whole feature groups: they must fit
                          (size_t)g.ksplit * T * 32 * gemm_groups(N, g, EPI_F32) * g.nb * 32 <=
                              (size_t)8 * ctx->rows_pad * h &&
-                         !getenv("RDLM_NO_FOLD_FUSION");
+                         !ctx->knobs.no_fold_fusion;
     if (do_fold) {
         epi.fold_counter = ctx->fold_counter; epi.fold_xin = fold->xin; epi.fold_xout = fold->xout;
         epi.fold_gain = fold->gain; epi.fold_xg = ctx->xn; epi.fold_ssq = ctx->ssq;
@@ -540,7 +660,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
 
 static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
     if (ctx->m.dtype == RDLM_F32) return 1;
-    if (ctx->forced_att_split > 0) return std::min(ctx->forced_att_split, ctx->att_max_split);
+    if (ctx->knobs.att_split > 0) return std::min(ctx->knobs.att_split, ctx->att_max_split);
     int wgs = ctx->m.n_heads * (ctx->grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
     int kb = (max_keys + 31) / 32;
     if (T == 1) {
@@ -559,7 +679,7 @@ static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
 static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, const float* gain, void* xn, int T) {
     const rdlm_model& m = ctx->m;
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
-    if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
+    if (m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !ctx->knobs.no_fold) {
         launch_fold(xin, xout, ctx->part, S, pst, gain, xn, ctx->ssq, ctx->rows_pad, m.hidden, ctx->n_tiles, T, ctx->st);
         ctx->ssq_count = fold_chunks(m.hidden);
         return true;
@@ -573,8 +693,14 @@ static bool norm_operand(rdlm_ctx* ctx, const float* xin, float* xout, int S, co
 // normalised operand (gain g1) is already in xn.  On exit it is x + the *S_out partials in part;
 // with next_gain the down projection may fold them itself and prepare the operand of the norm with
 // that gain (*next_ready).
-static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out,
-                          bool xn_ready = false, const float* next_gain = nullptr, bool* next_ready = nullptr) {
+#define PROPAGATE(call)                 \
+    do {                                \
+        int rc__ = (call);              \
+        if (rc__ != RDLM_OK) return rc__; \
+    } while (0)
+
+static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bool x_valid, int S_in, int* S_out,
+                         bool xn_ready = false, const float* next_gain = nullptr, bool* next_ready = nullptr) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
     hipStream_t st = ctx->st;
@@ -582,7 +708,7 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
     bool dn = true;
     if (!xn_ready) dn = norm_operand(ctx, x_valid ? ctx->x : nullptr, ctx->x, S_in, L.g1, ctx->xn, T);
     bool rope_done = false;
-    run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S, nullptr, false, dn, &L, &rope_done);
+    PROPAGATE(run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S, nullptr, false, dn, &L, &rope_done));
     if (!rope_done)
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
@@ -591,25 +717,27 @@ static void layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, bo
                      ctx->n_tiles, T, st);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
     bool folded = false;
-    run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded);
+    PROPAGATE(run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded));
     dn = folded ? true : norm_operand(ctx, ctx->x, ctx->x, S, L.g2, ctx->xn, T);
-    run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S, nullptr, false, dn);   // leaves silu(gate) * up in abuf
+    PROPAGATE(run_proj(ctx, PROJ_GU, ctx->xn, L.wgu, T, &S, nullptr, false, dn));   // leaves silu(gate) * up in abuf
     const FoldSpec fd = {ctx->x, ctx->x, next_gain};
     folded = false;
-    run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out, nullptr, false, false, nullptr, nullptr,
-             next_gain ? &fd : nullptr, &folded);
+    PROPAGATE(run_proj(ctx, PROJ_D, ctx->abuf, L.wd, T, S_out, nullptr, false, false, nullptr, nullptr,
+                       next_gain ? &fd : nullptr, &folded));
     if (next_ready) *next_ready = folded;
+    return RDLM_OK;
 }
 
 // e = P(tokens): embedding gather (scaled) and the prelude layers; result in e_out rows (erow0).
 // With z_cat (bf16 path, internal e buffer): the closing pass also writes the adapter operand
 // concat(e, z) for the recurrence that follows, and the function returns true.
-static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys,
-                            const float* z_cat = nullptr) {
+static int prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, int e_which, int T, int max_keys,
+                           const float* z_cat = nullptr, bool* cat_ready = nullptr) {
+    if (cat_ready) *cat_ready = false;
     const rdlm_model& m = ctx->m;
     // the gather also writes the RoPE table of the step's rows and, on the bf16 path, the operand
     // of the first layer's norm
-    const bool prep = m.dtype == RDLM_BF16 && m.n_prelude > 0 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD");
+    const bool prep = m.dtype == RDLM_BF16 && m.n_prelude > 0 && fold_chunks(m.hidden) > 0 && !ctx->knobs.no_fold;
     launch_embed(ctx->emb_canon, m.dtype, tokens, m.emb_scale, ctx->x, m.hidden, m.vocab, ctx->rope_tab, ctx->theta,
                  m.head_dim / 2, prep ? ctx->layers[0].g1 : nullptr, prep ? ctx->xn : nullptr, ctx->ssq, ctx->rows_pad,
                  ctx->tiles, ctx->n_tiles, T, ctx->st);
@@ -617,13 +745,14 @@ static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, 
     bool ready = prep;
     if (prep) ctx->ssq_count = fold_chunks(m.hidden);
     for (int l = 0; l < m.n_prelude; ++l)
-        layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S, ready,
-                      l + 1 < m.n_prelude ? ctx->layers[l + 1].g1 : nullptr, &ready);
+        PROPAGATE(layer_forward(ctx, ctx->layers[l], T, max_keys, true, S, &S, ready,
+                                l + 1 < m.n_prelude ? ctx->layers[l + 1].g1 : nullptr, &ready));
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
-    if (z_cat && e_which < 0 && m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !getenv("RDLM_NO_FOLD")) {
+    if (z_cat && e_which < 0 && m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !ctx->knobs.no_fold) {
         launch_prelude_end(ctx->x, ctx->part, S, pst, e_out, z_cat, ctx->abuf, m.hidden, ctx->tiles, ctx->n_tiles, T,
                            ctx->st);
-        return true;
+        if (cat_ready) *cat_ready = true;
+        return RDLM_OK;
     }
     // fold the pending partial sums: x <- x + sum part (no norm output needed)
     launch_addnorm(ctx->x, ctx->x, ctx->part, S, pst, ctx->gf, nullptr, ctx->fmt, m.hidden, m.rms_eps, ctx->n_tiles, T,
@@ -634,41 +763,42 @@ static bool prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, 
         else
             launch_copy_rows_out(ctx->x, e_out, m.hidden, e_which, ctx->tiles, ctx->n_tiles, T, ctx->st);
     }
-    return false;
+    return RDLM_OK;
 }
 
 // z <- R(z, e): adapter on concat(e, z), the core layers, closing norm; optional delta vs z_prev.
 // cat_ready: the adapter operand was already written (by the prelude's closing pass); x_for_coda:
 // also leave z' in the residual buffer, where the coda starts from.
-static void core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev, int update_prev, float* delta,
-                         int T, int max_keys, bool cat_ready = false, bool x_for_coda = false) {
+static int core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev, int update_prev, float* delta,
+                        int T, int max_keys, bool cat_ready = false, bool x_for_coda = false) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
     if (!cat_ready) launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
     int S;
     const FoldSpec fa = {nullptr, ctx->x, ctx->layers[m.n_prelude].g1};
     bool ready = false;
-    run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S, nullptr, false, false, nullptr, nullptr, &fa, &ready);
+    PROPAGATE(run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S, nullptr, false, false, nullptr, nullptr, &fa, &ready));
     bool x_valid = ready;
     for (int l = 0; l < m.n_core; ++l) {
-        layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S, ready,
-                      l + 1 < m.n_core ? ctx->layers[m.n_prelude + l + 1].g1 : nullptr, &ready);
+        PROPAGATE(layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S, ready,
+                                l + 1 < m.n_core ? ctx->layers[m.n_prelude + l + 1].g1 : nullptr, &ready));
         x_valid = true;
     }
     // before the coda: also leave z' in the residual buffer and, on the bf16 path, the operand of the
     // coda's first norm with the row totals of z'^2
-    const bool prep = x_for_coda && m.dtype == RDLM_BF16 && m.n_coda > 0 && !getenv("RDLM_NO_FOLD");
+    const bool prep = x_for_coda && m.dtype == RDLM_BF16 && m.n_coda > 0 && !ctx->knobs.no_fold;
     launch_final_norm(ctx->x, ctx->part, S, (size_t)ctx->rows_pad * h, ctx->gf, h, m.rms_eps, z, z_prev, update_prev,
                       delta, x_for_coda ? ctx->x : nullptr, prep ? ctx->layers[m.n_prelude + m.n_core].g1 : nullptr,
                       prep ? ctx->xn : nullptr, ctx->ssq + (size_t)SSQ_MAX_CHUNKS * ctx->rows_pad, ctx->tiles,
                       ctx->n_tiles, T, ctx->st);
     if (prep) ctx->ssq_count = 0;
     ctx->coda_ready = prep;
+    return RDLM_OK;
 }
 
 // C: coda layers on z; with sa: final norm, tied LM head and Sample -> ctx->drafts (+ logits).
-static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int T, int max_keys,
-                         bool x_ready = false) {
+static int coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int T, int max_keys,
+                        bool x_ready = false) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
     if (!x_ready) launch_copy_rows_in(z, ctx->x, h, 0, ctx->tiles, ctx->n_tiles, T, ctx->st);
@@ -677,11 +807,11 @@ static void coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, in
     ctx->coda_ready = false;
     const int l0 = m.n_prelude + m.n_core;
     for (int l = 0; l < m.n_coda; ++l)
-        layer_forward(ctx, ctx->layers[l0 + l], T, max_keys, true, S, &S, ready,
-                      l + 1 < m.n_coda ? ctx->layers[l0 + l + 1].g1 : (sa ? ctx->gout : nullptr), &ready);
-    if (!sa) return;
+        PROPAGATE(layer_forward(ctx, ctx->layers[l0 + l], T, max_keys, true, S, &S, ready,
+                                l + 1 < m.n_coda ? ctx->layers[l0 + l + 1].g1 : (sa ? ctx->gout : nullptr), &ready));
+    if (!sa) return RDLM_OK;
     bool dn = ready ? true : norm_operand(ctx, ctx->x, nullptr, S, ctx->gout, ctx->xn, T);
-    run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa, false, dn);
+    return run_proj(ctx, PROJ_HEAD, ctx->xn, ctx->emb_w, T, nullptr, sa, false, dn);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -743,9 +873,9 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
                            (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
-    prelude_forward(ctx, ctx->y, ctx->e, -1, T, n);
-    for (int i = 0; i < r; ++i) core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n);
-    coda_forward(ctx, ctx->z_store, nullptr, T, n);
+    PROPAGATE(prelude_forward(ctx, ctx->y, ctx->e, -1, T, n));
+    for (int i = 0; i < r; ++i) PROPAGATE(core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n));
+    PROPAGATE(coda_forward(ctx, ctx->z_store, nullptr, T, n));
     return check_launch(ctx);
 }
 
@@ -765,7 +895,23 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
-    prelude_forward(ctx, tokens_dev, e_out, 1, T, mk);
+    PROPAGATE(prelude_forward(ctx, tokens_dev, e_out, 1, T, mk));
+    return check_launch(ctx);
+}
+
+// the body of rdlm_core_step over whatever workspace the context currently points at
+static int core_step_run(rdlm_ctx* ctx, const SeqWindows& w, int T, int M, int mk, const float* e, float* z_inout,
+                         int r_inner, float* delta_out) {
+    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    if (delta_out)
+        HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
+    for (int i = 0; i < r_inner; ++i) {
+        bool last = i == r_inner - 1;
+        PROPAGATE(core_forward(ctx, e, z_inout, (last && delta_out) ? ctx->zp_api : nullptr, 0,
+                               (last && delta_out) ? ctx->delta : nullptr, T, mk));
+    }
+    if (delta_out) launch_copy_rows_out(ctx->delta, delta_out, 1, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     return check_launch(ctx);
 }
 
@@ -777,17 +923,7 @@ extern "C" int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_
     if (!e || !z_inout || r_inner < 1) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
-    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
-    launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
-    if (delta_out)
-        HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
-    for (int i = 0; i < r_inner; ++i) {
-        bool last = i == r_inner - 1;
-        core_forward(ctx, e, z_inout, (last && delta_out) ? ctx->zp_api : nullptr, 0,
-                     (last && delta_out) ? ctx->delta : nullptr, T, mk);
-    }
-    if (delta_out) launch_copy_rows_out(ctx->delta, delta_out, 1, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
-    return check_launch(ctx);
+    return core_step_run(ctx, w, T, M, mk, e, z_inout, r_inner, delta_out);
 }
 
 extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
@@ -802,7 +938,7 @@ extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* se
     launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr, nullptr, top_p};
-    coda_forward(ctx, z, &sa, T, mk);
+    PROPAGATE(coda_forward(ctx, z, &sa, T, mk));
     launch_copy_i32_out(ctx->drafts, tokens_out, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (logits_out) launch_copy_rows_out(ctx->logits, logits_out, ctx->m.vocab, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     return check_launch(ctx);
@@ -844,7 +980,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     launch_fill_i32(ctx->seq_step0, 0, ctx->max_seqs, ctx->st);
     HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * ctx->max_seqs, hipMemcpyHostToDevice));
     launch_build_tiles_sampler(ctx->seqs, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
-    int32_t act[2] = {n_seqs, 0};
+    int32_t act[3] = {n_seqs, 0, 0};
     HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
     ctx->sampler = sp;
     ctx->sp.n_new = sp.n_new; ctx->sp.r_inner = sp.r_inner; ctx->sp.r_total = sp.r_total; ctx->sp.w_max = sp.w_max;
@@ -906,7 +1042,8 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     std::swap(ctx->n_tiles, ctx->n_tiles_samp);
     // e <- P(y_current); without momentum or noise the closing pass of P also writes concat(e, z)
     const bool plain = !(s.eta > 0.f) && !(s.beta > 0.f);
-    bool cat_ready = prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys, plain ? ctx->z_store : nullptr);
+    bool cat_ready = false;
+    int rc = prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys, plain ? ctx->z_store : nullptr, &cat_ready);
     if (s.eta > 0.f)                                                             // Eq. 1
         launch_momentum(ctx->e, ctx->e_store, ctx->counts, s.eta, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (s.beta > 0.f)                                                            // Eq. 2
@@ -915,11 +1052,20 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
                          ctx->st);
     for (int i = 0; i < s.r_inner; ++i) {                                        // inner recurrence
         bool last = i == s.r_inner - 1;
-        core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
-                     last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
+        if (rc == RDLM_OK)
+            rc = core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
+                              last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
     }
     SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false, ctx->seq_step0, s.top_p};
-    coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);                     // p <- C(z); y_hat <- Sample(p)
+    if (rc == RDLM_OK) rc = coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);   // p <- C(z); y_hat <- Sample(p)
+    if (rc != RDLM_OK) {
+        // a projection could not be launched (no kernel instance for a launch shape set through
+        // rdlm_set_tuning): part of the step has run, so the sampler cannot go on from here
+        std::swap(ctx->tiles, ctx->tiles_samp);
+        std::swap(ctx->n_tiles, ctx->n_tiles_samp);
+        ctx->sampler_on = false;
+        return rc;
+    }
     // freeze, append, InitState of the appended positions, tile list of the next step
     launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
                     ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->step_ticket,
@@ -934,30 +1080,45 @@ extern "C" int rdlm_generate(rdlm_ctx* ctx, int32_t max_steps, int32_t* steps_ou
     if (!ctx->sampler_on) return RDLM_ESTATE;
     const rdlm_sampler& s = ctx->sampler;
     const int wave = (s.r_total + s.r_inner - 1) / s.r_inner;
+    const int step0 = ctx->step;                 // sampler steps taken before this call
     // fixed exit: the step count is known; adaptive: look at the device every few steps
-    int next_poll = s.adaptive ? 8 : wave + (s.n_new - 1 + s.headway - 1) / s.headway;
+    int next_poll = s.adaptive ? 8 : std::max(1, wave + (s.n_new - 1 + s.headway - 1) / s.headway - step0);
     int done_steps = 0;
+    bool nonfinite = false;
     for (int i = 1; i <= max_steps; ++i) {
         int rc = rdlm_sample_step(ctx);
         if (rc) return rc;
         done_steps = i;
         if (i >= next_poll || i == max_steps) {
-            HIPCHK(hipMemcpyAsync(ctx->n_active_host, ctx->n_active, 8, hipMemcpyDeviceToHost, ctx->st));
+            HIPCHK(hipMemcpyAsync(ctx->n_active_host, ctx->n_active, 12, hipMemcpyDeviceToHost, ctx->st));
             HIPCHK(hipStreamSynchronize(ctx->st));
+            nonfinite = ctx->n_active_host[2] != 0;
             if (ctx->n_active_host[0] == 0) {            // steps after the finishing one were no-ops
-                done_steps = ctx->n_active_host[1];
+                done_steps = std::max(0, ctx->n_active_host[1] - step0);
                 break;
             }
+            if (nonfinite) break;
             next_poll = i + (s.adaptive ? 8 : 1);
         }
     }
     HIPCHK(hipStreamSynchronize(ctx->st));
     if (steps_out) *steps_out = done_steps;
-    return RDLM_OK;
+    return nonfinite ? RDLM_ENUMERIC : RDLM_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
 // read-back
+
+extern "C" int rdlm_sampler_status(rdlm_ctx* ctx, int32_t* n_active_out, int32_t* nonfinite_out) {
+    if (!ctx) return RDLM_EINVAL;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    int32_t a[3] = {0, 0, 0};
+    HIPCHK(hipMemcpy(a, ctx->n_active, sizeof a, hipMemcpyDeviceToHost));
+    if (n_active_out) *n_active_out = a[0];
+    if (nonfinite_out) *nonfinite_out = a[2] != 0;
+    return RDLM_OK;
+}
 
 extern "C" int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap,
                                 int32_t* n_frozen_out) {

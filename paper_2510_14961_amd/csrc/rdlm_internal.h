@@ -119,6 +119,32 @@ __host__ __device__ inline float u24_open(uint32_t x) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Arrival ticket of a workgroup at a hand-over point: data that another workgroup will read has
+// been written with system-scope (write-through) stores; the workgroup then draws a ticket from a
+// system-scope counter, and whoever draws the last one reads the others' data back with
+// system-scope (cache-bypassing) loads.  Ordering, hardware side: s_waitcnt(0) holds every wave
+// until its stores have been acknowledged by memory, and the barrier holds thread 0's atomic until
+// every wave got there.  Compiler side: __syncthreads() carries workgroup-scope release and acquire
+// fences, which no store before it may sink below and no load after it may rise above, and the two
+// single-thread fences pin the wait itself between the stores and the barrier.  (A device-scope
+// release on the atomic would order the same accesses by the memory model's letter, but on this
+// multi-die part it is an L2 write-back per workgroup -- tens of microseconds per launch.)
+// Must be called by every thread of the workgroup.  The caller resets the counter to zero.
+#ifdef __HIPCC__
+__device__ __forceinline__ uint32_t draw_ticket(uint32_t* counter, uint32_t* shared_slot) {
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __builtin_amdgcn_s_waitcnt(0);
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    __syncthreads();
+    if (threadIdx.x == 0)
+        *shared_slot = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+    return *shared_slot;
+}
+#endif
+
+// ---------------------------------------------------------------------------------------------
 // Launchers (defined in the kernel sources).  All enqueue on `st`; none synchronises.
 
 // kind GEMM_STREAM: the waves of a workgroup split K (one row-tile group, weights streamed once);

@@ -26,6 +26,45 @@ def tol_latent(shape) -> float:
     return 1e-4 if shape.dtype == "f32" else 2e-2
 
 
+def assert_rows_close(got, ref, tol, what=""):
+    """Row-wise comparison of a [n, width] result with the oracle's: the whole matrix and every single
+    row within the rel-L2 bound, and no single element further off than 10 x tol x rms(ref) -- one
+    wrong element of ordinary size (1 rms) in an otherwise exact matrix fails the last bound, which
+    a norm over the matrix would not notice.  Returns (worst row rel-L2, worst element / rms)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.all(np.isfinite(got)), what
+    whole = rel_l2(got, ref)
+    rows = max(rel_l2(got[i], ref[i]) for i in range(got.shape[0]))
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    worst = float(np.max(np.abs(got - ref))) / max(rms, 1e-300)
+    assert whole < tol, (what, "whole matrix", whole)
+    assert rows < tol, (what, "worst row", rows)
+    assert worst < 10 * tol, (what, "worst element / rms", worst)
+    return rows, worst
+
+
+# Token tolerance tau (score units) of the tie-aware check, per shape family: four times the largest
+# logit error measured once for that family on MI355X (bf16 operands, float32 accumulation), as
+# constants -- not derived from the run under test.  Logit standard deviation: 0.02 sqrt(h) (unit-RMS
+# final hidden state against N(0, 0.02) embedding rows).
+#   small bf16 test shapes (h 160..288, vocab <= 512): measured max |logit error| 0.012
+#   workload 2 shape (h 1024, vocab 32768):             measured 0.05
+#   3.5B shape (h 5280, vocab 65536):                   measured 0.17 behind a prefix cache each side
+#                                                       filled itself, 0.12 teacher-forced
+TAU_SMALL_BF16 = 0.05
+TAU_MID_BF16 = 0.2
+TAU_BIG_BF16 = 0.7
+TAU_F32 = 1e-4
+
+
+def tau_for(shape) -> float:
+    if shape.dtype == "f32":
+        return TAU_F32
+    return TAU_SMALL_BF16 if shape.hidden < 1024 else TAU_MID_BF16 if shape.hidden < 4096 else TAU_BIG_BF16
+
+
 def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_jitter=0.1, emb_mul=1.0):
     """(Context on the GPU, oracle model, numpy weights) from one weight draw."""
     import torch
@@ -103,14 +142,13 @@ def teacher_forced_sampler_run(ctx, m, shape, prompt, r, n_new, seed, tol, max_p
         z_ref = m.core(e, z_before, pos, cache)
         logits = m.coda(z_ref, pos, cache)
         z_gpu = ctx.read_states(0, win_pos0, win_n)
-        err = rel_l2(z_gpu, z_ref)
-        assert err < tol, (t, err)
+        assert_rows_close(z_gpu, z_ref, tol, f"step {t}")
         d_gpu = ctx.read_deltas(0)
         assert len(d_gpu) == win_n
         d_ref = O.delta(z_ref, z_before)
         assert np.max(np.abs(d_gpu - d_ref)) < 4 * tol, t
         y_after, nf = ctx.read_tokens(0)
-        ex, ti = tie_aware_token_check(y_after[pos + 1], logits, tau=0.05 * float(np.std(logits)) + 1e-3)
+        ex, ti = tie_aware_token_check(y_after[pos + 1], logits, tau=tau_for(shape))
         total_exact += ex
         total_ties += ti
         k = 1 if t >= r else 0                      # the oldest state has had r recurrences

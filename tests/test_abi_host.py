@@ -80,3 +80,38 @@ def test_null_context_is_an_error_not_a_crash(lib):
     assert lib.rdlm_destroy(None) == -1
     assert lib.rdlm_strerror(-2).decode().startswith("exceeds")
     assert lib.rdlm_strerror(0).decode() == "ok"
+
+
+def test_new_status_code_has_a_message(lib):
+    assert "non-finite" in lib.rdlm_strerror(R.STATUS["ENUMERIC"]).decode()
+
+
+def test_workspace_bytes_is_a_host_side_size_query(lib):
+    m = _model()
+    small = lib.rdlm_workspace_bytes(C.byref(m), 1, 32)
+    big = lib.rdlm_workspace_bytes(C.byref(m), 1, 64)
+    assert 0 < small < big
+    assert small % 256 == 0
+    # the slab holds at least the logits of every padded row (2 row tiles for 1 sequence x 32 rows)
+    assert small >= 2 * 32 * 256 * 4
+    assert lib.rdlm_workspace_bytes(C.byref(_model(hidden=130)), 1, 32) == 0
+    assert lib.rdlm_workspace_bytes(C.byref(m), 0, 32) == 0
+    assert lib.rdlm_workspace_bytes(None, 1, 32) == 0
+
+
+def test_create_ws_rejects_a_bad_workspace_before_touching_the_device(lib):
+    m = _model()
+    n = lib.rdlm_num_weights(C.byref(m))
+    ptrs = (C.c_void_p * n)(*([1] * n))
+    out = C.c_void_p()
+    need = lib.rdlm_workspace_bytes(C.byref(m), 1, 32)
+    # misaligned
+    assert lib.rdlm_create_ws(C.byref(m), ptrs, 1, 64, 32, None, C.c_void_p(0x1001), need, C.byref(out)) == -1
+    # too small
+    assert lib.rdlm_create_ws(C.byref(m), ptrs, 1, 64, 32, None, C.c_void_p(0x1000), need - 1, C.byref(out)) == -2
+    assert not out.value
+
+
+def test_entry_points_added_later_refuse_a_null_context(lib):
+    assert lib.rdlm_set_tuning(None, b"no_fold", b"1") == -1
+    assert lib.rdlm_sampler_status(None, None, None) == -1

@@ -11,8 +11,8 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import (top_p_token_check, SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, make_pair, rel_l2,
-                      teacher_forced_sampler_run, tie_aware_token_check, tol_latent)
+from gpu_util import (top_p_token_check, SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, assert_rows_close, make_pair,
+                      rel_l2, tau_for, teacher_forced_sampler_run, tie_aware_token_check, tol_latent)
 
 pytestmark = pytest.mark.gpu
 
@@ -93,12 +93,14 @@ def test_prefill_fills_every_cache_like_the_oracle(shape):
     cache = m.new_cache(128)
     s_ref = m.prefill(prompt[:n], r, 1.0, 11, 0, cache)
     tol = tol_latent(shape)
-    assert rel_l2(ctx.read_states(0, 0, n), s_ref) < tol
+    worst = [assert_rows_close(ctx.read_states(0, 0, n), s_ref, tol, "latents")]
     names = m.P_layers + m.R_layers + m.C_layers
     for li, name in enumerate(names):
         k, v = ctx.read_kv(li, 0, 0, n)
-        assert rel_l2(k, cache.k[name][:n]) < tol, name
-        assert rel_l2(v, cache.v[name][:n]) < tol, name
+        worst.append(assert_rows_close(k.reshape(n, -1), cache.k[name][:n].reshape(n, -1), tol, name + " K"))
+        worst.append(assert_rows_close(v.reshape(n, -1), cache.v[name][:n].reshape(n, -1), tol, name + " V"))
+    print(f"[prefill {shape.dtype} h={shape.hidden}] worst row rel-L2 {max(w[0] for w in worst):.2e}, "
+          f"worst element/rms {max(w[1] for w in worst):.2e}", flush=True)
     ctx.close()
 
 
@@ -120,7 +122,7 @@ def test_single_step_blocks_teacher_forced(shape):
     e_ref = m.prelude(tokens[L:], pos, cache)
     e = torch.zeros(n, shape.hidden, device="cuda")
     ctx.prelude([0], [L], [n], _dev(tokens[L:].astype(np.int32)), e)
-    assert rel_l2(e.cpu().numpy(), e_ref) < tol
+    assert_rows_close(e.cpu().numpy(), e_ref, tol, "e")
     # R x 2 with delta
     z0 = np.stack([O.init_state(shape.hidden, p, 0, 1.0, 5) for p in pos])
     z1 = m.core(e_ref, z0, pos, cache)
@@ -128,7 +130,7 @@ def test_single_step_blocks_teacher_forced(shape):
     z = _dev(z0.astype(np.float32))
     d = torch.zeros(n, device="cuda")
     ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z, 2, d)
-    assert rel_l2(z.cpu().numpy(), z2) < tol
+    assert_rows_close(z.cpu().numpy(), z2, tol, "z after two recurrences")
     d_ref = O.delta(z2, z0)
     assert np.max(np.abs(d.cpu().numpy() - d_ref)) < 4 * tol
     # C + Sample, greedy and with Gumbel noise
@@ -138,14 +140,17 @@ def test_single_step_blocks_teacher_forced(shape):
         lg = torch.zeros(n, shape.vocab, device="cuda")
         ctx.coda_decode([0], [L], [n], _dev(z2.astype(np.float32)), temp, 77, step, tok, lg)
         got = lg.cpu().numpy()
-        assert rel_l2(got, logits_ref) < tol
+        assert_rows_close(got, logits_ref, tol, "logits")
         err = float(np.max(np.abs(got - logits_ref)))
         scores = logits_ref if temp == 0.0 else np.stack(
             [logits_ref[i] / temp + O.gumbel_noise(shape.vocab, int(pos[i]), 0, step, 77) for i in range(n)])
-        exact, ties = tie_aware_token_check(tok.cpu().numpy(), scores, tau=4 * err + 1e-6)
+        exact, ties = tie_aware_token_check(tok.cpu().numpy(), scores, tau=tau_for(shape))
+        print(f"[single step {shape.dtype} h={shape.hidden} T={temp}] max logit error {err:.3g}, tokens exact "
+              f"{exact}/{n}, near-ties {ties}", flush=True)
+        assert 4 * err <= tau_for(shape)                     # the constant still is four times the error
         if shape.dtype == "f32":
             assert ties == 0
-        assert exact >= n // 2
+        assert exact >= n - 3
     # Sample with a top-p filter: a wide and a narrow nucleus, judged on the GPU's own logits
     for temp, top_p, step in ((1.0, 0.9, 3), (0.5, 0.3, 4), (0.2, 0.95, 5)):
         tok = torch.zeros(n, dtype=torch.int32, device="cuda")
@@ -512,7 +517,8 @@ def test_bf16_sampler_steps_teacher_forced(shape):
     prompt = S.make_prompt(shape.vocab, 24, 6)
     exact, ties = teacher_forced_sampler_run(ctx, m, shape, prompt, r=6, n_new=10, seed=2, tol=tol_latent(shape),
                                              max_positions=128)
-    assert exact >= 0.8 * (exact + ties)
+    print(f"[teacher-forced {shape.head_dim}] drafted tokens exact {exact}, near-ties {ties}", flush=True)
+    assert exact >= 0.9 * (exact + ties)
     ctx.close()
 
 

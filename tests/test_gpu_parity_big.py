@@ -12,7 +12,8 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import rel_l2, teacher_forced_sampler_run, tie_aware_token_check, top_p_token_check
+from gpu_util import (TAU_BIG_BF16, assert_rows_close, rel_l2, teacher_forced_sampler_run, tie_aware_token_check,
+                      top_p_token_check)
 
 pytestmark = pytest.mark.gpu
 
@@ -82,9 +83,10 @@ def test_big_shape_single_step_blocks(big_pair):
     # (8e-3 when measured without a prefix); the 2e-2 bar is for latent states.
     assert rel_l2(got_lg, logits_ref) < 2 * tol
     err = float(np.max(np.abs(got_lg - logits_ref)))
-    exact, ties = tie_aware_token_check(tok.cpu().numpy(), logits_ref, tau=4 * err + 1e-6)
+    exact, ties = tie_aware_token_check(tok.cpu().numpy(), logits_ref, tau=TAU_BIG_BF16)
     print(f"[big] logits max abs err {err:.4f}, tokens exact {exact}/{n}, near-ties {ties}", flush=True)
-    assert exact >= n // 2
+    assert 4 * err <= TAU_BIG_BF16
+    assert exact >= n - 3                                   # measured 31 of 32
     # Sample with the paper's temperature 0.2 / top-p 0.95 at the full vocabulary, and a hot,
     # narrow nucleus; judged on the logits the GPU returned
     for temp, top_p, step in ((0.2, 0.95, 2), (1.5, 0.5, 3)):
@@ -101,7 +103,7 @@ def test_big_shape_sampler_steps_teacher_forced(big_pair):
     exact, ties = teacher_forced_sampler_run(ctx, m, shape, prompt, r=4, n_new=6, seed=2, tol=2e-2,
                                              max_positions=160)
     print(f"[big] sampler steps: drafted tokens exact {exact}, near-ties {ties}", flush=True)
-    assert exact >= 0.7 * (exact + ties)
+    assert exact >= 0.8 * (exact + ties)                    # measured 27 of 30
 
 
 def test_big_shape_wide_window_and_ragged_batch(big_pair):
@@ -179,7 +181,7 @@ def _run_steps(ctx, prompt, n_steps, seed=3, headway=1, n_new=100):
     return toks[: L + n_steps * headway].copy(), z
 
 
-def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_kernels(big_pair, monkeypatch):
+def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_kernels(big_pair):
     """The one-tile path folds split-K partial sums and KV-split partials inside the producing
     kernel: the last workgroup to arrive reads what the others wrote.  A read that came too
     early would see the previous launch's values, so (a) two runs of 40 full-shape steps (about
@@ -195,9 +197,9 @@ def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_k
     # the bf16 roundings that flips (measured 4e-3, the size of the path's bf16 error); one stale
     # 64-column group alone would be an error of sqrt(64 / 5280) = 0.11
     t4, z4 = _run_steps(ctx, prompt, 1)
-    monkeypatch.setenv("RDLM_NO_FOLD_FUSION", "1")
+    ctx.set_tuning("no_fold_fusion", "1")
     t3, z3 = _run_steps(ctx, prompt, 1)
-    monkeypatch.delenv("RDLM_NO_FOLD_FUSION")
+    ctx.set_tuning("no_fold_fusion", "0")
     assert np.array_equal(t4, t3)
     assert rel_l2(z4[0], z3[0]) < 2e-2
     # (c) two states appended per step: from step 17 on the window spans two row tiles (separate fold
