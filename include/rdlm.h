@@ -210,6 +210,12 @@ int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t c
                      int32_t* n_frozen_out);
 /* Latent states kept per position by the sampler (the state a position had when last updated). */
 int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host);
+/* z_prev of Alg. 2 per position: the state the position had at the end of the step before the last
+ * one that touched it (what delta_i of the last step compared against); same layout. */
+int rdlm_read_prev_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host);
+/* The in-flight window of a sequence as the next rdlm_sample_step will see it: position of its
+ * oldest state, number of states (0 once the sequence is finished), finished flag (each may be NULL). */
+int rdlm_read_window(rdlm_ctx* ctx, int32_t seq, int32_t* pos0_out, int32_t* n_out, int32_t* done_out);
 /* Sampler steps each position spent in flight (its recurrence count is this times r_inner). */
 int rdlm_read_counts(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t* counts_host);
 /* delta_i of the rows of the last sample_step, in row order of sequence seq's window at that

@@ -21,7 +21,8 @@ EXPORTED_SYMBOLS = [
     "rdlm_read_tokens", "rdlm_read_states", "rdlm_read_counts", "rdlm_read_deltas", "rdlm_read_kv",
     "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
     "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws",
-    "rdlm_sampler_status", "rdlm_set_tuning",
+    "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
+    "rdlm_read_window",
 ]
 
 STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
@@ -96,6 +97,8 @@ def load_library():
                                      C.POINTER(vp)]),
         "rdlm_sampler_status": (C.c_int, [vp, pi32, pi32]),
         "rdlm_set_tuning": (C.c_int, [vp, C.c_char_p, C.c_char_p]),
+        "rdlm_read_prev_states": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float)]),
+        "rdlm_read_window": (C.c_int, [vp, i32, pi32, pi32, pi32]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -278,6 +281,18 @@ class Context:
         self._chk(self.lib.rdlm_read_states(self.ctx, seq, pos0, n, buf.ctypes.data_as(C.POINTER(C.c_float))),
                   "rdlm_read_states")
         return buf
+
+    def read_prev_states(self, seq: int, pos0: int, n: int) -> np.ndarray:
+        buf = np.zeros((n, self.h), dtype=np.float32)
+        self._chk(self.lib.rdlm_read_prev_states(self.ctx, seq, pos0, n, buf.ctypes.data_as(C.POINTER(C.c_float))),
+                  "rdlm_read_prev_states")
+        return buf
+
+    def read_window(self, seq: int):
+        """(position of the oldest in-flight state, number of in-flight states, finished)"""
+        p, n, d = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        self._chk(self.lib.rdlm_read_window(self.ctx, seq, C.byref(p), C.byref(n), C.byref(d)), "rdlm_read_window")
+        return p.value, n.value, bool(d.value)
 
     def read_counts(self, seq: int, pos0: int, n: int) -> np.ndarray:
         buf = np.zeros(n, dtype=np.int32)

@@ -1144,6 +1144,28 @@ extern "C" int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_
     return RDLM_OK;
 }
 
+extern "C" int rdlm_read_prev_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host) {
+    if (!ctx || !z_host || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    HIPCHK(hipMemcpy(z_host, ctx->z_prev + ((size_t)seq * ctx->max_positions + pos0) * ctx->m.hidden,
+                     (size_t)n * ctx->m.hidden * 4, hipMemcpyDeviceToHost));
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_read_window(rdlm_ctx* ctx, int32_t seq, int32_t* pos0_out, int32_t* n_out, int32_t* done_out) {
+    if (!ctx || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    if (!ctx->sampler_on) return RDLM_ESTATE;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    SeqState q;
+    HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
+    if (pos0_out) *pos0_out = q.win_pos0;
+    if (n_out) *n_out = q.done ? 0 : q.win_n;
+    if (done_out) *done_out = q.done;
+    return RDLM_OK;
+}
+
 extern "C" int rdlm_read_counts(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t* counts_host) {
     if (!ctx || !counts_host || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
     if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;

@@ -49,11 +49,14 @@ def assert_rows_close(got, ref, tol, what=""):
 # logit error measured once for that family on MI355X (bf16 operands, float32 accumulation), as
 # constants -- not derived from the run under test.  Logit standard deviation: 0.02 sqrt(h) (unit-RMS
 # final hidden state against N(0, 0.02) embedding rows).
-#   small bf16 test shapes (h 160..288, vocab <= 512): measured max |logit error| 0.012
+#   small bf16 test shapes (h 160..288, vocab <= 512): measured max |logit error| 0.0024 for the coda
+#                                                       alone, about twice that through P, R and C
 #   workload 2 shape (h 1024, vocab 32768):             measured 0.05
-#   3.5B shape (h 5280, vocab 65536):                   measured 0.17 behind a prefix cache each side
-#                                                       filled itself, 0.12 teacher-forced
-TAU_SMALL_BF16 = 0.05
+#   3.5B shape (h 5280, vocab 65536):                   measured 0.167 behind a prefix cache each side
+#                                                       filled itself
+# (A legitimate near-tie has a gap of at most twice the logit error: the GPU preferred t' to the
+# oracle's best b, so oracle(b) - oracle(t') <= err(b) + err(t').)
+TAU_SMALL_BF16 = 0.02
 TAU_MID_BF16 = 0.2
 TAU_BIG_BF16 = 0.7
 TAU_F32 = 1e-4
@@ -81,6 +84,9 @@ def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_ji
     return ctx, O.RecurrentDepthLM(shape, w), w
 
 
+LAST_TIE_GAP = [0.0]     # largest gap among the near-ties the last calls accepted (reported by the tests)
+
+
 def tie_aware_token_check(gpu_tokens, oracle_scores, tau):
     """A GPU token is accepted iff the oracle's score of it is within tau of the oracle's best.
     Returns (number of exact matches, number accepted as near-ties); raises on a real mismatch."""
@@ -93,6 +99,7 @@ def tie_aware_token_check(gpu_tokens, oracle_scores, tau):
         else:
             gap = float(sc[best] - sc[int(t)])
             assert gap <= tau, f"row {i}: GPU token {int(t)} scores {gap:.4g} below the oracle's best {best} (tau {tau:.3g})"
+            LAST_TIE_GAP[0] = max(LAST_TIE_GAP[0], gap)
             ties += 1
     return exact, ties
 
