@@ -164,6 +164,24 @@ int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const 
                    const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
                    float* delta_out);
 
+/* rdlm_core_step for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same
+ * result, but every scratch buffer of the step (tile list, packed operands, split-K partial sums,
+ * fold and attention tickets, KV-split partials) lives in one file-scope device array of
+ * RDLM_STATIC_SCRATCH_BYTES bytes that each GPU the library runs on holds until the process ends;
+ * the call performs no hipMalloc / hipFree.  The caller still owns e, z_inout and delta_out; weights
+ * and the KV cache are the context's.  A call whose row tiles (sum over the windows of
+ * ceil(n_rows / 32)) need more than the array holds -- rdlm_core_step_static_bytes(ctx, tiles)
+ * tells -- is refused with RDLM_ECAPACITY and a message on stderr (3.5B shape: 2 tiles = 64 rows).
+ * All calls on one GPU share that GPU's array, whatever their context: the array keeps the last
+ * call's contents (the call clears the ticket words it needs at zero with a fill kernel, nothing
+ * else is read before it is written), and calls that overlap in time on one GPU race. */
+#define RDLM_STATIC_SCRATCH_BYTES (40u << 20)
+size_t rdlm_core_step_static_bytes(const rdlm_ctx* ctx, int32_t n_tiles);
+int rdlm_core_step_static(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                          const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
+                          float* delta_out);
+
 /* C + Sample on every given row (Alg. 1 lines 11-12): coda layers (caches overwritten), final
  * norm, tied LM head, then greedy or Gumbel-max at (seed, step), restricted to the top-p set when
  * 0 < top_p < 1 (App. "Dataset details": the paper samples at temperature 0.2, top-p 0.95).

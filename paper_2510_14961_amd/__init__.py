@@ -5,4 +5,4 @@ package only marshals arguments.  Importing the package does not load the librar
 Context does, and fails loudly if the library has not been built.
 """
 from .binding import (Context, RdlmError, load_library, library_path, weight_names,  # noqa: F401
-                      upload_weights, workspace_bytes, EXPORTED_SYMBOLS, STATUS)
+                      upload_weights, workspace_bytes, EXPORTED_SYMBOLS, STATUS, STATIC_SCRATCH_BYTES)

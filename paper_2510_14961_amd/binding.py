@@ -20,12 +20,13 @@ EXPORTED_SYMBOLS = [
     "rdlm_core_step", "rdlm_coda_decode", "rdlm_sampler_begin", "rdlm_sampler_join", "rdlm_sample_step", "rdlm_generate",
     "rdlm_read_tokens", "rdlm_read_states", "rdlm_read_counts", "rdlm_read_deltas", "rdlm_read_kv",
     "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
-    "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws",
-    "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
+    "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws", "rdlm_core_step_static",
+    "rdlm_core_step_static_bytes", "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
     "rdlm_read_window",
 ]
 
 STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
+STATIC_SCRATCH_BYTES = 40 << 20
 
 
 class RdlmError(RuntimeError):
@@ -95,6 +96,8 @@ def load_library():
         "rdlm_workspace_bytes": (C.c_size_t, [C.POINTER(_Model), i32, i32]),
         "rdlm_create_ws": (C.c_int, [C.POINTER(_Model), C.POINTER(vp), i32, i32, i32, vp, vp, C.c_size_t,
                                      C.POINTER(vp)]),
+        "rdlm_core_step_static": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, vp, i32, vp]),
+        "rdlm_core_step_static_bytes": (C.c_size_t, [vp, i32]),
         "rdlm_sampler_status": (C.c_int, [vp, pi32, pi32]),
         "rdlm_set_tuning": (C.c_int, [vp, C.c_char_p, C.c_char_p]),
         "rdlm_read_prev_states": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float)]),
@@ -233,6 +236,16 @@ class Context:
         d = C.c_void_p(delta_out.data_ptr()) if delta_out is not None else C.c_void_p()
         self._chk(self.lib.rdlm_core_step(self.ctx, len(s), _iptr(s), _iptr(p), _iptr(n), C.c_void_p(e.data_ptr()),
                                           C.c_void_p(z_inout.data_ptr()), r_inner, d), "rdlm_core_step")
+
+    def core_step_static(self, seq_ids, pos0, n_rows, e, z_inout, r_inner: int = 1, delta_out=None):
+        s, p, n = self._rows(seq_ids, pos0, n_rows)
+        d = C.c_void_p(delta_out.data_ptr()) if delta_out is not None else C.c_void_p()
+        self._chk(self.lib.rdlm_core_step_static(self.ctx, len(s), _iptr(s), _iptr(p), _iptr(n),
+                                                 C.c_void_p(e.data_ptr()), C.c_void_p(z_inout.data_ptr()), r_inner, d),
+                  "rdlm_core_step_static")
+
+    def core_step_static_bytes(self, n_tiles: int) -> int:
+        return int(self.lib.rdlm_core_step_static_bytes(self.ctx, n_tiles))
 
     def set_tuning(self, name: str, value: str):
         self._chk(self.lib.rdlm_set_tuning(self.ctx, name.encode(), str(value).encode()), "rdlm_set_tuning")

@@ -41,7 +41,8 @@ struct Knobs {
 
 // Scratch memory of a step: everything the kernels of one call write and read back, nothing that has
 // to survive the call except that the ticket words are zero between launches.  One slab, cut up by
-// carve_workspace: allocated by rdlm_create or handed in by the caller.
+// carve_workspace: the context's own (allocated by rdlm_create or handed in by the caller) or, for
+// rdlm_core_step_static, the file-scope device array below.
 struct Workspace {
     int max_tiles = 0, rows_pad = 0;
     TileDesc* tiles = nullptr;
@@ -401,6 +402,33 @@ extern "C" int rdlm_set_tuning(rdlm_ctx* ctx, const char* name, const char* valu
     return set_knob(&ctx->knobs, name, value);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Scratch for callers that cannot allocate (rdlm_core_step_static): a file-scope device array.  Its
+// name is a host-side stand-in, not a device address: the address is asked for once per device
+// (static_scratch_for) and only that pointer is ever handed to kernels or copies.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)RDLM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// address of the current device's copy of `scratch`; looked up at most once per device
+static int static_scratch_for(int* dev_out, void** ptr_out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return RDLM_EHIP;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            fprintf(stderr, "rdlm: hipGetSymbolAddress(scratch) failed on device %d: %s\n", dev, hipGetErrorString(e));
+            return RDLM_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    if (dev_out) *dev_out = dev;
+    if (ptr_out) *ptr_out = g_scratch_ptr[dev];
+    return RDLM_OK;
+}
+
 extern "C" size_t rdlm_workspace_bytes(const rdlm_model* m, int32_t max_seqs, int32_t max_rows) {
     if (!model_ok(m) || max_seqs < 1 || max_seqs > MAX_API_SEQS || max_rows < 1) return 0;
     return carve_workspace(nullptr, nullptr, *m, tiles_for(max_seqs, max_rows), 8, true);
@@ -432,7 +460,8 @@ extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptr
     ctx->fmt = m->dtype == RDLM_F32 ? ACT_F32 : ACT_BF16P;
     ctx->esz = m->dtype == RDLM_F32 ? 4 : 2;
     knobs_from_env(&ctx->knobs);
-    int rc = create_impl(ctx, weight_ptrs, workspace);
+    int rc = static_scratch_for(nullptr, nullptr);     // this device's static scratch, for rdlm_core_step_static
+    if (rc == RDLM_OK) rc = create_impl(ctx, weight_ptrs, workspace);
     if (rc != RDLM_OK) {
         for (void* p : ctx->allocs) (void)hipFree(p);
         if (ctx->n_active_host) (void)hipHostFree(ctx->n_active_host);
@@ -924,6 +953,49 @@ extern "C" int rdlm_core_step(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
     return core_step_run(ctx, w, T, M, mk, e, z_inout, r_inner, delta_out);
+}
+
+extern "C" size_t rdlm_core_step_static_bytes(const rdlm_ctx* ctx, int32_t n_tiles) {
+    if (!ctx || n_tiles < 1) return 0;
+    return carve_workspace(nullptr, nullptr, ctx->m, n_tiles, ctx->att_max_split, false);
+}
+
+extern "C" int rdlm_core_step_static(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+                                     const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
+                                     float* delta_out) {
+    if (!ctx || !e || !z_inout || r_inner < 1 || !seq_ids || !pos0 || !n_rows || n_seqs < 1) return RDLM_EINVAL;
+    if (n_seqs > MAX_API_SEQS) return RDLM_ECAPACITY;
+    // capacity is what fits the static array, not what the context was created for
+    int tiles = 0;
+    for (int i = 0; i < n_seqs; ++i) {
+        if (n_rows[i] < 1) return RDLM_EINVAL;
+        tiles += (n_rows[i] + 31) / 32;
+    }
+    const size_t need = carve_workspace(nullptr, nullptr, ctx->m, tiles, ctx->att_max_split, false);
+    if (need > STATIC_SCRATCH_BYTES) {
+        fprintf(stderr, "rdlm_core_step_static: %d row tiles of this model need %zu bytes of scratch, the static "
+                        "array holds %zu\n", tiles, need, STATIC_SCRATCH_BYTES);
+        return RDLM_ECAPACITY;
+    }
+    void* sp = nullptr;
+    int rc = static_scratch_for(nullptr, &sp);      // looked up by rdlm_create on this device; a table read here
+    if (rc) return rc;
+    // the context's workspace steps aside for the length of this call
+    const Workspace own = *ctx;
+    const int own_rows = ctx->max_rows;
+    carve_workspace(ctx, sp, ctx->m, tiles, ctx->att_max_split, false);
+    ctx->max_rows = tiles * 32;
+    SeqWindows w;
+    int T, M, mk;
+    rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
+    if (rc == RDLM_OK) {
+        // the array keeps whatever the last call (of any context) left: the ticket words must read zero
+        launch_fill_i32(reinterpret_cast<int32_t*>(ctx->ticket_lo), 0, ctx->ticket_bytes / 4, ctx->st);
+        rc = core_step_run(ctx, w, T, M, mk, e, z_inout, r_inner, delta_out);
+    }
+    static_cast<Workspace&>(*ctx) = own;
+    ctx->max_rows = own_rows;
+    return rc;
 }
 
 extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,

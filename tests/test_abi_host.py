@@ -113,5 +113,9 @@ def test_create_ws_rejects_a_bad_workspace_before_touching_the_device(lib):
 
 
 def test_entry_points_added_later_refuse_a_null_context(lib):
+    assert lib.rdlm_core_step_static(None, 1, None, None, None, None, None, 1, None) == -1
+    assert lib.rdlm_core_step_static_bytes(None, 1) == 0
     assert lib.rdlm_set_tuning(None, b"no_fold", b"1") == -1
     assert lib.rdlm_sampler_status(None, None, None) == -1
+    assert R.STATIC_SCRATCH_BYTES == int(re.search(r"RDLM_STATIC_SCRATCH_BYTES \((\d+)u << 20\)",
+                                                   open(os.path.join(ROOT, "include", "rdlm.h")).read()).group(1)) << 20
