@@ -639,3 +639,72 @@ def test_long_context_attention_splits():
     ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z, 1, None)
     assert max(rel_l2(a, b) for a, b in zip(z.cpu().numpy(), z1)) < tol
     ctx.close()
+
+
+def test_cfg2_full_length_bf16():
+    """Workload 2 at its own shape (hidden 1024, 16 heads x 64, MLP 2816, vocabulary 32768, P2/R4/C2,
+    bf16; prompt 128, r = 16, window 16, greedy, 256 new tokens).
+    (a) free-running: the GPU run and an oracle run of its own, both full length; the step and
+        position of the first token (draft or final) that differs is reported, and that token must
+        be a near-tie by the oracle's own logits of that step;
+    (b) teacher-forced: the whole GPU run again, each step recomputed by the oracle from the GPU's
+        inputs of that step: every latent row within 2e-2, every drafted token exact or a near-tie."""
+    import time
+    from gpu_util import TAU_MID_BF16
+    wl = S.WORKLOADS["cfg2"]
+    shape, sp = wl.shape, wl.sampler
+    L, N, r = wl.prompt_len, sp.n_new, sp.r
+    ctx, m, _ = make_pair(shape, seed=wl.weight_seed, gain_jitter=0.0, max_positions=L + N + r + 8, max_rows=L)
+    prompt = S.make_prompt(shape.vocab, L, wl.prompt_seed)
+    # (a) the oracle's own run, keeping per step the tokens and the five best scores of every window row
+    trace = {}
+
+    def hook(t, z_pos, zz, logits, y, e):
+        top = np.argsort(-logits, axis=1)[:, :5]
+        trace[t] = (list(z_pos), y.copy(), top, np.take_along_axis(logits, top, axis=1))
+
+    t0 = time.time()
+    ref = O.generate_diffusion_forcing(m, prompt, N, sp.r_inner, r, seed=sp.seed, hook=hook)
+    print(f"[cfg2] oracle free run: {ref.steps} steps in {time.time() - t0:.1f}s", flush=True)
+    assert ref.steps == N + r - 1
+    assert len(set(ref.tokens[L:].tolist())) > N // 4            # not a degenerate stream
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, L - 1, r, sp.alpha, sp.seed)
+    ctx.sampler_begin(1, n_new=N, r_inner=sp.r_inner, r_total=r, seed=sp.seed)
+    first = None
+    for t in range(1, ref.steps + 1):
+        ctx.sample_step()
+        y_gpu, nf = ctx.read_tokens(0)
+        z_pos, y_ref, top, top_v = trace[t]
+        hi = z_pos[-1] + 2
+        diff = np.nonzero(y_gpu[:hi] != y_ref[:hi])[0]
+        if len(diff):
+            p = int(diff[0])
+            row = p - 1 - z_pos[0]
+            assert 0 <= row < len(z_pos), (t, p, z_pos)
+            cand = top[row].tolist()
+            assert int(y_gpu[p]) in cand, (t, p, int(y_gpu[p]), cand)
+            gap = float(top_v[row][0] - top_v[row][cand.index(int(y_gpu[p]))])
+            assert gap <= TAU_MID_BF16, (t, p, gap)
+            first = (t, p, gap)
+            break
+    _, nf = ctx.read_tokens(0)
+    if first is None:
+        assert nf == L + N
+        assert np.array_equal(ctx.read_tokens(0)[0][: L + N], ref.tokens)
+        print(f"[cfg2] free-running: all {N} tokens and every draft identical to the oracle's", flush=True)
+    else:
+        print(f"[cfg2] free-running: first differing token at step {first[0]} of {ref.steps}, position {first[1]} "
+              f"(a near-tie, gap {first[2]:.4f} in the oracle's logits); {first[1] - L} generated positions "
+              f"before it identical", flush=True)
+    # (b) teacher-forced, full length
+    t0 = time.time()
+    exact, ties = teacher_forced_sampler_run(ctx, m, shape, prompt, r=r, n_new=N, seed=sp.seed, tol=tol_latent(shape),
+                                             max_positions=L + N + r + 8)
+    print(f"[cfg2] teacher-forced, {N + r - 1} steps in {time.time() - t0:.1f}s: drafted tokens exact {exact}, "
+          f"near-ties {ties} (largest accepted gap so far {LAST_TIE_GAP[0]:.3g})", flush=True)
+    assert exact + ties == sum(min(t, r) for t in range(1, N + r))       # every window row of every step
+    assert exact >= 0.97 * (exact + ties)
+    _, nf = ctx.read_tokens(0)
+    assert nf == L + N
+    ctx.close()

@@ -208,3 +208,91 @@ def test_big_shape_cross_workgroup_folds_are_repeatable_and_match_the_separate_k
     t6, z6 = _run_steps(ctx, prompt, 30, headway=2, n_new=64)
     assert np.array_equal(t5, t6)
     assert np.array_equal(z5, z6)
+
+
+# ---------------------------------------------------------------------------------------------
+# Workloads 3, 4 and 5 in the launch configurations bench.py times.  The oracle cannot run them end
+# to end, so the GPU sampler runs with the workload's own parameters up to a sampled step, and that
+# one step is recomputed by the oracle from the GPU's own inputs (gpu_util.teacher_forced_step).
+
+def _context_for(m, shape, n_seqs, max_positions, max_rows):
+    import torch
+    import paper_2510_14961_amd as R
+    dev = {}
+    for n, a in m.w.items():
+        dev.update(R.upload_weights(shape, [(n, a.astype(np.float32))]))
+    ctx = R.Context(shape, dev, n_seqs, max_positions, max_rows)
+    del dev
+    torch.cuda.empty_cache()
+    return ctx
+
+
+def _workload_steps(big_pair, name, sampled_steps, n_new=None):
+    from gpu_util import teacher_forced_step
+    shape, _, m = big_pair
+    wl = S.WORKLOADS[name]
+    sp = wl.sampler
+    assert wl.shape == shape
+    wave = -(-sp.r // sp.r_inner) * sp.headway
+    window = sp.w_max if (sp.adaptive and sp.w_max > 0) else wave
+    n_new = sp.n_new if n_new is None else n_new
+    max_positions = wl.prompt_len + n_new + window + sp.headway + 8
+    max_rows = max(wl.prompt_len, wl.n_seqs * (-(-window // 32) * 32))
+    t0 = time.time()
+    ctx = _context_for(m, shape, wl.n_seqs, max_positions, max_rows)
+    for q in range(wl.n_seqs):
+        ctx.set_tokens(q, S.make_prompt(shape.vocab, wl.prompt_len, wl.prompt_seed, seq=q))
+        ctx.prefill(q, wl.prompt_len - 1, sp.r, sp.alpha, sp.seed)
+    spec = dict(n_new=n_new, r_inner=sp.r_inner, r_total=sp.r, headway=sp.headway, alpha=sp.alpha, w_max=sp.w_max,
+                adaptive=sp.adaptive, eps=sp.eps, temperature=sp.temperature, seed=sp.seed, pad_token=sp.pad_token)
+    ctx.sampler_begin(wl.n_seqs, **spec)
+    print(f"[{name}] context + prefill of {wl.n_seqs} x {wl.prompt_len - 1} positions in {time.time() - t0:.1f}s", flush=True)
+    t, results = 0, []
+    for target in sampled_steps:
+        while t < target - 1:
+            ctx.sample_step()
+            t += 1
+        t0 = time.time()
+        t += 1
+        res = teacher_forced_step(ctx, m, shape, spec, wl.n_seqs, t, tol=2e-2, tau=TAU_BIG_BF16, label=name)
+        print(f"[{name}] step {t}: {res['rows']} rows behind up to {res['max_keys']} keys, worst row rel-L2 "
+              f"{res['worst_row']:.4f}, worst delta error {res['worst_delta']:.2e}, frozen {res['frozen']}, drafted "
+              f"tokens exact {res['exact']}, near-ties {res['ties']} (largest accepted gap so far "
+              f"{LAST_TIE_GAP[0]:.3g}); oracle step {time.time() - t0:.1f}s", flush=True)
+        results.append(res)
+    ctx.close()
+    return results
+
+
+def test_cfg3_window_32_behind_the_512_token_prompt(big_pair):
+    """Workload 3: window 32 (one row tile, the folding split-K GEMMs, the one-tile attention kernel)
+    behind 512+ cached positions; one step while the wave fills, two in steady state."""
+    res = _workload_steps(big_pair, "cfg3", [7, 33, 40])
+    assert [r["rows"] for r in res] == [7, 32, 32]
+    assert [r["frozen"] for r in res] == [0, 1, 1]
+    assert res[-1]["max_keys"] >= 512 + 32
+    total = sum(r["exact"] + r["ties"] for r in res)
+    assert sum(r["exact"] for r in res) >= 0.85 * total
+
+
+def test_cfg5_window_128_behind_the_4096_token_prompt(big_pair):
+    """Workload 5: headway 4, 128-row window (four row tiles: the row-sharing GEMMs, the grouped
+    attention kernel with eight KV splits and its merge kernel) behind 4096+ cached positions."""
+    res = _workload_steps(big_pair, "cfg5", [33, 36])
+    assert [r["rows"] for r in res] == [128, 128]
+    assert [r["frozen"] for r in res] == [4, 4]
+    assert res[-1]["max_keys"] >= 4096 + 128
+    total = sum(r["exact"] + r["ties"] for r in res)
+    assert sum(r["exact"] for r in res) >= 0.85 * total
+
+
+def test_cfg4_eight_sequences_adaptive_exit_temperature_one(big_pair):
+    """Workload 4: eight sequences behind 1024-token prompts, Alg. 2 (exit on delta_i < 1e-3, cap 64,
+    wavefront limit 64), Gumbel-max sampling at temperature 1: a ragged step while the waves fill
+    and a 512-row step (sixteen row tiles) at the cap; k* per sequence decided on the device."""
+    res = _workload_steps(big_pair, "cfg4", [9, 66], n_new=96)
+    assert res[0]["rows"] <= 8 * 9
+    assert res[1]["rows"] >= 8 * 32                      # at or near the 64-state cap in every sequence
+    assert res[1]["max_keys"] >= 1024 + 32
+    total = sum(r["exact"] + r["ties"] for r in res)
+    assert sum(r["exact"] for r in res) >= 0.85 * total
