@@ -95,6 +95,66 @@ def cpu_baseline(shape, w64, prompt_len, window, budget_s=20.0):
                       f"cache prefix filled with random values, prefill not run), {per_step:.2f} s/step, 1 token/step"}
 
 
+def machine_reference(ctx, shape):
+    """What the machine does beside the kernels: a plain streaming read of the gate/up weights in the
+    dominant kernel's own launch shape (and a wider one), and the matrix instruction from registers."""
+    names = __import__("paper_2510_14961_amd").weight_names(shape)
+    gu = names.index("R0.wg")
+    out = {}
+    best = 0.0
+    for wgs, waves in ((224, 4), (256, 4), (512, 4), (1024, 4)):
+        ms, nbytes = ctx.time_stream_read(gu, wgs, waves, 40)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[f"stream_read_{wgs}x{waves}_GBps"] = gbs
+        best = max(best, gbs)
+    out["hbm_stream_GBps"] = best
+    ms, fl = ctx.time_mfma_loop(1024, 20000, 1)            # a short burst: the clock has not dropped yet
+    out["mfma_bf16_burst_TFLOPs"] = fl / (ms * 1e-3) / 1e12
+    ms, fl = ctx.time_mfma_loop(1024, 20000, 40)           # about a third of a second: the sustained clock
+    out["mfma_bf16_sustained_TFLOPs"] = fl / (ms * 1e-3) / 1e12
+    out["note"] = ("plain nontemporal streaming read of one layer's packed gate/up weights (layers in turn), "
+                   "workgroups x waves as named; v_mfma_f32_32x32x16_bf16 from registers, 1024 workgroups x 4 waves x "
+                   "4 accumulators")
+    return out
+
+
+def core_sweep(args):
+    """Core step (adapter + core layers + closing norm, r' = 1) over window rows x cached context."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape = S.BIG
+    rows_grid = [1, 4, 16, 32, 64, 128, 256, 512, 1024, 2048, 4095]
+    ctx_grid = [0, 512, 4096]
+    dev, _ = build_weights(shape, 1, False, args.threads)
+    ctx = R.Context(shape, dev, 1, max(ctx_grid) + max(rows_grid) + 1, max(rows_grid))
+    del dev
+    torch.cuda.empty_cache()
+    h, F = shape.hidden, shape.mlp
+    core_params = shape.n_core * (4 * h * h + 3 * h * F) + 2 * h * h
+    table = []
+    for c in ctx_grid:
+        for rows in rows_grid:
+            iters = 20 if rows <= 256 else 5 if rows <= 1024 else 3
+            ms = ctx.time_core_step(0, c, rows, iters)
+            kv = shape.n_core * 2 * (c + rows) * h * 2
+            table.append({"rows": rows, "context": c, "ms": ms,
+                          "weight_GBps": core_params * 2 / (ms * 1e-3) / 1e9,
+                          "kv_bytes": kv, "TFLOPs": 2.0 * core_params * rows / (ms * 1e-3) / 1e12})
+            log(f"[sweep] rows {rows:5d} context {c:5d}: {ms:8.3f} ms")
+    ref = machine_reference(ctx, shape)
+    # ridge: the flat (weight-streaming) time of the narrow windows against the slope of the wide ones
+    ridge = {}
+    for c in ctx_grid:
+        t = {r["rows"]: r["ms"] for r in table if r["context"] == c}
+        flat = min(t[1], t[4], t[16], t[32])
+        slope = (t[4095] - t[1024]) / (4095 - 1024)
+        ridge[str(c)] = {"flat_ms": flat, "ms_per_row_wide": slope, "ridge_rows": flat / slope}
+    print(json.dumps({"core_step_sweep": table, "ridge": ridge, "machine": ref,
+                      "model_ridge_rows": MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9),
+                      "shape": "3.5B: 5280 x 55 x 96, mlp 17920, 4 core layers + adapter, bf16"}), flush=True)
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +174,10 @@ def main():
                     help="rows of the large-window core step timed against the MFMA peak (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
+    ap.add_argument("--core-sweep", action="store_true",
+                    help="instead of the benchmark: time one core step (r' = 1) at the 3.5B shape over a grid of window "
+                         "rows x cached context, print the table and the measured ridge (rows at which the step "
+                         "turns from weight-streaming bound to matrix-core bound) as JSON")
     ap.add_argument("--threads", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -125,6 +189,9 @@ def main():
     import paper_2510_14961_amd as R
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.core_sweep:
+        core_sweep(args)
+        return
     wl = S.WORKLOADS[args.workload]
     shape, sp = wl.shape, wl.sampler
     if args.headway > 0:
@@ -219,6 +286,7 @@ def main():
         except Exception:
             traffic = None
     core_ms = ctx.time_core_step(0, wl.prompt_len, min(window, max_rows), 20)
+    machine = machine_reference(ctx, shape) if shape.dtype == "bf16" and shape.hidden >= 2048 else None
     h, F, V = shape.hidden, shape.mlp, shape.vocab
     layer_b = (4 * h * h + 3 * h * F) * 2
     core_bytes = shape.n_core * layer_b + 2 * h * h * 2
@@ -305,6 +373,8 @@ def main():
                    "context_at_end": int(nf2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "achievable": machine["hbm_stream_GBps"] if machine else None,
+                     "frac_of_achievable": achieved / machine["hbm_stream_GBps"] if machine else None,
                      "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier "
                                        "run of this command, scaled by a 1 GiB copy; not measured by this run)"
                                        if traffic is not None else None,
@@ -314,6 +384,7 @@ def main():
         "whole_step": {"weight_bytes": step_bytes, "GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                        "frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "core_step": {"ms": core_ms, "weight_bytes": core_bytes, "GBps": core_bytes / (core_ms * 1e-3) / 1e9},
+        "machine_reference": machine,
         "autoregressive_same_path": ar,
         "adaptive_autoregressive_same_path": ada,
         "paper_default_settings": pd,

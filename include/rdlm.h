@@ -247,8 +247,9 @@ int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_
 /* ---- kernel-level entry points (measurement and unit tests) ------------------------------- */
 /* Tuning knobs of a context (launch shapes, fusion switches); the same names in upper case with
  * the prefix RDLM_ are read from the environment once, by rdlm_create.  Names: "att_split" (forced
- * number of KV splits, 0 = automatic), "no_rope_fusion", "no_fold_fusion", "no_fold" ("1" / "0"),
- * "plan_<p>" = "nb,waves,unroll,ksplit" and "planr_<p>" = "[s]mt,nb,waves,unroll,ksplit" with <p> in
+ * number of KV splits, 0 = automatic), "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm"
+ * ("1" / "0"), "plan_<p>" = "nb,waves,unroll,ksplit" and "planr_<p>" = "[s]mt,nb,waves,unroll,ksplit" or
+ * "l<blocks>,<row tiles per wave>,<waves>,<k tiles per stage>,<ring depth>,<ksplit>" with <p> in
  * qkv, o, gu, d, a, head ("" = default).  A launch shape without a kernel instance makes the calls
  * that would use it return RDLM_EINVAL (and ends a running sampler: part of the step has run). */
 int rdlm_set_tuning(rdlm_ctx* ctx, const char* name, const char* value);
@@ -265,6 +266,19 @@ int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m, int32_t iters, f
  * the cache content at those positions is overwritten.  Synchronises. */
 int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_t iters,
                         float* ms_out);
+
+/* The machine beside the kernels ("achievable" next to the published peaks):
+ * rdlm_time_stream_read -- a plain streaming read (nontemporal 16-byte loads, `workgroups` x `waves`
+ *   waves, waves <= 4, one contiguous slice each) over the packed weights of projection w_index,
+ *   going round the layers like rdlm_time_linear; average ms per launch and the bytes one launch
+ *   reads.  bf16 models only.
+ * rdlm_time_mfma_loop -- `workgroups` x 4 waves, each `inner_iters` rounds of four independent
+ *   v_mfma_f32_32x32x16_bf16 on registers; average ms per launch and the flops of one launch.
+ * Both synchronise. */
+int rdlm_time_stream_read(rdlm_ctx* ctx, int32_t w_index, int32_t workgroups, int32_t waves, int32_t iters,
+                          float* ms_out, size_t* bytes_out);
+int rdlm_time_mfma_loop(rdlm_ctx* ctx, int32_t workgroups, int32_t inner_iters, int32_t launches, float* ms_out,
+                        double* flops_out);
 
 /* Per-launch timing of one GEMM shape inside the model path: while enabled, every launch of the
  * projection with n_out output and k_in input features (e.g. 2*mlp x hidden = gate/up) is

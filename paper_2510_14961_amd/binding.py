@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "rdlm_linear", "rdlm_time_linear", "rdlm_time_core_step", "rdlm_profile_gemm_begin",
     "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws", "rdlm_core_step_static",
     "rdlm_core_step_static_bytes", "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
-    "rdlm_read_window",
+    "rdlm_read_window", "rdlm_time_stream_read", "rdlm_time_mfma_loop",
 ]
 
 STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
@@ -102,6 +102,8 @@ def load_library():
         "rdlm_set_tuning": (C.c_int, [vp, C.c_char_p, C.c_char_p]),
         "rdlm_read_prev_states": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float)]),
         "rdlm_read_window": (C.c_int, [vp, i32, pi32, pi32, pi32]),
+        "rdlm_time_stream_read": (C.c_int, [vp, i32, i32, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_size_t)]),
+        "rdlm_time_mfma_loop": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_double)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -341,6 +343,20 @@ class Context:
         ms = C.c_float(0)
         self._chk(self.lib.rdlm_time_core_step(self.ctx, seq, pos0, n, iters, C.byref(ms)), "rdlm_time_core_step")
         return ms.value
+
+    def time_stream_read(self, w_index: int, workgroups: int, waves: int, iters: int):
+        """(ms per launch, bytes read per launch)"""
+        ms, nb = C.c_float(0), C.c_size_t(0)
+        self._chk(self.lib.rdlm_time_stream_read(self.ctx, w_index, workgroups, waves, iters, C.byref(ms), C.byref(nb)),
+                  "rdlm_time_stream_read")
+        return ms.value, nb.value
+
+    def time_mfma_loop(self, workgroups: int, inner_iters: int, launches: int):
+        """(ms per launch, flops per launch)"""
+        ms, fl = C.c_float(0), C.c_double(0)
+        self._chk(self.lib.rdlm_time_mfma_loop(self.ctx, workgroups, inner_iters, launches, C.byref(ms), C.byref(fl)),
+                  "rdlm_time_mfma_loop")
+        return ms.value, fl.value
 
     def profile_gemm_begin(self, n_out: int, k_in: int, max_launches: int):
         self._chk(self.lib.rdlm_profile_gemm_begin(self.ctx, n_out, k_in, max_launches), "rdlm_profile_gemm_begin")

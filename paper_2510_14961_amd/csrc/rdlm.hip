@@ -35,6 +35,7 @@ struct Knobs {
     bool no_rope_fusion = false;     // RoPE + cache writes in a kernel of their own instead of the QKV epilogue
     bool no_fold_fusion = false;     // split-K folds in fold_k launches instead of the producing GEMM
     bool no_fold = false;            // full RMSNorm kernels instead of the deferred 1/rms factor
+    bool no_lds_gemm = false;        // steps with three row tiles and more: the row-sharing kernel everywhere
     bool has_plan[PROJ_COUNT] = {}, has_plan_rows[PROJ_COUNT] = {};
     GemmPlan plan[PROJ_COUNT], plan_rows[PROJ_COUNT];
 };
@@ -352,6 +353,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
     if (is("no_rope_fusion")) { k->no_rope_fusion = atoi(value) != 0; return RDLM_OK; }
     if (is("no_fold_fusion")) { k->no_fold_fusion = atoi(value) != 0; return RDLM_OK; }
     if (is("no_fold")) { k->no_fold = atoi(value) != 0; return RDLM_OK; }
+    if (is("no_lds_gemm")) { k->no_lds_gemm = atoi(value) != 0; return RDLM_OK; }
     for (int pj = 0; pj < PROJ_COUNT; ++pj) {
         char nm[32];
         // plan_<proj> = "nb,waves,unroll,ksplit": the one-tile launch shape ("" = default again)
@@ -368,6 +370,15 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
         if (is(nm)) {
             GemmPlan o = {0, 0, 0, 0, 1, GEMM_ROWS};
             const bool stream = value[0] == 's';
+            if (value[0] == 'l') {      // "l<blocks>,<row tiles per wave>,<waves>,<k tiles per stage>,<ring depth>,<ksplit>"
+                int mtw = 0;
+                o.kind = GEMM_LDS;
+                k->has_plan_rows[pj] =
+                    sscanf(value + 1, "%d,%d,%d,%d,%d,%d", &o.nb, &mtw, &o.waves, &o.unroll, &o.depth, &o.ksplit) == 6;
+                o.mt = mtw * o.waves;
+                if (k->has_plan_rows[pj]) k->plan_rows[pj] = o;
+                return k->has_plan_rows[pj] ? RDLM_OK : RDLM_EINVAL;
+            }
             k->has_plan_rows[pj] =
                 sscanf(value + (stream ? 1 : 0), "%d,%d,%d,%d,%d", &o.mt, &o.nb, &o.waves, &o.unroll, &o.ksplit) == 5;
             if (stream) o.kind = GEMM_STREAM;
@@ -379,7 +390,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
 }
 
 static void knobs_from_env(Knobs* k) {
-    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold"};
+    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm"};
     auto env_of = [](const char* name) {
         char buf[48] = "RDLM_";
         size_t n = strlen(buf);
@@ -546,11 +557,43 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                 : proj == PROJ_A  ? GemmPlan{4, 1, 4, 2, 4, GEMM_ROWS}
                                   : GemmPlan{4, 1, 8, 4, 3, GEMM_ROWS};
         else g = GemmPlan{8, 1, 8, 2, deep ? 3 : 2, GEMM_ROWS};
+        // Three row tiles and more: where it measured faster (3.5B shape, 96 .. 4095 rows), the kernel
+        // whose operands all go straight from global memory into an LDS ring (kernels_gemm_lds.hip):
+        // {row tiles per workgroup, feature blocks per workgroup, waves, k tiles per stage, K split, kind, ring depth}.
+        // Five blocks per workgroup give the gate/up projection 224 equal workgroups, eight the LM head 256.
+        if (T >= 3 && !ctx->knobs.no_lds_gemm) {
+            auto lds = [](int fb, int mtw, int wm, int ku, int d, int ks) { return GemmPlan{mtw * wm, fb, wm, ku, ks, GEMM_LDS, d}; };
+            const int tier = T <= 4 ? 0 : T <= 8 ? 1 : T <= 16 ? 2 : T <= 32 ? 3 : 4;
+            switch (proj) {
+                case PROJ_GU: g = tier == 0 ? lds(5, 1, 4, 2, 6, 1) : tier == 1 ? lds(5, 1, 8, 1, 8, 1) : lds(5, 2, 8, 1, 6, 1); break;
+                case PROJ_D:
+                    if (tier == 0) g = lds(5, 1, 4, 2, 6, 7);
+                    else if (tier == 1) g = lds(5, 2, 4, 2, 4, 7);
+                    break;
+                case PROJ_HEAD:
+                    if (tier == 0) g = lds(8, 1, 4, 2, 6, 1);
+                    else if (tier == 1 || tier == 3) g = lds(8, 1, 8, 1, 6, 1);
+                    else if (tier == 4) g = lds(5, 2, 8, 1, 6, 1);
+                    break;
+                case PROJ_O:
+                    if (tier == 3) g = lds(8, 1, 8, 1, 6, 3);
+                    else if (tier == 4) g = lds(4, 2, 8, 1, 6, 2);
+                    break;
+                case PROJ_A:
+                    if (tier == 1) g = lds(4, 1, 4, 2, 6, 3);
+                    else if (tier == 2) g = lds(4, 1, 8, 1, 8, 3);
+                    break;
+                case PROJ_QKV:
+                    if (tier == 1) g = lds(4, 1, 4, 2, 6, 1);
+                    break;
+                default: break;
+            }
+        }
         if (ctx->knobs.has_plan_rows[proj]) g = ctx->knobs.plan_rows[proj];
     }
     if (!split_ok) g.ksplit = 1;
     if (split_ok) {     // at least 4 k tiles per wave, at most 8 partial outputs
-        int kmax = std::max(1, (K / 16) / ((g.kind == GEMM_ROWS ? 1 : g.waves) * 4));
+        int kmax = std::max(1, (K / 16) / ((g.kind == GEMM_STREAM ? g.waves : 1) * 4));
         g.ksplit = std::max(1, std::min(std::min(g.ksplit, 8), kmax));
     }
     return g;
@@ -659,7 +702,8 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         ok = launch_gemm_bf16(xin, W, out, N, K, (size_t)ctx->rows_pad * N, g, epi, ctx->n_tiles, T, ctx->st);
     }
     if (!ok) {      // no instance for this plan: the plain one-block kernel always exists
-        if (g.mt > 1) {
+        if (g.kind == GEMM_LDS) g = {4, 1, 4, 4, 1, GEMM_ROWS};     // (the row-sharing kernel's plain instance)
+        else if (g.mt > 1) {
             g = {g.mt, 1, 4, g.mt == 2 ? 8 : 4, 1, GEMM_ROWS};
             epi.fold_counter = nullptr;         // the row-sharing kernel leaves plain partial sums
         }
@@ -1386,6 +1430,68 @@ extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, 
     (void)hipEventDestroy(a);
     (void)hipEventDestroy(b);
     *ms_out = ms / iters;
+    return check_launch(ctx);
+}
+
+// What the machine does with nothing but the reads: the packed weights of projection w_index of
+// every layer in turn (so that no launch finds its bytes in a cache), `workgroups` x `waves` waves,
+// each reading one contiguous slice.
+extern "C" int rdlm_time_stream_read(rdlm_ctx* ctx, int32_t w_index, int32_t workgroups, int32_t waves, int32_t iters,
+                                     float* ms_out, size_t* bytes_out) {
+    if (!ctx || !ms_out || iters < 1 || workgroups < 1 || waves < 1 || waves > 4) return RDLM_EINVAL;
+    if (ctx->m.dtype != RDLM_BF16) return RDLM_EINVAL;
+    const void* W; int proj, N, K;
+    int rc = weight_by_index(ctx, w_index, &W, &proj, &N, &K);
+    if (rc) return rc;
+    const size_t unit = (size_t)workgroups * waves * 1024;
+    const size_t bytes = (size_t)N * K * 2 / unit * unit;       // whole 1 KiB units per wave, inside the tensor
+    if (bytes == 0) return RDLM_EINVAL;
+    std::vector<const void*> ring;
+    if (w_index >= 1 && w_index < 1 + 7 * (int)ctx->layers.size())
+        for (int l = 0; l < (int)ctx->layers.size(); ++l) {
+            const void* Wl; int pj, n2, k2;
+            if (weight_by_index(ctx, 1 + 7 * l + (w_index - 1) % 7, &Wl, &pj, &n2, &k2) == RDLM_OK) ring.push_back(Wl);
+        }
+    if (ring.empty()) ring.push_back(W);
+    uint32_t* sink = reinterpret_cast<uint32_t*>(ctx->delta);
+    hipEvent_t a, b;
+    HIPCHK(hipEventCreate(&a));
+    HIPCHK(hipEventCreate(&b));
+    for (int i = 0; i < 2; ++i) launch_stream_read(ring[i % ring.size()], bytes, workgroups, waves, sink, ctx->st);
+    HIPCHK(hipEventRecord(a, ctx->st));
+    for (int i = 0; i < iters; ++i) launch_stream_read(ring[i % ring.size()], bytes, workgroups, waves, sink, ctx->st);
+    HIPCHK(hipEventRecord(b, ctx->st));
+    HIPCHK(hipEventSynchronize(b));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, a, b));
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    *ms_out = ms / iters;
+    if (bytes_out) *bytes_out = bytes;
+    return check_launch(ctx);
+}
+
+// What the matrix cores do from registers alone: `workgroups` x 4 waves, each `inner_iters` rounds of
+// four independent v_mfma_f32_32x32x16_bf16.  Long launches also show the clock the chip sustains
+// under matrix load.
+extern "C" int rdlm_time_mfma_loop(rdlm_ctx* ctx, int32_t workgroups, int32_t inner_iters, int32_t launches,
+                                   float* ms_out, double* flops_out) {
+    if (!ctx || !ms_out || workgroups < 1 || inner_iters < 1 || launches < 1) return RDLM_EINVAL;
+    if ((size_t)workgroups * 256 > (size_t)8 * ctx->rows_pad * ctx->m.hidden) return RDLM_ECAPACITY;   // written to `part`
+    hipEvent_t a, b;
+    HIPCHK(hipEventCreate(&a));
+    HIPCHK(hipEventCreate(&b));
+    double flops = launch_mfma_loop(ctx->part, workgroups, 16, ctx->st);
+    HIPCHK(hipEventRecord(a, ctx->st));
+    for (int i = 0; i < launches; ++i) flops = launch_mfma_loop(ctx->part, workgroups, inner_iters, ctx->st);
+    HIPCHK(hipEventRecord(b, ctx->st));
+    HIPCHK(hipEventSynchronize(b));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, a, b));
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    *ms_out = ms / launches;
+    if (flops_out) *flops_out = flops;
     return check_launch(ctx);
 }
 

@@ -149,8 +149,10 @@ __device__ __forceinline__ uint32_t draw_ticket(uint32_t* counter, uint32_t* sha
 
 // kind GEMM_STREAM: the waves of a workgroup split K (one row-tile group, weights streamed once);
 // kind GEMM_ROWS: the waves own different feature blocks and share the activation tiles through LDS.
-enum { GEMM_STREAM = 0, GEMM_ROWS = 1 };
-struct GemmPlan { int mt, nb, waves, unroll, ksplit, kind = GEMM_STREAM; };
+// kind GEMM_LDS: every operand tile goes straight from global memory into LDS, the waves own different
+// row tiles and share the weight tiles (see kernels_gemm_lds.hip); `depth` = stages of its LDS ring.
+enum { GEMM_STREAM = 0, GEMM_ROWS = 1, GEMM_LDS = 2 };
+struct GemmPlan { int mt, nb, waves, unroll, ksplit, kind = GEMM_STREAM, depth = 0; };
 
 // What the GEMM does with a finished output tile.
 enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_ROPE_KV = 3 };
@@ -285,6 +287,8 @@ void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int
 bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride,
                       GemmPlan plan, const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles,
                       hipStream_t st);
+bool launch_gemm_lds(const void* xp, const void* wp, float* out, int N, int K, size_t part_stride, GemmPlan plan,
+                     const GemmEpilogue& epi, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 int gemm_groups(int N, const GemmPlan& plan, int epi_kind);
 void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_groups, size_t cand_stride,
                          int32_t* tok_out, const int32_t* n_tiles, int max_tiles, hipStream_t st);
@@ -295,6 +299,10 @@ void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
 void launch_pack_weight(const void* w0, const void* w1, int split, void* w_packed, int N, int K, int layout,
                         int n_heads, int head_dim, hipStream_t st);
 void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st);   // f32 rows -> packed bf16
+
+// reference kernels (measurement only) -------------------------------------------------------
+void launch_stream_read(const void* p, size_t bytes, int workgroups, int waves, uint32_t* sink, hipStream_t st);
+double launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
 
 // attention -----------------------------------------------------------------------------------
 // q: f32 [rows][H*d] (RDLM_F32) or bf16 [rows][H*d]; caches per the model dtype; out: activation
