@@ -118,6 +118,40 @@ def machine_reference(ctx, shape):
     return out
 
 
+def gemm_probe(args):
+    """Every projection alone (the kernel and launch shape the model path picks for that row count), going
+    round the layers' weights; flops = 2 x rows x N x K, bytes = the weights once."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape = S.BIG
+    rows_list = [int(x) for x in args.gemm_probe.split(",")]
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+    dev, _ = build_weights(shape, 1, False, args.threads)
+    ctx = R.Context(shape, dev, 1, max(rows_list) + 64, max(rows_list))
+    del dev
+    torch.cuda.empty_cache()
+    names = R.weight_names(shape)
+    h, F, V = shape.hidden, shape.mlp, shape.vocab
+    projs = {"gate_up": ("R0.wg", 2 * F, h), "qkv": ("R0.wqkv", 3 * h, h), "out": ("R0.wo", h, h),
+             "down": ("R0.wd", h, F), "adapter": ("wa", h, 2 * h), "lm_head": ("emb", V, h)}
+    out = []
+    for rows in rows_list:
+        for pname, (wname, N, K) in projs.items():
+            ms = ctx.time_linear(names.index(wname), rows, 8 if rows > 256 else 24)
+            out.append({"projection": pname, "rows": rows, "us": ms * 1e3, "TFLOPs": 2.0 * rows * N * K / (ms * 1e-3) / 1e12,
+                        "weight_GBps": N * K * 2 / (ms * 1e-3) / 1e9})
+            log(f"[probe] {pname:8s} rows {rows:5d}: {ms * 1e3:8.1f} us")
+    print(json.dumps({"gemm_probe": out}), flush=True)
+    ctx.close()
+
+
 def core_sweep(args):
     """Core step (adapter + core layers + closing norm, r' = 1) over window rows x cached context."""
     import torch
@@ -178,6 +212,9 @@ def main():
                     help="instead of the benchmark: time one core step (r' = 1) at the 3.5B shape over a grid of window "
                          "rows x cached context, print the table and the measured ridge (rows at which the step "
                          "turns from weight-streaming bound to matrix-core bound) as JSON")
+    ap.add_argument("--gemm-probe", default="",
+                    help="instead of the benchmark: time every projection of the 3.5B shape alone at these row counts "
+                         "(comma separated), print JSON; the command to run under rocprofv3 --pmc for per-kernel counters")
     ap.add_argument("--threads", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -191,6 +228,9 @@ def main():
     torch.cuda.set_device(0)
     if args.core_sweep:
         core_sweep(args)
+        return
+    if args.gemm_probe:
+        gemm_probe(args)
         return
     wl = S.WORKLOADS[args.workload]
     shape, sp = wl.shape, wl.sampler

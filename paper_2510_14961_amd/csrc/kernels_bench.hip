@@ -36,7 +36,7 @@ __global__ __launch_bounds__(256) void stream_read_k(const u32x4* __restrict__ p
 // bytes must be a multiple of workgroups * waves * 1024; the launch reads exactly `bytes`.
 void launch_stream_read(const void* p, size_t bytes, int workgroups, int waves, uint32_t* sink, hipStream_t st) {
     const size_t units_per_wave = bytes / 1024 / ((size_t)workgroups * waves);
-    hipLaunchKernelGGL(stream_read_k<2>, dim3(workgroups), dim3(waves * 64), 0, st, (const u32x4*)p, units_per_wave, sink);
+    hipLaunchKernelGGL(stream_read_k<8>, dim3(workgroups), dim3(waves * 64), 0, st, (const u32x4*)p, units_per_wave, sink);
 }
 
 // NACC independent accumulators per wave, `iters` rounds of NACC matrix instructions from registers.
