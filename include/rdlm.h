@@ -125,6 +125,47 @@ int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptrs, int32_t 
                    int32_t max_positions, int32_t max_rows, void* hip_stream, void* workspace,
                    size_t workspace_bytes, rdlm_ctx** out);
 
+/* ---- paged KV cache, eviction and re-admission --------------------------------------------- */
+/* App. "Larger batch sizes" observes that with diffusion forcing the slots of a batch are
+ * fungible: a sequence's states can be taken off the device and bundled into a later forward
+ * call.  For that the KV cache of every layer is a pool of blocks of 32 positions, and a sequence
+ * slot owns just the blocks its positions so far need: a per-slot block table (device memory,
+ * max_seqs x ceil(max_positions / 32) entries) maps (slot, position / 32) to a pool block.  Blocks
+ * are handed out lazily by the calls that write new positions (prefill, sampler steps, the building
+ * blocks) and go back to the pool on rdlm_seq_release / rdlm_seq_evict / rdlm_destroy.
+ *
+ * rdlm_create sizes the pool so that every slot can reach max_positions (it can never run dry);
+ * rdlm_create_paged sizes it to kv_pool_positions (>= 32, rounded up to whole blocks) positions in
+ * total, shared by all slots.  A call that needs more blocks than the pool has left returns
+ * RDLM_ECAPACITY and changes nothing; release or evict a sequence and call it again. */
+int rdlm_create_paged(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                      int32_t max_positions, int32_t max_rows, int32_t kv_pool_positions,
+                      void* hip_stream, rdlm_ctx** out);
+/* Blocks in the pool and blocks not owned by any slot right now (either pointer may be NULL). */
+int rdlm_kv_blocks(const rdlm_ctx* ctx, int32_t* total_out, int32_t* free_out);
+/* Give the blocks of slot seq back to the pool and, in a running sampler, take the slot out of it
+ * (it contributes no rows until a sequence is joined or admitted there).  Tokens already read stay
+ * readable; cache, states and window of the sequence are gone.  Synchronises the stream. */
+int rdlm_seq_release(rdlm_ctx* ctx, int32_t seq);
+/* Evict: copy everything that makes up the sequence in slot seq -- its cache blocks of all layers,
+ * latents s, previous-step latents, conditioning e, tokens, per-position step counts, and (inside
+ * a running sampler) its window record, step count and the sampler's parameters -- into host_buf
+ * (host memory, cap >= rdlm_seq_evict_bytes(ctx, seq) bytes, else RDLM_ECAPACITY), then release the
+ * slot as rdlm_seq_release does.  The buffer is self-contained and position-independent: it names
+ * no slot and no block.  Synchronises the stream. */
+size_t rdlm_seq_evict_bytes(const rdlm_ctx* ctx, int32_t seq);
+int rdlm_seq_evict(rdlm_ctx* ctx, int32_t seq, void* host_buf, size_t cap);
+/* Re-admit an evicted sequence into slot seq, which must be empty (never used, or released /
+ * evicted; RDLM_ESTATE otherwise), of this context or of another one created for the same model.
+ * If the sequence was evicted out of a running sampler, a sampler with the same parameters must
+ * be running here (RDLM_ESTATE otherwise); the sequence then goes on from the step it had reached,
+ * and since its generator counters are keyed by its own step count and by the slot number it
+ * started in (kept in the buffer), its tokens and states are those of a run that was never
+ * interrupted, whichever slot and blocks it now occupies.  RDLM_ECAPACITY if the pool has too few
+ * free blocks or the slot table / row budget of the running sampler is exceeded (nothing changes),
+ * RDLM_EINVAL for a buffer that is not an eviction record of this model.  Synchronises the stream. */
+int rdlm_seq_admit(rdlm_ctx* ctx, int32_t seq, const void* host_buf, size_t bytes);
+
 const char* rdlm_strerror(int status);
 int rdlm_last_hip_error(const rdlm_ctx* ctx);   /* hipError_t of the last failed HIP call, or 0 */
 
@@ -132,7 +173,7 @@ int rdlm_last_hip_error(const rdlm_ctx* ctx);   /* hipError_t of the last failed
 size_t rdlm_device_bytes(const rdlm_ctx* ctx);
 
 /* ---- sequence text ------------------------------------------------------------------------ */
-/* Set the known tokens of a sequence (y_frozen = y_current = x, Alg. 1 lines 1-2); tokens_host
+/* Set the known tokens of a sequence (y_frozen = y_current = x, Alg. 1, initialisation); tokens_host
  * [n] int32 in [0, vocab).  Synchronises the stream.  If a sampler is running, the sequence leaves
  * it (its slot contributes no rows) until rdlm_sampler_join puts it back. */
 int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens_host, int32_t n);
@@ -155,7 +196,7 @@ int rdlm_init_state(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float a
 int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, const int32_t* pos0,
                  const int32_t* n_rows, const int32_t* tokens_dev, float* e_out);
 
-/* r_inner recurrences z <- R(z, e) over all given rows at once (Alg. 1 lines 8-10), each row
+/* r_inner recurrences z <- R(z, e) over all given rows at once (Alg. 1, inner recurrence), each row
  * attending to the cache prefix plus the rows before it in this step; core caches at those
  * positions are overwritten.  delta_out (device float32 [M], may be NULL) receives
  * ||z_new - z_in|| / ||z_new|| per row (Eq. 3 with z_prev = the z passed in).
@@ -182,7 +223,7 @@ int rdlm_core_step_static(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids,
                           const int32_t* n_rows, const float* e, float* z_inout, int32_t r_inner,
                           float* delta_out);
 
-/* C + Sample on every given row (Alg. 1 lines 11-12): coda layers (caches overwritten), final
+/* C + Sample on every given row (Alg. 1, decode and sample): coda layers (caches overwritten), final
  * norm, tied LM head, then greedy or Gumbel-max at (seed, step), restricted to the top-p set when
  * 0 < top_p < 1 (App. "Dataset details": the paper samples at temperature 0.2, top-p 0.95).
  * tokens_out: device int32 [M]; logits_out: device float32 [M, vocab] or NULL. */
@@ -192,7 +233,7 @@ int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_ids, cons
 
 /* Start the sampler on sequences 0..n_seqs-1: each needs rdlm_set_tokens (L >= 1 tokens) and
  * rdlm_prefill of its first L-1 positions before.  Creates one fresh state at position L-1
- * (Alg. 1 line 3).  Needs L + n_new + w_max + headway <= max_positions and
+ * (Alg. 1, initial state).  Needs L + n_new + w_max + headway <= max_positions and
  * n_seqs * roundup32(w_max) <= max_rows. */
 int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t n_seqs);
 
@@ -240,7 +281,9 @@ int rdlm_read_counts(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, int32_
  * step; n_out = number of rows it had. */
 int rdlm_read_deltas(rdlm_ctx* ctx, int32_t seq, float* delta_host, int32_t cap, int32_t* n_out);
 /* K and V rows of one layer (0-based over P, R, C layers in order) in natural order:
- * float32 [n, n_heads, head_dim] each (host). */
+ * float32 [n, n_heads, head_dim] each (host).  Positions beyond the cache blocks the slot owns
+ * (the newest window positions before the step that computes them) read as zeros; a slot that
+ * owns no block at all (never used, released, evicted) is RDLM_ESTATE. */
 int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_t n,
                  float* k_host, float* v_host);
 

@@ -354,7 +354,7 @@ def noise_level(beta: float, steps_done: int, n_steps: int) -> float:
 def mix_noise(z: np.ndarray, level: float, position: int, seq: int, step: int, alpha: float,
               seed: int) -> np.ndarray:
     """z' = (1 - beta_t) z + beta_t z_noise, z_noise = InitState(1, alpha) drawn afresh at every
-    sampler step (Eq. 2; Alg. 1 lines 6-7): counter (., position, seq, step) tagged TAG_NOISE."""
+    sampler step (Eq. 2; Alg. 1, noise on the conditioning): counter (., position, seq, step) tagged TAG_NOISE."""
     if level == 0.0:
         return z
     noise = init_state(z.shape[0], position, seq, alpha, seed, step=step, tag=TAG_NOISE)

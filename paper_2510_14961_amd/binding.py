@@ -23,6 +23,8 @@ EXPORTED_SYMBOLS = [
     "rdlm_profile_gemm_read", "rdlm_workspace_bytes", "rdlm_create_ws", "rdlm_core_step_static",
     "rdlm_core_step_static_bytes", "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
     "rdlm_read_window", "rdlm_time_stream_read", "rdlm_time_mfma_loop",
+    "rdlm_create_paged", "rdlm_kv_blocks", "rdlm_seq_release", "rdlm_seq_evict_bytes", "rdlm_seq_evict",
+    "rdlm_seq_admit",
 ]
 
 STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
@@ -96,6 +98,12 @@ def load_library():
         "rdlm_workspace_bytes": (C.c_size_t, [C.POINTER(_Model), i32, i32]),
         "rdlm_create_ws": (C.c_int, [C.POINTER(_Model), C.POINTER(vp), i32, i32, i32, vp, vp, C.c_size_t,
                                      C.POINTER(vp)]),
+        "rdlm_create_paged": (C.c_int, [C.POINTER(_Model), C.POINTER(vp), i32, i32, i32, i32, vp, C.POINTER(vp)]),
+        "rdlm_kv_blocks": (C.c_int, [vp, pi32, pi32]),
+        "rdlm_seq_release": (C.c_int, [vp, i32]),
+        "rdlm_seq_evict_bytes": (C.c_size_t, [vp, i32]),
+        "rdlm_seq_evict": (C.c_int, [vp, i32, vp, C.c_size_t]),
+        "rdlm_seq_admit": (C.c_int, [vp, i32, vp, C.c_size_t]),
         "rdlm_core_step_static": (C.c_int, [vp, i32, pi32, pi32, pi32, vp, vp, i32, vp]),
         "rdlm_core_step_static_bytes": (C.c_size_t, [vp, i32]),
         "rdlm_sampler_status": (C.c_int, [vp, pi32, pi32]),
@@ -155,9 +163,11 @@ class Context:
     """One rdlm_ctx.  Methods carry the names of the C functions without the prefix."""
 
     def __init__(self, shape, dev_weights: Dict[str, "object"], max_seqs: int, max_positions: int,
-                 max_rows: int, stream=None, workspace=None):
+                 max_rows: int, stream=None, workspace=None, kv_pool_positions=None):
         """workspace: None (the library allocates its step workspace) or a CUDA uint8 tensor of at
-        least workspace_bytes(shape, max_seqs, max_rows) bytes that the caller keeps alive."""
+        least workspace_bytes(shape, max_seqs, max_rows) bytes that the caller keeps alive.
+        kv_pool_positions: None (every slot can reach max_positions) or the total number of cached
+        positions all slots share (rdlm_create_paged)."""
         import torch
         self.lib = load_library()
         self.shape = shape
@@ -174,7 +184,12 @@ class Context:
             ptrs[i] = t.data_ptr()
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         handle = C.c_void_p()
-        if workspace is None:
+        if kv_pool_positions is not None:
+            assert workspace is None
+            rc = self.lib.rdlm_create_paged(C.byref(self.model), ptrs, max_seqs, max_positions, max_rows,
+                                            int(kv_pool_positions), C.c_void_p(self.stream.cuda_stream),
+                                            C.byref(handle))
+        elif workspace is None:
             rc = self.lib.rdlm_create(C.byref(self.model), ptrs, max_seqs, max_positions, max_rows,
                                       C.c_void_p(self.stream.cuda_stream), C.byref(handle))
         else:
@@ -275,6 +290,27 @@ class Context:
 
     def sampler_join(self, seq: int):
         self._chk(self.lib.rdlm_sampler_join(self.ctx, seq), "rdlm_sampler_join")
+
+    def kv_blocks(self):
+        """(blocks of 32 positions in the KV pool, blocks no slot owns)"""
+        t, f = C.c_int32(0), C.c_int32(0)
+        self._chk(self.lib.rdlm_kv_blocks(self.ctx, C.byref(t), C.byref(f)), "rdlm_kv_blocks")
+        return t.value, f.value
+
+    def seq_release(self, seq: int):
+        self._chk(self.lib.rdlm_seq_release(self.ctx, seq), "rdlm_seq_release")
+
+    def seq_evict(self, seq: int) -> np.ndarray:
+        """Evict slot seq; returns the host record rdlm_seq_admit takes."""
+        n = self.lib.rdlm_seq_evict_bytes(self.ctx, seq)
+        buf = np.empty(n, np.uint8)
+        self._chk(self.lib.rdlm_seq_evict(self.ctx, seq, buf.ctypes.data_as(C.c_void_p), n), "rdlm_seq_evict")
+        return buf
+
+    def seq_admit(self, seq: int, record: np.ndarray):
+        record = np.ascontiguousarray(record, dtype=np.uint8)
+        self._chk(self.lib.rdlm_seq_admit(self.ctx, seq, record.ctypes.data_as(C.c_void_p), record.size),
+                  "rdlm_seq_admit")
 
     def sample_step(self):
         self._chk(self.lib.rdlm_sample_step(self.ctx), "rdlm_sample_step")

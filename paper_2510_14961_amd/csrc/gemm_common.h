@@ -152,8 +152,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
             if (sec == 2) {
                 if (valid) {
                     const int u0 = 32 * j + f0;
-                    uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) + (size_t)td[b].seq * A.epi.seq_stride +
-                                   (((size_t)(pos >> 5) * H + head) * D + u0) * 32 + vt_slot(pos & 31);
+                    uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) +
+                                   kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h) +
+                                   ((size_t)head * D + u0) * 32 + vt_slot(pos & 31);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         Vt[(size_t)i * 32] = f32_to_bf16(lo[i]);
@@ -177,9 +178,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                     *reinterpret_cast<ushort4*>(dst) = p0;
                     *reinterpret_cast<ushort4*>(dst + HALF) = p1;
                 } else if (valid) {
-                    uint16_t* Kc = reinterpret_cast<uint16_t*>(A.epi.kc) + (size_t)td[b].seq * A.epi.seq_stride;
-                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos, head, u0, H, D)) = p0;
-                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos, head, u0 + HALF, H, D)) = p1;
+                    uint16_t* Kc = reinterpret_cast<uint16_t*>(A.epi.kc) +
+                                   kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h);
+                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos & 31, head, u0, H, D)) = p0;
+                    *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos & 31, head, u0 + HALF, H, D)) = p1;
                 }
             }
         } else {   // EPI_ARGMAX
@@ -190,7 +192,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                 uint32_t x[4];
                 // a sequence counts its sampler steps from the step it joined at
                 const int lstep = A.epi.step - (A.epi.seq_step0 ? A.epi.seq_step0[td[b].seq] : 0);
-                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].seq, ((uint32_t)lstep << 4) | TAG_SAMPLE, A.epi.k0,
+                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].rng, ((uint32_t)lstep << 4) | TAG_SAMPLE, A.epi.k0,
                               A.epi.k1, x);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));

@@ -81,7 +81,7 @@ template <int D, int MTQ>
 __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(const uint16_t* __restrict__ q,
                                                                const uint16_t* __restrict__ kc,
                                                                const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
-                                                               int H, size_t seq_stride, int nsplit, float* __restrict__ ws,
+                                                               int H, KvPages kvp, int nsplit, float* __restrict__ ws,
                                                                uint32_t* __restrict__ tickets,
                                                                const TileDesc* tiles, const int32_t* n_tiles) {
     constexpr int DK = D / 16;      // k steps of the score contraction
@@ -104,8 +104,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     const int n_keys = td.pos0 + 32 * (ng - 1) + n_valid_last;   // keys 0..n_keys-1 are visible to the group
     const int nkb = (n_keys + 31) >> 5;
     const int kb_lo = (int)(((long long)nkb * sp) / nsplit), kb_hi = (int)(((long long)nkb * (sp + 1)) / nsplit);
-    const uint16_t* K = kc + (size_t)td.seq * seq_stride;
-    const uint16_t* Vt = vc + (size_t)td.seq * seq_stride;
+    const size_t block_elems = (size_t)32 * h;                // one block of 32 positions, all heads
     const float scale = 1.0f / sqrtf((float)D);
 
     bf16x8 qv[MTQ][DK];
@@ -125,10 +124,11 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
 
     bf16x8 kA[DK], vA[2 * DB], kB[DK], vB[2 * DB];
     auto load = [&](bf16x8(&kv)[DK], bf16x8(&vv)[2 * DB], int kb) {
-        const uint16_t* kr = K + k_cache_off(kb * 32 + col, hd, g * 8, H, D);
+        const size_t base = kv_block_base(kvp, td.seq, kb, block_elems);
+        const uint16_t* kr = kc + base + k_cache_off(col, hd, g * 8, H, D);
 #pragma unroll
         for (int i = 0; i < DK; ++i) kv[i] = *reinterpret_cast<const bf16x8*>(kr + i * 512);
-        const uint16_t* vr = Vt + ((size_t)kb * H + hd) * D * 32 + (size_t)col * 32 + g * 8;
+        const uint16_t* vr = vc + base + (size_t)hd * D * 32 + (size_t)col * 32 + g * 8;
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
             vv[2 * d] = *reinterpret_cast<const bf16x8*>(vr + (size_t)d * 32 * 32);
@@ -309,7 +309,7 @@ template <int D>
 __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* __restrict__ q,
                                                                 const uint16_t* __restrict__ kc,
                                                                 const uint16_t* __restrict__ vc, uint16_t* __restrict__ out,
-                                                                int H, size_t seq_stride, int nsplit, float* __restrict__ ws,
+                                                                int H, KvPages kvp, int nsplit, float* __restrict__ ws,
                                                                 const TileDesc* tiles, const int32_t* n_tiles) {
     constexpr int DK = D / 16, DB = D / 32;
     constexpr int SLOTS = (DK + 2 * DB) * 64;               // 16-byte slots of one staged K + V block
@@ -326,8 +326,6 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     const int n_keys = td.pos0 + 32 * (ng - 1) + tiles[t + ng - 1].n_valid;
     const int nkb = (n_keys + 31) >> 5;
     const int kb_lo = (int)(((long long)nkb * sp) / nsplit), kb_hi = (int)(((long long)nkb * (sp + 1)) / nsplit);
-    const uint16_t* K = kc + (size_t)td.seq * seq_stride;
-    const uint16_t* Vt = vc + (size_t)td.seq * seq_stride;
     const float scale = 1.0f / sqrtf((float)D);
     const bool active = wave < ng;
     const int tq = t + (active ? wave : 0);                   // this wave's row tile
@@ -348,7 +346,7 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     float m_run = -INFINITY, l_run = 0.f;
 
     // slot s < DK*64: K operand (k step s/64, lane s%64); then V operand (j = (s - DK*64)/64).
-    // Both advance by 32*H*D elements per key block, so a slot's address is base + kb * stride.
+    // A slot's address is the key block's place in the pool (block table) plus its offset in the block.
     static_assert(SLOTS % (ATT_GROUP * 64) == 0, "every thread stages the same number of slots");
     const size_t kb_stride = (size_t)32 * H * D;
     const uint16_t* fbase[PER];
@@ -356,14 +354,15 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     for (int p = 0; p < PER; ++p) {
         const int s = threadIdx.x + p * ATT_GROUP * 64;
         const int ln = s & 63, c = ln & 31, gg = ln >> 5, i = s >> 6, j = i - DK;
-        const uint16_t* sk = K + k_cache_off(c, hd, gg * 8 + (i < DK ? i : 0) * 16, H, D);
-        const uint16_t* sv = Vt + (size_t)hd * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
+        const uint16_t* sk = kc + k_cache_off(c, hd, gg * 8 + (i < DK ? i : 0) * 16, H, D);
+        const uint16_t* sv = vc + (size_t)hd * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
         fbase[p] = i < DK ? sk : sv;
     }
     bf16x8 fetch0[PER], fetch1[PER];
     auto load = [&](bf16x8(&fetch)[PER], int kb) {
+        const size_t base = kv_block_base(kvp, td.seq, kb, kb_stride);
 #pragma unroll
-        for (int p = 0; p < PER; ++p) fetch[p] = *reinterpret_cast<const bf16x8*>(fbase[p] + (size_t)kb * kb_stride);
+        for (int p = 0; p < PER; ++p) fetch[p] = *reinterpret_cast<const bf16x8*>(fbase[p] + base);
     };
     auto put = [&](bf16x8(&fetch)[PER], int buf) {
 #pragma unroll
@@ -486,7 +485,7 @@ __global__ __launch_bounds__(256) void attn_merge_k(const float* __restrict__ ws
 constexpr int ATT_F32_MAXKEYS = 8192;
 __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, const float* __restrict__ kc,
                                                     const float* __restrict__ vc, float* __restrict__ out, int H, int d,
-                                                    size_t seq_stride, const TileDesc* tiles, const int32_t* n_tiles) {
+                                                    KvPages kvp, const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sc[ATT_F32_MAXKEYS];
     __shared__ float red[8];
     int r = blockIdx.x, hd = blockIdx.y, t = r >> 5, j = r & 31;
@@ -499,13 +498,12 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
         return;
     }
     int nk = td.pos0 + j + 1;
-    const float* K = kc + (size_t)td.seq * seq_stride;
-    const float* V = vc + (size_t)td.seq * seq_stride;
+    const size_t block_elems = (size_t)32 * h;
     const float* qr = q + (size_t)r * h + hd * d;
     float scale = 1.0f / sqrtf((float)d);
     float mx = -INFINITY;
     for (int k = threadIdx.x; k < nk; k += blockDim.x) {
-        const float* kr = K + (size_t)k * h + hd * d;
+        const float* kr = kc + kv_block_base(kvp, td.seq, k >> 5, block_elems) + (size_t)(k & 31) * h + hd * d;
         float s = 0.f;
         for (int c = 0; c < d; ++c) s = fmaf(qr[c], kr[c], s);
         s *= scale;
@@ -529,17 +527,18 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
     sum = red[4] + red[5] + red[6] + red[7];
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
         float acc = 0.f;
-        for (int k = 0; k < nk; ++k) acc = fmaf(sc[k], V[(size_t)k * h + hd * d + c], acc);
+        for (int k = 0; k < nk; ++k)
+            acc = fmaf(sc[k], vc[kv_block_base(kvp, td.seq, k >> 5, block_elems) + (size_t)(k & 31) * h + hd * d + c], acc);
         orow[c] = acc / sum;
     }
 }
 
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws, uint32_t* tickets,
+                      KvPages kv, int nsplit, bool grouped, float* ws, uint32_t* tickets,
                       const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     if (dtype == 0) {
         hipLaunchKernelGGL(attn_f32_k, dim3(max_tiles * 32, H), dim3(256), 0, st, (const float*)q, (const float*)kc,
-                           (const float*)vc, (float*)out, H, d, seq_stride_elems, tiles, n_tiles);
+                           (const float*)vc, (float*)out, H, d, kv, tiles, n_tiles);
         return;
     }
     if (nsplit > ATT_MAX_SPLIT) nsplit = ATT_MAX_SPLIT;
@@ -549,13 +548,13 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
     if (d == D_) {                                                                                                \
         if (!grouped) {         /* merges its KV splits itself */                                                 \
             hipLaunchKernelGGL((attn_bf16_k<D_, 1>), grid, dim3(ATT_WAVES * 64), 0, st, (const uint16_t*)q,       \
-                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \
+                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, kv,                   \
                                nsplit, ws, tickets, tiles, n_tiles);                                              \
             return;                                                                                               \
         }                                                                                                         \
         else                                                                                                      \
             hipLaunchKernelGGL(attn_group_k<D_>, grid, dim3(ATT_GROUP * 64), 0, st, (const uint16_t*)q,           \
-                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, seq_stride_elems,     \
+                               (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, kv,                   \
                                nsplit, ws, tiles, n_tiles);                                                       \
         if (nsplit > 1)                                                                                           \
             hipLaunchKernelGGL(attn_merge_k<D_>, dim3(H, max_tiles, (32 * (D_ / 4) + 255) / 256), dim3(256), 0,   \

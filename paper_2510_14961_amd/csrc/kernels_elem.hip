@@ -2,7 +2,7 @@
 // concat, residual-add + RMSNorm (which also folds the split-K partial sums of the preceding
 // GEMM), end-of-recurrence norm + convergence reduction (Eq. 3), RoPE + KV-cache write
 // (Sec. 3.2: in-place overwrite), SwiGLU, Gaussian state init, sampling, and the sampler's
-// device-side bookkeeping (Alg. 1 lines 13-16, Alg. 2 freeze / append).
+// device-side bookkeeping (Alg. 1 assign / freeze / append, Alg. 2).
 #include "rdlm_internal.h"
 
 namespace rdlm {
@@ -35,13 +35,15 @@ __device__ inline float4 ld4(const float* p) { return *reinterpret_cast<const fl
 
 // ---------------------------------------------------------------------------------------------
 // tile descriptors
-__global__ void build_tiles_api_k(SeqWindows w, int mode, int max_positions, TileDesc* tiles, int32_t* n_tiles) {
+__global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, int max_positions, TileDesc* tiles,
+                                  int32_t* n_tiles) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     int t = 0, c = 0;
     for (int i = 0; i < w.n; ++i) {
         for (int off = 0; off < w.rows[i]; off += TILE_ROWS) {
             TileDesc d;
             d.seq = w.seq[i];
+            d.rng = ident[w.seq[i]];
             d.pos0 = w.pos0[i] + off;
             d.n_valid = min(TILE_ROWS, w.rows[i] - off);
             if (mode == 0) {            // caller-owned compact arrays
@@ -60,8 +62,8 @@ __global__ void build_tiles_api_k(SeqWindows w, int mode, int max_positions, Til
     *n_tiles = t;
 }
 
-__global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positions, TileDesc* tiles,
-                                      int32_t* n_tiles) {
+__global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
+                                      TileDesc* tiles, int32_t* n_tiles) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     int t = 0, c = 0;
     for (int s = 0; s < n_seqs; ++s) {
@@ -72,6 +74,7 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, int n_seqs, int max_positi
         for (int off = 0; off < rows; off += TILE_ROWS) {
             TileDesc d;
             d.seq = s;
+            d.rng = ident[s];
             d.pos0 = q.win_pos0 + off;
             d.n_valid = min(TILE_ROWS, rows - off);
             d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
@@ -351,7 +354,7 @@ __global__ void rope_table_k(float2* table, const float* theta, int half, const 
 // 32 positions of a block together.
 template <int DT>
 __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t part_stride, void* qout, void* kc,
-                                                  void* vc, int H, int d, const float2* table, size_t seq_stride,
+                                                  void* vc, int H, int d, const float2* table, KvPages kv,
                                                   const TileDesc* tiles, const int32_t* n_tiles) {
     extern __shared__ float sv[];                       // [32][d + 1]
     const int hd = blockIdx.x, t = blockIdx.y;
@@ -378,16 +381,17 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
             float* q = reinterpret_cast<float*>(qout);
             q[(size_t)r * h + c0] = qa; q[(size_t)r * h + c1] = qb;
             if (valid) {
-                float* K = reinterpret_cast<float*>(kc) + (size_t)ds.seq * seq_stride + (size_t)pos * h;
+                float* K = reinterpret_cast<float*>(kc) + kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h) +
+                           (size_t)(pos & 31) * h;
                 K[c0] = ka; K[c1] = kb;
             }
         } else {
             uint16_t* q = reinterpret_cast<uint16_t*>(qout);
             q[(size_t)r * h + c0] = f32_to_bf16(qa); q[(size_t)r * h + c1] = f32_to_bf16(qb);
             if (valid) {
-                uint16_t* K = reinterpret_cast<uint16_t*>(kc) + (size_t)ds.seq * seq_stride;
-                K[k_cache_off(pos, hd, i, H, d)] = f32_to_bf16(ka);
-                K[k_cache_off(pos, hd, i + half, H, d)] = f32_to_bf16(kb);
+                uint16_t* K = reinterpret_cast<uint16_t*>(kc) + kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h);
+                K[k_cache_off(pos & 31, hd, i, H, d)] = f32_to_bf16(ka);
+                K[k_cache_off(pos & 31, hd, i + half, H, d)] = f32_to_bf16(kb);
             }
         }
     }
@@ -395,17 +399,19 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
     if (DT == 0) {
         for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
             const int j = idx / d, dd = idx - j * d;
-            if (j < ds.n_valid)
-                reinterpret_cast<float*>(vc)[(size_t)ds.seq * seq_stride + (size_t)(ds.pos0 + j) * h + hd * d + dd] =
-                    sv[j * (d + 1) + dd];
+            if (j < ds.n_valid) {
+                const int pos = ds.pos0 + j;
+                reinterpret_cast<float*>(vc)[kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h) + (size_t)(pos & 31) * h +
+                                             hd * d + dd] = sv[j * (d + 1) + dd];
+            }
         }
     } else {
         // transposed V: [position block][head][dim][32 slots]; lanes run over the rows of the tile
         for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
             const int dd = idx >> 5, j = idx & 31, pos = ds.pos0 + j;
             if (j < ds.n_valid)
-                reinterpret_cast<uint16_t*>(vc)[(size_t)ds.seq * seq_stride +
-                                                (((size_t)(pos >> 5) * H + hd) * d + dd) * 32 + vt_slot(pos & 31)] =
+                reinterpret_cast<uint16_t*>(vc)[kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h) +
+                                                ((size_t)hd * d + dd) * 32 + vt_slot(pos & 31)] =
                     f32_to_bf16(sv[j * (d + 1) + dd]);
         }
     }
@@ -496,7 +502,7 @@ __global__ void noise_mix_k(float* z, const int32_t* counts, float beta, int n_s
     float* zr = z + srow * h;
     for (int blk = threadIdx.x; blk * 4 < h; blk += blockDim.x) {
         float g[4];
-        gauss4(blk, d.pos0 + j, d.seq, k0, k1, alpha, g, ((uint32_t)lstep << 4) | TAG_NOISE);
+        gauss4(blk, d.pos0 + j, d.rng, k0, k1, alpha, g, ((uint32_t)lstep << 4) | TAG_NOISE);
         for (int i = 0; i < 4 && blk * 4 + i < h; ++i) zr[blk * 4 + i] = (1.0f - b) * zr[blk * 4 + i] + b * g[i];
     }
 }
@@ -517,7 +523,7 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
         float g[4] = {0.f, 0.f, 0.f, 0.f};
         if (temperature > 0.f) {
             uint32_t x[4];
-            philox4x32_10(b, pos, d.seq, ((uint32_t)(step - (seq_step0 ? seq_step0[d.seq] : 0)) << 4) | TAG_SAMPLE, k0, k1, x);
+            philox4x32_10(b, pos, d.rng, ((uint32_t)(step - (seq_step0 ? seq_step0[d.seq] : 0)) << 4) | TAG_SAMPLE, k0, k1, x);
             for (int i = 0; i < 4; ++i) g[i] = -logf(-logf(u24_open(x[i])));
         }
         for (int i = 0; i < 4 && b * 4 + i < V; ++i) {
@@ -677,7 +683,7 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
         for (int c = 0; c < 4; ++c) any = any || e[i][c] >= thr;
         if (!any) continue;
         uint32_t x[4];
-        philox4x32_10(v0 >> 2, pos, d.seq, ((uint32_t)lstep << 4) | TAG_SAMPLE, k0, k1, x);
+        philox4x32_10(v0 >> 2, pos, d.rng, ((uint32_t)lstep << 4) | TAG_SAMPLE, k0, k1, x);
         const float4 l = ld4(lg + v0);
         const float lv[4] = {l.x, l.y, l.z, l.w};
 #pragma unroll
@@ -705,12 +711,12 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
 }
 
 // End of a sampler step, one workgroup per sequence (its rows in parallel): the drafts become
-// y_current and the step counters advance (Alg. 1 line 13), the longest freezable prefix k* is
-// frozen (Alg. 1 line 14 / Eq. 3), new states are appended unless the wavefront is full (Alg. 1
-// line 16, Alg. 2) and drawn (InitState).  The last workgroup to finish then builds the tile list
+// y_current and the step counters advance (Alg. 1, assign), the longest freezable prefix k* is
+// frozen (Alg. 1 freeze / Eq. 3), new states are appended unless the wavefront is full (Alg. 1
+// append, Alg. 2) and drawn (InitState).  The last workgroup to finish then builds the tile list
 // of the next step from all updated windows: the sequence records are handed over with
 // system-scope stores and loads around a ticket (no device-scope fence), as the GEMM folds are.
-__global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y,
+__global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y,
                                                    int32_t* counts, int max_positions, const int32_t* drafts,
                                                    const float* delta, float* z, float* z_prev, int h,
                                                    TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step,
@@ -780,7 +786,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
                 if (p.init_mode == 1) {
                     for (int i = 0; i < 4 && blk * 4 + i < h; ++i) g[i] = z[left + blk * 4 + i];
                 } else {
-                    gauss4(blk, pos, s, p.seed_lo, p.seed_hi, p.alpha, g);
+                    gauss4(blk, pos, ident[s], p.seed_lo, p.seed_hi, p.alpha, g);
                 }
                 for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
                     const size_t o = (base + pos) * h + blk * 4 + i;
@@ -817,6 +823,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, int n_seqs, Sa
                 for (int off = 0; off < rows; off += TILE_ROWS) {
                     TileDesc d;
                     d.seq = sq;
+                    d.rng = ident[sq];
                     d.pos0 = s_pos0[j] + off;
                     d.n_valid = min(TILE_ROWS, rows - off);
                     d.zrow0 = d.yrow0 = sq * max_positions + d.pos0;
@@ -854,7 +861,8 @@ __global__ void seq_join_k(SeqState* seqs, int32_t* seq_step0, int seq, int prom
 __global__ void seq_retire_k(SeqState* seqs, int seq, int prompt_len) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     SeqState& q = seqs[seq];
-    q.done = 1; q.win_n = 0; q.cur_rows = 0; q.last_rows = 0; q.prompt_len = prompt_len; q.n_frozen = prompt_len;
+    q.done = 1; q.win_n = 0; q.cur_rows = 0; q.last_rows = 0;
+    if (prompt_len >= 0) { q.prompt_len = prompt_len; q.n_frozen = prompt_len; }   // < 0: the text stays readable
 }
 
 __global__ void fill_i32_k(int32_t* p, int32_t v, size_t n) {
@@ -863,35 +871,46 @@ __global__ void fill_i32_k(int32_t* p, int32_t v, size_t n) {
 }
 
 template <int DT>
-__global__ void read_kv_k(const void* kc, const void* vc, int H, int d, int pos0, int n, float* k_out, float* v_out) {
+__global__ void read_kv_k(const void* kc, const void* vc, KvPages kv, int seq, int H, int d, int pos0, int n, float* k_out,
+                          float* v_out) {
     int i = blockIdx.x, pos = pos0 + i, h = H * d;
+    const size_t base = kv_block_base(kv, seq, pos >> 5, (size_t)32 * h);
     for (int c = threadIdx.x; c < h; c += blockDim.x) {
         if (DT == 0) {
-            k_out[(size_t)i * h + c] = reinterpret_cast<const float*>(kc)[(size_t)pos * h + c];
-            v_out[(size_t)i * h + c] = reinterpret_cast<const float*>(vc)[(size_t)pos * h + c];
+            k_out[(size_t)i * h + c] = reinterpret_cast<const float*>(kc)[base + (size_t)(pos & 31) * h + c];
+            v_out[(size_t)i * h + c] = reinterpret_cast<const float*>(vc)[base + (size_t)(pos & 31) * h + c];
         } else {
             int hd = c / d, dd = c - hd * d;
-            k_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(kc)[k_cache_off(pos, hd, dd, H, d)]);
+            k_out[(size_t)i * h + c] =
+                bf16_to_f32(reinterpret_cast<const uint16_t*>(kc)[base + k_cache_off(pos & 31, hd, dd, H, d)]);
             v_out[(size_t)i * h + c] = bf16_to_f32(reinterpret_cast<const uint16_t*>(vc)[
-                (((size_t)(pos >> 5) * H + hd) * d + dd) * 32 + vt_slot(pos & 31)]);
+                base + ((size_t)hd * d + dd) * 32 + vt_slot(pos & 31)]);
         }
     }
+}
+
+__global__ void table_set_k(int32_t* table, BlockIds ids) {
+    if ((int)threadIdx.x < ids.n) table[ids.first + threadIdx.x] = ids.id[threadIdx.x];
 }
 
 // ---------------------------------------------------------------------------------------------
 // launchers
 
-void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, 0, 0, tiles, n_tiles);
+void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, ident, 0, 0, tiles, n_tiles);
 }
-void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* tiles, int32_t* n_tiles,
-                              hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, 1, max_positions, tiles, n_tiles);
+void launch_build_tiles_store(const SeqWindows& w, const int32_t* ident, int max_positions, TileDesc* tiles,
+                              int32_t* n_tiles, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, ident, 1, max_positions, tiles, n_tiles);
 }
-void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions, TileDesc* tiles,
+void launch_build_tiles_sampler(const SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions, TileDesc* tiles,
                                 int32_t* n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_sampler_k, dim3(1), dim3(64), 0, st, const_cast<SeqState*>(seqs), n_seqs,
+    hipLaunchKernelGGL(build_tiles_sampler_k, dim3(1), dim3(64), 0, st, const_cast<SeqState*>(seqs), ident, n_seqs,
                        max_positions, tiles, n_tiles);
+}
+void launch_table_set(int32_t* table, BlockIds ids, hipStream_t st) {
+    if (ids.n <= 0) return;
+    hipLaunchKernelGGL(table_set_k, dim3(1), dim3(64), 0, st, table, ids);
 }
 void launch_embed(const void* emb, int dtype, const int32_t* tokens, float scale, float* x, int h, int V,
                   float* rope_table, const float* theta, int half, const float* gain, void* xg, float* ssq,
@@ -973,16 +992,16 @@ void launch_rope_table(float* table, const float* theta, int half, const TileDes
                        half, tiles, n_tiles);
 }
 void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc, int dtype,
-                    int H, int d, const float* table, size_t seq_stride_elems, const TileDesc* tiles,
+                    int H, int d, const float* table, KvPages kv, const TileDesc* tiles,
                     const int32_t* n_tiles, int max_tiles, hipStream_t st) {
     const size_t lds = (size_t)32 * (d + 1) * sizeof(float);
     const float2* tb = reinterpret_cast<const float2*>(table);
     if (dtype == 0)
         hipLaunchKernelGGL(rope_kv_k<0>, dim3(H, max_tiles), dim3(256), lds, st, qkv, S, part_stride, q, kc, vc, H, d,
-                           tb, seq_stride_elems, tiles, n_tiles);
+                           tb, kv, tiles, n_tiles);
     else
         hipLaunchKernelGGL(rope_kv_k<1>, dim3(H, max_tiles), dim3(256), lds, st, qkv, S, part_stride, q, kc, vc, H, d,
-                           tb, seq_stride_elems, tiles, n_tiles);
+                           tb, kv, tiles, n_tiles);
 }
 void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
                    const int32_t* n_tiles, int max_tiles, hipStream_t st) {
@@ -1021,10 +1040,10 @@ void launch_sample_top_p(const float* logits, int V, float temperature, float to
     hipLaunchKernelGGL(sample_top_p_k, dim3(max_tiles * 32), dim3(TOPP_THREADS), 0, st, logits, V, temperature, top_p,
                        k0, k1, step, seq_step0, tok_out, tiles, n_tiles);
 }
-void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
-                     const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
-                     int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st) {
-    hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(256), 0, st, seqs, n_seqs, p, y, counts, max_positions, drafts,
+void launch_step_end(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
+                     int max_positions, const int32_t* drafts, const float* delta, float* z, float* z_prev, int h,
+                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st) {
+    hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(256), 0, st, seqs, ident, n_seqs, p, y, counts, max_positions, drafts,
                        delta, z, z_prev, h, tiles, n_tiles, n_active, step, ticket);
 }
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st) {
@@ -1037,11 +1056,13 @@ void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st) {
     if (!n) return;
     hipLaunchKernelGGL(fill_i32_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
 }
-void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n, float* k_out,
-                    float* v_out, hipStream_t st) {
+void launch_read_kv(const void* kc, const void* vc, KvPages kv, int seq, int dtype, int H, int d, int pos0, int n,
+                    float* k_out, float* v_out, hipStream_t st) {
     if (n <= 0) return;
-    if (dtype == 0) hipLaunchKernelGGL(read_kv_k<0>, dim3(n), dim3(256), 0, st, kc, vc, H, d, pos0, n, k_out, v_out);
-    else hipLaunchKernelGGL(read_kv_k<1>, dim3(n), dim3(256), 0, st, kc, vc, H, d, pos0, n, k_out, v_out);
+    if (dtype == 0)
+        hipLaunchKernelGGL(read_kv_k<0>, dim3(n), dim3(256), 0, st, kc, vc, kv, seq, H, d, pos0, n, k_out, v_out);
+    else
+        hipLaunchKernelGGL(read_kv_k<1>, dim3(n), dim3(256), 0, st, kc, vc, kv, seq, H, d, pos0, n, k_out, v_out);
 }
 
 }  // namespace rdlm

@@ -21,8 +21,8 @@ struct Layer {
     void* wo = nullptr;
     void* wgu = nullptr;     // gate rows then up rows: [2F, h]
     void* wd = nullptr;
-    void* kc = nullptr;      // K cache: f32 [max_seqs][ctx_pad][H][d]; bf16 per 32-position block in operand order (k_cache_off)
-    void* vc = nullptr;      // V cache: f32 same layout; bf16 transposed per 32-position block
+    void* kc = nullptr;      // K pool: [kv_pool_blocks] blocks of 32 positions; f32 [32][H][d], bf16 in operand order (k_cache_off)
+    void* vc = nullptr;      // V pool: f32 same layout; bf16 transposed per block
 };
 
 enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT };
@@ -81,6 +81,14 @@ struct rdlm_ctx : Workspace {
     float* theta = nullptr;
     int ssq_count = 0;              // slots per row the last producer of the normalised operand filled
     int att_max_split = 8;
+    // paged KV cache: block table (device and host copy), free list, blocks held per slot
+    int32_t* blk_table = nullptr;        // [max_seqs][blocks_per_seq] physical block of each logical block
+    int blocks_per_seq = 0, kv_pool_blocks = 0;
+    std::vector<int32_t> tbl_host;
+    std::vector<int> free_blocks, seq_blocks;
+    std::vector<int> pos_bound;          // sampler: positions a sequence may have reached before the next step
+    int32_t* seq_ident = nullptr;        // [max_seqs] identity of the slot's sequence in the random generator's counters
+    std::vector<int32_t> ident_host;
     // sampler state
     SeqState* seqs = nullptr;
     int32_t* y = nullptr;
@@ -282,7 +290,7 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp, void* workspace) {
     ++wi;
     const int nl = m.n_prelude + m.n_core + m.n_coda;
     ctx->layers.resize(nl);
-    const size_t cache_elems = (size_t)ctx->max_seqs * ctx->ctx_pad * h;
+    const size_t cache_elems = (size_t)ctx->kv_pool_blocks * 32 * h;
     for (int l = 0; l < nl; ++l) {
         Layer& L = ctx->layers[l];
         if ((rc = take_gain(ctx, wp[wi++], h, &L.g1))) return rc;
@@ -324,6 +332,18 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp, void* workspace) {
         carve_workspace(ctx, slab, m, ctx->max_tiles, ctx->att_max_split, true);
         launch_fill_i32(reinterpret_cast<int32_t*>(slab), 0, need / 4, ctx->st);
     }
+    // block table: every entry names a valid block (0) until a block is assigned, so that a clamped read
+    // of an entry that no sequence owns yet stays inside the pool
+    DALLOC(ctx->blk_table, (size_t)ctx->max_seqs * ctx->blocks_per_seq * 4, true);
+    ctx->tbl_host.assign((size_t)ctx->max_seqs * ctx->blocks_per_seq, 0);
+    ctx->seq_blocks.assign(ctx->max_seqs, 0);
+    ctx->pos_bound.assign(ctx->max_seqs, 0);
+    ctx->free_blocks.resize(ctx->kv_pool_blocks);
+    for (int i = 0; i < ctx->kv_pool_blocks; ++i) ctx->free_blocks[i] = ctx->kv_pool_blocks - 1 - i;   // block 0 goes out first
+    DALLOC(ctx->seq_ident, 4 * ctx->max_seqs + 64, true);
+    ctx->ident_host.resize(ctx->max_seqs);
+    for (int q = 0; q < ctx->max_seqs; ++q) ctx->ident_host[q] = q;
+    HIPCHK(hipMemcpy(ctx->seq_ident, ctx->ident_host.data(), 4 * ctx->max_seqs, hipMemcpyHostToDevice));
     // sampler state
     const size_t SP = (size_t)ctx->max_seqs * ctx->max_positions;
     DALLOC(ctx->seqs, sizeof(SeqState) * ctx->max_seqs, true);
@@ -445,9 +465,9 @@ extern "C" size_t rdlm_workspace_bytes(const rdlm_model* m, int32_t max_seqs, in
     return carve_workspace(nullptr, nullptr, *m, tiles_for(max_seqs, max_rows), 8, true);
 }
 
-extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
-                              int32_t max_positions, int32_t max_rows, void* hip_stream, void* workspace,
-                              size_t workspace_bytes, rdlm_ctx** out) {
+static int create_any(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs, int32_t max_positions,
+                      int32_t max_rows, int32_t kv_pool_positions, void* hip_stream, void* workspace,
+                      size_t workspace_bytes, rdlm_ctx** out) {
     if (!out) return RDLM_EINVAL;
     *out = nullptr;
     if (!model_ok(m) || !weight_ptrs) return RDLM_EINVAL;
@@ -464,6 +484,9 @@ extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptr
     ctx->max_seqs = max_seqs;
     ctx->max_positions = max_positions;
     ctx->ctx_pad = (max_positions + 31) / 32 * 32;
+    ctx->blocks_per_seq = ctx->ctx_pad / 32;
+    // pool: by default every slot can reach max_positions at once; a smaller pool is shared by need
+    ctx->kv_pool_blocks = kv_pool_positions > 0 ? (kv_pool_positions + 31) / 32 : max_seqs * ctx->blocks_per_seq;
     ctx->max_rows = max_rows;
     ctx->max_tiles = tiles_for(max_seqs, max_rows);
     ctx->rows_pad = ctx->max_tiles * 32;
@@ -483,9 +506,83 @@ extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptr
     return RDLM_OK;
 }
 
+extern "C" int rdlm_create_ws(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                              int32_t max_positions, int32_t max_rows, void* hip_stream, void* workspace,
+                              size_t workspace_bytes, rdlm_ctx** out) {
+    return create_any(m, weight_ptrs, max_seqs, max_positions, max_rows, 0, hip_stream, workspace, workspace_bytes, out);
+}
+
 extern "C" int rdlm_create(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
                            int32_t max_positions, int32_t max_rows, void* hip_stream, rdlm_ctx** out) {
-    return rdlm_create_ws(m, weight_ptrs, max_seqs, max_positions, max_rows, hip_stream, nullptr, 0, out);
+    return create_any(m, weight_ptrs, max_seqs, max_positions, max_rows, 0, hip_stream, nullptr, 0, out);
+}
+
+extern "C" int rdlm_create_paged(const rdlm_model* m, const void* const* weight_ptrs, int32_t max_seqs,
+                                 int32_t max_positions, int32_t max_rows, int32_t kv_pool_positions, void* hip_stream,
+                                 rdlm_ctx** out) {
+    if (kv_pool_positions < 32) return RDLM_EINVAL;
+    return create_any(m, weight_ptrs, max_seqs, max_positions, max_rows, kv_pool_positions, hip_stream, nullptr, 0, out);
+}
+
+// ---------------------------------------------------------------------------------------------
+// paged KV cache: host-side block bookkeeping
+
+static KvPages kv_pages(const rdlm_ctx* ctx) {
+    KvPages kv;
+    kv.table = ctx->blk_table;
+    kv.stride = ctx->blocks_per_seq;
+    return kv;
+}
+
+// Make sure the slot owns blocks for positions [0, n_positions).  New table entries are enqueued on the
+// stream (a small kernel, entries by value), i.e. ordered before the kernels that use them.
+static int ensure_blocks(rdlm_ctx* ctx, int seq, int n_positions) {
+    const int need = (std::min(n_positions, ctx->ctx_pad) + 31) / 32;
+    int have = ctx->seq_blocks[seq];
+    if (need <= have) return RDLM_OK;
+    if (need - have > (int)ctx->free_blocks.size()) return RDLM_ECAPACITY;     // pool exhausted: nothing taken
+    while (have < need) {
+        BlockIds ids;
+        ids.n = 0;
+        ids.first = seq * ctx->blocks_per_seq + have;
+        while (have < need && ids.n < 16) {
+            const int id = ctx->free_blocks.back();
+            ctx->free_blocks.pop_back();
+            ctx->tbl_host[(size_t)seq * ctx->blocks_per_seq + have] = id;
+            ids.id[ids.n++] = id;
+            ++have;
+        }
+        launch_table_set(ctx->blk_table, ids, ctx->st);
+    }
+    ctx->seq_blocks[seq] = have;
+    return RDLM_OK;
+}
+
+static void release_blocks(rdlm_ctx* ctx, int seq) {
+    for (int b = ctx->seq_blocks[seq] - 1; b >= 0; --b)
+        ctx->free_blocks.push_back(ctx->tbl_host[(size_t)seq * ctx->blocks_per_seq + b]);
+    ctx->seq_blocks[seq] = 0;
+}
+
+extern "C" int rdlm_kv_blocks(const rdlm_ctx* ctx, int32_t* total_out, int32_t* free_out) {
+    if (!ctx) return RDLM_EINVAL;
+    if (total_out) *total_out = ctx->kv_pool_blocks;
+    if (free_out) *free_out = (int32_t)ctx->free_blocks.size();
+    return RDLM_OK;
+}
+
+extern "C" int rdlm_seq_release(rdlm_ctx* ctx, int32_t seq) {
+    if (!ctx || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));          // nothing in flight may still read the blocks
+    if (ctx->sampler_on) {
+        launch_seq_retire(ctx->seqs, seq, -1, ctx->st);         // frozen text stays readable
+        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
+                                   ctx->n_tiles_samp, ctx->st);
+    }
+    release_blocks(ctx, seq);
+    ctx->pos_bound[seq] = 0;
+    return check_launch(ctx);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -664,7 +761,7 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
         // RoPE and the cache writes happen in the GEMM epilogue
         epi.kind = EPI_ROPE_KV;
         epi.q_out = ctx->q; epi.kc = rope_layer->kc; epi.vc = rope_layer->vc; epi.rope_table = ctx->rope_tab;
-        epi.seq_stride = (size_t)ctx->ctx_pad * h;
+        epi.kv = kv_pages(ctx);
         epi.tiles = ctx->tiles;
     } else if (!plain && proj == PROJ_HEAD && sa) {
         epi.kind = EPI_ARGMAX;
@@ -784,8 +881,8 @@ static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, boo
     PROPAGATE(run_proj(ctx, PROJ_QKV, ctx->xn, L.wqkv, T, &S, nullptr, false, dn, &L, &rope_done));
     if (!rope_done)
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
-                       (size_t)ctx->ctx_pad * h, ctx->tiles, ctx->n_tiles, T, st);
-    launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, (size_t)ctx->ctx_pad * h,
+                       kv_pages(ctx), ctx->tiles, ctx->n_tiles, T, st);
+    launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, kv_pages(ctx),
                      att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
                      ctx->n_tiles, T, st);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
@@ -890,7 +987,7 @@ static int coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int
 // ---------------------------------------------------------------------------------------------
 // argument checking shared by the row-based calls
 
-static int check_rows(const rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const int32_t* pos0,
+static int check_rows(rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const int32_t* pos0,
                       const int32_t* n_rows, SeqWindows* w, int* T, int* M, int* max_keys) {
     if (!ctx || !seq_ids || !pos0 || !n_rows || n_seqs < 1) return RDLM_EINVAL;
     if (n_seqs > MAX_API_SEQS) return RDLM_ECAPACITY;
@@ -911,7 +1008,16 @@ static int check_rows(const rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, c
     *T = tiles; *M = rows; *max_keys = mk;
     bool grouped = false;
     for (int i = 0; i < n_seqs; ++i) grouped = grouped || n_rows[i] > TILE_ROWS;
-    const_cast<rdlm_ctx*>(ctx)->grouped = grouped;
+    ctx->grouped = grouped;
+    // cache blocks for the rows' positions (the rows attend to everything before them: blocks from 0 on)
+    int need = 0;
+    for (int i = 0; i < n_seqs; ++i)
+        need += std::max(0, (pos0[i] + n_rows[i] + 31) / 32 - ctx->seq_blocks[seq_ids[i]]);
+    if (need > (int)ctx->free_blocks.size()) return RDLM_ECAPACITY;
+    for (int i = 0; i < n_seqs; ++i) {
+        int rc = ensure_blocks(ctx, seq_ids[i], pos0[i] + n_rows[i]);
+        if (rc) return rc;
+    }
     return RDLM_OK;
 }
 
@@ -927,9 +1033,12 @@ extern "C" int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens
     HIPCHK(hipStreamSynchronize(ctx->st));
     HIPCHK(hipMemcpy(ctx->y + base, tokens_host, (size_t)n * 4, hipMemcpyHostToDevice));
     ctx->prompt_len[seq] = n;
+    ctx->pos_bound[seq] = 0;
+    ctx->ident_host[seq] = seq;         // a slot that starts over is its own sequence again
+    launch_fill_i32(ctx->seq_ident + seq, seq, 1, ctx->st);
     if (ctx->sampler_on) {          // the slot leaves the running sampler until it joins again
         launch_seq_retire(ctx->seqs, seq, n, ctx->st);
-        launch_build_tiles_sampler(ctx->seqs, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp,
+        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp,
                                    ctx->st);
     }
     return check_launch(ctx);
@@ -939,13 +1048,14 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     if (!ctx || seq < 0 || n < 0 || r < 0) return RDLM_EINVAL;
     if (seq >= ctx->max_seqs || n > ctx->max_rows || n > ctx->max_positions) return RDLM_ECAPACITY;
     if (n == 0) return RDLM_OK;
+    PROPAGATE(ensure_blocks(ctx, seq, n));
     SeqWindows w;
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
-    launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
-    launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, 0, n, (size_t)seq * ctx->max_positions, alpha,
-                           (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
+    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, ctx->ident_host[seq], 0, n,
+                           (size_t)seq * ctx->max_positions, alpha, (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
     PROPAGATE(prelude_forward(ctx, ctx->y, ctx->e, -1, T, n));
     for (int i = 0; i < r; ++i) PROPAGATE(core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n));
     PROPAGATE(coda_forward(ctx, ctx->z_store, nullptr, T, n));
@@ -967,7 +1077,7 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
     if (!tokens_dev || !e_out) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
-    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
     PROPAGATE(prelude_forward(ctx, tokens_dev, e_out, 1, T, mk));
     return check_launch(ctx);
 }
@@ -975,7 +1085,7 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
 // the body of rdlm_core_step over whatever workspace the context currently points at
 static int core_step_run(rdlm_ctx* ctx, const SeqWindows& w, int T, int M, int mk, const float* e, float* z_inout,
                          int r_inner, float* delta_out) {
-    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (delta_out)
         HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
@@ -1051,7 +1161,7 @@ extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* se
     if (ctx && top_p > 0.f && top_p < 1.f && (ctx->m.vocab > TOPP_MAX_VOCAB || ctx->m.vocab % 4)) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
-    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr, nullptr, top_p};
     PROPAGATE(coda_forward(ctx, z, &sa, T, mk));
@@ -1080,22 +1190,26 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
         if (ctx->prompt_len[q] < 1) return RDLM_ESTATE;
         if ((long long)ctx->prompt_len[q] + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
     }
+    for (int q = 0; q < n_seqs; ++q) {                  // the first state sits at position L - 1
+        PROPAGATE(ensure_blocks(ctx, q, ctx->prompt_len[q]));
+        ctx->pos_bound[q] = ctx->prompt_len[q];
+    }
     HIPCHK(hipStreamSynchronize(ctx->st));
     std::vector<SeqState> hs(ctx->max_seqs);            // slots beyond n_seqs: finished, no rows
     memset(hs.data(), 0, sizeof(SeqState) * ctx->max_seqs);
-    for (int q = n_seqs; q < ctx->max_seqs; ++q) hs[q].done = 1;
+    for (int q = n_seqs; q < ctx->max_seqs; ++q) { hs[q].done = 1; ctx->pos_bound[q] = 0; }
     for (int q = 0; q < n_seqs; ++q) {
         const int L = ctx->prompt_len[q];
         hs[q].prompt_len = L; hs[q].n_frozen = L; hs[q].win_pos0 = L - 1; hs[q].win_n = 1;
         size_t base = (size_t)q * ctx->max_positions;
         launch_fill_i32(ctx->y + base + L, sp.pad_token, ctx->max_positions - L, ctx->st);
         launch_fill_i32(ctx->counts + base, 0, ctx->max_positions, ctx->st);
-        launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, q, L - 1, 1, base + L - 1, sp.alpha,
-                               (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
+        launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, ctx->ident_host[q], L - 1, 1, base + L - 1,
+                               sp.alpha, (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
     }
     launch_fill_i32(ctx->seq_step0, 0, ctx->max_seqs, ctx->st);
     HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * ctx->max_seqs, hipMemcpyHostToDevice));
-    launch_build_tiles_sampler(ctx->seqs, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
+    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
     int32_t act[3] = {n_seqs, 0, 0};
     HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
     ctx->sampler = sp;
@@ -1122,15 +1236,162 @@ extern "C" int rdlm_sampler_join(rdlm_ctx* ctx, int32_t seq) {
     if ((long long)L + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
     const int n = std::max(ctx->samp_seqs, seq + 1);
     if (n * ((sp.w_max + 31) / 32) > ctx->max_tiles || n * sp.w_max > ctx->max_rows) return RDLM_ECAPACITY;
+    PROPAGATE(ensure_blocks(ctx, seq, L));
+    ctx->pos_bound[seq] = L;
     const size_t base = (size_t)seq * ctx->max_positions;
     launch_fill_i32(ctx->y + base + L, sp.pad_token, ctx->max_positions - L, ctx->st);
     launch_fill_i32(ctx->counts + base, 0, ctx->max_positions, ctx->st);
-    launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, seq, L - 1, 1, base + L - 1, sp.alpha,
-                           (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
+    launch_init_state_rows(ctx->z_store, ctx->z_prev, ctx->m.hidden, ctx->ident_host[seq], L - 1, 1, base + L - 1,
+                           sp.alpha, (uint32_t)sp.seed, (uint32_t)(sp.seed >> 32), ctx->st);
     launch_seq_join(ctx->seqs, ctx->seq_step0, seq, L, ctx->step, ctx->st);
     ctx->samp_seqs = n;
     ctx->joined = true;
-    launch_build_tiles_sampler(ctx->seqs, n, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
+    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
+    return check_launch(ctx);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eviction and re-admission of a sequence (App. "Larger batch sizes": hidden-state slots are fungible,
+// can be evicted from a device and bundled into a later forward call, possibly elsewhere).  What makes
+// up a sequence is copied to host memory as it is -- its cache blocks of every layer, its latents,
+// z_prev, conditioning, tokens, step counters and window record -- and its blocks go back to the pool;
+// re-admission puts the same bytes into whatever blocks and slot are free, so the sequence goes on
+// exactly as if it had never left (its random draws are keyed by its identity, not by the slot).
+
+struct EvictHeader {
+    uint32_t magic, version;
+    rdlm_model model;
+    int32_t n_pos, n_blocks, prompt_len, ident, in_sampler, local_steps, pos_bound, pad;
+    SeqState st;
+    rdlm_sampler sampler;
+};
+constexpr uint32_t EVICT_MAGIC = 0x4d4c4452u;   // "RDLM"
+
+static size_t evict_bytes(const rdlm_ctx* ctx, int n_pos, int n_blocks) {
+    const size_t h = ctx->m.hidden;
+    return sizeof(EvictHeader) + (size_t)n_pos * 4 * 2 + (size_t)3 * n_pos * h * 4 +
+           (size_t)ctx->layers.size() * 2 * n_blocks * 32 * h * ctx->esz;
+}
+
+// Rows of the per-position stores worth keeping: every cached position, the prompt, and the window, which
+// may already reach one step beyond the cached positions (plus the draft of its last position).
+static int evict_rows(const rdlm_ctx* ctx, int seq) {
+    const int reach = ctx->pos_bound[seq] > 0 ? ctx->pos_bound[seq] + 1 : 0;
+    return std::min(ctx->max_positions, std::max({ctx->seq_blocks[seq] * 32, ctx->prompt_len[seq], reach}));
+}
+
+extern "C" size_t rdlm_seq_evict_bytes(const rdlm_ctx* ctx, int32_t seq) {
+    if (!ctx || seq < 0 || seq >= ctx->max_seqs) return 0;
+    return evict_bytes(ctx, evict_rows(ctx, seq), ctx->seq_blocks[seq]);
+}
+
+extern "C" int rdlm_seq_evict(rdlm_ctx* ctx, int32_t seq, void* host_buf, size_t cap) {
+    if (!ctx || !host_buf || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    const int nb = ctx->seq_blocks[seq];
+    const int n_pos = evict_rows(ctx, seq);
+    if (cap < evict_bytes(ctx, n_pos, nb)) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    EvictHeader hd;
+    memset(&hd, 0, sizeof hd);
+    hd.magic = EVICT_MAGIC; hd.version = 1; hd.model = ctx->m;
+    hd.n_pos = n_pos; hd.n_blocks = nb; hd.prompt_len = ctx->prompt_len[seq]; hd.ident = ctx->ident_host[seq];
+    hd.pos_bound = ctx->pos_bound[seq];
+    hd.in_sampler = ctx->sampler_on && seq < ctx->samp_seqs && ctx->pos_bound[seq] > 0;
+    if (hd.in_sampler) {
+        int32_t step0 = 0;
+        HIPCHK(hipMemcpy(&hd.st, ctx->seqs + seq, sizeof(SeqState), hipMemcpyDeviceToHost));
+        HIPCHK(hipMemcpy(&step0, ctx->seq_step0 + seq, 4, hipMemcpyDeviceToHost));
+        hd.local_steps = ctx->step - step0;
+        hd.sampler = ctx->sampler;
+    }
+    char* out = static_cast<char*>(host_buf);
+    memcpy(out, &hd, sizeof hd); out += sizeof hd;
+    const size_t h = ctx->m.hidden, row0 = (size_t)seq * ctx->max_positions;
+    auto take = [&](const void* dev, size_t bytes) -> int {
+        if (bytes) HIPCHK(hipMemcpy(out, dev, bytes, hipMemcpyDeviceToHost));
+        out += bytes;
+        return RDLM_OK;
+    };
+    PROPAGATE(take(ctx->y + row0, (size_t)n_pos * 4));
+    PROPAGATE(take(ctx->counts + row0, (size_t)n_pos * 4));
+    PROPAGATE(take(ctx->z_store + row0 * h, (size_t)n_pos * h * 4));
+    PROPAGATE(take(ctx->z_prev + row0 * h, (size_t)n_pos * h * 4));
+    PROPAGATE(take(ctx->e_store + row0 * h, (size_t)n_pos * h * 4));
+    const size_t blk_bytes = (size_t)32 * h * ctx->esz;
+    for (const Layer& L : ctx->layers)
+        for (const void* pool : {L.kc, L.vc})
+            for (int b = 0; b < nb; ++b)
+                PROPAGATE(take(static_cast<const char*>(pool) + (size_t)ctx->tbl_host[(size_t)seq * ctx->blocks_per_seq + b] * blk_bytes,
+                               blk_bytes));
+    // the slot is empty from here on
+    if (ctx->sampler_on) {
+        launch_seq_retire(ctx->seqs, seq, 0, ctx->st);
+        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
+                                   ctx->n_tiles_samp, ctx->st);
+    }
+    release_blocks(ctx, seq);
+    ctx->pos_bound[seq] = 0;
+    ctx->prompt_len[seq] = 0;
+    return check_launch(ctx);
+}
+
+extern "C" int rdlm_seq_admit(rdlm_ctx* ctx, int32_t seq, const void* host_buf, size_t bytes) {
+    if (!ctx || !host_buf || seq < 0 || bytes < sizeof(EvictHeader)) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    EvictHeader hd;
+    memcpy(&hd, host_buf, sizeof hd);
+    if (hd.magic != EVICT_MAGIC || hd.version != 1 || memcmp(&hd.model, &ctx->m, sizeof(rdlm_model)) != 0) return RDLM_EINVAL;
+    if (hd.n_pos < 0 || hd.n_blocks < 0 || bytes < evict_bytes(ctx, hd.n_pos, hd.n_blocks))
+        return RDLM_EINVAL;
+    if (hd.n_pos > ctx->max_positions || hd.n_blocks > ctx->blocks_per_seq) return RDLM_ECAPACITY;
+    if (ctx->seq_blocks[seq] != 0 || ctx->pos_bound[seq] > 0) return RDLM_ESTATE;       // the slot must be empty (released)
+    if (hd.in_sampler) {
+        if (!ctx->sampler_on || memcmp(&hd.sampler, &ctx->sampler, sizeof(rdlm_sampler)) != 0) return RDLM_ESTATE;
+        const rdlm_sampler& sp = ctx->sampler;
+        const int n = std::max(ctx->samp_seqs, seq + 1);
+        if (n * ((sp.w_max + 31) / 32) > ctx->max_tiles || n * sp.w_max > ctx->max_rows) return RDLM_ECAPACITY;
+        if ((long long)hd.prompt_len + sp.n_new + sp.w_max + sp.headway + 1 > ctx->max_positions) return RDLM_ECAPACITY;
+    }
+    if (hd.n_blocks > (int)ctx->free_blocks.size()) return RDLM_ECAPACITY;
+    PROPAGATE(ensure_blocks(ctx, seq, hd.n_blocks * 32));
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    const char* in = static_cast<const char*>(host_buf) + sizeof hd;
+    const size_t h = ctx->m.hidden, row0 = (size_t)seq * ctx->max_positions;
+    auto put = [&](void* dev, size_t nbytes) -> int {
+        if (nbytes) HIPCHK(hipMemcpy(dev, in, nbytes, hipMemcpyHostToDevice));
+        in += nbytes;
+        return RDLM_OK;
+    };
+    const int pad = ctx->sampler_on ? ctx->sampler.pad_token : 0;
+    launch_fill_i32(ctx->y + row0, pad, ctx->max_positions, ctx->st);
+    launch_fill_i32(ctx->counts + row0, 0, ctx->max_positions, ctx->st);
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    PROPAGATE(put(ctx->y + row0, (size_t)hd.n_pos * 4));
+    PROPAGATE(put(ctx->counts + row0, (size_t)hd.n_pos * 4));
+    PROPAGATE(put(ctx->z_store + row0 * h, (size_t)hd.n_pos * h * 4));
+    PROPAGATE(put(ctx->z_prev + row0 * h, (size_t)hd.n_pos * h * 4));
+    PROPAGATE(put(ctx->e_store + row0 * h, (size_t)hd.n_pos * h * 4));
+    const size_t blk_bytes = (size_t)32 * h * ctx->esz;
+    for (const Layer& L : ctx->layers)
+        for (void* pool : {L.kc, L.vc})
+            for (int b = 0; b < hd.n_blocks; ++b)
+                PROPAGATE(put(static_cast<char*>(pool) + (size_t)ctx->tbl_host[(size_t)seq * ctx->blocks_per_seq + b] * blk_bytes,
+                              blk_bytes));
+    ctx->prompt_len[seq] = hd.prompt_len;
+    ctx->ident_host[seq] = hd.ident;
+    launch_fill_i32(ctx->seq_ident + seq, hd.ident, 1, ctx->st);
+    if (hd.in_sampler) {
+        HIPCHK(hipMemcpy(ctx->seqs + seq, &hd.st, sizeof(SeqState), hipMemcpyHostToDevice));
+        launch_fill_i32(ctx->seq_step0 + seq, ctx->step - hd.local_steps, 1, ctx->st);
+        ctx->pos_bound[seq] = hd.pos_bound;
+        ctx->samp_seqs = std::max(ctx->samp_seqs, seq + 1);
+        ctx->joined = true;
+        // (the device's count of unfinished sequences is brought up to date by the next step's bookkeeping)
+        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
+                                   ctx->n_tiles_samp, ctx->st);
+    }
+    HIPCHK(hipStreamSynchronize(ctx->st));
     return check_launch(ctx);
 }
 
@@ -1139,8 +1400,23 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     if (!ctx->sampler_on) return RDLM_ESTATE;
     const rdlm_sampler& s = ctx->sampler;
     const rdlm_model& m = ctx->m;
-    const int t = ++ctx->step;
     const int n = ctx->samp_seqs;
+    // cache blocks for the positions the windows may cover in this step (a window ends at most `headway`
+    // positions further on after every step); a pool that cannot supply them refuses the step before
+    // anything is enqueued -- release or evict a sequence and call again
+    {
+        int need = 0;
+        for (int q = 0; q < n; ++q)
+            if (ctx->pos_bound[q] > 0) need += std::max(0, (ctx->pos_bound[q] + 31) / 32 - ctx->seq_blocks[q]);
+        if (need > (int)ctx->free_blocks.size()) return RDLM_ECAPACITY;
+        for (int q = 0; q < n; ++q) {
+            if (ctx->pos_bound[q] <= 0) continue;       // slot not in the sampler
+            PROPAGATE(ensure_blocks(ctx, q, ctx->pos_bound[q]));
+            const int cap = std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max + s.headway);
+            ctx->pos_bound[q] = std::min(cap, ctx->pos_bound[q] + s.headway);
+        }
+    }
+    const int t = ++ctx->step;
     // upper bound of the wave size at this step: it grows by at most `headway` per step, and a
     // state stays at most ceil(r / r') steps (then it and every older state are freezable), so no
     // more than that many generations of `headway` states are in flight -- also under the
@@ -1183,7 +1459,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
         return rc;
     }
     // freeze, append, InitState of the appended positions, tile list of the next step
-    launch_step_end(ctx->seqs, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
+    launch_step_end(ctx->seqs, ctx->seq_ident, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
                     ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->step_ticket,
                     ctx->st);
     std::swap(ctx->tiles, ctx->tiles_samp);
@@ -1315,14 +1591,21 @@ extern "C" int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t p
     if ((size_t)n * h * 2 > (size_t)ctx->rows_pad * 2 * ctx->m.mlp) return RDLM_ECAPACITY;   // staged in gu
     HIPCHK(hipStreamSynchronize(ctx->st));
     const Layer& L = ctx->layers[layer];
-    size_t off = (size_t)seq * ctx->ctx_pad * h * ctx->esz;
+    // positions beyond the slot's blocks have no entries yet (a window's newest positions get theirs in the
+    // step that computes them): they read as zeros; a slot without any block has no cache at all
+    const int owned = ctx->seq_blocks[seq] * 32;
+    if (owned == 0) return RDLM_ESTATE;
+    const int n_dev = std::max(0, std::min(n, owned - pos0));
     float* kd = ctx->gu;
     float* vd = ctx->gu + (size_t)n * h;
-    launch_read_kv(reinterpret_cast<const char*>(L.kc) + off, reinterpret_cast<const char*>(L.vc) + off, ctx->m.dtype,
-                   ctx->m.n_heads, ctx->m.head_dim, pos0, n, kd, vd, ctx->st);
+    launch_read_kv(L.kc, L.vc, kv_pages(ctx), seq, ctx->m.dtype, ctx->m.n_heads, ctx->m.head_dim, pos0, n_dev, kd, vd, ctx->st);
     HIPCHK(hipStreamSynchronize(ctx->st));
-    HIPCHK(hipMemcpy(k_host, kd, (size_t)n * h * 4, hipMemcpyDeviceToHost));
-    HIPCHK(hipMemcpy(v_host, vd, (size_t)n * h * 4, hipMemcpyDeviceToHost));
+    if (n_dev) {
+        HIPCHK(hipMemcpy(k_host, kd, (size_t)n_dev * h * 4, hipMemcpyDeviceToHost));
+        HIPCHK(hipMemcpy(v_host, vd, (size_t)n_dev * h * 4, hipMemcpyDeviceToHost));
+    }
+    memset(k_host + (size_t)n_dev * h, 0, (size_t)(n - n_dev) * h * 4);
+    memset(v_host + (size_t)n_dev * h, 0, (size_t)(n - n_dev) * h * 4);
     return RDLM_OK;
 }
 
@@ -1354,7 +1637,7 @@ static int linear_setup(rdlm_ctx* ctx, int m_rows, int* T) {
     SeqWindows w;
     w.n = 1; w.seq[0] = 0; w.pos0[0] = 0; w.rows[0] = m_rows;
     *T = (m_rows + 31) / 32;
-    launch_build_tiles_api(w, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
     return RDLM_OK;
 }
 
@@ -1392,6 +1675,7 @@ extern "C" int rdlm_time_linear(rdlm_ctx* ctx, int32_t w_index, int32_t m_rows, 
     int rc = weight_by_index(ctx, w_index, &W, &proj, &N, &K);
     if (rc) return rc;
     if ((rc = linear_setup(ctx, m_rows, &T))) return rc;
+    if ((rc = ensure_blocks(ctx, 0, m_rows))) return rc;       // the QKV projection writes these positions of slot 0
     // Gaussian rows as input (values do not affect timing; keeps everything finite)
     void* xin = proj_input(ctx, K);
     float* stage = (size_t)K <= (size_t)3 * ctx->m.hidden ? ctx->qkv : ctx->gu;   // both idle here
@@ -1526,11 +1810,12 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
                                    float* ms_out) {
     if (!ctx || !ms_out || iters < 1 || seq < 0 || pos0 < 0 || n < 1) return RDLM_EINVAL;
     if (seq >= ctx->max_seqs || n > ctx->max_rows || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;
+    PROPAGATE(ensure_blocks(ctx, seq, pos0 + n));
     SeqWindows w;
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
-    launch_build_tiles_store(w, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, pos0, n, zrow0, 1.0f, 7u, 0u, ctx->st);

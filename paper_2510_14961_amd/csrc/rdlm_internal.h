@@ -19,7 +19,20 @@ struct TileDesc {
     int32_t crow0;    // compact row index (rows of all tiles concatenated without padding)
     int32_t group;    // attention: tiles t..t+group-1 (same sequence, consecutive positions) are served
                       // together by the workgroup of tile t; 0 = served by an earlier tile's workgroup
+    int32_t rng;      // identity of the sequence in the counters of the random generator (its slot number
+                      // unless the sequence moved in from another slot)
 };
+
+// Paged KV cache (App. "Larger batch sizes": state slots are fungible): a layer's K and V entries live in
+// a pool of blocks of 32 positions x hidden elements; logical block b of the sequence in slot s is
+// physical block table[s * stride + b].  Inside a block the layouts are those of k_cache_off / vt_slot.
+struct KvPages {
+    const int32_t* table = nullptr;   // device [slots][stride]
+    int32_t stride = 0;               // logical blocks per slot
+};
+__device__ inline size_t kv_block_base(const KvPages& kv, int seq, int block, size_t block_elems) {
+    return (size_t)kv.table[(size_t)seq * kv.stride + block] * block_elems;
+}
 constexpr int ATT_GROUP = 4;
 
 constexpr int TILE_ROWS = 32;
@@ -177,7 +190,7 @@ struct GemmEpilogue {
     void* vc = nullptr;
     const float* rope_table = nullptr;   // [rows][d/2] (cos, sin)
     int n_heads = 0, head_dim = 0;
-    size_t seq_stride = 0;
+    KvPages kv;
     // Deferred RMSNorm: when row_ssq is set, the input rows were stored as x * gain without the
     // 1/rms factor; every output row is multiplied by 1/sqrt(sum_c row_ssq[row][c] / h + eps).
     const float* row_ssq = nullptr;      // [slot][ssq_stride rows]
@@ -200,12 +213,16 @@ struct GemmEpilogue {
 constexpr int SSQ_MAX_CHUNKS = 256;   // slots per row: chunks of fold_k, or feature groups of a folding GEMM
 
 // elementwise / row kernels ------------------------------------------------------------------
-void launch_build_tiles_api(const SeqWindows& w, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+// ident: per slot, the sequence's identity in the random generator's counters
+void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
 // same, but rows map to the library's per-(sequence, position) stores instead of compact arrays
-void launch_build_tiles_store(const SeqWindows& w, int max_positions, TileDesc* tiles, int32_t* n_tiles,
-                              hipStream_t st);
-void launch_build_tiles_sampler(const SeqState* seqs, int n_seqs, int max_positions,
+void launch_build_tiles_store(const SeqWindows& w, const int32_t* ident, int max_positions, TileDesc* tiles,
+                              int32_t* n_tiles, hipStream_t st);
+void launch_build_tiles_sampler(const SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
                                 TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+// block table entries table[first + i] = ids[i], i < n <= 16 (new blocks of a growing sequence)
+struct BlockIds { int32_t n; int32_t first; int32_t id[16]; };
+void launch_table_set(int32_t* table, BlockIds ids, hipStream_t st);
 // x[row] = scale * emb[token of the row]; with rope_table: also the (cos, sin) table of the rows;
 // with xg (bf16 path): also bf16(x * gain) as packed operand and the fold_chunks(h) per-chunk sums of
 // squares of each row (what fold_k would leave for the first layer's norm)
@@ -245,7 +262,7 @@ void launch_prelude_end(const float* xin, const float* part, int S, size_t part_
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles,
                        const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_rope_kv(const float* qkv, int S, size_t part_stride, void* q, void* kc, void* vc,
-                    int dtype, int H, int d, const float* table, size_t seq_stride_elems,
+                    int dtype, int H, int d, const float* table, KvPages kv,
                     const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_swiglu(const float* gu, int S, size_t part_stride, void* act, int fmt, int F,
                    const int32_t* n_tiles, int max_tiles, hipStream_t st);
@@ -272,13 +289,13 @@ void launch_sample_top_p(const float* logits, int V, float temperature, float to
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st);
 void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st);
 // End of a sampler step in one launch (one workgroup per sequence): drafts -> y_current, step
-// counters, k*, freeze, append (Alg. 1 lines 13-16 / Alg. 2), Gaussian states of the appended
+// counters, k*, freeze, append (Alg. 1 assign / freeze / append, Alg. 2), Gaussian states of the appended
 // positions, and the tile list of the next step.  ticket: one device word, zero between launches.
-void launch_step_end(SeqState* seqs, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts, int max_positions,
-                     const int32_t* drafts, const float* delta, float* z, float* z_prev, int h, TileDesc* tiles,
-                     int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st);
+void launch_step_end(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
+                     int max_positions, const int32_t* drafts, const float* delta, float* z, float* z_prev, int h,
+                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
-void launch_read_kv(const void* kc, const void* vc, int dtype, int H, int d, int pos0, int n,
+void launch_read_kv(const void* kc, const void* vc, KvPages kv, int seq, int dtype, int H, int d, int pos0, int n,
                     float* k_out, float* v_out, hipStream_t st);
 
 // GEMMs ---------------------------------------------------------------------------------------
@@ -308,7 +325,7 @@ double launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
 // q: f32 [rows][H*d] (RDLM_F32) or bf16 [rows][H*d]; caches per the model dtype; out: activation
 // format of the model dtype, width H*d.  ws: split-KV partials.
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
-                      size_t seq_stride_elems, int nsplit, bool grouped, float* ws,
+                      KvPages kv, int nsplit, bool grouped, float* ws,
                       uint32_t* tickets /* [max_tiles][H], zero between launches */, const TileDesc* tiles,
                       const int32_t* n_tiles, int max_tiles, hipStream_t st);
 size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);

@@ -69,7 +69,7 @@ def tau_for(shape) -> float:
     return TAU_SMALL_BF16 if shape.hidden < 1024 else TAU_MID_BF16 if shape.hidden < 4096 else TAU_BIG_BF16
 
 
-def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_jitter=0.1, emb_mul=1.0):
+def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_jitter=0.1, emb_mul=1.0, **ctx_kw):
     """(Context on the GPU, oracle model, numpy weights) from one weight draw."""
     import torch
     import paper_2510_14961_amd as R
@@ -79,7 +79,7 @@ def make_pair(shape, seed=1, max_seqs=1, max_positions=128, max_rows=64, gain_ji
         if shape.dtype == "bf16":
             w["emb"] = S.bf16_bits_to_f32(S.f32_to_bf16_bits(w["emb"]))
     dev = R.upload_weights(shape, w)
-    ctx = R.Context(shape, dev, max_seqs, max_positions, max_rows)
+    ctx = R.Context(shape, dev, max_seqs, max_positions, max_rows, **ctx_kw)
     del dev
     torch.cuda.synchronize()
     return ctx, O.RecurrentDepthLM(shape, w), w
