@@ -169,6 +169,15 @@ __global__ void concat_k(const float* e, const float* z, void* cat, int h, const
     if (t >= *n_tiles) return;
     TileDesc d = tiles[t];
     bool valid = j < d.n_valid;
+    if (!e || !z) {      // one half alone, as an operand of width h (adapter product cut in two)
+        const float* sr = e ? e + ((size_t)d.erow0 + j) * h : z + ((size_t)d.zrow0 + j) * h;
+        for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
+            float4 v = make_float4(0, 0, 0, 0);
+            if (valid) v = ld4(sr + k);
+            act_store4<FMT>(cat, h, r, k, v.x, v.y, v.z, v.w);
+        }
+        return;
+    }
     const float* er = e + ((size_t)d.erow0 + j) * h;
     const float* zr = z + ((size_t)d.zrow0 + j) * h;
     for (int k = threadIdx.x * 4; k < 2 * h; k += blockDim.x * 4) {
@@ -228,8 +237,8 @@ __global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, 
 // End of the prelude on the bf16 path: e = x + sum part (f32, padded rows) and the adapter operand
 // concat(e, z) as packed bf16 in one pass; a row is cut into `chunks` pieces like fold_k.
 __global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const float* part, int S, size_t part_stride,
-                                                      float* e_out, const float* z, void* cat, int h, int chunks,
-                                                      const TileDesc* tiles, const int32_t* n_tiles) {
+                                                      float* e_out, const float* z, void* cat, void* cat_e, int h,
+                                                      int chunks, const TileDesc* tiles, const int32_t* n_tiles) {
     const int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
     if (t >= *n_tiles) return;
     const TileDesc d = tiles[t];
@@ -242,6 +251,11 @@ __global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const flo
     float4 zz = make_float4(0, 0, 0, 0);
     if (valid) zz = ld4(z + ((size_t)d.zrow0 + j) * h + k);
     else v = make_float4(0, 0, 0, 0);
+    if (cat_e) {         // the two halves as operands of their own (adapter product cut in two)
+        act_store4<ACT_BF16P>(cat_e, h, r, k, v.x, v.y, v.z, v.w);
+        act_store4<ACT_BF16P>(cat, h, r, k, zz.x, zz.y, zz.z, zz.w);
+        return;
+    }
     act_store4<ACT_BF16P>(cat, 2 * h, r, k, v.x, v.y, v.z, v.w);
     act_store4<ACT_BF16P>(cat, 2 * h, r, h + k, zz.x, zz.y, zz.z, zz.w);
 }
@@ -969,11 +983,11 @@ void launch_fold(const float* xin, float* xout, const float* part, int S, size_t
                        ssq, ssq_stride, h, c, n_tiles);
 }
 void launch_prelude_end(const float* xin, const float* part, int S, size_t part_stride, float* e_out, const float* z,
-                        void* cat, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                        void* cat, void* cat_e, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
                         hipStream_t st) {
     const int c = fold_chunks(h);
     hipLaunchKernelGGL(prelude_end_k, dim3(c, max_tiles * 32), dim3(256), 0, st, xin, part, S, part_stride, e_out, z,
-                       cat, h, c, tiles, n_tiles);
+                       cat, cat_e, h, c, tiles, n_tiles);
 }
 void launch_final_norm(const float* xin, const float* part, int S, size_t part_stride, const float* gain,
                        int h, float eps, float* z, float* z_prev, int update_prev, float* delta, float* xcopy,

@@ -624,7 +624,7 @@ bool launch_gemm_bf16(const void* xp, const void* wp, float* out, int N, int K, 
 // canonical row canon_col(layout, b, f); canonical rows below `split` come from w0, the others
 // from w1 (the gate and up matrices are separate tensors).
 __global__ void pack_weight_k(const uint16_t* w0, const uint16_t* w1, int split, uint16_t* wp, int N, int K,
-                              int layout, int n_heads, int head_dim) {
+                              int layout, int n_heads, int head_dim, int ld) {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;       // one lane-vector (8 elements) each
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
     if (idx >= total) return;
@@ -633,15 +633,15 @@ __global__ void pack_weight_k(const uint16_t* w0, const uint16_t* w1, int split,
     int kt = (int)(tile % (K / 16));
     int nb = (int)(tile / (K / 16));
     int n = canon_col(layout, nb, lane & 31, N, n_heads, head_dim);
-    const uint16_t* src = (n < split ? w0 + (size_t)n * K : w1 + (size_t)(n - split) * K) + kt * 16 + (lane >> 5) * 8;
+    const uint16_t* src = (n < split ? w0 + (size_t)n * ld : w1 + (size_t)(n - split) * ld) + kt * 16 + (lane >> 5) * 8;
     uint4 v = *reinterpret_cast<const uint4*>(src);
     *reinterpret_cast<uint4*>(wp + idx * 8) = v;
 }
 void launch_pack_weight(const void* w0, const void* w1, int split, void* wp, int N, int K, int layout, int n_heads,
-                        int head_dim, hipStream_t st) {
+                        int head_dim, hipStream_t st, int ld) {
     size_t total = (size_t)(N / 32) * (K / 16) * 64;
     hipLaunchKernelGGL(pack_weight_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const uint16_t*)w0,
-                       (const uint16_t*)w1, split, (uint16_t*)wp, N, K, layout, n_heads, head_dim);
+                       (const uint16_t*)w1, split, (uint16_t*)wp, N, K, layout, n_heads, head_dim, ld ? ld : K);
 }
 
 // f32 rows [rows][K] -> packed bf16 activation tiles (rows rounded up to 32 must be allocated)

@@ -36,6 +36,7 @@ struct Knobs {
     bool no_fold_fusion = false;     // split-K folds in fold_k launches instead of the producing GEMM
     bool no_fold = false;            // full RMSNorm kernels instead of the deferred 1/rms factor
     bool no_lds_gemm = false;        // steps with three row tiles and more: the row-sharing kernel everywhere
+    bool no_hoist = false;           // several recurrences per call: W_a . [e; z] in one product every time
     bool has_plan[PROJ_COUNT] = {}, has_plan_rows[PROJ_COUNT] = {};
     GemmPlan plan[PROJ_COUNT], plan_rows[PROJ_COUNT];
 };
@@ -52,6 +53,7 @@ struct Workspace {
     int32_t* n_tiles_samp = nullptr;
     float *x = nullptr, *e = nullptr, *qkv = nullptr, *gu = nullptr, *part = nullptr, *logits = nullptr;
     float *delta = nullptr, *zp_api = nullptr, *att_ws = nullptr;
+    float* xe = nullptr;            // bf16: W_e . e of the current rows, kept over the recurrences of a call
     void *xn = nullptr, *abuf = nullptr, *q = nullptr, *att = nullptr;
     int32_t* drafts = nullptr;
     float* ssq = nullptr;           // [SSQ_MAX_CHUNKS + 1][rows_pad] partial sums of squares of the folded rows
@@ -76,6 +78,9 @@ struct rdlm_ctx : Workspace {
     void* emb_canon = nullptr;
     void* emb_w = nullptr;
     void* wa = nullptr;
+    void* wa_e = nullptr;                // bf16: the two [h, h] halves of W_a packed on their own (the e half's
+    void* wa_z = nullptr;                // product is computed once for all recurrences of a call)
+    bool hoist_split = false;            // this step's prelude leaves e and z as separate adapter operands
     float* gf = nullptr;
     float* gout = nullptr;
     float* theta = nullptr;
@@ -255,6 +260,7 @@ static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, in
     w.part = (float*)take(8 * R * h * 4);
     w.delta = (float*)take(R * 4);
     w.zp_api = (float*)take(R * h * 4);
+    if (m.dtype == RDLM_BF16) w.xe = (float*)take(R * h * 4);
     w.xn = take(R * h * esz);
     w.abuf = take(R * wide * esz);
     w.q = take(R * h * esz);
@@ -310,6 +316,14 @@ static int create_impl(rdlm_ctx* ctx, const void* const* wp, void* workspace) {
         if ((rc = take_matrix(ctx, wp[wi++], h, F, &L.wd))) return rc;
         DALLOC(L.kc, cache_elems * esz, true);
         DALLOC(L.vc, cache_elems * esz, true);
+    }
+    if (m.dtype == RDLM_BF16) {
+        const uint16_t* src = static_cast<const uint16_t*>(wp[wi]);
+        const size_t half = (size_t)h * h * 2;
+        DALLOC(ctx->wa_e, half, false);
+        DALLOC(ctx->wa_z, half, false);
+        launch_pack_weight(src, src, h, ctx->wa_e, h, h, WL_NATURAL, m.n_heads, m.head_dim, ctx->st, 2 * h);
+        launch_pack_weight(src + h, src + h, h, ctx->wa_z, h, h, WL_NATURAL, m.n_heads, m.head_dim, ctx->st, 2 * h);
     }
     if ((rc = take_matrix(ctx, wp[wi++], h, 2 * h, &ctx->wa))) return rc;
     if ((rc = take_gain(ctx, wp[wi++], h, &ctx->gf))) return rc;
@@ -374,6 +388,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
     if (is("no_fold_fusion")) { k->no_fold_fusion = atoi(value) != 0; return RDLM_OK; }
     if (is("no_fold")) { k->no_fold = atoi(value) != 0; return RDLM_OK; }
     if (is("no_lds_gemm")) { k->no_lds_gemm = atoi(value) != 0; return RDLM_OK; }
+    if (is("no_hoist")) { k->no_hoist = atoi(value) != 0; return RDLM_OK; }
     for (int pj = 0; pj < PROJ_COUNT; ++pj) {
         char nm[32];
         // plan_<proj> = "nb,waves,unroll,ksplit": the one-tile launch shape ("" = default again)
@@ -410,7 +425,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
 }
 
 static void knobs_from_env(Knobs* k) {
-    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm"};
+    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm", "no_hoist"};
     auto env_of = [](const char* name) {
         char buf[48] = "RDLM_";
         size_t n = strlen(buf);
@@ -919,8 +934,8 @@ static int prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, i
                                 l + 1 < m.n_prelude ? ctx->layers[l + 1].g1 : nullptr, &ready));
     const size_t pst = (size_t)ctx->rows_pad * m.hidden;
     if (z_cat && e_which < 0 && m.dtype == RDLM_BF16 && fold_chunks(m.hidden) > 0 && !ctx->knobs.no_fold) {
-        launch_prelude_end(ctx->x, ctx->part, S, pst, e_out, z_cat, ctx->abuf, m.hidden, ctx->tiles, ctx->n_tiles, T,
-                           ctx->st);
+        launch_prelude_end(ctx->x, ctx->part, S, pst, e_out, z_cat, ctx->abuf, ctx->hoist_split ? ctx->att : nullptr,
+                           m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
         if (cat_ready) *cat_ready = true;
         return RDLM_OK;
     }
@@ -939,16 +954,44 @@ static int prelude_forward(rdlm_ctx* ctx, const int32_t* tokens, float* e_out, i
 // z <- R(z, e): adapter on concat(e, z), the core layers, closing norm; optional delta vs z_prev.
 // cat_ready: the adapter operand was already written (by the prelude's closing pass); x_for_coda:
 // also leave z' in the residual buffer, where the coda starts from.
+//
+// hoist (several recurrences on the same e; Sec. 3.2: e is computed once, only s changes between
+// recurrences): W_a . [e; z] = W_e . e + W_z . z, and the first term is the same every time.
+// 1 = first recurrence: compute W_e . e into ctx->xe, then add W_z . z; 2 = a later one: reuse ctx->xe.
+// Both halves are [h, h] products, i.e. they run with the output projection's launch shapes.
+static bool hoist_ok(const rdlm_ctx* ctx, int n_recurrences) {
+    return n_recurrences > 1 && ctx->m.dtype == RDLM_BF16 && !ctx->knobs.no_hoist;
+}
 static int core_forward(rdlm_ctx* ctx, const float* e, float* z, float* z_prev, int update_prev, float* delta,
-                        int T, int max_keys, bool cat_ready = false, bool x_for_coda = false) {
+                        int T, int max_keys, bool cat_ready = false, bool x_for_coda = false, int hoist = 0) {
     const rdlm_model& m = ctx->m;
     const int h = m.hidden;
-    if (!cat_ready) launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+    const float* g1 = ctx->layers[m.n_prelude].g1;
     int S;
-    const FoldSpec fa = {nullptr, ctx->x, ctx->layers[m.n_prelude].g1};
     bool ready = false;
-    PROPAGATE(run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S, nullptr, false, false, nullptr, nullptr, &fa, &ready));
-    bool x_valid = ready;
+    bool x_valid;
+    if (hoist) {
+        if (hoist == 1) {
+            if (!cat_ready) launch_concat(e, nullptr, ctx->att, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+            const FoldSpec fe = {nullptr, ctx->xe, g1};
+            PROPAGATE(run_proj(ctx, PROJ_O, ctx->att, ctx->wa_e, T, &S, nullptr, false, false, nullptr, nullptr, &fe, &ready));
+            if (!ready) norm_operand(ctx, nullptr, ctx->xe, S, g1, ctx->xn, T);
+        }
+        if (!(cat_ready && hoist == 1)) launch_concat(nullptr, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+        const FoldSpec fz = {ctx->xe, ctx->x, g1};
+        ready = false;
+        PROPAGATE(run_proj(ctx, PROJ_O, ctx->abuf, ctx->wa_z, T, &S, nullptr, false, false, nullptr, nullptr, &fz, &ready));
+        if (!ready) {        // partial sums pending: x = xe + their sum; the first layer's operand is ready
+            ready = norm_operand(ctx, ctx->xe, ctx->x, S, g1, ctx->xn, T);   // only on the deferred-norm path
+            S = 0;
+        }
+        x_valid = true;
+    } else {
+        if (!cat_ready) launch_concat(e, z, ctx->abuf, ctx->fmt, h, ctx->tiles, ctx->n_tiles, T, ctx->st);
+        const FoldSpec fa = {nullptr, ctx->x, g1};
+        PROPAGATE(run_proj(ctx, PROJ_A, ctx->abuf, ctx->wa, T, &S, nullptr, false, false, nullptr, nullptr, &fa, &ready));
+        x_valid = ready;
+    }
     for (int l = 0; l < m.n_core; ++l) {
         PROPAGATE(layer_forward(ctx, ctx->layers[m.n_prelude + l], T, max_keys, x_valid, S, &S, ready,
                                 l + 1 < m.n_core ? ctx->layers[m.n_prelude + l + 1].g1 : nullptr, &ready));
@@ -1057,7 +1100,9 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, ctx->ident_host[seq], 0, n,
                            (size_t)seq * ctx->max_positions, alpha, (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
     PROPAGATE(prelude_forward(ctx, ctx->y, ctx->e, -1, T, n));
-    for (int i = 0; i < r; ++i) PROPAGATE(core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n));
+    for (int i = 0; i < r; ++i)
+        PROPAGATE(core_forward(ctx, ctx->e, ctx->z_store, nullptr, 0, nullptr, T, n, false, false,
+                               hoist_ok(ctx, r) ? (i == 0 ? 1 : 2) : 0));
     PROPAGATE(coda_forward(ctx, ctx->z_store, nullptr, T, n));
     return check_launch(ctx);
 }
@@ -1092,7 +1137,8 @@ static int core_step_run(rdlm_ctx* ctx, const SeqWindows& w, int T, int M, int m
     for (int i = 0; i < r_inner; ++i) {
         bool last = i == r_inner - 1;
         PROPAGATE(core_forward(ctx, e, z_inout, (last && delta_out) ? ctx->zp_api : nullptr, 0,
-                               (last && delta_out) ? ctx->delta : nullptr, T, mk));
+                               (last && delta_out) ? ctx->delta : nullptr, T, mk, false, false,
+                               hoist_ok(ctx, r_inner) ? (i == 0 ? 1 : 2) : 0));
     }
     if (delta_out) launch_copy_rows_out(ctx->delta, delta_out, 1, 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     return check_launch(ctx);
@@ -1435,7 +1481,10 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     // e <- P(y_current); without momentum or noise the closing pass of P also writes concat(e, z)
     const bool plain = !(s.eta > 0.f) && !(s.beta > 0.f);
     bool cat_ready = false;
+    const bool hoist = hoist_ok(ctx, s.r_inner);
+    ctx->hoist_split = hoist;
     int rc = prelude_forward(ctx, ctx->y, ctx->e, -1, T, max_keys, plain ? ctx->z_store : nullptr, &cat_ready);
+    ctx->hoist_split = false;
     if (s.eta > 0.f)                                                             // Eq. 1
         launch_momentum(ctx->e, ctx->e_store, ctx->counts, s.eta, m.hidden, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (s.beta > 0.f)                                                            // Eq. 2
@@ -1446,7 +1495,8 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
         bool last = i == s.r_inner - 1;
         if (rc == RDLM_OK)
             rc = core_forward(ctx, ctx->e, ctx->z_store, last ? ctx->z_prev : nullptr, last ? 1 : 0,
-                              last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last);
+                              last ? ctx->delta : nullptr, T, max_keys, cat_ready && i == 0, last,
+                              hoist ? (i == 0 ? 1 : 2) : 0);
     }
     SampleArgs sa = {s.temperature, ctx->sp.seed_lo, ctx->sp.seed_hi, t, false, ctx->seq_step0, s.top_p};
     if (rc == RDLM_OK) rc = coda_forward(ctx, ctx->z_store, &sa, T, max_keys, true);   // p <- C(z); y_hat <- Sample(p)

@@ -235,6 +235,7 @@ void launch_copy_rows_out(const float* x, float* dst, int width, int which /*0=z
                           const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_copy_i32_out(const int32_t* src, int32_t* dst, const TileDesc* tiles,
                          const int32_t* n_tiles, int max_tiles, hipStream_t st);
+// adapter operand concat(e, z) of width 2h; with e or z null: the other one alone, width h
 void launch_concat(const float* e, const float* z, void* cat, int fmt, int h, const TileDesc* tiles,
                    const int32_t* n_tiles, int max_tiles, hipStream_t st);
 void launch_addnorm(const float* xin, float* xout, const float* part, int S, size_t part_stride,
@@ -254,9 +255,10 @@ void launch_final_norm(const float* xin, const float* part, int S, size_t part_s
                        float* ssq_tot /* with xg: sum of z'^2 per row */,
                        const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st);
 // bf16 path, end of the prelude: e_out (f32, padded rows) = xin + sum part, and the packed adapter
-// operand cat = concat(e, z) with z read from the latent store rows of the tiles
+// operand cat = concat(e, z) with z read from the latent store rows of the tiles; with cat_e the two
+// halves become operands of width h of their own (e in cat_e, z in cat)
 void launch_prelude_end(const float* xin, const float* part, int S, size_t part_stride, float* e_out, const float* z,
-                        void* cat, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
+                        void* cat, void* cat_e, int h, const TileDesc* tiles, const int32_t* n_tiles, int max_tiles,
                         hipStream_t st);
 // table: [rows][d/2] (cos, sin) pairs written by launch_rope_table for the current tiles
 void launch_rope_table(float* table, const float* theta, int half, const TileDesc* tiles,
@@ -312,9 +314,10 @@ void launch_argmax_final(const float* cand_val, const int32_t* cand_idx, int n_g
 // f32: x [rows][K], w [N][K], out [rows][N]
 void launch_gemm_f32(const float* x, const float* w, float* out, int N, int K,
                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
-// canonical bf16 rows [N][K] (rows < split from w0, the rest from w1) -> packed blocks in `layout`
+// canonical bf16 rows [N][K] (rows < split from w0, the rest from w1) -> packed blocks in `layout`;
+// ld: elements between consecutive source rows (0 = K; larger: K columns out of a wider matrix)
 void launch_pack_weight(const void* w0, const void* w1, int split, void* w_packed, int N, int K, int layout,
-                        int n_heads, int head_dim, hipStream_t st);
+                        int n_heads, int head_dim, hipStream_t st, int ld = 0);
 void launch_pack_rows(const float* x, void* xp, int rows, int K, hipStream_t st);   // f32 rows -> packed bf16
 
 // reference kernels (measurement only) -------------------------------------------------------

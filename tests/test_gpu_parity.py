@@ -522,6 +522,54 @@ def test_bf16_sampler_steps_teacher_forced(shape):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", [SMALL_BF16_D64, SMALL_BF16_D96], ids=["bf16_d64", "bf16_d96"])
+def test_bf16_inner_recurrences_share_the_e_half_of_the_adapter(shape):
+    """r' > 1 on the bf16 path: e stays the same over the inner recurrences (Sec. 3.2), so its half of the
+    adapter product W_a [e; s] is computed once per step and added to the s half of every recurrence.
+    Sampler steps with r' = 3 recomputed by the oracle (which multiplies the concatenation every time) from
+    the GPU's inputs; then the same step with momentum and state noise -- where the adapter operands are
+    written by a different kernel -- against the library's own run with the product left in one piece."""
+    from gpu_util import teacher_forced_step
+    ctx, m, _ = make_pair(shape, seed=4, max_positions=128, max_rows=64)
+    prompt = S.make_prompt(shape.vocab, 30, 6)
+    spec = dict(n_new=12, r_inner=3, r_total=9, seed=2)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, len(prompt) - 1, 9, 1.0, 2)
+    ctx.sampler_begin(1, **spec)
+    rows = 0
+    for t in range(1, 8):
+        out = teacher_forced_step(ctx, m, shape, spec, 1, t, label="r'=3")
+        rows += out["rows"]
+    assert rows == 1 + 2 + 3 * 5
+    got = {}
+    for no_hoist in ("1", "0"):
+        ctx.set_tuning("no_hoist", no_hoist)
+        ctx.set_tokens(0, prompt)
+        ctx.prefill(0, len(prompt) - 1, 9, 1.0, 2)
+        ctx.sampler_begin(1, eta=0.2, beta=0.4, temperature=0.7, **spec)
+        for _ in range(3):
+            ctx.sample_step()
+        p0, n, _ = ctx.read_window(0)
+        got[no_hoist] = (p0, n, ctx.read_states(0, p0, n), ctx.read_tokens(0)[0].copy())
+    assert got["0"][:2] == got["1"][:2]
+    # (two summation orders, then bf16 operands downstream: a fraction of the distance to the oracle)
+    assert_rows_close(got["0"][2], got["1"][2], tol_latent(shape) / 2, "cut product against whole product")
+    # and the first step of that run against the oracle (until a draft differs both see the same inputs)
+    states = {}
+
+    def hook(t, z_pos, zz, logits, y, e):
+        states[t] = (list(z_pos), zz.copy())
+
+    O.generate_diffusion_forcing(m, prompt, 12, 3, 9, seed=2, eta=0.2, beta=0.4, temperature=0.7, T=2, hook=hook)
+    ctx.set_tokens(0, prompt)
+    ctx.prefill(0, len(prompt) - 1, 9, 1.0, 2)
+    ctx.sampler_begin(1, eta=0.2, beta=0.4, temperature=0.7, **spec)
+    ctx.sample_step()
+    z_pos, zz = states[1]
+    assert_rows_close(ctx.read_states(0, z_pos[0], len(z_pos)), zz, tol_latent(shape), "first step with momentum and noise")
+    ctx.close()
+
+
 def test_mid_shape_fp32_free_running_prefix():
     """The mid workload's architecture in fp32 storage, reduced vocabulary and lengths: greedy
     tokens of a free run are identical to the oracle's."""
