@@ -315,11 +315,12 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     constexpr int SLOTS = (DK + 2 * DB) * 64;               // 16-byte slots of one staged K + V block
     constexpr int PER = (SLOTS + ATT_GROUP * 64 - 1) / (ATT_GROUP * 64);
     __shared__ bf16x8 stage[2][SLOTS];
-    const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
-    const TileDesc td = tiles[t];                             // read together with the count
-    if (t >= *n_tiles) return;
+    // grid (heads, groups, splits): one workgroup per attention group, found through the leader list
+    const int hd = blockIdx.x, sp = blockIdx.z;
+    if ((int)blockIdx.y >= n_tiles[1]) return;
+    const int t = n_tiles[TILE_LEADERS + blockIdx.y];
+    const TileDesc td = tiles[t];
     const int ng = min(td.group, ATT_GROUP);
-    if (ng <= 0) return;                                      // served by its group leader
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int h = H * D;
@@ -535,7 +536,7 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
 
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
                       KvPages kv, int nsplit, bool grouped, float* ws, uint32_t* tickets,
-                      const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st) {
+                      const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st, int max_groups) {
     if (dtype == 0) {
         hipLaunchKernelGGL(attn_f32_k, dim3(max_tiles * 32, H), dim3(256), 0, st, (const float*)q, (const float*)kc,
                            (const float*)vc, (float*)out, H, d, kv, tiles, n_tiles);
@@ -543,7 +544,8 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
     }
     if (nsplit > ATT_MAX_SPLIT) nsplit = ATT_MAX_SPLIT;
     if (nsplit < 1) nsplit = 1;
-    dim3 grid(H, max_tiles, nsplit);
+    if (max_groups <= 0 || max_groups > max_tiles) max_groups = max_tiles;
+    dim3 grid(H, grouped ? max_groups : max_tiles, nsplit);
 #define RDLM_ATT(D_)                                                                                              \
     if (d == D_) {                                                                                                \
         if (!grouped) {         /* merges its KV splits itself */                                                 \

@@ -38,7 +38,7 @@ __device__ inline float4 ld4(const float* p) { return *reinterpret_cast<const fl
 __global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, int max_positions, TileDesc* tiles,
                                   int32_t* n_tiles) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int t = 0, c = 0;
+    int t = 0, c = 0, nl = 0;
     for (int i = 0; i < w.n; ++i) {
         for (int off = 0; off < w.rows[i]; off += TILE_ROWS) {
             TileDesc d;
@@ -55,17 +55,19 @@ __global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, 
             d.crow0 = c + off;
             const int k = off / TILE_ROWS, left = (w.rows[i] - off + TILE_ROWS - 1) / TILE_ROWS;
             d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
+            if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
             tiles[t++] = d;
         }
         c += w.rows[i];
     }
-    *n_tiles = t;
+    n_tiles[0] = t;
+    n_tiles[1] = nl;
 }
 
 __global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
                                       TileDesc* tiles, int32_t* n_tiles) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int t = 0, c = 0;
+    int t = 0, c = 0, nl = 0;
     for (int s = 0; s < n_seqs; ++s) {
         SeqState& q = seqs[s];
         int rows = q.done ? 0 : q.win_n;
@@ -82,11 +84,13 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int 
             d.crow0 = c + off;
             const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
             d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
+            if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
             tiles[t++] = d;
         }
         c += rows;
     }
-    *n_tiles = t;
+    n_tiles[0] = t;
+    n_tiles[1] = nl;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -818,7 +822,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
     // tile list of the next step: the records of up to 256 sequences at a time are fetched in
     // parallel, one thread lays the tiles out in sequence order
     __shared__ int32_t s_done[256], s_win_n[256], s_pos0[256];
-    int t = 0, c = 0, active = 0;
+    int t = 0, c = 0, active = 0, nl = 0;
     for (int s0 = 0; s0 < n_seqs; s0 += 256) {
         const int i = s0 + tid;
         if (i < n_seqs) {
@@ -845,6 +849,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
                     d.crow0 = c + off;
                     const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
                     d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
+                    if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
                     tiles[t++] = d;
                 }
                 c += rows;
@@ -856,7 +861,8 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
         // n_active[1] remembers the step at which the last sequence finished (0 = still running)
         if (active == 0 && n_active[0] != 0) n_active[1] = step;
         n_active[0] = active;
-        *n_tiles = t;
+        n_tiles[0] = t;
+        n_tiles[1] = nl;
         if (gridDim.x > 1) __hip_atomic_store(ticket_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }

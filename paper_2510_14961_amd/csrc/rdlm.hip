@@ -80,6 +80,7 @@ struct rdlm_ctx : Workspace {
     void* wa = nullptr;
     void* wa_e = nullptr;                // bf16: the two [h, h] halves of W_a packed on their own (the e half's
     void* wa_z = nullptr;                // product is computed once for all recurrences of a call)
+    int att_groups = 0;                  // bound on the attention groups of the current tile list (0: the tile count)
     bool hoist_split = false;            // this step's prelude leaves e and z as separate adapter operands
     float* gf = nullptr;
     float* gout = nullptr;
@@ -252,7 +253,7 @@ static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, in
     w.step_ticket = (uint32_t*)take(64);
     w.ticket_bytes = off;
     w.tiles = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
-    w.n_tiles = (int32_t*)take(64);
+    w.n_tiles = (int32_t*)take(tile_count_bytes(max_tiles));
     w.x = (float*)take(R * h * 4);
     w.qkv = (float*)take(R * 3 * h * 4);
     // f32 gate/up sums: the f32 path's GEMM output, rdlm_linear's, and the staging area of rdlm_read_kv
@@ -270,7 +271,7 @@ static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, in
     if (m.dtype == RDLM_BF16) w.att_ws = (float*)take(attention_ws_floats(max_tiles, m.n_heads, m.head_dim, att_max_split) * 4);
     if (full) {
         w.tiles_samp = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
-        w.n_tiles_samp = (int32_t*)take(64);
+        w.n_tiles_samp = (int32_t*)take(tile_count_bytes(max_tiles));
         w.e = (float*)take(R * h * 4);
         w.logits = (float*)take(R * V * 4);
         w.drafts = (int32_t*)take(R * 4);
@@ -899,7 +900,7 @@ static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, boo
                        kv_pages(ctx), ctx->tiles, ctx->n_tiles, T, st);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, kv_pages(ctx),
                      att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
-                     ctx->n_tiles, T, st);
+                     ctx->n_tiles, T, st, ctx->att_groups);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
     bool folded = false;
     PROPAGATE(run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded));
@@ -1052,6 +1053,8 @@ static int check_rows(rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const i
     bool grouped = false;
     for (int i = 0; i < n_seqs; ++i) grouped = grouped || n_rows[i] > TILE_ROWS;
     ctx->grouped = grouped;
+    ctx->att_groups = 0;
+    for (int i = 0; i < n_seqs; ++i) ctx->att_groups += ((n_rows[i] + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP;
     // cache blocks for the rows' positions (the rows attend to everything before them: blocks from 0 on)
     int need = 0;
     for (int i = 0; i < n_seqs; ++i)
@@ -1096,6 +1099,7 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
     launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, ctx->ident_host[seq], 0, n,
                            (size_t)seq * ctx->max_positions, alpha, (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
@@ -1472,6 +1476,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     int wmax_now = (int)std::min<long long>(std::min<long long>(s.w_max, in_flight), grow);   // (a joined sequence restarts at 1: still a bound)
     const int T = n * ((wmax_now + 31) / 32);
     ctx->grouped = wmax_now > TILE_ROWS;
+    ctx->att_groups = n * (((wmax_now + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP);
     int max_keys = 0;
     for (int q = 0; q < n; ++q)
         max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
@@ -1865,6 +1870,7 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
     launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;

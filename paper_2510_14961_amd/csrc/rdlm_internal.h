@@ -36,6 +36,11 @@ __device__ inline size_t kv_block_base(const KvPages& kv, int seq, int block, si
 constexpr int ATT_GROUP = 4;
 
 constexpr int TILE_ROWS = 32;
+// The word block behind a tile list: [0] number of tiles, [1] number of attention groups, and from
+// TILE_LEADERS on the tile index of each group's first tile (so that the grouped attention kernels
+// launch one workgroup per group and split, none for the tiles a group serves).
+constexpr int TILE_LEADERS = 16;
+inline size_t tile_count_bytes(int max_tiles) { return (size_t)(TILE_LEADERS + max_tiles) * 4; }
 constexpr int MAX_API_SEQS = 64;      // sequences per API call (descriptor passed as a kernel argument)
 
 struct SeqWindows {                   // by-value kernel argument of build_tiles
@@ -330,7 +335,8 @@ double launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
                       KvPages kv, int nsplit, bool grouped, float* ws,
                       uint32_t* tickets /* [max_tiles][H], zero between launches */, const TileDesc* tiles,
-                      const int32_t* n_tiles, int max_tiles, hipStream_t st);
+                      const int32_t* n_tiles, int max_tiles, hipStream_t st,
+                      int max_groups = 0 /* grouped: the host's bound on the number of attention groups (0: max_tiles) */);
 size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);
 
 }  // namespace rdlm
