@@ -189,6 +189,44 @@ def core_sweep(args):
     ctx.close()
 
 
+def batch_sweep(args):
+    """Batches of sequences with short windows (App. "Larger batch sizes"): sampler steps of n sequences x
+    window w (fixed exit, r' = 1, r = w) at the 3.5B shape behind 512-token prompts, with the rows of the
+    sequences packed into shared row tiles and with one row tile per sequence."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape = S.BIG
+    grid = [(1, 32), (2, 16), (4, 8), (8, 4), (16, 2), (8, 32)]
+    dev, _ = build_weights(shape, 1, False, args.threads)
+    out = []
+    for n_seqs, w in grid:
+        row = {"sequences": n_seqs, "window": w, "rows": n_seqs * w}
+        for packed in (True, False):
+            ctx = R.Context(shape, dev, n_seqs, 512 + 256, 512)
+            ctx.set_tuning("no_pack", "0" if packed else "1")
+            for q in range(n_seqs):
+                ctx.set_tokens(q, S.make_prompt(shape.vocab, 512, 5, seq=q))
+                ctx.prefill(q, 511, 1, 1.0, 1)         # (timing only: one recurrence fills the caches)
+            ctx.sampler_begin(n_seqs, n_new=200, r_inner=1, r_total=w, seed=1)
+            for _ in range(w + 4):
+                ctx.sample_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            K = 40
+            for _ in range(K):
+                ctx.sample_step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) / K * 1e3
+            key = "packed" if packed else "tile_per_sequence"
+            row[key + "_ms_per_step"] = ms
+            row[key + "_tokens_per_s"] = n_seqs / ms * 1e3
+            log(f"[batch] {n_seqs:2d} x window {w:2d} {key}: {ms:.3f} ms/step")
+            ctx.close()
+        out.append(row)
+    print(json.dumps({"batch_sweep": out, "shape": "3.5B: 5280 x 55 x 96, mlp 17920, P2/R4/C2, bf16, prompt 512, greedy"}),
+          flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +246,9 @@ def main():
                     help="rows of the large-window core step timed against the MFMA peak (0 = skip)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) to scale rocprofv3 --pmc counters")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="instead of the benchmark: sampler steps of batches of sequences with short windows, rows "
+                         "packed into shared row tiles against one row tile per sequence")
     ap.add_argument("--core-sweep", action="store_true",
                     help="instead of the benchmark: time one core step (r' = 1) at the 3.5B shape over a grid of window "
                          "rows x cached context, print the table and the measured ridge (rows at which the step "
@@ -226,6 +267,9 @@ def main():
     import paper_2510_14961_amd as R
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.batch_sweep:
+        batch_sweep(args)
+        return
     if args.core_sweep:
         core_sweep(args)
         return

@@ -92,12 +92,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
     constexpr bool PAIRED = (EPI == EPI_SWIGLU || EPI == EPI_ROPE_KV);
     constexpr int UQ = PAIRED ? 2 : 4;
 
-    // per row tile: tile descriptor (sc: deferred RMSNorm factor of the lane's row)
+    // per row tile: the descriptor of the lane's own row -- the rows of a tile may belong to different
+    // sequences (sc: deferred RMSNorm factor of the lane's row)
     TileDesc td[MT];
 #pragma unroll
     for (int b = 0; b < MT; ++b) {
         const int t = min(t0 + b, n_tiles - 1);
-        if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = A.epi.tiles[t];
+        if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = A.epi.tiles[t * 32 + col];
     }
     float best_v[MT];
     int best_i[MT];
@@ -147,8 +148,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
             const int D = A.epi.head_dim, HALF = D >> 1, H = A.epi.n_heads, h = H * D;
             const int hb = h >> 5, sec = blk[a] / hb, r = blk[a] - sec * hb, per = D >> 5;
             const int head = r / per, j = r - head * per;
-            const int pos = td[b].pos0 + col;
-            const bool valid = col < td[b].n_valid;
+            const int pos = td[b].pos0;
+            const bool valid = td[b].n_valid > 0;
             if (sec == 2) {
                 if (valid) {
                     const int u0 = 32 * j + f0;
@@ -192,7 +193,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                 uint32_t x[4];
                 // a sequence counts its sampler steps from the step it joined at
                 const int lstep = A.epi.step - (A.epi.seq_step0 ? A.epi.seq_step0[td[b].seq] : 0);
-                philox4x32_10(c0 >> 2, td[b].pos0 + col, td[b].rng, ((uint32_t)lstep << 4) | TAG_SAMPLE, A.epi.k0,
+                philox4x32_10(c0 >> 2, td[b].pos0, td[b].rng, ((uint32_t)lstep << 4) | TAG_SAMPLE, A.epi.k0,
                               A.epi.k1, x);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) gn[i] = -logf(-logf(u24_open(x[i])));

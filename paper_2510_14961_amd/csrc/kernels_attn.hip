@@ -89,8 +89,10 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     __shared__ float sm[ATT_WAVES][2][32];
     __shared__ float so[ATT_WAVES][DB * 16][64];
     const int hd = blockIdx.x, t = blockIdx.y, sp = blockIdx.z;
+    // `tiles` are the segments here: up to 32 rows of one sequence at physical rows prow0 .. (several
+    // segments may share a physical row tile: only the segment's own rows are read and written)
     const TileDesc td = tiles[t];                             // valid memory for every t of the grid; read
-    if (t >= *n_tiles) return;                                // together with the count, used only behind it
+    if (t >= n_tiles[2]) return;                              // together with the count, used only behind it
     int ng = 1;
     if (MTQ > 1) {
         ng = min(td.group, MTQ);
@@ -112,7 +114,8 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     float m_run[MTQ], l_run[MTQ];                             // l_run: this half-wave's share of the sum
 #pragma unroll
     for (int b = 0; b < MTQ; ++b) {
-        const uint16_t* qr = q + ((size_t)(t + min(b, ng - 1)) * 32 + col) * h + hd * D + g * 8;
+        const TileDesc tb = b == 0 ? td : tiles[t + min(b, ng - 1)];
+        const uint16_t* qr = q + ((size_t)tb.prow0 + min(col, tb.n_valid - 1)) * h + hd * D + g * 8;
 #pragma unroll
         for (int i = 0; i < DK; ++i) qv[b][i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
 #pragma unroll
@@ -199,7 +202,9 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
         __syncthreads();
         // wave w finishes the register quads with quad % ATT_WAVES == w; register (d, i) of lane
         // (col, g) is dim 32d + 8*(i/4) + 4g + i%4 of query `col`
-        const int row = (t + b) * 32 + col;
+        const TileDesc tb = b == 0 ? td : tiles[t + b];
+        const int row = tb.prow0 + col;
+        const bool own = col < tb.n_valid;                    // rows beyond belong to other segments or to nobody
         // split partials: [m[32], l[32], O in accumulator order [quad][i][lane]] (a wave writes 256
         // contiguous bytes), written through to memory when another workgroup will merge them
         float* rec = ws + (((size_t)(t + b) * H + hd) * nsplit + sp) * att_rec_floats(D);
@@ -219,7 +224,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
                 ushort4 pk;
                 pk.x = f32_to_bf16(v[0] * inv); pk.y = f32_to_bf16(v[1] * inv);
                 pk.z = f32_to_bf16(v[2] * inv); pk.w = f32_to_bf16(v[3] * inv);
-                *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
+                if (own) *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
             } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
             pk.z = f32_to_bf16(acc[2] * inv); pk.w = f32_to_bf16(acc[3] * inv);
             const int quad = wave + (k0 + k) * ATT_WAVES;
             const int dim = 32 * (quad >> 2) + 8 * (quad & 3) + 4 * g;
-            *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + col, hd * D + dim, h)) = pk;
+            if (col < td.n_valid) *reinterpret_cast<ushort4*>(out + packed_off(td.prow0 + col, hd * D + dim, h)) = pk;
         }
         __builtin_amdgcn_sched_barrier(0);      // keep the next round's loads behind this round
     }
@@ -329,13 +334,15 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     const int kb_lo = (int)(((long long)nkb * sp) / nsplit), kb_hi = (int)(((long long)nkb * (sp + 1)) / nsplit);
     const float scale = 1.0f / sqrtf((float)D);
     const bool active = wave < ng;
-    const int tq = t + (active ? wave : 0);                   // this wave's row tile
+    const int tq = t + (active ? wave : 0);                   // this wave's segment (they follow each other, also physically)
     const int pos0 = td.pos0 + 32 * (active ? wave : 0);
     const int qpos = pos0 + col;
+    const int prow = td.prow0 + 32 * (active ? wave : 0);     // its first physical row
+    const int nv = (active && wave == ng - 1) ? tiles[t + ng - 1].n_valid : 32;   // rows of the segment
 
     bf16x8 qv[DK];
     {
-        const uint16_t* qr = q + ((size_t)tq * 32 + col) * h + hd * D + g * 8;
+        const uint16_t* qr = q + ((size_t)prow + min(col, nv - 1)) * h + hd * D + g * 8;
 #pragma unroll
         for (int i = 0; i < DK; ++i) qv[i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
     }
@@ -414,7 +421,7 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     }
     if (!active) return;
     const float L = l_run + __shfl_xor(l_run, 32);
-    const int row = tq * 32 + col;
+    const int row = prow + col;
     float* rec = ws + (((size_t)tq * H + hd) * nsplit + sp) * att_rec_floats(D);
     const float inv = L > 0.f ? 1.0f / L : 0.f;
 #pragma unroll
@@ -427,7 +434,7 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
                 ushort4 pk;
                 pk.x = f32_to_bf16(v0 * inv); pk.y = f32_to_bf16(v1 * inv);
                 pk.z = f32_to_bf16(v2 * inv); pk.w = f32_to_bf16(v3 * inv);
-                *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
+                if (col < nv) *reinterpret_cast<ushort4*>(out + packed_off(row, hd * D + dim, h)) = pk;
             } else {
                 *reinterpret_cast<float4*>(rec + 64 + (size_t)col * D + dim) = make_float4(v0, v1, v2, v3);
             }
@@ -442,9 +449,10 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
 // the thread are issued before the first use.
 template <int D>
 __global__ __launch_bounds__(256) void attn_merge_k(const float* __restrict__ ws, uint16_t* __restrict__ out, int H,
-                                                     int nsplit, const int32_t* n_tiles) {
-    const int hd = blockIdx.x, t = blockIdx.y;
-    if (t >= *n_tiles) return;
+                                                     int nsplit, const TileDesc* tiles, const int32_t* n_tiles) {
+    const int hd = blockIdx.x, t = blockIdx.y;                // t: segment
+    if (t >= n_tiles[2]) return;
+    const TileDesc td = tiles[t];
     const int idx = blockIdx.z * blockDim.x + threadIdx.x;
     if (idx >= 32 * (D / 4)) return;
     const float* base = ws + ((size_t)t * H + hd) * nsplit * att_rec_floats(D);
@@ -479,7 +487,7 @@ __global__ __launch_bounds__(256) void attn_merge_k(const float* __restrict__ ws
     ushort4 pk;
     pk.x = f32_to_bf16(acc.x * inv); pk.y = f32_to_bf16(acc.y * inv);
     pk.z = f32_to_bf16(acc.z * inv); pk.w = f32_to_bf16(acc.w * inv);
-    *reinterpret_cast<ushort4*>(out + packed_off(t * 32 + col, hd * D + dim, H * D)) = pk;
+    if (col < td.n_valid) *reinterpret_cast<ushort4*>(out + packed_off(td.prow0 + col, hd * D + dim, H * D)) = pk;
 }
 
 // f32 path: one workgroup per (row, head); scores kept in LDS.
@@ -489,9 +497,9 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
                                                     KvPages kvp, const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sc[ATT_F32_MAXKEYS];
     __shared__ float red[8];
-    int r = blockIdx.x, hd = blockIdx.y, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc td = tiles[t];
+    int r = blockIdx.x, hd = blockIdx.y, j = 0;               // (the row's own descriptor)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc td = tiles[r];
     int h = H * d;
     float* orow = out + (size_t)r * h + hd * d;
     if (j >= td.n_valid) {
@@ -536,7 +544,9 @@ __global__ __launch_bounds__(256) void attn_f32_k(const float* __restrict__ q, c
 
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
                       KvPages kv, int nsplit, bool grouped, float* ws, uint32_t* tickets,
-                      const TileDesc* tiles, const int32_t* n_tiles, int max_tiles, hipStream_t st, int max_groups) {
+                      const TileDesc* tiles, int rows_pad, const int32_t* n_tiles, int max_tiles, hipStream_t st,
+                      int max_groups) {
+    const TileDesc* segs = tiles + rows_pad;
     if (dtype == 0) {
         hipLaunchKernelGGL(attn_f32_k, dim3(max_tiles * 32, H), dim3(256), 0, st, (const float*)q, (const float*)kc,
                            (const float*)vc, (float*)out, H, d, kv, tiles, n_tiles);
@@ -551,16 +561,16 @@ void launch_attention(const void* q, const void* kc, const void* vc, void* out, 
         if (!grouped) {         /* merges its KV splits itself */                                                 \
             hipLaunchKernelGGL((attn_bf16_k<D_, 1>), grid, dim3(ATT_WAVES * 64), 0, st, (const uint16_t*)q,       \
                                (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, kv,                   \
-                               nsplit, ws, tickets, tiles, n_tiles);                                              \
+                               nsplit, ws, tickets, segs, n_tiles);                                               \
             return;                                                                                               \
         }                                                                                                         \
         else                                                                                                      \
             hipLaunchKernelGGL(attn_group_k<D_>, grid, dim3(ATT_GROUP * 64), 0, st, (const uint16_t*)q,           \
                                (const uint16_t*)kc, (const uint16_t*)vc, (uint16_t*)out, H, kv,                   \
-                               nsplit, ws, tiles, n_tiles);                                                       \
+                               nsplit, ws, segs, n_tiles);                                                        \
         if (nsplit > 1)                                                                                           \
             hipLaunchKernelGGL(attn_merge_k<D_>, dim3(H, max_tiles, (32 * (D_ / 4) + 255) / 256), dim3(256), 0,   \
-                               st, ws, (uint16_t*)out, H, nsplit, n_tiles);                                       \
+                               st, ws, (uint16_t*)out, H, nsplit, segs, n_tiles);                                 \
         return;                                                                                                   \
     }
     RDLM_ATT(32) RDLM_ATT(64) RDLM_ATT(96) RDLM_ATT(128)

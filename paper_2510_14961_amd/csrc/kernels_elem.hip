@@ -35,62 +35,101 @@ __device__ inline float4 ld4(const float* p) { return *reinterpret_cast<const fl
 
 // ---------------------------------------------------------------------------------------------
 // tile descriptors
-__global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, int max_positions, TileDesc* tiles,
-                                  int32_t* n_tiles) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int t = 0, c = 0, nl = 0;
-    for (int i = 0; i < w.n; ++i) {
-        for (int off = 0; off < w.rows[i]; off += TILE_ROWS) {
+//
+// Lays the windows of a step out on physical rows.  Thread 0 of one workgroup calls add() for every
+// window in sequence order and then counts(); after a barrier all threads of the workgroup call rows().
+// A window of more than 32 rows gets whole row tiles (one segment per tile, groups of up to ATT_GROUP
+// segments for the attention kernels); shorter windows are packed one after the other into the row
+// tile that is open, as long as they fit (`pack`), so a batch of short windows shares row tiles.
+struct TileLayout {
+    TileDesc* tiles;        // [rows_pad] row descriptors, then the segments
+    int32_t* n_tiles;
+    int rows_pad, pack;
+    int n_seg = 0, n_phys = 0, n_lead = 0, c = 0, open_row = 0, open_cap = 0;
+    // store_base < 0: caller-owned compact arrays; else row of position 0 of the sequence in the library's stores
+    __device__ int add(int seq, int rng, int pos0, int nrows, long long store_base) {
+        if (nrows <= 0) return n_phys * TILE_ROWS;
+        int first;
+        const bool small = pack && nrows <= TILE_ROWS;
+        if (small && open_cap >= nrows) {
+            first = open_row; open_row += nrows; open_cap -= nrows;
+        } else {
+            first = n_phys * TILE_ROWS;
+            n_phys += (nrows + TILE_ROWS - 1) / TILE_ROWS;
+            open_row = first + nrows;
+            open_cap = small ? TILE_ROWS - nrows : 0;
+        }
+        TileDesc* segs = tiles + rows_pad;
+        for (int off = 0; off < nrows; off += TILE_ROWS) {
             TileDesc d;
-            d.seq = w.seq[i];
-            d.rng = ident[w.seq[i]];
-            d.pos0 = w.pos0[i] + off;
-            d.n_valid = min(TILE_ROWS, w.rows[i] - off);
-            if (mode == 0) {            // caller-owned compact arrays
+            d.seq = seq; d.rng = rng;
+            d.pos0 = pos0 + off;
+            d.n_valid = min(TILE_ROWS, nrows - off);
+            d.prow0 = first + off;
+            if (store_base < 0) {
                 d.zrow0 = d.erow0 = d.yrow0 = c + off;
-            } else {                    // library stores indexed by (seq, position)
-                d.zrow0 = d.yrow0 = w.seq[i] * max_positions + d.pos0;
-                d.erow0 = t * TILE_ROWS;
+            } else {
+                d.zrow0 = d.yrow0 = (int)(store_base + d.pos0);
+                d.erow0 = d.prow0;
             }
             d.crow0 = c + off;
-            const int k = off / TILE_ROWS, left = (w.rows[i] - off + TILE_ROWS - 1) / TILE_ROWS;
+            const int k = off / TILE_ROWS, left = (nrows - off + TILE_ROWS - 1) / TILE_ROWS;
             d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
-            if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
-            tiles[t++] = d;
+            if (d.group > 0) n_tiles[TILE_LEADERS + n_lead++] = n_seg;
+            segs[n_seg++] = d;
         }
-        c += w.rows[i];
+        c += nrows;
+        return first;
     }
-    n_tiles[0] = t;
-    n_tiles[1] = nl;
+    __device__ void counts() { n_tiles[0] = n_phys; n_tiles[1] = n_lead; n_tiles[2] = n_seg; }
+    // all threads, after a barrier behind counts(): the descriptor of every physical row
+    __device__ void rows() {
+        const int np = n_tiles[0], ns = n_tiles[2];
+        TileDesc pad;
+        pad.seq = 0; pad.pos0 = 0; pad.n_valid = 0; pad.zrow0 = pad.erow0 = pad.yrow0 = pad.crow0 = 0; pad.group = 0; pad.rng = 0;
+        for (int r = threadIdx.x; r < np * TILE_ROWS; r += blockDim.x) { pad.prow0 = r; tiles[r] = pad; }
+        __syncthreads();
+        const TileDesc* segs = tiles + rows_pad;
+        for (int sg = 0; sg < ns; ++sg) {
+            const TileDesc d = segs[sg];
+            for (int j = threadIdx.x; j < d.n_valid; j += blockDim.x) {
+                TileDesc rd = d;
+                rd.pos0 += j; rd.zrow0 += j; rd.erow0 += j; rd.yrow0 += j; rd.crow0 += j; rd.prow0 += j;
+                rd.n_valid = 1; rd.group = 0;
+                tiles[d.prow0 + j] = rd;
+            }
+        }
+    }
+};
+
+__global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, int max_positions, TileDesc* tiles,
+                                  int32_t* n_tiles, int rows_pad, int pack) {
+    TileLayout lay;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    if (threadIdx.x == 0) {
+        for (int i = 0; i < w.n; ++i)
+            lay.add(w.seq[i], ident[w.seq[i]], w.pos0[i], w.rows[i], mode == 0 ? -1LL : (long long)w.seq[i] * max_positions);
+        lay.counts();
+    }
+    __syncthreads();
+    lay.rows();
 }
 
 __global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
-                                      TileDesc* tiles, int32_t* n_tiles) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int t = 0, c = 0, nl = 0;
-    for (int s = 0; s < n_seqs; ++s) {
-        SeqState& q = seqs[s];
-        int rows = q.done ? 0 : q.win_n;
-        q.cur_tile0 = t;                                // first tile of this sequence
-        q.cur_rows = rows;
-        for (int off = 0; off < rows; off += TILE_ROWS) {
-            TileDesc d;
-            d.seq = s;
-            d.rng = ident[s];
-            d.pos0 = q.win_pos0 + off;
-            d.n_valid = min(TILE_ROWS, rows - off);
-            d.zrow0 = d.yrow0 = s * max_positions + d.pos0;
-            d.erow0 = t * TILE_ROWS;
-            d.crow0 = c + off;
-            const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
-            d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
-            if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
-            tiles[t++] = d;
+                                      TileDesc* tiles, int32_t* n_tiles, int rows_pad, int pack) {
+    TileLayout lay;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    if (threadIdx.x == 0) {
+        for (int s = 0; s < n_seqs; ++s) {
+            SeqState& q = seqs[s];
+            const int rows = q.done ? 0 : q.win_n;
+            q.cur_rows = rows;
+            q.cur_row0 = lay.add(s, ident[s], q.win_pos0, rows, (long long)s * max_positions);
         }
-        c += rows;
+        lay.counts();
     }
-    n_tiles[0] = t;
-    n_tiles[1] = nl;
+    __syncthreads();
+    lay.rows();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -100,9 +139,9 @@ __global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float*
                         float2* rope_table, const float* theta, int half, const float* gain, void* xg, float* ssq,
                         size_t ssq_stride, const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sh[16];
-    int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.y, c = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     bool valid = j < d.n_valid;
     int tok = valid ? tokens[d.yrow0 + j] : 0;
     tok = min(max(tok, 0), V - 1);
@@ -137,9 +176,9 @@ __global__ void embed_k(const T* emb, const int32_t* tokens, float scale, float*
 
 __global__ void copy_rows_in_k(const float* src, float* x, int h, int which, const TileDesc* tiles,
                                const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     bool valid = j < d.n_valid;
     size_t srow = (size_t)(which == 0 ? d.zrow0 : d.erow0) + j;
     for (int k = threadIdx.x * 4; k < h; k += blockDim.x * 4) {
@@ -150,9 +189,9 @@ __global__ void copy_rows_in_k(const float* src, float* x, int h, int which, con
 
 __global__ void copy_rows_out_k(const float* x, float* dst, int width, int which, const TileDesc* tiles,
                                 const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     if (j >= d.n_valid) return;
     size_t drow = (size_t)(which == 0 ? d.zrow0 : which == 1 ? d.erow0 : d.crow0) + j;
     for (int k = threadIdx.x; k < width; k += blockDim.x)
@@ -160,18 +199,18 @@ __global__ void copy_rows_out_k(const float* x, float* dst, int width, int which
 }
 
 __global__ void copy_i32_out_k(const int32_t* src, int32_t* dst, const TileDesc* tiles, const int32_t* n_tiles) {
-    int r = blockIdx.x * blockDim.x + threadIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x * blockDim.x + threadIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     if (j < d.n_valid) dst[d.crow0 + j] = src[r];
 }
 
 template <int FMT>
 __global__ void concat_k(const float* e, const float* z, void* cat, int h, const TileDesc* tiles,
                          const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     bool valid = j < d.n_valid;
     if (!e || !z) {      // one half alone, as an operand of width h (adapter product cut in two)
         const float* sr = e ? e + ((size_t)d.erow0 + j) * h : z + ((size_t)d.zrow0 + j) * h;
@@ -243,9 +282,9 @@ __global__ __launch_bounds__(256) void addnorm_k(const float* xin, float* xout, 
 __global__ __launch_bounds__(256) void prelude_end_k(const float* xin, const float* part, int S, size_t part_stride,
                                                       float* e_out, const float* z, void* cat, void* cat_e, int h,
                                                       int chunks, const TileDesc* tiles, const int32_t* n_tiles) {
-    const int r = blockIdx.y, c = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    const TileDesc d = tiles[t];
+    const int r = blockIdx.y, c = blockIdx.x, j = 0;   // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    const TileDesc d = tiles[r];
     const bool valid = j < d.n_valid;
     const int cw = h / chunks;
     const int k = c * cw + threadIdx.x * 4;
@@ -298,9 +337,9 @@ __global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float
                                                      void* xg, float* ssq_tot, const TileDesc* tiles,
                                                      const int32_t* n_tiles) {
     __shared__ float sh[16];
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     bool valid = j < d.n_valid;
     constexpr int RV = ROW_VEC * 256 / NT;          // float4 per thread: h <= 8192
     float4 v[RV];
@@ -355,9 +394,9 @@ __global__ __launch_bounds__(NT) void final_norm_k(const float* xin, const float
 // cos / sin of pos * theta_i for every row of the step, computed once per step.
 __global__ void rope_table_k(float2* table, const float* theta, int half, const TileDesc* tiles,
                              const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    int pos = tiles[t].pos0 + j;
+    int r = blockIdx.x;
+    if ((r >> 5) >= *n_tiles) return;
+    int pos = tiles[r].pos0;
     for (int i = threadIdx.x; i < half; i += blockDim.x) {
         float sn, cs;
         sincosf((float)pos * theta[i], &sn, &cs);
@@ -375,9 +414,9 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
                                                   void* vc, int H, int d, const float2* table, KvPages kv,
                                                   const TileDesc* tiles, const int32_t* n_tiles) {
     extern __shared__ float sv[];                       // [32][d + 1]
-    const int hd = blockIdx.x, t = blockIdx.y;
+    const int hd = blockIdx.x, t = blockIdx.y;          // physical row tile: its rows may belong to several sequences
     if (t >= *n_tiles) return;
-    const TileDesc ds = tiles[t];
+    const TileDesc* rowd = tiles + (size_t)t * 32;
     const int h = H * d, half = d >> 1;
     auto at = [&](int row, int colidx) {
         float v = 0.f;
@@ -386,8 +425,9 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
     };
     for (int idx = threadIdx.x; idx < 32 * half; idx += blockDim.x) {
         const int j = idx / half, i = idx - j * half;
-        const int r = t * 32 + j, pos = ds.pos0 + j;
-        const bool valid = j < ds.n_valid;
+        const TileDesc ds = rowd[j];
+        const int r = t * 32 + j, pos = ds.pos0;
+        const bool valid = ds.n_valid > 0;
         const float2 cssn = table[(size_t)r * half + i];
         const int c0 = hd * d + i, c1 = c0 + half;
         const float q0 = at(r, c0), q1 = at(r, c1), k0 = at(r, h + c0), k1 = at(r, h + c1);
@@ -417,8 +457,9 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
     if (DT == 0) {
         for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
             const int j = idx / d, dd = idx - j * d;
-            if (j < ds.n_valid) {
-                const int pos = ds.pos0 + j;
+            const TileDesc ds = rowd[j];
+            if (ds.n_valid > 0) {
+                const int pos = ds.pos0;
                 reinterpret_cast<float*>(vc)[kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h) + (size_t)(pos & 31) * h +
                                              hd * d + dd] = sv[j * (d + 1) + dd];
             }
@@ -426,8 +467,10 @@ __global__ __launch_bounds__(256) void rope_kv_k(const float* qkv, int S, size_t
     } else {
         // transposed V: [position block][head][dim][32 slots]; lanes run over the rows of the tile
         for (int idx = threadIdx.x; idx < 32 * d; idx += blockDim.x) {
-            const int dd = idx >> 5, j = idx & 31, pos = ds.pos0 + j;
-            if (j < ds.n_valid)
+            const int dd = idx >> 5, j = idx & 31;
+            const TileDesc ds = rowd[j];
+            const int pos = ds.pos0;
+            if (ds.n_valid > 0)
                 reinterpret_cast<uint16_t*>(vc)[kv_block_base(kv, ds.seq, pos >> 5, (size_t)32 * h) +
                                                 ((size_t)hd * d + dd) * 32 + vt_slot(pos & 31)] =
                     f32_to_bf16(sv[j * (d + 1) + dd]);
@@ -485,9 +528,9 @@ __global__ void init_state_rows_k(float* z, float* z_prev, int h, int seq, int p
 // Momentum on the conditioning (Eq. 1), one workgroup per row.
 __global__ void momentum_k(float* e, float* e_store, const int32_t* counts, float eta, int h, const TileDesc* tiles,
                            const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     if (j >= d.n_valid) return;
     const size_t srow = (size_t)d.zrow0 + j;               // (sequence, position) row of the stores
     const bool first = counts[srow] == 0;                   // no previous conditioning yet
@@ -509,9 +552,9 @@ __global__ void momentum_k(float* e, float* e_store, const int32_t* counts, floa
 __global__ void noise_mix_k(float* z, const int32_t* counts, float beta, int n_steps, float alpha, uint32_t k0,
                             uint32_t k1, int step, const int32_t* seq_step0, int h, const TileDesc* tiles,
                             const int32_t* n_tiles) {
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     if (j >= d.n_valid) return;
     const size_t srow = (size_t)d.zrow0 + j;
     const float b = beta * fmaxf(0.0f, 1.0f - (float)counts[srow] / (float)n_steps);
@@ -530,9 +573,9 @@ __global__ void sample_k(const float* logits, int V, float temperature, uint32_t
                          const int32_t* seq_step0, int32_t* tok_out, const TileDesc* tiles, const int32_t* n_tiles) {
     __shared__ float sv[256];
     __shared__ int si[256];
-    int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    TileDesc d = tiles[t];
+    int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    TileDesc d = tiles[r];
     int pos = d.pos0 + j;
     const float* lg = logits + (size_t)r * V;
     float best = -INFINITY;
@@ -591,9 +634,9 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
     __shared__ int wtot[TOPP_THREADS / 64];
     __shared__ float cand[TOPP_CAND];
     __shared__ uint32_t thr_sh;
-    const int r = blockIdx.x, t = r >> 5, j = r & 31;
-    if (t >= *n_tiles) return;
-    const TileDesc d = tiles[t];
+    const int r = blockIdx.x, j = 0;          // (the row's own descriptor: offsets within it are 0)
+    if ((r >> 5) >= *n_tiles) return;
+    const TileDesc d = tiles[r];
     const int pos = d.pos0 + j;
     const float* lg = logits + (size_t)r * V;
     const float invT = 1.0f / temperature;
@@ -738,7 +781,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
                                                    int32_t* counts, int max_positions, const int32_t* drafts,
                                                    const float* delta, float* z, float* z_prev, int h,
                                                    TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step,
-                                                   uint32_t* ticket_ctr) {
+                                                   uint32_t* ticket_ctr, int rows_pad, int pack) {
     __shared__ int first_open;                       // first row of the window that is not freezable
     __shared__ SeqState cur;
     __shared__ uint32_t ticket;
@@ -752,7 +795,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
         const int rows = q.cur_rows;                 // rows this sequence had in the step just run
         const size_t base = (size_t)s * max_positions;
         if (!q.done && rows > 0) {
-            const int row0 = q.cur_tile0 * TILE_ROWS;   // its rows are contiguous in padded row space
+            const int row0 = q.cur_row0;                // its rows are contiguous in physical row space
             for (int i = tid; i < rows; i += blockDim.x) {
                 const int pos = q.win_pos0 + i;
                 y[base + pos + 1] = drafts[row0 + i];                    // y_current <- [y_frozen, y_hat]
@@ -770,7 +813,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
             __syncthreads();
             if (tid == 0) {
                 const int k = min(first_open, rows);                     // longest freezable prefix
-                q.last_rows = rows; q.last_pos0 = q.win_pos0; q.last_tile0 = q.cur_tile0;
+                q.last_rows = rows; q.last_pos0 = q.win_pos0; q.last_row0 = q.cur_row0;
                 q.n_frozen += k; q.win_pos0 += k; q.win_n -= k;
                 q.new_n = 0;
                 if (q.n_frozen - q.prompt_len >= p.n_new) {
@@ -820,9 +863,11 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
         __syncthreads();
     }
     // tile list of the next step: the records of up to 256 sequences at a time are fetched in
-    // parallel, one thread lays the tiles out in sequence order
+    // parallel, one thread lays the windows out in sequence order, all write the row descriptors
     __shared__ int32_t s_done[256], s_win_n[256], s_pos0[256];
-    int t = 0, c = 0, active = 0, nl = 0;
+    TileLayout lay;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    int active = 0;
     for (int s0 = 0; s0 < n_seqs; s0 += 256) {
         const int i = s0 + tid;
         if (i < n_seqs) {
@@ -836,23 +881,8 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
                 const int sq = s0 + j;
                 if (!s_done[j]) active++;
                 const int rows = s_done[j] ? 0 : s_win_n[j];
-                seqs[sq].cur_tile0 = t;
                 seqs[sq].cur_rows = rows;
-                for (int off = 0; off < rows; off += TILE_ROWS) {
-                    TileDesc d;
-                    d.seq = sq;
-                    d.rng = ident[sq];
-                    d.pos0 = s_pos0[j] + off;
-                    d.n_valid = min(TILE_ROWS, rows - off);
-                    d.zrow0 = d.yrow0 = sq * max_positions + d.pos0;
-                    d.erow0 = t * TILE_ROWS;
-                    d.crow0 = c + off;
-                    const int k = off / TILE_ROWS, left = (rows - off + TILE_ROWS - 1) / TILE_ROWS;
-                    d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
-                    if (d.group > 0) n_tiles[TILE_LEADERS + nl++] = t;
-                    tiles[t++] = d;
-                }
-                c += rows;
+                seqs[sq].cur_row0 = lay.add(sq, ident[sq], s_pos0[j], rows, (long long)sq * max_positions);
             }
         }
         __syncthreads();
@@ -861,10 +891,11 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
         // n_active[1] remembers the step at which the last sequence finished (0 = still running)
         if (active == 0 && n_active[0] != 0) n_active[1] = step;
         n_active[0] = active;
-        n_tiles[0] = t;
-        n_tiles[1] = nl;
-        if (gridDim.x > 1) __hip_atomic_store(ticket_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        lay.counts();
     }
+    __syncthreads();
+    lay.rows();
+    if (tid == 0 && gridDim.x > 1) __hip_atomic_store(ticket_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Continuous batching: a sequence (tokens set, first L-1 positions prefilled) enters a running
@@ -874,7 +905,7 @@ __global__ void seq_join_k(SeqState* seqs, int32_t* seq_step0, int seq, int prom
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     SeqState q;
     q.prompt_len = prompt_len; q.n_frozen = prompt_len; q.win_pos0 = prompt_len - 1; q.win_n = 1; q.done = 0;
-    q.last_rows = 0; q.last_pos0 = 0; q.new_pos0 = 0; q.new_n = 0; q.last_tile0 = 0; q.cur_rows = 0; q.cur_tile0 = 0;
+    q.last_rows = 0; q.last_pos0 = 0; q.new_pos0 = 0; q.new_n = 0; q.last_row0 = 0; q.cur_rows = 0; q.cur_row0 = 0;
     seqs[seq] = q;
     seq_step0[seq] = step;
 }
@@ -916,17 +947,19 @@ __global__ void table_set_k(int32_t* table, BlockIds ids) {
 // ---------------------------------------------------------------------------------------------
 // launchers
 
-void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, ident, 0, 0, tiles, n_tiles);
+void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, int rows_pad,
+                            bool pack, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(256), 0, st, w, ident, 0, 0, tiles, n_tiles, rows_pad, pack ? 1 : 0);
 }
 void launch_build_tiles_store(const SeqWindows& w, const int32_t* ident, int max_positions, TileDesc* tiles,
-                              int32_t* n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(64), 0, st, w, ident, 1, max_positions, tiles, n_tiles);
+                              int32_t* n_tiles, int rows_pad, bool pack, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_api_k, dim3(1), dim3(256), 0, st, w, ident, 1, max_positions, tiles, n_tiles, rows_pad,
+                       pack ? 1 : 0);
 }
 void launch_build_tiles_sampler(const SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions, TileDesc* tiles,
-                                int32_t* n_tiles, hipStream_t st) {
-    hipLaunchKernelGGL(build_tiles_sampler_k, dim3(1), dim3(64), 0, st, const_cast<SeqState*>(seqs), ident, n_seqs,
-                       max_positions, tiles, n_tiles);
+                                int32_t* n_tiles, int rows_pad, bool pack, hipStream_t st) {
+    hipLaunchKernelGGL(build_tiles_sampler_k, dim3(1), dim3(256), 0, st, const_cast<SeqState*>(seqs), ident, n_seqs,
+                       max_positions, tiles, n_tiles, rows_pad, pack ? 1 : 0);
 }
 void launch_table_set(int32_t* table, BlockIds ids, hipStream_t st) {
     if (ids.n <= 0) return;
@@ -1062,9 +1095,10 @@ void launch_sample_top_p(const float* logits, int V, float temperature, float to
 }
 void launch_step_end(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
                      int max_positions, const int32_t* drafts, const float* delta, float* z, float* z_prev, int h,
-                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st) {
+                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, int rows_pad,
+                     bool pack, hipStream_t st) {
     hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(256), 0, st, seqs, ident, n_seqs, p, y, counts, max_positions, drafts,
-                       delta, z, z_prev, h, tiles, n_tiles, n_active, step, ticket);
+                       delta, z, z_prev, h, tiles, n_tiles, n_active, step, ticket, rows_pad, pack ? 1 : 0);
 }
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st) {
     hipLaunchKernelGGL(seq_join_k, dim3(1), dim3(64), 0, st, seqs, seq_step0, seq, prompt_len, step);

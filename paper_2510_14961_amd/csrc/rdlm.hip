@@ -36,6 +36,7 @@ struct Knobs {
     bool no_fold_fusion = false;     // split-K folds in fold_k launches instead of the producing GEMM
     bool no_fold = false;            // full RMSNorm kernels instead of the deferred 1/rms factor
     bool no_lds_gemm = false;        // steps with three row tiles and more: the row-sharing kernel everywhere
+    bool no_pack = false;            // every sequence's rows start a row tile of their own (short windows are not packed)
     bool no_hoist = false;           // several recurrences per call: W_a . [e; z] in one product every time
     bool has_plan[PROJ_COUNT] = {}, has_plan_rows[PROJ_COUNT] = {};
     GemmPlan plan[PROJ_COUNT], plan_rows[PROJ_COUNT];
@@ -80,6 +81,7 @@ struct rdlm_ctx : Workspace {
     void* wa = nullptr;
     void* wa_e = nullptr;                // bf16: the two [h, h] halves of W_a packed on their own (the e half's
     void* wa_z = nullptr;                // product is computed once for all recurrences of a call)
+    int seg_tiles = 0;                   // bound on the segments (runs of up to 32 rows of one sequence) of the current tile list
     int att_groups = 0;                  // bound on the attention groups of the current tile list (0: the tile count)
     bool hoist_split = false;            // this step's prelude leaves e and z as separate adapter operands
     float* gf = nullptr;
@@ -252,7 +254,7 @@ static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, in
     w.att_tickets = (uint32_t*)take((size_t)max_tiles * m.n_heads * 4);
     w.step_ticket = (uint32_t*)take(64);
     w.ticket_bytes = off;
-    w.tiles = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
+    w.tiles = (TileDesc*)take(sizeof(TileDesc) * (R + max_tiles));     // row descriptors, then the segments
     w.n_tiles = (int32_t*)take(tile_count_bytes(max_tiles));
     w.x = (float*)take(R * h * 4);
     w.qkv = (float*)take(R * 3 * h * 4);
@@ -270,7 +272,7 @@ static size_t carve_workspace(Workspace* ws, void* base, const rdlm_model& m, in
     w.rope_tab = (float*)take(R * (m.head_dim / 2) * 8);
     if (m.dtype == RDLM_BF16) w.att_ws = (float*)take(attention_ws_floats(max_tiles, m.n_heads, m.head_dim, att_max_split) * 4);
     if (full) {
-        w.tiles_samp = (TileDesc*)take(sizeof(TileDesc) * max_tiles);
+        w.tiles_samp = (TileDesc*)take(sizeof(TileDesc) * (R + max_tiles));
         w.n_tiles_samp = (int32_t*)take(tile_count_bytes(max_tiles));
         w.e = (float*)take(R * h * 4);
         w.logits = (float*)take(R * V * 4);
@@ -390,6 +392,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
     if (is("no_fold")) { k->no_fold = atoi(value) != 0; return RDLM_OK; }
     if (is("no_lds_gemm")) { k->no_lds_gemm = atoi(value) != 0; return RDLM_OK; }
     if (is("no_hoist")) { k->no_hoist = atoi(value) != 0; return RDLM_OK; }
+    if (is("no_pack")) { k->no_pack = atoi(value) != 0; return RDLM_OK; }      // (refused while a sampler runs, see rdlm_set_tuning)
     for (int pj = 0; pj < PROJ_COUNT; ++pj) {
         char nm[32];
         // plan_<proj> = "nb,waves,unroll,ksplit": the one-tile launch shape ("" = default again)
@@ -426,7 +429,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
 }
 
 static void knobs_from_env(Knobs* k) {
-    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm", "no_hoist"};
+    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm", "no_hoist", "no_pack"};
     auto env_of = [](const char* name) {
         char buf[48] = "RDLM_";
         size_t n = strlen(buf);
@@ -446,6 +449,8 @@ static void knobs_from_env(Knobs* k) {
 
 extern "C" int rdlm_set_tuning(rdlm_ctx* ctx, const char* name, const char* value) {
     if (!ctx) return RDLM_EINVAL;
+    // the running sampler's tile list was laid out with the current setting
+    if (name && !strcmp(name, "no_pack") && ctx->sampler_on) return RDLM_ESTATE;
     return set_knob(&ctx->knobs, name, value);
 }
 
@@ -594,7 +599,7 @@ extern "C" int rdlm_seq_release(rdlm_ctx* ctx, int32_t seq) {
     if (ctx->sampler_on) {
         launch_seq_retire(ctx->seqs, seq, -1, ctx->st);         // frozen text stays readable
         launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
-                                   ctx->n_tiles_samp, ctx->st);
+                                   ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     }
     release_blocks(ctx, seq);
     ctx->pos_bound[seq] = 0;
@@ -898,9 +903,10 @@ static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, boo
     if (!rope_done)
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        kv_pages(ctx), ctx->tiles, ctx->n_tiles, T, st);
+    const int segs = ctx->seg_tiles > 0 ? ctx->seg_tiles : T;      // attention works on segments, not on row tiles
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, kv_pages(ctx),
-                     att_split_for(ctx, T, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
-                     ctx->n_tiles, T, st, ctx->att_groups);
+                     att_split_for(ctx, segs, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
+                     ctx->rows_pad, ctx->n_tiles, segs, st, ctx->att_groups);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
     bool folded = false;
     PROPAGATE(run_proj(ctx, PROJ_O, ctx->att, L.wo, T, &S, nullptr, false, false, nullptr, nullptr, &fo, &folded));
@@ -1031,6 +1037,21 @@ static int coda_forward(rdlm_ctx* ctx, const float* z, const SampleArgs* sa, int
 // ---------------------------------------------------------------------------------------------
 // argument checking shared by the row-based calls
 
+// Row tiles that windows of the given sizes take, laid out in order: a window of more than 32 rows gets
+// whole tiles; shorter ones are packed into the tile that is open as long as they fit.
+static int phys_tiles(const int32_t* rows, int n, bool pack) {
+    int np = 0, cap = 0;
+    for (int i = 0; i < n; ++i) {
+        const int r = rows[i];
+        if (r <= 0) continue;
+        const bool small = pack && r <= TILE_ROWS;
+        if (small && cap >= r) { cap -= r; continue; }
+        np += (r + TILE_ROWS - 1) / TILE_ROWS;
+        cap = small ? TILE_ROWS - r : 0;
+    }
+    return np;
+}
+
 static int check_rows(rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const int32_t* pos0,
                       const int32_t* n_rows, SeqWindows* w, int* T, int* M, int* max_keys) {
     if (!ctx || !seq_ids || !pos0 || !n_rows || n_seqs < 1) return RDLM_EINVAL;
@@ -1049,7 +1070,10 @@ static int check_rows(rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const i
         mk = std::max(mk, pos0[i] + n_rows[i]);
     }
     if (rows > ctx->max_rows || tiles > ctx->max_tiles) return RDLM_ECAPACITY;
-    *T = tiles; *M = rows; *max_keys = mk;
+    // row tiles of the step: windows of up to 32 rows share row tiles (the layout of TileLayout::add)
+    *T = phys_tiles(n_rows, n_seqs, !ctx->knobs.no_pack);
+    ctx->seg_tiles = tiles;
+    *M = rows; *max_keys = mk;
     bool grouped = false;
     for (int i = 0; i < n_seqs; ++i) grouped = grouped || n_rows[i] > TILE_ROWS;
     ctx->grouped = grouped;
@@ -1084,7 +1108,7 @@ extern "C" int rdlm_set_tokens(rdlm_ctx* ctx, int32_t seq, const int32_t* tokens
     launch_fill_i32(ctx->seq_ident + seq, seq, 1, ctx->st);
     if (ctx->sampler_on) {          // the slot leaves the running sampler until it joins again
         launch_seq_retire(ctx->seqs, seq, n, ctx->st);
-        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp,
+        launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack,
                                    ctx->st);
     }
     return check_launch(ctx);
@@ -1099,8 +1123,9 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->seg_tiles = T;
     ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
-    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, ctx->ident_host[seq], 0, n,
                            (size_t)seq * ctx->max_positions, alpha, (uint32_t)seed, (uint32_t)(seed >> 32), ctx->st);
     PROPAGATE(prelude_forward(ctx, ctx->y, ctx->e, -1, T, n));
@@ -1126,7 +1151,7 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
     if (!tokens_dev || !e_out) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
-    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     PROPAGATE(prelude_forward(ctx, tokens_dev, e_out, 1, T, mk));
     return check_launch(ctx);
 }
@@ -1134,7 +1159,7 @@ extern "C" int rdlm_prelude(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* seq_id
 // the body of rdlm_core_step over whatever workspace the context currently points at
 static int core_step_run(rdlm_ctx* ctx, const SeqWindows& w, int T, int M, int mk, const float* e, float* z_inout,
                          int r_inner, float* delta_out) {
-    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     if (delta_out)
         HIPCHK(hipMemcpyAsync(ctx->zp_api, z_inout, (size_t)M * ctx->m.hidden * 4, hipMemcpyDeviceToDevice, ctx->st));
@@ -1211,7 +1236,7 @@ extern "C" int rdlm_coda_decode(rdlm_ctx* ctx, int32_t n_seqs, const int32_t* se
     if (ctx && top_p > 0.f && top_p < 1.f && (ctx->m.vocab > TOPP_MAX_VOCAB || ctx->m.vocab % 4)) return RDLM_EINVAL;
     int rc = check_rows(ctx, n_seqs, seq_ids, pos0, n_rows, &w, &T, &M, &mk);
     if (rc) return rc;
-    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     SampleArgs sa = {temperature, (uint32_t)seed, (uint32_t)(seed >> 32), step, logits_out != nullptr, nullptr, top_p};
     PROPAGATE(coda_forward(ctx, z, &sa, T, mk));
@@ -1259,7 +1284,7 @@ extern "C" int rdlm_sampler_begin(rdlm_ctx* ctx, const rdlm_sampler* s, int32_t 
     }
     launch_fill_i32(ctx->seq_step0, 0, ctx->max_seqs, ctx->st);
     HIPCHK(hipMemcpy(ctx->seqs, hs.data(), sizeof(SeqState) * ctx->max_seqs, hipMemcpyHostToDevice));
-    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
+    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n_seqs, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     int32_t act[3] = {n_seqs, 0, 0};
     HIPCHK(hipMemcpy(ctx->n_active, act, sizeof(act), hipMemcpyHostToDevice));
     ctx->sampler = sp;
@@ -1296,7 +1321,7 @@ extern "C" int rdlm_sampler_join(rdlm_ctx* ctx, int32_t seq) {
     launch_seq_join(ctx->seqs, ctx->seq_step0, seq, L, ctx->step, ctx->st);
     ctx->samp_seqs = n;
     ctx->joined = true;
-    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->st);
+    launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, n, ctx->max_positions, ctx->tiles_samp, ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     return check_launch(ctx);
 }
 
@@ -1378,7 +1403,7 @@ extern "C" int rdlm_seq_evict(rdlm_ctx* ctx, int32_t seq, void* host_buf, size_t
     if (ctx->sampler_on) {
         launch_seq_retire(ctx->seqs, seq, 0, ctx->st);
         launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
-                                   ctx->n_tiles_samp, ctx->st);
+                                   ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     }
     release_blocks(ctx, seq);
     ctx->pos_bound[seq] = 0;
@@ -1439,7 +1464,7 @@ extern "C" int rdlm_seq_admit(rdlm_ctx* ctx, int32_t seq, const void* host_buf, 
         ctx->joined = true;
         // (the device's count of unfinished sequences is brought up to date by the next step's bookkeeping)
         launch_build_tiles_sampler(ctx->seqs, ctx->seq_ident, ctx->samp_seqs, ctx->max_positions, ctx->tiles_samp,
-                                   ctx->n_tiles_samp, ctx->st);
+                                   ctx->n_tiles_samp, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     }
     HIPCHK(hipStreamSynchronize(ctx->st));
     return check_launch(ctx);
@@ -1474,7 +1499,11 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     long long grow = 1 + (long long)(t - 1) * s.headway;
     const long long in_flight = (long long)((s.r_total + s.r_inner - 1) / s.r_inner) * s.headway;
     int wmax_now = (int)std::min<long long>(std::min<long long>(s.w_max, in_flight), grow);   // (a joined sequence restarts at 1: still a bound)
-    const int T = n * ((wmax_now + 31) / 32);
+    const int segs = n * ((wmax_now + 31) / 32);
+    // row tiles: windows of up to 32 rows are packed in sequence order into the tile that is open, so a tile
+    // that is closed holds at least floor(32 / wmax_now) of them
+    const int T = (!ctx->knobs.no_pack && wmax_now <= TILE_ROWS) ? (n + TILE_ROWS / wmax_now - 1) / (TILE_ROWS / wmax_now) : segs;
+    ctx->seg_tiles = segs;
     ctx->grouped = wmax_now > TILE_ROWS;
     ctx->att_groups = n * (((wmax_now + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP);
     int max_keys = 0;
@@ -1515,7 +1544,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     }
     // freeze, append, InitState of the appended positions, tile list of the next step
     launch_step_end(ctx->seqs, ctx->seq_ident, n, ctx->sp, ctx->y, ctx->counts, ctx->max_positions, ctx->drafts, ctx->delta,
-                    ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->step_ticket,
+                    ctx->z_store, ctx->z_prev, m.hidden, ctx->tiles, ctx->n_tiles, ctx->n_active, t, ctx->step_ticket, ctx->rows_pad, !ctx->knobs.no_pack,
                     ctx->st);
     std::swap(ctx->tiles, ctx->tiles_samp);
     std::swap(ctx->n_tiles, ctx->n_tiles_samp);
@@ -1631,7 +1660,7 @@ extern "C" int rdlm_read_deltas(rdlm_ctx* ctx, int32_t seq, float* delta_host, i
     HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
     int n = std::min(cap, q.last_rows);
     if (n > 0)
-        HIPCHK(hipMemcpy(delta_host, ctx->delta + (size_t)q.last_tile0 * 32, (size_t)n * 4, hipMemcpyDeviceToHost));
+        HIPCHK(hipMemcpy(delta_host, ctx->delta + (size_t)q.last_row0, (size_t)n * 4, hipMemcpyDeviceToHost));
     *n_out = q.last_rows;
     return RDLM_OK;
 }
@@ -1692,7 +1721,8 @@ static int linear_setup(rdlm_ctx* ctx, int m_rows, int* T) {
     SeqWindows w;
     w.n = 1; w.seq[0] = 0; w.pos0[0] = 0; w.rows[0] = m_rows;
     *T = (m_rows + 31) / 32;
-    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->st);
+    ctx->seg_tiles = *T;
+    launch_build_tiles_api(w, ctx->seq_ident, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     return RDLM_OK;
 }
 
@@ -1870,8 +1900,9 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->seg_tiles = T;
     ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
-    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->st);
+    launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
     launch_rope_table(ctx->rope_tab, ctx->theta, ctx->m.head_dim / 2, ctx->tiles, ctx->n_tiles, T, ctx->st);
     const size_t zrow0 = (size_t)seq * ctx->max_positions + pos0;
     launch_init_state_rows(ctx->z_store, nullptr, ctx->m.hidden, seq, pos0, n, zrow0, 1.0f, 7u, 0u, ctx->st);

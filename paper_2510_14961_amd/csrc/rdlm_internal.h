@@ -8,7 +8,17 @@ namespace rdlm {
 
 // A step works on "tiles" of up to 32 rows.  Every tile belongs to one sequence and covers
 // contiguous positions; rows of a tile beyond n_valid are padding (computed, never stored into
-// caches or states).  Internal activations use the padded row index tile*32 + j.
+// caches or states).  Internal activations use the padded ("physical") row index.
+//
+// Two kinds of descriptor share this struct and one device array (`tiles`):
+//   tiles[r], r < rows_pad: the descriptor of physical row r alone -- pos0 is the row's position, the
+//     *row0 fields its own rows in the arrays it reads and writes, n_valid 1 (0: padding row);
+//   tiles[rows_pad + s]: segment s, up to 32 rows of one sequence at consecutive positions, at physical
+//     rows prow0 .. prow0 + n_valid - 1.
+// The matrix products and the row-wise kernels work on physical rows in tiles of 32 (descriptor by row);
+// attention works on segments.  A sequence with more than 32 rows owns whole physical tiles, one segment
+// each; sequences with fewer rows are packed, several segments to a physical tile (a batch of short
+// windows then costs the products one row tile, not one per sequence).
 struct TileDesc {
     int32_t seq;      // sequence (selects the KV-cache slab)
     int32_t pos0;     // absolute position of row 0 of the tile
@@ -21,6 +31,7 @@ struct TileDesc {
                       // together by the workgroup of tile t; 0 = served by an earlier tile's workgroup
     int32_t rng;      // identity of the sequence in the counters of the random generator (its slot number
                       // unless the sequence moved in from another slot)
+    int32_t prow0;    // physical row of the segment's first row (of the row itself in a row descriptor)
 };
 
 // Paged KV cache (App. "Larger batch sizes": state slots are fungible): a layer's K and V entries live in
@@ -36,9 +47,10 @@ __device__ inline size_t kv_block_base(const KvPages& kv, int seq, int block, si
 constexpr int ATT_GROUP = 4;
 
 constexpr int TILE_ROWS = 32;
-// The word block behind a tile list: [0] number of tiles, [1] number of attention groups, and from
-// TILE_LEADERS on the tile index of each group's first tile (so that the grouped attention kernels
-// launch one workgroup per group and split, none for the tiles a group serves).
+// The word block behind a tile list: [0] number of physical row tiles, [1] number of attention groups,
+// [2] number of segments, and from TILE_LEADERS on the segment index of each group's first segment (so
+// that the grouped attention kernels launch one workgroup per group and split, none for the segments a
+// group serves).
 constexpr int TILE_LEADERS = 16;
 inline size_t tile_count_bytes(int max_tiles) { return (size_t)(TILE_LEADERS + max_tiles) * 4; }
 constexpr int MAX_API_SEQS = 64;      // sequences per API call (descriptor passed as a kernel argument)
@@ -61,9 +73,9 @@ struct SeqState {
     int32_t last_pos0;
     int32_t new_pos0;     // states appended by the last bookkeeping pass: [new_pos0, new_pos0+new_n)
     int32_t new_n;
-    int32_t last_tile0;   // first row tile the sequence had in the last step
-    int32_t cur_rows;     // rows / first row tile of the sequence in the tile list built for the next step
-    int32_t cur_tile0;
+    int32_t last_row0;    // first physical row the sequence had in the last step
+    int32_t cur_rows;     // rows / first physical row of the sequence in the tile list built for the next step
+    int32_t cur_row0;
 };
 
 struct SamplerParams {
@@ -219,12 +231,14 @@ constexpr int SSQ_MAX_CHUNKS = 256;   // slots per row: chunks of fold_k, or fea
 
 // elementwise / row kernels ------------------------------------------------------------------
 // ident: per slot, the sequence's identity in the random generator's counters
-void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+// tiles: [rows_pad] row descriptors followed by the segments; pack: short windows share row tiles
+void launch_build_tiles_api(const SeqWindows& w, const int32_t* ident, TileDesc* tiles, int32_t* n_tiles, int rows_pad,
+                            bool pack, hipStream_t st);
 // same, but rows map to the library's per-(sequence, position) stores instead of compact arrays
 void launch_build_tiles_store(const SeqWindows& w, const int32_t* ident, int max_positions, TileDesc* tiles,
-                              int32_t* n_tiles, hipStream_t st);
+                              int32_t* n_tiles, int rows_pad, bool pack, hipStream_t st);
 void launch_build_tiles_sampler(const SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
-                                TileDesc* tiles, int32_t* n_tiles, hipStream_t st);
+                                TileDesc* tiles, int32_t* n_tiles, int rows_pad, bool pack, hipStream_t st);
 // block table entries table[first + i] = ids[i], i < n <= 16 (new blocks of a growing sequence)
 struct BlockIds { int32_t n; int32_t first; int32_t id[16]; };
 void launch_table_set(int32_t* table, BlockIds ids, hipStream_t st);
@@ -300,7 +314,8 @@ void launch_seq_retire(SeqState* seqs, int seq, int prompt_len, hipStream_t st);
 // positions, and the tile list of the next step.  ticket: one device word, zero between launches.
 void launch_step_end(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y, int32_t* counts,
                      int max_positions, const int32_t* drafts, const float* delta, float* z, float* z_prev, int h,
-                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, hipStream_t st);
+                     TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, int rows_pad,
+                     bool pack, hipStream_t st);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t st);
 void launch_read_kv(const void* kc, const void* vc, KvPages kv, int seq, int dtype, int H, int d, int pos0, int n,
                     float* k_out, float* v_out, hipStream_t st);
@@ -334,8 +349,9 @@ double launch_mfma_loop(float* out, int workgroups, int iters, hipStream_t st);
 // format of the model dtype, width H*d.  ws: split-KV partials.
 void launch_attention(const void* q, const void* kc, const void* vc, void* out, int dtype, int H, int d,
                       KvPages kv, int nsplit, bool grouped, float* ws,
-                      uint32_t* tickets /* [max_tiles][H], zero between launches */, const TileDesc* tiles,
-                      const int32_t* n_tiles, int max_tiles, hipStream_t st,
+                      uint32_t* tickets /* [max_tiles][H], zero between launches */,
+                      const TileDesc* tiles /* row descriptors, then the segments */, int rows_pad,
+                      const int32_t* n_tiles, int max_tiles /* bound on the segments */, hipStream_t st,
                       int max_groups = 0 /* grouped: the host's bound on the number of attention groups (0: max_tiles) */);
 size_t attention_ws_floats(int max_tiles, int H, int d, int nsplit);
 
