@@ -267,6 +267,9 @@ int rdlm_sampler_status(rdlm_ctx* ctx, int32_t* n_active_out, int32_t* nonfinite
  * Copies min(cap, max_positions) entries of y_current (frozen, then current drafts, then pad). */
 int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap,
                      int32_t* n_frozen_out);
+/* The frozen text alone (y_frozen of Alg. 1 / Alg. 2: the prompt and the tokens made final so far):
+ * *n_out = |y_frozen|, of which min(cap, |y_frozen|) tokens are copied. */
+int rdlm_read_frozen(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap, int32_t* n_out);
 /* Latent states kept per position by the sampler (the state a position had when last updated). */
 int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host);
 /* z_prev of Alg. 2 per position: the state the position had at the end of the step before the last

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "rdlm_core_step_static_bytes", "rdlm_sampler_status", "rdlm_set_tuning", "rdlm_read_prev_states",
     "rdlm_read_window", "rdlm_time_stream_read", "rdlm_time_mfma_loop",
     "rdlm_create_paged", "rdlm_kv_blocks", "rdlm_seq_release", "rdlm_seq_evict_bytes", "rdlm_seq_evict",
-    "rdlm_seq_admit",
+    "rdlm_seq_admit", "rdlm_read_frozen",
 ]
 
 STATUS = {"OK": 0, "EINVAL": -1, "ECAPACITY": -2, "ENOMEM": -3, "EHIP": -4, "ESTATE": -5, "ENUMERIC": -6}
@@ -86,6 +86,7 @@ def load_library():
         "rdlm_sample_step": (C.c_int, [vp]),
         "rdlm_generate": (C.c_int, [vp, i32, pi32]),
         "rdlm_read_tokens": (C.c_int, [vp, i32, pi32, i32, pi32]),
+        "rdlm_read_frozen": (C.c_int, [vp, i32, pi32, i32, pi32]),
         "rdlm_read_states": (C.c_int, [vp, i32, i32, i32, C.POINTER(C.c_float)]),
         "rdlm_read_counts": (C.c_int, [vp, i32, i32, i32, pi32]),
         "rdlm_read_deltas": (C.c_int, [vp, i32, C.POINTER(C.c_float), i32, pi32]),
@@ -338,6 +339,13 @@ class Context:
         self._chk(self.lib.rdlm_read_prev_states(self.ctx, seq, pos0, n, buf.ctypes.data_as(C.POINTER(C.c_float))),
                   "rdlm_read_prev_states")
         return buf
+
+    def read_frozen(self, seq: int):
+        """the frozen text: prompt + tokens made final so far"""
+        buf = np.zeros(self.max_positions, np.int32)
+        n = C.c_int32(0)
+        self._chk(self.lib.rdlm_read_frozen(self.ctx, seq, _iptr(buf), len(buf), C.byref(n)), "rdlm_read_frozen")
+        return buf[: n.value].copy()
 
     def read_window(self, seq: int):
         """(position of the oldest in-flight state, number of in-flight states, finished)"""

@@ -114,10 +114,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
     float m_run[MTQ], l_run[MTQ];                             // l_run: this half-wave's share of the sum
 #pragma unroll
     for (int b = 0; b < MTQ; ++b) {
-        const TileDesc tb = b == 0 ? td : tiles[t + min(b, ng - 1)];
-        const uint16_t* qr = q + ((size_t)tb.prow0 + min(col, tb.n_valid - 1)) * h + hd * D + g * 8;
+        // The queries are asked for before the descriptor is there, at the rows the segment has when no
+        // rows are packed (segment t = row tile t: valid memory in any case), and asked for again only if
+        // the segment starts elsewhere -- so the usual case does not wait for two loads in a row.
+        const uint16_t* qr0 = q + ((size_t)(t + b) * 32 + col) * h + hd * D + g * 8;
 #pragma unroll
-        for (int i = 0; i < DK; ++i) qv[b][i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
+        for (int i = 0; i < DK; ++i) qv[b][i] = *reinterpret_cast<const bf16x8*>(qr0 + i * 16);
+        const TileDesc tb = b == 0 ? td : tiles[t + min(b, ng - 1)];
+        if (tb.prow0 != (t + b) * 32) {
+            const uint16_t* qr = q + ((size_t)tb.prow0 + min(col, tb.n_valid - 1)) * h + hd * D + g * 8;
+#pragma unroll
+            for (int i = 0; i < DK; ++i) qv[b][i] = *reinterpret_cast<const bf16x8*>(qr + i * 16);
+        }
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -125,9 +133,18 @@ __global__ __launch_bounds__(ATT_WAVES * 64, D <= 96 ? 2 : 1) void attn_bf16_k(c
         m_run[b] = -INFINITY; l_run[b] = 0.f;
     }
 
+    // block table entries of the split's first 64 key blocks, one per lane, fetched once (next to the
+    // queries): the loads of a key block then do not wait for a table lookup of their own
+    int entry = 0;
+    if (kb_lo < kb_hi) entry = kvp.table[(size_t)td.seq * kvp.stride + min(kb_lo + lane, kb_hi - 1)];
+    auto block_base = [&](int kb) -> size_t {
+        const int rel = kb - kb_lo;
+        const int id = rel < 64 ? __builtin_amdgcn_readlane(entry, rel) : kvp.table[(size_t)td.seq * kvp.stride + kb];
+        return (size_t)id * block_elems;
+    };
     bf16x8 kA[DK], vA[2 * DB], kB[DK], vB[2 * DB];
     auto load = [&](bf16x8(&kv)[DK], bf16x8(&vv)[2 * DB], int kb) {
-        const size_t base = kv_block_base(kvp, td.seq, kb, block_elems);
+        const size_t base = block_base(kb);
         const uint16_t* kr = kc + base + k_cache_off(col, hd, g * 8, H, D);
 #pragma unroll
         for (int i = 0; i < DK; ++i) kv[i] = *reinterpret_cast<const bf16x8*>(kr + i * 512);
@@ -366,9 +383,13 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
         const uint16_t* sv = vc + (size_t)hd * D * 32 + (size_t)c * 32 + gg * 8 + (size_t)(j >> 1) * 32 * 32 + (j & 1) * 16;
         fbase[p] = i < DK ? sk : sv;
     }
+    int entry = 0;                                            // block table entries of the first 64 key blocks, one per lane
+    if (kb_lo < kb_hi) entry = kvp.table[(size_t)td.seq * kvp.stride + min(kb_lo + lane, kb_hi - 1)];
     bf16x8 fetch0[PER], fetch1[PER];
     auto load = [&](bf16x8(&fetch)[PER], int kb) {
-        const size_t base = kv_block_base(kvp, td.seq, kb, kb_stride);
+        const int rel = kb - kb_lo;
+        const int id = rel < 64 ? __builtin_amdgcn_readlane(entry, rel) : kvp.table[(size_t)td.seq * kvp.stride + kb];
+        const size_t base = (size_t)id * kb_stride;
 #pragma unroll
         for (int p = 0; p < PER; ++p) fetch[p] = *reinterpret_cast<const bf16x8*>(fbase[p] + base);
     };

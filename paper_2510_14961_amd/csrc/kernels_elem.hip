@@ -41,8 +41,10 @@ __device__ inline float4 ld4(const float* p) { return *reinterpret_cast<const fl
 // A window of more than 32 rows gets whole row tiles (one segment per tile, groups of up to ATT_GROUP
 // segments for the attention kernels); shorter windows are packed one after the other into the row
 // tile that is open, as long as they fit (`pack`), so a batch of short windows shares row tiles.
+constexpr int TILE_LDS_SEGS = 64;
 struct TileLayout {
     TileDesc* tiles;        // [rows_pad] row descriptors, then the segments
+    TileDesc* sh_segs = nullptr;   // LDS copy of the first TILE_LDS_SEGS segments
     int32_t* n_tiles;
     int rows_pad, pack;
     int n_seg = 0, n_phys = 0, n_lead = 0, c = 0, open_row = 0, open_cap = 0;
@@ -76,17 +78,42 @@ struct TileLayout {
             const int k = off / TILE_ROWS, left = (nrows - off + TILE_ROWS - 1) / TILE_ROWS;
             d.group = (k % ATT_GROUP == 0) ? min(ATT_GROUP, left) : 0;
             if (d.group > 0) n_tiles[TILE_LEADERS + n_lead++] = n_seg;
+            if (n_seg < TILE_LDS_SEGS) sh_segs[n_seg] = d;
             segs[n_seg++] = d;
         }
         c += nrows;
         return first;
     }
-    __device__ void counts() { n_tiles[0] = n_phys; n_tiles[1] = n_lead; n_tiles[2] = n_seg; }
+    // counts and (up to TILE_LDS_SEGS) segments also go to LDS, so that the other threads of the workgroup
+    // need no trip through memory to write the row descriptors
+    __device__ void counts(int* sh_counts) {
+        n_tiles[0] = n_phys; n_tiles[1] = n_lead; n_tiles[2] = n_seg;
+        sh_counts[0] = n_phys; sh_counts[1] = n_seg;
+    }
     // all threads, after a barrier behind counts(): the descriptor of every physical row
-    __device__ void rows() {
-        const int np = n_tiles[0], ns = n_tiles[2];
+    __device__ void rows(const int* sh_counts, const TileDesc* sh_segs) {
+        const int np = sh_counts[0], ns = sh_counts[1];
         TileDesc pad;
         pad.seq = 0; pad.pos0 = 0; pad.n_valid = 0; pad.zrow0 = pad.erow0 = pad.yrow0 = pad.crow0 = 0; pad.group = 0; pad.rng = 0;
+        if (ns <= TILE_LDS_SEGS) {
+            // one pass: every row looks its segment up in LDS (segments are in ascending row order)
+            for (int r = threadIdx.x; r < np * TILE_ROWS; r += blockDim.x) {
+                TileDesc rd = pad;
+                rd.prow0 = r;
+                for (int sg = 0; sg < ns; ++sg) {
+                    const int p0 = sh_segs[sg].prow0;
+                    if (r >= p0 && r < p0 + sh_segs[sg].n_valid) {
+                        const int j = r - p0;
+                        rd = sh_segs[sg];
+                        rd.pos0 += j; rd.zrow0 += j; rd.erow0 += j; rd.yrow0 += j; rd.crow0 += j; rd.prow0 = r;
+                        rd.n_valid = 1; rd.group = 0;
+                        break;
+                    }
+                }
+                tiles[r] = rd;
+            }
+            return;
+        }
         for (int r = threadIdx.x; r < np * TILE_ROWS; r += blockDim.x) { pad.prow0 = r; tiles[r] = pad; }
         __syncthreads();
         const TileDesc* segs = tiles + rows_pad;
@@ -104,21 +131,25 @@ struct TileLayout {
 
 __global__ void build_tiles_api_k(SeqWindows w, const int32_t* ident, int mode, int max_positions, TileDesc* tiles,
                                   int32_t* n_tiles, int rows_pad, int pack) {
+    __shared__ int sh_counts[2];
+    __shared__ TileDesc sh_segs[TILE_LDS_SEGS];
     TileLayout lay;
-    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack; lay.sh_segs = sh_segs;
     if (threadIdx.x == 0) {
         for (int i = 0; i < w.n; ++i)
             lay.add(w.seq[i], ident[w.seq[i]], w.pos0[i], w.rows[i], mode == 0 ? -1LL : (long long)w.seq[i] * max_positions);
-        lay.counts();
+        lay.counts(sh_counts);
     }
     __syncthreads();
-    lay.rows();
+    lay.rows(sh_counts, sh_segs);
 }
 
 __global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int n_seqs, int max_positions,
                                       TileDesc* tiles, int32_t* n_tiles, int rows_pad, int pack) {
+    __shared__ int sh_counts[2];
+    __shared__ TileDesc sh_segs[TILE_LDS_SEGS];
     TileLayout lay;
-    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack; lay.sh_segs = sh_segs;
     if (threadIdx.x == 0) {
         for (int s = 0; s < n_seqs; ++s) {
             SeqState& q = seqs[s];
@@ -126,10 +157,10 @@ __global__ void build_tiles_sampler_k(SeqState* seqs, const int32_t* ident, int 
             q.cur_rows = rows;
             q.cur_row0 = lay.add(s, ident[s], q.win_pos0, rows, (long long)s * max_positions);
         }
-        lay.counts();
+        lay.counts(sh_counts);
     }
     __syncthreads();
-    lay.rows();
+    lay.rows(sh_counts, sh_segs);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -865,8 +896,10 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
     // tile list of the next step: the records of up to 256 sequences at a time are fetched in
     // parallel, one thread lays the windows out in sequence order, all write the row descriptors
     __shared__ int32_t s_done[256], s_win_n[256], s_pos0[256];
+    __shared__ int sh_counts[2];
+    __shared__ TileDesc sh_segs[TILE_LDS_SEGS];
     TileLayout lay;
-    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack;
+    lay.tiles = tiles; lay.n_tiles = n_tiles; lay.rows_pad = rows_pad; lay.pack = pack; lay.sh_segs = sh_segs;
     int active = 0;
     for (int s0 = 0; s0 < n_seqs; s0 += 256) {
         const int i = s0 + tid;
@@ -891,10 +924,10 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
         // n_active[1] remembers the step at which the last sequence finished (0 = still running)
         if (active == 0 && n_active[0] != 0) n_active[1] = step;
         n_active[0] = active;
-        lay.counts();
+        lay.counts(sh_counts);
     }
     __syncthreads();
-    lay.rows();
+    lay.rows(sh_counts, sh_segs);
     if (tid == 0 && gridDim.x > 1) __hip_atomic_store(ticket_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 

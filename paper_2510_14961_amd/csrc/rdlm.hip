@@ -1611,6 +1611,23 @@ extern "C" int rdlm_read_tokens(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host
     return RDLM_OK;
 }
 
+// The frozen text only (y_frozen of Alg. 1 / Alg. 2): prompt and the tokens made final so far.
+extern "C" int rdlm_read_frozen(rdlm_ctx* ctx, int32_t seq, int32_t* tokens_host, int32_t cap, int32_t* n_out) {
+    if (!ctx || !tokens_host || !n_out || cap < 0 || seq < 0) return RDLM_EINVAL;
+    if (seq >= ctx->max_seqs) return RDLM_ECAPACITY;
+    HIPCHK(hipStreamSynchronize(ctx->st));
+    int nf = ctx->prompt_len[seq];
+    if (ctx->sampler_on) {
+        SeqState q;
+        HIPCHK(hipMemcpy(&q, ctx->seqs + seq, sizeof(q), hipMemcpyDeviceToHost));
+        nf = q.n_frozen;
+    }
+    *n_out = nf;
+    const int n = std::min(std::min(cap, nf), ctx->max_positions);
+    if (n > 0) HIPCHK(hipMemcpy(tokens_host, ctx->y + (size_t)seq * ctx->max_positions, (size_t)n * 4, hipMemcpyDeviceToHost));
+    return RDLM_OK;
+}
+
 extern "C" int rdlm_read_states(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int32_t n, float* z_host) {
     if (!ctx || !z_host || seq < 0 || pos0 < 0 || n < 0) return RDLM_EINVAL;
     if (seq >= ctx->max_seqs || (long long)pos0 + n > ctx->max_positions) return RDLM_ECAPACITY;

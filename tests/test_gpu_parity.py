@@ -189,6 +189,7 @@ def test_top_p_free_running_fp32(temp, top_p):
     toks, n_frozen = ctx.read_tokens(0)
     assert steps == ref.steps and n_frozen == 12 + n_new
     assert np.array_equal(toks[: n_frozen], ref.tokens)
+    assert np.array_equal(ctx.read_frozen(0), ref.tokens)
     if temp == 1.0:
         base = O.generate_diffusion_forcing(m, prompt, n_new, r_inner, r, temperature=temp, seed=6)
         assert not np.array_equal(base.tokens, ref.tokens)
