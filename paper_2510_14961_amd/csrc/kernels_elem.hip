@@ -98,18 +98,25 @@ struct TileLayout {
         if (ns <= TILE_LDS_SEGS) {
             // one pass: every row looks its segment up in LDS (segments are in ascending row order)
             for (int r = threadIdx.x; r < np * TILE_ROWS; r += blockDim.x) {
-                TileDesc rd = pad;
-                rd.prow0 = r;
+                int found = -1;
                 for (int sg = 0; sg < ns; ++sg) {
                     const int p0 = sh_segs[sg].prow0;
-                    if (r >= p0 && r < p0 + sh_segs[sg].n_valid) {
-                        const int j = r - p0;
-                        rd = sh_segs[sg];
-                        rd.pos0 += j; rd.zrow0 += j; rd.erow0 += j; rd.yrow0 += j; rd.crow0 += j; rd.prow0 = r;
-                        rd.n_valid = 1; rd.group = 0;
-                        break;
-                    }
+                    if (r >= p0 && r < p0 + sh_segs[sg].n_valid) found = sg;
                 }
+                const int sg = max(found, 0);
+                const int j = r - sh_segs[sg].prow0;
+                const bool ok = found >= 0;
+                TileDesc rd;
+                rd.seq = ok ? sh_segs[sg].seq : 0;
+                rd.pos0 = ok ? sh_segs[sg].pos0 + j : 0;
+                rd.n_valid = ok ? 1 : 0;
+                rd.zrow0 = ok ? sh_segs[sg].zrow0 + j : 0;
+                rd.erow0 = ok ? sh_segs[sg].erow0 + j : 0;
+                rd.yrow0 = ok ? sh_segs[sg].yrow0 + j : 0;
+                rd.crow0 = ok ? sh_segs[sg].crow0 + j : 0;
+                rd.group = 0;
+                rd.rng = ok ? sh_segs[sg].rng : 0;
+                rd.prow0 = r;
                 tiles[r] = rd;
             }
             return;
@@ -808,7 +815,7 @@ __global__ __launch_bounds__(TOPP_THREADS) void sample_top_p_k(const float* logi
 // append, Alg. 2) and drawn (InitState).  The last workgroup to finish then builds the tile list
 // of the next step from all updated windows: the sequence records are handed over with
 // system-scope stores and loads around a ticket (no device-scope fence), as the GEMM folds are.
-__global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y,
+__global__ __launch_bounds__(1024) void step_end_k(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerParams p, int32_t* y,
                                                    int32_t* counts, int max_positions, const int32_t* drafts,
                                                    const float* delta, float* z, float* z_prev, int h,
                                                    TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step,
@@ -870,15 +877,18 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
             // InitState for the appended positions: a random draw, or ("continuous compute", App.,
             // additional hyperparameter sweeps) the latest state of the position one step to the
             // left, which is the last row of the window this step ran on
+            // (the draws are the bulk of this kernel's time -- a counter-based generator and a Box-Muller
+            // transform per four values -- which is why the workgroup has 1024 threads)
             const int nb = (h + 3) / 4;
             const size_t left = (base + q.new_pos0 - 1) * h;
+            const int id = ident[s];
             for (int idx = tid; idx < q.new_n * nb; idx += blockDim.x) {
                 const int a = idx / nb, blk = idx - a * nb, pos = q.new_pos0 + a;
                 float g[4];
                 if (p.init_mode == 1) {
                     for (int i = 0; i < 4 && blk * 4 + i < h; ++i) g[i] = z[left + blk * 4 + i];
                 } else {
-                    gauss4(blk, pos, ident[s], p.seed_lo, p.seed_hi, p.alpha, g);
+                    gauss4(blk, pos, id, p.seed_lo, p.seed_hi, p.alpha, g);
                 }
                 for (int i = 0; i < 4 && blk * 4 + i < h; ++i) {
                     const size_t o = (base + pos) * h + blk * 4 + i;
@@ -903,7 +913,7 @@ __global__ __launch_bounds__(256) void step_end_k(SeqState* seqs, const int32_t*
     int active = 0;
     for (int s0 = 0; s0 < n_seqs; s0 += 256) {
         const int i = s0 + tid;
-        if (i < n_seqs) {
+        if (tid < 256 && i < n_seqs) {
             s_done[tid] = __hip_atomic_load(&seqs[i].done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             s_win_n[tid] = __hip_atomic_load(&seqs[i].win_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
             s_pos0[tid] = __hip_atomic_load(&seqs[i].win_pos0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -1130,7 +1140,7 @@ void launch_step_end(SeqState* seqs, const int32_t* ident, int n_seqs, SamplerPa
                      int max_positions, const int32_t* drafts, const float* delta, float* z, float* z_prev, int h,
                      TileDesc* tiles, int32_t* n_tiles, int32_t* n_active, int step, uint32_t* ticket, int rows_pad,
                      bool pack, hipStream_t st) {
-    hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(256), 0, st, seqs, ident, n_seqs, p, y, counts, max_positions, drafts,
+    hipLaunchKernelGGL(step_end_k, dim3(n_seqs), dim3(1024), 0, st, seqs, ident, n_seqs, p, y, counts, max_positions, drafts,
                        delta, z, z_prev, h, tiles, n_tiles, n_active, step, ticket, rows_pad, pack ? 1 : 0);
 }
 void launch_seq_join(SeqState* seqs, int32_t* seq_step0, int seq, int prompt_len, int step, hipStream_t st) {
