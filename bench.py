@@ -227,6 +227,48 @@ def batch_sweep(args):
           flush=True)
 
 
+def window_sweep(args):
+    """Tokens in flight against throughput (Sec. 4.2: wavefront size and headway; the paper finds its optimum
+    at 64-128 tokens on A100 and calls it accelerator-specific).  3.5B shape, batch 1, prompt 512, r = 32, fixed
+    exit, greedy.  (a) headway h = 1..16 at r' = 1: window 32 h, h tokens frozen per step; (b) inner recurrences
+    r' = 1..32 at headway 1: window 32 / r', down to the autoregressive sampler at r' = r (end of Sec. 3.3)."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape = S.BIG
+    r = 32
+    dev, _ = build_weights(shape, 1, False, args.threads)
+    ctx = R.Context(shape, dev, 1, 512 + 16 * 200 + 640, 512)
+    del dev
+    torch.cuda.empty_cache()
+    prompt = S.make_prompt(shape.vocab, 512, 5, seq=0)
+    out = []
+    for r_inner, headway in [(1, 1), (1, 2), (1, 3), (1, 4), (1, 6), (1, 8), (1, 12), (1, 16),
+                             (2, 1), (4, 1), (8, 1), (16, 1), (32, 1)]:
+        fill = -(-r // r_inner)
+        K = 40 if r_inner <= 4 else 12
+        ctx.set_tokens(0, prompt)
+        ctx.prefill(0, 511, 1, 1.0, 1)                 # (timing only: one recurrence fills the caches)
+        ctx.sampler_begin(1, n_new=(fill + K + 8) * headway, r_inner=r_inner, r_total=r, headway=headway, seed=1)
+        for _ in range(fill + 4):
+            ctx.sample_step()
+        n0 = ctx.read_tokens(0, 1)[1]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            ctx.sample_step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        tokens = ctx.read_tokens(0, 1)[1] - n0
+        row = {"r_inner": r_inner, "headway": headway, "window": fill * headway, "ms_per_step": dt / K * 1e3,
+               "tokens_per_step": tokens / K, "tokens_per_s": tokens / dt}
+        out.append(row)
+        log(f"[window] r' {r_inner:2d} headway {headway:2d} window {row['window']:4d}: {row['ms_per_step']:.3f} ms/step, "
+            f"{row['tokens_per_s']:.0f} tokens/s")
+    print(json.dumps({"window_sweep": out, "shape": "3.5B: 5280 x 55 x 96, mlp 17920, P2/R4/C2, bf16, prompt 512, "
+                      "r 32, fixed exit, greedy, batch 1"}), flush=True)
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,6 +291,8 @@ def main():
     ap.add_argument("--batch-sweep", action="store_true",
                     help="instead of the benchmark: sampler steps of batches of sequences with short windows, rows "
                          "packed into shared row tiles against one row tile per sequence")
+    ap.add_argument("--window-sweep", action="store_true",
+                    help="tokens/s against the number of tokens in flight: headway 1..16 and r' 1..32 (Sec. 4.2)")
     ap.add_argument("--core-sweep", action="store_true",
                     help="instead of the benchmark: time one core step (r' = 1) at the 3.5B shape over a grid of window "
                          "rows x cached context, print the table and the measured ridge (rows at which the step "
@@ -267,6 +311,9 @@ def main():
     import paper_2510_14961_amd as R
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.window_sweep:
+        window_sweep(args)
+        return
     if args.batch_sweep:
         batch_sweep(args)
         return
