@@ -1420,8 +1420,18 @@ extern "C" int rdlm_seq_admit(rdlm_ctx* ctx, int32_t seq, const void* host_buf, 
     if (hd.n_pos < 0 || hd.n_blocks < 0 || bytes < evict_bytes(ctx, hd.n_pos, hd.n_blocks))
         return RDLM_EINVAL;
     if (hd.n_pos > ctx->max_positions || hd.n_blocks > ctx->blocks_per_seq) return RDLM_ECAPACITY;
+    // what the record says about itself must hang together before any of it reaches the device
+    if (hd.prompt_len < 0 || hd.prompt_len > hd.n_pos || hd.pos_bound < 0 || hd.pos_bound > ctx->max_positions ||
+        hd.local_steps < 0)
+        return RDLM_EINVAL;
     if (ctx->seq_blocks[seq] != 0 || ctx->pos_bound[seq] > 0) return RDLM_ESTATE;       // the slot must be empty (released)
     if (hd.in_sampler) {
+        const SeqState& q = hd.st;
+        if (q.prompt_len != hd.prompt_len || q.n_frozen < q.prompt_len || q.win_pos0 < 0 || q.win_n < 0 ||
+            q.win_n > std::max(hd.sampler.w_max, 1) || q.new_pos0 < 0 || q.new_n < 0 ||
+            (long long)q.win_pos0 + q.win_n > hd.pos_bound || (long long)q.new_pos0 + q.new_n > hd.pos_bound ||
+            q.n_frozen > hd.pos_bound || hd.pos_bound > hd.n_pos)
+            return RDLM_EINVAL;
         if (!ctx->sampler_on || memcmp(&hd.sampler, &ctx->sampler, sizeof(rdlm_sampler)) != 0) return RDLM_ESTATE;
         const rdlm_sampler& sp = ctx->sampler;
         const int n = std::max(ctx->samp_seqs, seq + 1);

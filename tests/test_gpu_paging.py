@@ -165,6 +165,15 @@ def test_a_record_moves_between_contexts_and_bad_records_are_refused():
     with pytest.raises(R.RdlmError) as e:                # cut short
         b.seq_admit(1, rec[: len(rec) // 2])
     assert e.value.status == R.STATUS["EINVAL"]
+    # a record whose fields contradict each other never reaches the device: 32-bit words of the header are
+    # magic, version, the model (12 words), then n_pos, n_blocks, prompt_len (word 16), ..., pos_bound (word 20), and the window record from
+    # word 22 on (prompt_len, n_frozen, win_pos0, win_n, ...)
+    for word, value in ((16, -1), (25, 1 << 20), (24, -5), (20, 1 << 30)):
+        bad = rec.copy()
+        bad.view(np.int32)[word] = value
+        with pytest.raises(R.RdlmError) as e:
+            b.seq_admit(1, bad)
+        assert e.value.status == R.STATUS["EINVAL"], (word, value)
     b.seq_admit(1, rec)                                  # the sequence started as number 0 of context a
     b.generate(1000)
     _check_against_own_run(b, m, 1, p, 0, n_new, r, kw)
