@@ -683,7 +683,10 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             auto lds = [](int fb, int mtw, int wm, int ku, int d, int ks) { return GemmPlan{mtw * wm, fb, wm, ku, ks, GEMM_LDS, d}; };
             const int tier = T <= 4 ? 0 : T <= 8 ? 1 : T <= 16 ? 2 : T <= 32 ? 3 : 4;
             switch (proj) {
-                case PROJ_GU: g = tier == 0 ? lds(5, 1, 4, 2, 6, 1) : tier == 1 ? lds(5, 1, 8, 1, 8, 1) : lds(5, 2, 8, 1, 6, 1); break;
+                case PROJ_GU:
+                    g = tier == 0 ? lds(5, 1, 4, 2, 6, 1) : tier == 1 ? (T <= 6 ? lds(5, 2, 4, 2, 4, 1) : lds(5, 1, 8, 1, 8, 1))
+                                                                      : lds(5, 2, 8, 1, 6, 1);
+                    break;
                 case PROJ_D:
                     if (tier == 0) g = lds(5, 1, 4, 2, 6, 7);
                     else if (tier == 1) g = lds(5, 2, 4, 2, 4, 7);
@@ -691,6 +694,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                 case PROJ_HEAD:
                     if (tier == 0) g = lds(8, 1, 4, 2, 6, 1);
                     else if (tier == 1 || tier == 3) g = lds(8, 1, 8, 1, 6, 1);
+                    else if (tier == 2) g = lds(4, 2, 8, 1, 6, 1);
                     else if (tier == 4) g = lds(5, 2, 8, 1, 6, 1);
                     break;
                 case PROJ_O:
