@@ -283,6 +283,9 @@ def main():
     ap.add_argument("--paper-default-steps", type=int, default=48,
                     help="sampler steps timed with the paper's default sampler settings (r'=4, wavefront limit 128, "
                          "eps 0.03, momentum 0.1, temperature 0.2, top-p 0.95); 0 = skip")
+    ap.add_argument("--settle-ms", type=float, default=200.0,
+                    help="untimed sampler steps (in chunks of 8) for this long after the wave fill and before "
+                         "--warmup (at most 256 steps), so that the timed steps see the machine's steady state; 0 = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-window-rows", type=int, default=4095,
                     help="rows of the large-window core step timed against the MFMA peak (0 = skip)")
@@ -336,7 +339,9 @@ def main():
     # converges before the cap), under the adaptive one
     fill_steps = -(-sp.r // sp.r_inner)
     K2_max = 64
-    n_new = max(sp.n_new, (fill_steps + K + W + K2_max + 1) * sp.headway)   # never finish inside the timed steps
+    # untimed lead-in after the wave fill (see --settle-ms), at most this many steps
+    settle_cap = 256 if args.settle_ms > 0 else 0
+    n_new = max(sp.n_new, (fill_steps + settle_cap + K + W + K2_max + 1) * sp.headway)   # never finish inside the timed steps
     max_positions = wl.prompt_len + n_new + window + sp.headway + 8
     max_rows = max(wl.prompt_len, n_seqs * (-(-window // 32) * 32))
     want_cpu = not args.no_cpu_baseline and args.workload in ("cfg2", "cfg3")
@@ -374,6 +379,23 @@ def main():
     # nothing is frozen before that many steps have run; after them every step freezes tokens
     for _ in range(fill_steps):
         ctx.sample_step()
+    # lead-in (untimed, not part of --warmup either): the headline is the steady-state rate of a generation.
+    # For 100-150 ms after a prefill every weight-streaming kernel runs about 5 % slower on this machine
+    # (its memory side takes that long to come back up after the matrix-core-heavy phase); the rate of
+    # that phase is measured on its first steps and reported beside the headline, not hidden.
+    torch.cuda.synchronize()
+    settle_steps, first_ms, t_settle, chunk_ms = 0, None, time.perf_counter(), []
+    while settle_steps < settle_cap and (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        t1 = time.perf_counter()
+        for _ in range(8):
+            ctx.sample_step()
+        torch.cuda.synchronize()
+        chunk_ms.append((time.perf_counter() - t1) / 8 * 1e3)
+        if first_ms is None:
+            first_ms = chunk_ms[0]
+        settle_steps += 8
+    if chunk_ms:
+        log("[bench] lead-in, ms/step by chunks of 8 steps: " + " ".join(f"{x:.3f}" for x in chunk_ms))
     for _ in range(W):
         ctx.sample_step()
     torch.cuda.synchronize()
@@ -501,6 +523,7 @@ def main():
                                + (f", adaptive exit eps={sp.eps}" if sp.adaptive else "")
                                + (f", headway {sp.headway}" if sp.headway > 1 else ""),
                    "tokens_in_timed_region": int(tokens), "fill_steps": int(fill_steps),
+                   "lead_in_steps": int(settle_steps), "ms_per_step_right_after_prefill": first_ms,
                    "context_at_end": int(nf2)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

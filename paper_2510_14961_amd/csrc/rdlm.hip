@@ -1520,9 +1520,11 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     ctx->seg_tiles = segs;
     ctx->grouped = wmax_now > TILE_ROWS;
     ctx->att_groups = n * (((wmax_now + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP);
-    int max_keys = 0;
+    // keys a window can see in this step (only the launch shape of the attention kernels depends on it):
+    // the host's bound on where the windows end, which follows the step count
+    int max_keys = 1;
     for (int q = 0; q < n; ++q)
-        max_keys = std::max(max_keys, std::min(ctx->max_positions, ctx->prompt_len[q] + s.n_new + s.w_max));
+        if (ctx->pos_bound[q] > 0) max_keys = std::max(max_keys, ctx->pos_bound[q]);
     // the tile list of this step was built by sampler_begin or by the end of the previous step
     std::swap(ctx->tiles, ctx->tiles_samp);
     std::swap(ctx->n_tiles, ctx->n_tiles_samp);
