@@ -450,10 +450,16 @@ def main():
     if args.ar_tokens > 0 and not sp.adaptive:
         ctx.set_tokens(0, prompts[0])          # caches of the prompt prefix are still in place
         ar_kw = dict(sampler_kw, r_inner=sp.r, headway=1, w_max=0)
-        ctx.sampler_begin(1, n_new=args.ar_tokens + 2, **ar_kw)
+        ar_lead = 16 if args.settle_ms > 0 else 0          # same untimed lead-in as the headline leg
+        ctx.sampler_begin(1, n_new=args.ar_tokens + 2 + ar_lead, **ar_kw)
         ctx.sample_step()
         ctx.sample_step()
         torch.cuda.synchronize()
+        t_settle = time.perf_counter()
+        while ar_lead > 0 and (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+            ctx.sample_step()
+            torch.cuda.synchronize()
+            ar_lead -= 1
         t0 = time.perf_counter()
         for _ in range(args.ar_tokens):
             ctx.sample_step()
