@@ -164,15 +164,19 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                 }
             } else {
                 const int u0 = 16 * j + f0;                  // < HALF; partner u0 + HALF
-                const float2* __restrict__ table = reinterpret_cast<const float2*>(A.epi.rope_table);
+                // the lane's four (cos, sin) pairs are 32 contiguous bytes of its row's table (u0 is a
+                // multiple of 4, the table 16-byte aligned): two 16-byte loads
+                const float4* __restrict__ table4 =
+                    reinterpret_cast<const float4*>(A.epi.rope_table + 2 * (row * HALF + u0));
+                const float4 t01 = table4[0], t23 = table4[1];
+                const float cs_c[4] = {t01.x, t01.z, t23.x, t23.z}, cs_s[4] = {t01.y, t01.w, t23.y, t23.w};
                 ushort4 p0, p1;
                 uint16_t* p0p = reinterpret_cast<uint16_t*>(&p0);
                 uint16_t* p1p = reinterpret_cast<uint16_t*>(&p1);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float2 cs = table[row * HALF + u0 + i];
-                    p0p[i] = f32_to_bf16(lo[i] * cs.x - hi[i] * cs.y);
-                    p1p[i] = f32_to_bf16(hi[i] * cs.x + lo[i] * cs.y);
+                    p0p[i] = f32_to_bf16(lo[i] * cs_c[i] - hi[i] * cs_s[i]);
+                    p1p[i] = f32_to_bf16(hi[i] * cs_c[i] + lo[i] * cs_s[i]);
                 }
                 if (sec == 0) {
                     uint16_t* dst = reinterpret_cast<uint16_t*>(A.epi.q_out) + row * h + head * D + u0;

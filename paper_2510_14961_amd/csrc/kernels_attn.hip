@@ -339,8 +339,11 @@ __global__ __launch_bounds__(ATT_GROUP * 64) void attn_group_k(const uint16_t* _
     __shared__ bf16x8 stage[2][SLOTS];
     // grid (heads, groups, splits): one workgroup per attention group, found through the leader list
     const int hd = blockIdx.x, sp = blockIdx.z;
-    if ((int)blockIdx.y >= n_tiles[1]) return;
-    const int t = n_tiles[TILE_LEADERS + blockIdx.y];
+    // (groups in reverse order: under the causal mask the later groups of a sequence see the most keys, and
+    // the workgroups that take longest should start first)
+    const int n_groups = n_tiles[1];
+    if ((int)blockIdx.y >= n_groups) return;
+    const int t = n_tiles[TILE_LEADERS + n_groups - 1 - (int)blockIdx.y];
     const TileDesc td = tiles[t];
     const int ng = min(td.group, ATT_GROUP);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
