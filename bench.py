@@ -237,7 +237,8 @@ def window_sweep(args):
     shape = S.BIG
     r = 32
     dev, _ = build_weights(shape, 1, False, args.threads)
-    ctx = R.Context(shape, dev, 1, 512 + 16 * 200 + 640, 512)
+    lead_cap = 160                                          # untimed lead-in after the wave fill (see --settle-ms)
+    ctx = R.Context(shape, dev, 1, 512 + 16 * (32 + lead_cap + 40 + 8) + 640, 512)
     del dev
     torch.cuda.empty_cache()
     prompt = S.make_prompt(shape.vocab, 512, 5, seq=0)
@@ -248,9 +249,17 @@ def window_sweep(args):
         K = 40 if r_inner <= 4 else 12
         ctx.set_tokens(0, prompt)
         ctx.prefill(0, 511, 1, 1.0, 1)                 # (timing only: one recurrence fills the caches)
-        ctx.sampler_begin(1, n_new=(fill + K + 8) * headway, r_inner=r_inner, r_total=r, headway=headway, seed=1)
+        ctx.sampler_begin(1, n_new=(fill + lead_cap + K + 8) * headway, r_inner=r_inner, r_total=r, headway=headway,
+                          seed=1)
         for _ in range(fill + 4):
             ctx.sample_step()
+        torch.cuda.synchronize()
+        lead, t_lead = 0, time.perf_counter()
+        while lead < lead_cap - 4 and (time.perf_counter() - t_lead) * 1e3 < args.settle_ms:
+            for _ in range(4):
+                ctx.sample_step()
+            torch.cuda.synchronize()
+            lead += 4
         n0 = ctx.read_tokens(0, 1)[1]
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -32,6 +32,7 @@ enum Proj { PROJ_QKV = 0, PROJ_O, PROJ_GU, PROJ_D, PROJ_A, PROJ_HEAD, PROJ_COUNT
 // inside a step.
 struct Knobs {
     int att_split = 0;               // > 0: forced number of KV splits of the attention kernels
+    long long att_group_keys = -1;   // >= 0: segments x visible keys from which the grouped attention kernel is used
     bool no_rope_fusion = false;     // RoPE + cache writes in a kernel of their own instead of the QKV epilogue
     bool no_fold_fusion = false;     // split-K folds in fold_k launches instead of the producing GEMM
     bool no_fold = false;            // full RMSNorm kernels instead of the deferred 1/rms factor
@@ -387,6 +388,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
     if (!name || !value) return RDLM_EINVAL;
     auto is = [&](const char* n) { return strcasecmp(name, n) == 0; };
     if (is("att_split")) { k->att_split = atoi(value); return RDLM_OK; }
+    if (is("att_group_keys")) { k->att_group_keys = *value ? atoll(value) : -1; return RDLM_OK; }
     if (is("no_rope_fusion")) { k->no_rope_fusion = atoi(value) != 0; return RDLM_OK; }
     if (is("no_fold_fusion")) { k->no_fold_fusion = atoi(value) != 0; return RDLM_OK; }
     if (is("no_fold")) { k->no_fold = atoi(value) != 0; return RDLM_OK; }
@@ -429,7 +431,7 @@ static int set_knob(Knobs* k, const char* name, const char* value) {
 }
 
 static void knobs_from_env(Knobs* k) {
-    static const char* names[] = {"att_split", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm", "no_hoist", "no_pack"};
+    static const char* names[] = {"att_split", "att_group_keys", "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm", "no_hoist", "no_pack"};
     auto env_of = [](const char* name) {
         char buf[48] = "RDLM_";
         size_t n = strlen(buf);
@@ -853,10 +855,21 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
     return RDLM_OK;
 }
 
-static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys) {
+// Sequences with several row tiles: the grouped kernel reads every K/V block once for up to four row tiles,
+// but its workgroups walk their key blocks one after the other; the one-tile kernel, launched per segment,
+// reads the blocks once per tile with four waves on different blocks.  Below about ATT_GROUP_KEYS
+// (segments x visible keys, i.e. K/V traffic of the per-segment launch) the second is faster.
+constexpr long long ATT_GROUP_KEYS = 7000;
+static bool att_grouped_for(const rdlm_ctx* ctx, int T, int max_keys) {
+    if (!ctx->grouped || ctx->m.dtype == RDLM_F32) return ctx->grouped;
+    const long long lim = ctx->knobs.att_group_keys >= 0 ? ctx->knobs.att_group_keys : ATT_GROUP_KEYS;
+    return (long long)T * max_keys > lim;
+}
+
+static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys, bool grouped) {
     if (ctx->m.dtype == RDLM_F32) return 1;
     if (ctx->knobs.att_split > 0) return std::min(ctx->knobs.att_split, ctx->att_max_split);
-    int wgs = ctx->m.n_heads * (ctx->grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
+    int wgs = ctx->m.n_heads * (grouped ? (T + ATT_GROUP - 1) / ATT_GROUP : T);
     int kb = (max_keys + 31) / 32;
     if (T == 1) {
         // one tile: n_heads workgroups per split.  Measured at 55 heads x 96: four splits pay from
@@ -908,8 +921,9 @@ static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, boo
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        kv_pages(ctx), ctx->tiles, ctx->n_tiles, T, st);
     const int segs = ctx->seg_tiles > 0 ? ctx->seg_tiles : T;      // attention works on segments, not on row tiles
+    const bool grouped = att_grouped_for(ctx, segs, max_keys);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, kv_pages(ctx),
-                     att_split_for(ctx, segs, max_keys), ctx->grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
+                     att_split_for(ctx, segs, max_keys, grouped), grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
                      ctx->rows_pad, ctx->n_tiles, segs, st, ctx->att_groups);
     const FoldSpec fo = {ctx->x, ctx->x, L.g2};
     bool folded = false;
