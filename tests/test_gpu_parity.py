@@ -661,6 +661,39 @@ def test_one_tile_window_behind_long_context_kv_splits(shape_name, forced_split,
     ctx.close()
 
 
+@pytest.mark.parametrize("shape_name", ["d96", "d64", "d32"])
+@pytest.mark.parametrize("path", ["grouped", "per_segment"])
+def test_window_of_several_row_tiles_through_either_attention_kernel(shape_name, path):
+    """A ragged window of three row tiles behind 300 cached positions, once through the grouped attention
+    kernel (K/V blocks staged once per group of row tiles, KV splits merged by a kernel of its own) and once
+    through the one-tile kernel launched per segment -- the host picks between them by the K/V traffic of the
+    launch, here each is forced ("att_group_keys") so that both are compared with the oracle at every head
+    size, and with each other."""
+    torch = _torch()
+    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32}[shape_name]
+    ctx, m, _ = make_pair(shape, max_positions=420, max_rows=320)
+    ctx.set_tuning("att_group_keys", "0" if path == "grouped" else "1000000000")
+    L, n = 300, 77
+    tokens = S.make_prompt(shape.vocab, L + n, 15)
+    ctx.set_tokens(0, tokens[:L])
+    ctx.prefill(0, L, 1, 1.0, 5)
+    cache = m.new_cache(420)
+    s_ref = m.prefill(tokens[:L], 1, 1.0, 5, 0, cache)
+    tol = tol_latent(shape)
+    assert_rows_close(ctx.read_states(0, 0, L), s_ref, tol, "prefill states, " + path)
+    pos = np.arange(L, L + n)
+    e_ref = m.prelude(tokens[L:], pos, cache)
+    z0 = np.stack([O.init_state(shape.hidden, p, 0, 1.0, 5) for p in pos])
+    z1 = m.core(e_ref, z0, pos, cache)
+    e = torch.zeros(n, shape.hidden, device="cuda")
+    ctx.prelude([0], [L], [n], _dev(tokens[L:].astype(np.int32)), e)
+    assert_rows_close(e.cpu().numpy(), e_ref, tol, "conditioning, " + path)
+    z = _dev(z0.astype(np.float32))
+    ctx.core_step([0], [L], [n], _dev(e_ref.astype(np.float32)), z, 1, None)
+    assert_rows_close(z.cpu().numpy(), z1, tol, "core step, " + path)
+    ctx.close()
+
+
 def test_long_context_attention_splits():
     """A context of more than a thousand positions (many key blocks, several KV splits merged) in
     front of a ragged window, head dim 96."""
