@@ -293,7 +293,7 @@ int rdlm_read_kv(rdlm_ctx* ctx, int32_t layer, int32_t seq, int32_t pos0, int32_
 /* ---- kernel-level entry points (measurement and unit tests) ------------------------------- */
 /* Tuning knobs of a context (launch shapes, fusion switches); the same names in upper case with
  * the prefix RDLM_ are read from the environment once, by rdlm_create.  Names: "att_split" (forced
- * number of KV splits, 0 = automatic), "att_group_keys" (segments x visible keys from which sequences with
+ * number of KV splits, 0 = automatic), "att_group_keys" (row tiles of a sequence x visible keys from which sequences with
  * several row tiles go through the grouped attention kernel; "" = default), "no_rope_fusion", "no_fold_fusion", "no_fold", "no_lds_gemm",
  * "no_hoist" (several recurrences per call: the e half of the adapter product is recomputed every
  * time instead of once), "no_pack" (every sequence's rows start a row tile of their own instead of short

@@ -118,6 +118,7 @@ struct rdlm_ctx : Workspace {
     std::vector<void*> allocs;
     bool coda_ready = false;        // the closing norm of the recurrence left the coda's first operand in xn
     bool grouped = false;           // current step: some sequence has several row tiles (grouped attention)
+    int seq_tiles_max = 1;          // current step: most row tiles of one sequence
     Knobs knobs;
     // per-launch GEMM timing
     int prof_n = 0, prof_k = 0, prof_used = 0;
@@ -858,12 +859,13 @@ static int run_proj(rdlm_ctx* ctx, int proj, const void* xin, const void* W, int
 // Sequences with several row tiles: the grouped kernel reads every K/V block once for up to four row tiles,
 // but its workgroups walk their key blocks one after the other; the one-tile kernel, launched per segment,
 // reads the blocks once per tile with four waves on different blocks.  Below about ATT_GROUP_KEYS
-// (segments x visible keys, i.e. K/V traffic of the per-segment launch) the second is faster.
+// (row tiles of a sequence x visible keys, i.e. the K/V traffic the per-segment launch spends on one
+// sequence) the second is faster, whatever the number of sequences in the step.
 constexpr long long ATT_GROUP_KEYS = 7000;
-static bool att_grouped_for(const rdlm_ctx* ctx, int T, int max_keys) {
+static bool att_grouped_for(const rdlm_ctx* ctx, int max_keys) {
     if (!ctx->grouped || ctx->m.dtype == RDLM_F32) return ctx->grouped;
     const long long lim = ctx->knobs.att_group_keys >= 0 ? ctx->knobs.att_group_keys : ATT_GROUP_KEYS;
-    return (long long)T * max_keys > lim;
+    return (long long)ctx->seq_tiles_max * max_keys > lim;
 }
 
 static int att_split_for(const rdlm_ctx* ctx, int T, int max_keys, bool grouped) {
@@ -921,7 +923,7 @@ static int layer_forward(rdlm_ctx* ctx, const Layer& L, int T, int max_keys, boo
         launch_rope_kv(ctx->qkv, 1, 0, ctx->q, L.kc, L.vc, m.dtype, m.n_heads, m.head_dim, ctx->rope_tab,
                        kv_pages(ctx), ctx->tiles, ctx->n_tiles, T, st);
     const int segs = ctx->seg_tiles > 0 ? ctx->seg_tiles : T;      // attention works on segments, not on row tiles
-    const bool grouped = att_grouped_for(ctx, segs, max_keys);
+    const bool grouped = att_grouped_for(ctx, max_keys);
     launch_attention(ctx->q, L.kc, L.vc, ctx->att, m.dtype, m.n_heads, m.head_dim, kv_pages(ctx),
                      att_split_for(ctx, segs, max_keys, grouped), grouped, ctx->att_ws, ctx->att_tickets, ctx->tiles,
                      ctx->rows_pad, ctx->n_tiles, segs, st, ctx->att_groups);
@@ -1093,7 +1095,11 @@ static int check_rows(rdlm_ctx* ctx, int n_seqs, const int32_t* seq_ids, const i
     ctx->seg_tiles = tiles;
     *M = rows; *max_keys = mk;
     bool grouped = false;
-    for (int i = 0; i < n_seqs; ++i) grouped = grouped || n_rows[i] > TILE_ROWS;
+    ctx->seq_tiles_max = 1;
+    for (int i = 0; i < n_seqs; ++i) {
+        grouped = grouped || n_rows[i] > TILE_ROWS;
+        ctx->seq_tiles_max = std::max(ctx->seq_tiles_max, (n_rows[i] + 31) / 32);
+    }
     ctx->grouped = grouped;
     ctx->att_groups = 0;
     for (int i = 0; i < n_seqs; ++i) ctx->att_groups += ((n_rows[i] + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP;
@@ -1141,6 +1147,7 @@ extern "C" int rdlm_prefill(rdlm_ctx* ctx, int32_t seq, int32_t n, int32_t r, fl
     w.n = 1; w.seq[0] = seq; w.pos0[0] = 0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->seq_tiles_max = T;
     ctx->seg_tiles = T;
     ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
     launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
@@ -1533,6 +1540,7 @@ extern "C" int rdlm_sample_step(rdlm_ctx* ctx) {
     const int T = (!ctx->knobs.no_pack && wmax_now <= TILE_ROWS) ? (n + TILE_ROWS / wmax_now - 1) / (TILE_ROWS / wmax_now) : segs;
     ctx->seg_tiles = segs;
     ctx->grouped = wmax_now > TILE_ROWS;
+    ctx->seq_tiles_max = (wmax_now + TILE_ROWS - 1) / TILE_ROWS;
     ctx->att_groups = n * (((wmax_now + 31) / 32 + ATT_GROUP - 1) / ATT_GROUP);
     // keys a window can see in this step (only the launch shape of the attention kernels depends on it):
     // the host's bound on where the windows end, which follows the step count
@@ -1947,6 +1955,7 @@ extern "C" int rdlm_time_core_step(rdlm_ctx* ctx, int32_t seq, int32_t pos0, int
     w.n = 1; w.seq[0] = seq; w.pos0[0] = pos0; w.rows[0] = n;
     const int T = (n + 31) / 32;
     ctx->grouped = T > 1;
+    ctx->seq_tiles_max = T;
     ctx->seg_tiles = T;
     ctx->att_groups = (T + ATT_GROUP - 1) / ATT_GROUP;
     launch_build_tiles_store(w, ctx->seq_ident, ctx->max_positions, ctx->tiles, ctx->n_tiles, ctx->rows_pad, !ctx->knobs.no_pack, ctx->st);
