@@ -52,8 +52,7 @@ enum { RDLM_F32 = 0, RDLM_BF16 = 1 };
 
 /* Shape of the model.  dtype is the storage type of the matrices (and of the KV cache and GEMM
  * operands); accumulation, norms, softmax and the latent state are always float32.
- * RDLM_BF16 needs hidden % 32 == 0, mlp % 32 == 0, vocab % 32 == 0 and head_dim 32, 64 or 96
- * (the attention kernels for 128 are not covered by parity tests and stay switched off).
+ * RDLM_BF16 needs hidden % 32 == 0, mlp % 32 == 0, vocab % 32 == 0 and head_dim 32, 64, 96 or 128.
  * Both types need hidden <= 8192 (row kernels keep a row in registers), mlp >= hidden (staging
  * buffers are sized by mlp) and an even head_dim; anything else is RDLM_EINVAL from rdlm_create. */
 typedef struct {

@@ -195,7 +195,7 @@ static bool model_ok(const rdlm_model* m) {
         if (m->hidden % 4 || m->mlp % 4) return false;
     } else if (m->dtype == RDLM_BF16) {
         if (m->hidden % 32 || m->mlp % 32 || m->vocab % 32) return false;
-        if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 96) return false;
+        if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 96 && m->head_dim != 128) return false;
     } else {
         return false;
     }

@@ -13,6 +13,8 @@ SMALL_BF16_D96 = S.ModelShape(vocab=384, hidden=288, n_heads=3, head_dim=96, mlp
                               n_prelude=1, n_core=2, n_coda=1, dtype="bf16")
 SMALL_BF16_D32 = S.ModelShape(vocab=256, hidden=160, n_heads=5, head_dim=32, mlp=224,
                               n_prelude=1, n_core=1, n_coda=1, dtype="bf16")
+SMALL_BF16_D128 = S.ModelShape(vocab=256, hidden=256, n_heads=2, head_dim=128, mlp=384,
+                               n_prelude=1, n_core=2, n_coda=1, dtype="bf16")
 
 
 def rel_l2(a, b) -> float:

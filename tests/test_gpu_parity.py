@@ -11,7 +11,7 @@ import pytest
 
 import synth_inputs as S
 from oracle import rdlm_oracle as O
-from gpu_util import (top_p_token_check, SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, assert_rows_close, make_pair,
+from gpu_util import (top_p_token_check, SMALL_BF16_D32, SMALL_BF16_D64, SMALL_BF16_D96, SMALL_BF16_D128, assert_rows_close, make_pair,
                       rel_l2, tau_for, teacher_forced_sampler_run, tie_aware_token_check, tol_latent, LAST_TIE_GAP)
 
 pytestmark = pytest.mark.gpu
@@ -30,8 +30,8 @@ def _dev(a, dtype=None):
     return t.cuda()
 
 
-ALL_SHAPES = [S.TINY, SMALL_BF16_D64, SMALL_BF16_D96, SMALL_BF16_D32]
-IDS = ["tiny_f32", "bf16_d64", "bf16_d96", "bf16_d32"]
+ALL_SHAPES = [S.TINY, SMALL_BF16_D64, SMALL_BF16_D96, SMALL_BF16_D32, SMALL_BF16_D128]
+IDS = ["tiny_f32", "bf16_d64", "bf16_d96", "bf16_d32", "bf16_d128"]
 
 
 # ------------------------------------------------------------------------------------------
@@ -625,14 +625,14 @@ def test_same_seed_twice_is_bitwise_identical():
     ctx.close()
 
 
-@pytest.mark.parametrize("shape_name,forced_split", [("d96", 0), ("d64", 8), ("d32", 0), ("d96", 2)])
+@pytest.mark.parametrize("shape_name,forced_split", [("d96", 0), ("d64", 8), ("d32", 0), ("d96", 2), ("d128", 0), ("d128", 8)])
 def test_one_tile_window_behind_long_context_kv_splits(shape_name, forced_split, monkeypatch):
     """One ragged row tile behind 1600 cached positions: the one-tile attention kernel splits the keys
     four ways by itself at this length (eight and two when forced), and the last workgroup of a
     head to arrive merges the splits -- in rounds of two accumulator quads, of which head sizes
-    96, 64 and 32 have three, two and one per wave."""
+    128, 96, 64 and 32 have four, three, two and one per wave."""
     torch = _torch()
-    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32}[shape_name]
+    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32, "d128": SMALL_BF16_D128}[shape_name]
     if forced_split:
         monkeypatch.setenv("RDLM_ATT_SPLIT", str(forced_split))      # read when the context is created
     ctx, m, _ = make_pair(shape, max_positions=1700, max_rows=1632)
@@ -661,7 +661,7 @@ def test_one_tile_window_behind_long_context_kv_splits(shape_name, forced_split,
     ctx.close()
 
 
-@pytest.mark.parametrize("shape_name", ["d96", "d64", "d32"])
+@pytest.mark.parametrize("shape_name", ["d96", "d64", "d32", "d128"])
 @pytest.mark.parametrize("path", ["grouped", "per_segment"])
 def test_window_of_several_row_tiles_through_either_attention_kernel(shape_name, path):
     """A ragged window of three row tiles behind 300 cached positions, once through the grouped attention
@@ -670,7 +670,7 @@ def test_window_of_several_row_tiles_through_either_attention_kernel(shape_name,
     launch, here each is forced ("att_group_keys") so that both are compared with the oracle at every head
     size, and with each other."""
     torch = _torch()
-    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32}[shape_name]
+    shape = {"d96": SMALL_BF16_D96, "d64": SMALL_BF16_D64, "d32": SMALL_BF16_D32, "d128": SMALL_BF16_D128}[shape_name]
     ctx, m, _ = make_pair(shape, max_positions=420, max_rows=320)
     ctx.set_tuning("att_group_keys", "0" if path == "grouped" else "1000000000")
     L, n = 300, 77
