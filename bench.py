@@ -278,6 +278,35 @@ def window_sweep(args):
     ctx.close()
 
 
+def attention_paths(args):
+    """Windows of several row tiles: the core step (four layers) with the grouped attention kernel and with the
+    one-tile kernel launched per segment, each forced through the "att_group_keys" knob, over rows x context --
+    the measurement behind the rule the host applies (row tiles of a sequence x visible keys)."""
+    import torch
+    import paper_2510_14961_amd as R
+    shape = S.BIG
+    dev, _ = build_weights(shape, 1, False, args.threads)
+    ctx = R.Context(shape, dev, 1, 8192 + 600, 512)
+    del dev
+    torch.cuda.empty_cache()
+    ctx.time_core_step(0, 512, 64, 5)
+    out = []
+    for rows in (64, 128, 256, 512):
+        for c in (512, 1024, 2048, 4096, 8192):
+            row = {"rows": rows, "context": c, "tiles_x_keys": (rows // 32) * (c + rows)}
+            for key, lim in (("grouped_us", "0"), ("per_segment_us", "1000000000")):
+                ctx.set_tuning("att_group_keys", lim)
+                row[key] = ctx.time_core_step(0, c, rows, 10) * 1e3
+            ctx.set_tuning("att_group_keys", "")
+            row["default_us"] = ctx.time_core_step(0, c, rows, 10) * 1e3
+            out.append(row)
+            log(f"[attention] rows {rows:4d} context {c:5d}: grouped {row['grouped_us']:8.1f} us, per segment "
+                f"{row['per_segment_us']:8.1f} us, default {row['default_us']:8.1f} us")
+    print(json.dumps({"attention_paths": out, "shape": "3.5B: 5280 x 55 x 96, four core layers + adapter, bf16"}),
+          flush=True)
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -305,6 +334,8 @@ def main():
                          "packed into shared row tiles against one row tile per sequence")
     ap.add_argument("--window-sweep", action="store_true",
                     help="tokens/s against the number of tokens in flight: headway 1..16 and r' 1..32 (Sec. 4.2)")
+    ap.add_argument("--attention-paths", action="store_true",
+                    help="core step with the grouped and with the per-segment attention kernel over rows x context")
     ap.add_argument("--core-sweep", action="store_true",
                     help="instead of the benchmark: time one core step (r' = 1) at the 3.5B shape over a grid of window "
                          "rows x cached context, print the table and the measured ridge (rows at which the step "
@@ -325,6 +356,9 @@ def main():
     torch.cuda.set_device(0)
     if args.window_sweep:
         window_sweep(args)
+        return
+    if args.attention_paths:
+        attention_paths(args)
         return
     if args.batch_sweep:
         batch_sweep(args)
