@@ -709,7 +709,8 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
                     else if (tier == 2) g = lds(4, 1, 8, 1, 8, 3);
                     break;
                 case PROJ_QKV:
-                    if (tier == 1) g = lds(4, 1, 4, 2, 6, 1);
+                    if (tier == 0) g = lds(2, 1, 4, 2, 6, 1);
+                    else if (tier == 1) g = lds(4, 1, 4, 2, 6, 1);
                     break;
                 default: break;
             }
