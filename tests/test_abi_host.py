@@ -119,3 +119,13 @@ def test_entry_points_added_later_refuse_a_null_context(lib):
     assert lib.rdlm_sampler_status(None, None, None) == -1
     assert R.STATIC_SCRATCH_BYTES == int(re.search(r"RDLM_STATIC_SCRATCH_BYTES \((\d+)u << 20\)",
                                                    open(os.path.join(ROOT, "include", "rdlm.h")).read()).group(1)) << 20
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus 2 says so and exits non-zero before it touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
