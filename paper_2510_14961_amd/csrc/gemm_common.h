@@ -85,7 +85,8 @@ __device__ __forceinline__ void gemm_row_scales(const GemmArgs& A, int t0, int n
 template <int MT, int NB, int WAVES, int DEAL, int EPI, class QuadSum, class CV, class CI, bool OWN_ROWS = false>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk)[NB], int t0, int n_tiles, int ks,
                                               int grp, const float (&sc)[MT], QuadSum quad_sum, CV& cand_v,
-                                              CI& cand_i) {
+                                              CI& cand_i, const TileDesc* pre_td = nullptr,
+                                              const int* pre_kvblk = nullptr) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nblk = A.N >> 5;
     const int col = lane & 31, g = lane >> 5;
@@ -98,7 +99,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
 #pragma unroll
     for (int b = 0; b < MT; ++b) {
         const int t = min(t0 + b, n_tiles - 1);
-        if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = A.epi.tiles[t * 32 + col];
+        // (pre_td / pre_kvblk: the descriptor and the cache block of the lane's row, fetched by the caller
+        // before its K loop so that the stores below do not wait for two loads in a row)
+        if (EPI == EPI_ARGMAX || EPI == EPI_ROPE_KV) td[b] = pre_td ? pre_td[b] : A.epi.tiles[t * 32 + col];
     }
     float best_v[MT];
     int best_i[MT];
@@ -154,7 +157,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                 if (valid) {
                     const int u0 = 32 * j + f0;
                     uint16_t* Vt = reinterpret_cast<uint16_t*>(A.epi.vc) +
-                                   kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h) +
+                                   (pre_kvblk ? (size_t)pre_kvblk[b] * ((size_t)32 * h)
+                                              : kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h)) +
                                    ((size_t)head * D + u0) * 32 + vt_slot(pos & 31);
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -184,7 +188,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& A, const int (&blk
                     *reinterpret_cast<ushort4*>(dst + HALF) = p1;
                 } else if (valid) {
                     uint16_t* Kc = reinterpret_cast<uint16_t*>(A.epi.kc) +
-                                   kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h);
+                                   (pre_kvblk ? (size_t)pre_kvblk[b] * ((size_t)32 * h)
+                                              : kv_block_base(A.epi.kv, td[b].seq, pos >> 5, (size_t)32 * h));
                     *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos & 31, head, u0, H, D)) = p0;
                     *reinterpret_cast<ushort4*>(Kc + k_cache_off(pos & 31, head, u0 + HALF, H, D)) = p1;
                 }

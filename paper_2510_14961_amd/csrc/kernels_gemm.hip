@@ -138,6 +138,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GEMM_KERNEL_PARAMS) {
     const int kbeg = (int)(((long long)K16 * sl) / slices), kend = (int)(((long long)K16 * (sl + 1)) / slices);
     float sc[MT];
     gemm_row_scales<MT>(A, t0, n_tiles, sc);        // late_count: tile 0, as n_tiles = 1 stands in
+    // RoPE / cache epilogue over one row tile: the lane's row descriptor and, once it is there, the cache block
+    // of the row's position are asked for up front, so the epilogue's stores do not wait for two dependent
+    // loads.  The descriptor is valid memory for every row of tile t0; when the tile count is only looked at
+    // after the K loop it may be a stale one, so the table index is clamped to the table (the epilogue, which
+    // runs only for tiles of this step, then finds the entry of its own row).
+    constexpr bool PRE = (EPI == EPI_ROPE_KV && MT == 1);
+    TileDesc pre_td[1];
+    int pre_kvblk[1] = {0};
+    if constexpr (PRE) pre_td[0] = A.epi.tiles[(size_t)t0 * 32 + (lane & 31)];
+    auto pre_lookup = [&]() {
+        if constexpr (PRE)
+            pre_kvblk[0] = A.epi.kv.table[(size_t)min(max(pre_td[0].seq, 0), A.epi.kv.slots - 1) * A.epi.kv.stride +
+                                          min(max(pre_td[0].pos0 >> 5, 0), A.epi.kv.stride - 1)];
+    };
 
     f32x16 acc[NB][MT];
 #pragma unroll
@@ -187,6 +201,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GEMM_KERNEL_PARAMS) {
     int batches = (kend - kbeg) / U;
     if (batches > 0) {                              // double-buffered: one batch in flight while one is consumed
         load(wa, xa, kt); kt += U;
+        pre_lookup();
         int rem = batches - 1;
         while (rem >= 2) {
             load(wb, xb, kt); kt += U;
@@ -203,6 +218,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GEMM_KERNEL_PARAMS) {
             compute(wa, xa);
         }
     }
+    if (batches <= 0) pre_lookup();
     for (; kt < kend; ++kt) {
 #pragma unroll
         for (int a = 0; a < NB; ++a) {
@@ -268,7 +284,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_bf16_k(GEMM_KERNEL_PARAMS) {
                 }
             }
         };
-        gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i);
+        gemm_epilogue<MT, NB, WAVES, WAVES, EPI>(A, blk, t0, n_tiles, ks, grp, sc, quad_sum, cand_v, cand_i,
+                                                 PRE ? pre_td : nullptr, PRE ? pre_kvblk : nullptr);
     }
     if constexpr (EPI == EPI_F32 && MT == 1 && (NB == 1 || NB == 2 || NB == 4))
         if (A.epi.fold_counter) gemm_fold_tail<NB, WAVES * 64>(A, grp, t0);

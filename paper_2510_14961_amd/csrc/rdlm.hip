@@ -555,6 +555,7 @@ static KvPages kv_pages(const rdlm_ctx* ctx) {
     KvPages kv;
     kv.table = ctx->blk_table;
     kv.stride = ctx->blocks_per_seq;
+    kv.slots = ctx->max_seqs;
     return kv;
 }
 

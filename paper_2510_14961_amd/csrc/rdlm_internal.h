@@ -40,6 +40,7 @@ struct TileDesc {
 struct KvPages {
     const int32_t* table = nullptr;   // device [slots][stride]
     int32_t stride = 0;               // logical blocks per slot
+    int32_t slots = 0;                // rows of the table
 };
 __device__ inline size_t kv_block_base(const KvPages& kv, int seq, int block, size_t block_elems) {
     return (size_t)kv.table[(size_t)seq * kv.stride + block] * block_elems;
