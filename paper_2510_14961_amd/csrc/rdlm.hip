@@ -622,11 +622,12 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
     const bool split_ok = proj == PROJ_O || proj == PROJ_D || proj == PROJ_A;
     if (T == 1) {
         switch (proj) {
-            case PROJ_GU: g = {1, 5, 4, 2, 1}; break;
+            // (alternating runs inside the sampler step, 3.5B shape: eight waves with one k tile per batch
+            // beat four waves with two for gate/up by 0.7 us per launch, two waves with four for QKV by 0.8)
+            case PROJ_GU: g = {1, 5, 8, 1, 1}; break;
             case PROJ_HEAD: g = {1, 4, 4, 2, 1}; break;
-            case PROJ_QKV: g = {1, 2, 2, 4, 1}; break;
-            case PROJ_D: g = {1, 2, 8, 2, 3}; break;
-            default: g = {1, 2, 8, 1, 3}; break;       // O, A
+            case PROJ_QKV: g = {1, 2, 8, 1, 1}; break;
+            default: g = {1, 2, 8, 1, 3}; break;       // O, D, A
         }
         if (ctx->knobs.has_plan[proj]) g = ctx->knobs.plan[proj];
     } else {
