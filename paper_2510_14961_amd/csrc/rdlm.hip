@@ -661,7 +661,7 @@ static GemmPlan plan_for(const rdlm_ctx* ctx, int proj, int N, int K, int T) {
             switch (proj) {
                 case PROJ_GU: g = {2, 5, 4, 2, 1}; break;
                 case PROJ_HEAD: g = {2, 4, 4, 2, 1}; break;
-                case PROJ_QKV: g = {2, 2, 2, 4, 1}; break;
+                case PROJ_QKV: g = {2, 2, 8, 1, 1}; break;
                 case PROJ_A: g = GemmPlan{2, 1, 8, 4, 8, GEMM_ROWS}; break;
                 default: g = {2, 2, 8, 1, 3}; break;       // O, D
             }
